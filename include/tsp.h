@@ -1,0 +1,225 @@
+/*
+ * tsp - tiled mixed-precision sparse matrix-matrix multiply C = A*B for AMD MI355X (gfx950).
+ *
+ * C ABI of libtsp.so.  The library follows the tSparse pipeline (paper Sections 3 and 4,
+ * Algorithm 1): CSR inputs are cut into 16x16 tiles of which only the non-empty ones are
+ * kept, with an occupancy bitmap each (Section 2.1.2); a task list of contributing
+ * (A tile, B tile) pairs is built per output tile, sorted by output tile (Section 4.1); a
+ * counting pass sizes the output from the bitmaps alone (Section 4.2); the multiplication
+ * pass multiplies every pair as a small dense block, fp16 inputs with fp32 accumulation
+ * (Sections 2.6 and 4.3), on the matrix cores; the result is written back as CSR.
+ *
+ * Conventions
+ *  - Every function returns TSP_OK (0) or a negative tsp_status.  No exceptions, no aborts.
+ *  - All matrix arrays are DEVICE pointers.  Structs and out-parameters are HOST memory.
+ *  - `stream` arguments are a hipStream_t passed as void* (NULL = the default stream).  All
+ *    device work of a call is enqueued on that stream.  Calls that have to size an allocation
+ *    synchronise the stream; each function says how often.
+ *  - A handle may be used by one host thread and one stream at a time.
+ *  - CSR inputs must be canonical: row_ptr[0] = 0, row_ptr non-decreasing, row_ptr[rows] = nnz,
+ *    column indices inside [0, cols) and strictly ascending within a row.  With validation on
+ *    (the default) a violation returns TSP_ERR_NOT_CANONICAL; with it off the behaviour is
+ *    undefined.  A stored entry is structural whatever its value (an explicit 0.0 counts).
+ *  - The output pattern is structural: position (i,j) is present when some k has a_ik and
+ *    b_kj stored, also when the terms cancel (the counting pass of Section 4.2 defines the
+ *    size; the numeric-zero compaction of Section 4.4 is not applied).
+ */
+#ifndef TSP_H
+#define TSP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    TSP_OK = 0,
+    TSP_ERR_INVALID_ARG = -1,     /* NULL pointer, negative size, unknown enum value                  */
+    TSP_ERR_SHAPE_MISMATCH = -2,  /* A.cols != B.rows                                                 */
+    TSP_ERR_NOT_CANONICAL = -3,   /* input CSR violates the conventions above (validation on)         */
+    TSP_ERR_ALLOC_FAILED = -4,    /* the device allocator returned NULL                               */
+    TSP_ERR_INDEX_OVERFLOW = -5,  /* a size exceeds the index width of the format (see tsp_csr)       */
+    TSP_ERR_HIP = -6,             /* a HIP runtime call failed; tsp_last_hip_error() has the code     */
+    TSP_ERR_UNSUPPORTED = -7      /* a documented limit of this build is exceeded                     */
+} tsp_status;
+
+enum { TSP_I32 = 0, TSP_I64 = 1 };   /* row_ptr element type   */
+enum { TSP_F16 = 0, TSP_F32 = 1 };   /* value element type     */
+
+/*
+ * CSR matrix, device arrays.  Inputs: row_ptr is int32[rows+1] (TSP_I32) or int64[rows+1]
+ * (TSP_I64); col_idx is int32[nnz]; val is IEEE binary16 bit patterns uint16[nnz] (TSP_F16) or
+ * float[nnz] (TSP_F32, rounded to nearest-even fp16 on the device before use, the input
+ * conversion the paper includes in its timing, Section 6.3).  Limits: rows, cols < 2^31 - 16,
+ * nnz < 2^31.  Outputs of this library: row_ptr int64[rows+1], col_idx int32[nnz], val
+ * float[nnz].
+ */
+typedef struct {
+    int64_t rows, cols, nnz;
+    void *row_ptr;
+    int32_t *col_idx;
+    void *val;
+    int32_t row_ptr_type;   /* TSP_I32 | TSP_I64 */
+    int32_t val_type;       /* TSP_F16 | TSP_F32 */
+} tsp_csr;
+
+/*
+ * Device allocator used for every workspace and output array.  alloc returns a device pointer
+ * aligned to at least 256 bytes, or NULL; free releases a pointer alloc returned.  Both are
+ * called from the host thread that calls the library; `stream` is the stream of that call.
+ * The handle keeps freed blocks in a cache of its own and reuses them, so in the steady state
+ * (same problem sizes call after call) the callbacks are not invoked.
+ */
+typedef struct {
+    void *(*alloc)(void *user, size_t bytes, void *stream);
+    void (*free)(void *user, void *ptr, void *stream);
+    void *user;
+} tsp_allocator;
+
+typedef struct tsp_context *tsp_handle;
+typedef struct tsp_tiles_s *tsp_tiles;   /* a matrix in tile (bitmap) format, device resident */
+typedef struct tsp_plan_s *tsp_plan;     /* task list + output pattern of one product          */
+
+/* Option keys for tsp_set_option. */
+enum {
+    TSP_OPT_VALIDATE = 1,      /* 1 (default): check that CSR inputs are canonical                 */
+    TSP_OPT_PHASE_TIMERS = 2   /* 1: bracket every phase with HIP events on the call's stream and   */
+                               /*    report the durations in tsp_stats; 0 (default): no events      */
+};
+
+/* Phases reported in tsp_stats.phase_us, in pipeline order. */
+enum {
+    TSP_PHASE_CONVERT = 0,     /* CSR -> tiles: occupancy scan + packing (Section 2.1.2)            */
+    TSP_PHASE_SYMBOLIC = 1,    /* tile correspondence, zero-product cull, sizing, task list (4.1)   */
+    TSP_PHASE_COUNT = 2,       /* counting pass on bitmaps, row_ptr of C (Section 4.2)              */
+    TSP_PHASE_NUMERIC = 3,     /* multiplication pass + CSR emission (Sections 4.3, 4.4)            */
+    TSP_PHASE_COUNT_ = 4
+};
+
+/* Counters and timings of the most recent tsp_spgemm / phase calls on a handle. */
+typedef struct {
+    int64_t a_tiles, b_tiles;        /* non-empty tiles of the operands                              */
+    int64_t candidate_pairs;         /* (A tile, B tile) pairs with matching inner tile index         */
+    int64_t pairs;                   /* pairs left after the zero-product cull = task list length     */
+    int64_t c_tiles;                 /* output tiles (all structurally non-empty)                     */
+    int64_t c_nnz;                   /* structural nonzeros of C                                      */
+    int64_t workspace_bytes;         /* bytes currently held by the handle (cache + live objects)     */
+    int64_t workspace_peak_bytes;    /* high-water mark of the above                                  */
+    float phase_us[TSP_PHASE_COUNT_];/* device time per phase of the last call, if timers are on      */
+    float total_us;                  /* first event to last event of the last tsp_spgemm, if timers on */
+} tsp_stats;
+
+/* Create a handle on the current HIP device.  allocator == NULL selects hipMalloc/hipFree. */
+int tsp_create(tsp_handle *handle, const tsp_allocator *allocator);
+
+/* Free every block the handle still holds (cache and live objects) and the handle itself. */
+int tsp_destroy(tsp_handle handle);
+
+int tsp_set_option(tsp_handle handle, int key, int64_t value);
+
+/* Return every cached (not live) block to the allocator. */
+int tsp_trim(tsp_handle handle, void *stream);
+
+/*
+ * C = A*B (paper Section 2.2, Algorithm 1), CSR in, CSR out, everything on `stream`.
+ * A and B are borrowed and never modified; they may be the same object (A*A converts once).
+ * On success *C is filled: rows = A.rows, cols = B.cols, nnz, row_ptr (TSP_I64), col_idx,
+ * val (TSP_F32), the three arrays freshly taken from the handle's allocator and owned by the
+ * caller, who releases them with tsp_csr_free.  Columns ascend strictly within each row.
+ * On failure *C is zeroed and nothing is leaked.  When the call returns, the stream has been
+ * synchronised (the sizes of the task list and of C are read back to size the allocations,
+ * the step Algorithm 1 calls AllocateMemGPU) and C is complete.
+ * Errors: INVALID_ARG, SHAPE_MISMATCH, NOT_CANONICAL, ALLOC_FAILED, INDEX_OVERFLOW, HIP,
+ * UNSUPPORTED (B has more than 2^24 tile columns, i.e. B.cols > 268 million).
+ */
+int tsp_spgemm(tsp_handle handle, const tsp_csr *A, const tsp_csr *B, tsp_csr *C, void *stream);
+
+/* Release the arrays of a matrix returned by this library and zero the struct. */
+int tsp_csr_free(tsp_handle handle, tsp_csr *C, void *stream);
+
+/* ----- the pipeline phase by phase (tsp_spgemm is exactly these calls in order) ----------- */
+
+enum {
+    TSP_FORM_LEFT = 1,    /* element storage for use as the left operand  (row-wise groups)    */
+    TSP_FORM_RIGHT = 2    /* element storage for use as the right operand (column-wise groups) */
+};
+
+/*
+ * CSR -> tile format (Section 2.1.2 with 16x16 tiles): tile occupancy scan, then per-tile
+ * packing.  `forms` is a bit set of TSP_FORM_*.  Synchronises the stream once (tile count).
+ * The result is owned by the caller (tsp_tiles_free).
+ */
+int tsp_convert(tsp_handle handle, const tsp_csr *A, int forms, tsp_tiles *out, void *stream);
+int tsp_tiles_free(tsp_handle handle, tsp_tiles tiles, void *stream);
+
+/*
+ * Read-only view of a tile matrix, for inspection and tests.  Device pointers unless noted.
+ * Tiles are stored tile-row by tile-row, ascending tile column inside a tile-row (CSR of
+ * tiles).  row_mask[t*16 + r] has bit c set when slot (r,c) of tile t is occupied.
+ * Element storage is in 16-byte groups of 8 fp16 values, zero filled where a slot is empty,
+ * and only non-empty groups are stored.  Left form: group id g = h*16 + r holds slots
+ * (r, 8h..8h+7); right form: group id g = h*16 + c holds slots (8h..8h+7, c).  Bit g of the
+ * group mask says whether group g is stored; the stored groups of a tile are consecutive, in
+ * ascending g, starting at group index *_group_off[t] of the form's element array.
+ */
+typedef struct {
+    int64_t rows, cols;              /* of the matrix (host values)                                 */
+    int64_t tile_rows, tile_cols;    /* ceil(rows/16), ceil(cols/16)                                */
+    int64_t ntiles;
+    int32_t forms;
+    const int32_t *tile_row_ptr;     /* int32[tile_rows + 1]                                        */
+    const int32_t *tile_col;         /* int32[ntiles]                                               */
+    const uint16_t *row_mask;        /* uint16[ntiles * 16]                                         */
+    const uint32_t *left_group_mask, *right_group_mask;   /* uint32[ntiles] (always present)        */
+    const uint32_t *left_group_off, *right_group_off;     /* uint32[ntiles] (NULL if form absent)   */
+    const uint16_t *left_elements, *right_elements;       /* fp16 bits, 8 per group (NULL if absent) */
+    int64_t left_groups_capacity, right_groups_capacity;  /* groups the element arrays can hold     */
+} tsp_tiles_view;
+int tsp_tiles_get_view(tsp_tiles tiles, tsp_tiles_view *view);
+
+/*
+ * Symbolic phase + counting pass for C = A*B on tile matrices (Sections 4.1 and 4.2, Algorithm 1
+ * lines 1-17): tile correspondence, zero-product cull on the occupancy words, sizing scans, task
+ * list grouped by output tile (output tiles row-major, pairs of a tile in ascending inner
+ * index), boolean product of the bitmaps per output tile, row_ptr of C.  A needs no particular
+ * form, nor does B.  Synchronises the stream twice (task-list size; nnz of C).
+ */
+int tsp_symbolic(tsp_handle handle, tsp_tiles A, tsp_tiles B, tsp_plan *out, void *stream);
+int tsp_plan_free(tsp_handle handle, tsp_plan plan, void *stream);
+
+/* Read-only view of a plan.  Device pointers unless noted. */
+typedef struct {
+    int64_t c_rows, c_cols;          /* host values                                                 */
+    int64_t c_tile_rows;
+    int64_t c_tiles, pairs, c_nnz, candidate_pairs;
+    const int32_t *c_tile_row_ptr;   /* int32[c_tile_rows + 1]                                      */
+    const int32_t *c_tile_row;       /* int32[c_tiles]                                              */
+    const int32_t *c_tile_col;       /* int32[c_tiles], ascending inside a tile-row                 */
+    const int64_t *pair_off;         /* int64[c_tiles + 1] segment offsets into the task list       */
+    const int32_t *pair_a, *pair_b;  /* int32[pairs] tile index in A / in B                         */
+    const uint16_t *c_row_mask;      /* uint16[c_tiles * 16] structural pattern of each output tile */
+    const uint32_t *c_row_off;       /* uint32[c_tiles * 16] entries of CSR row 16I+r before tile   */
+    const int64_t *c_row_ptr;        /* int64[c_rows + 1]                                           */
+} tsp_plan_view;
+int tsp_plan_get_view(tsp_plan plan, tsp_plan_view *view);
+
+/*
+ * Multiplication pass + CSR emission (Sections 4.3, 4.4): every task-list pair is multiplied
+ * as a 16x16x16 block product on the matrix cores, fp16 inputs, fp32 accumulation, the pairs of
+ * one output tile accumulated in registers in task-list order; the tile's structural entries
+ * are written straight to their CSR positions.  A must hold TSP_FORM_LEFT, B TSP_FORM_RIGHT,
+ * and the plan must come from tsp_symbolic on the same pair of tile matrices.  Allocates C
+ * (see tsp_spgemm for ownership).  Does not synchronise.
+ */
+int tsp_numeric(tsp_handle handle, tsp_tiles A, tsp_tiles B, tsp_plan plan, tsp_csr *C, void *stream);
+
+int tsp_get_stats(tsp_handle handle, tsp_stats *out);
+const char *tsp_strerror(int status);
+int tsp_last_hip_error(tsp_handle handle);   /* hipError_t of the last TSP_ERR_HIP on this handle */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TSP_H */

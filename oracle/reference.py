@@ -55,13 +55,14 @@ def _ptr(a: np.ndarray):
 
 
 class _Operand:
-    """Contiguous int64/int32/uint16 views of a CSR matrix for the C calls."""
+    """Contiguous int64/int32/float64 arrays of a CSR matrix for the C calls."""
 
     def __init__(self, m):
         self.rows, self.cols = int(m.rows), int(m.cols)
         self.row_ptr = np.ascontiguousarray(m.row_ptr, dtype=np.int64)
         self.col = np.ascontiguousarray(m.col_idx, dtype=np.int32)
-        self.val = np.ascontiguousarray(np.asarray(m.val, dtype=np.float16).view(np.uint16))
+        # the inputs are fp16 numbers; widening them to fp64 is exact
+        self.val = np.ascontiguousarray(np.asarray(m.val, dtype=np.float16).astype(np.float64))
 
 
 def row_nnz(A, B, row_begin: int = 0, row_end: int | None = None):

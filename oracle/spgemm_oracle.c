@@ -5,9 +5,10 @@
  *
  * What it computes is the plain definition of the sparse product (paper Section 2.2):
  * an output position (i,j) exists when some k has both a_ik and b_kj stored, and its
- * value is the sum over those k of a_ik*b_kj.  Inputs are IEEE fp16 bit patterns; the
- * mixed-precision unit the paper targets multiplies them exactly and accumulates in
- * fp32 (Section 2.6), so the reference value is the exact products summed in fp64.
+ * value is the sum over those k of a_ik*b_kj.  Inputs are fp16 numbers, handed over
+ * widened (exactly) to fp64 by the caller; the mixed-precision unit the paper targets
+ * multiplies them exactly and accumulates in fp32 (Section 2.6), so the reference value
+ * is the exact products (22 significant bits at most) summed in fp64.
  * Beside each value the oracle returns s_ij = sum_k |a_ik||b_kj|, the scale of the
  * acceptance bound |c - c_ref| <= 1e-5*s + 1e-7.
  *
@@ -21,22 +22,6 @@
 #include <stdlib.h>
 #include <string.h>
 #include <math.h>
-
-/* IEEE 754 binary16 bit pattern -> double (exact). */
-static double half_bits_to_double(uint16_t h)
-{
-    int sign = (h >> 15) & 1;
-    int exponent = (h >> 10) & 0x1f;
-    int mantissa = h & 0x3ff;
-    double v;
-    if (exponent == 0)
-        v = ldexp((double)mantissa, -24);                    /* zero and subnormals */
-    else if (exponent == 31)
-        v = mantissa ? NAN : INFINITY;
-    else
-        v = ldexp((double)(mantissa | 0x400), exponent - 25);
-    return sign ? -v : v;
-}
 
 static int compare_int32(const void *a, const void *b)
 {
@@ -81,8 +66,8 @@ int64_t oracle_spgemm_row_nnz(int64_t n_cols_b,
  * Returns the number of entries written, or -1 when memory runs out.
  */
 int64_t oracle_spgemm_rows(int64_t n_cols_b,
-                           const int64_t *a_row_ptr, const int32_t *a_col, const uint16_t *a_val,
-                           const int64_t *b_row_ptr, const int32_t *b_col, const uint16_t *b_val,
+                           const int64_t *a_row_ptr, const int32_t *a_col, const double *a_val,
+                           const int64_t *b_row_ptr, const int32_t *b_col, const double *b_val,
                            int64_t row_begin, int64_t row_end,
                            int32_t *c_col, double *c_val, double *c_abs)
 {
@@ -98,10 +83,10 @@ int64_t oracle_spgemm_rows(int64_t n_cols_b,
         int64_t count = 0;
         for (int64_t p = a_row_ptr[i]; p < a_row_ptr[i + 1]; ++p) {
             int64_t k = a_col[p];
-            double a = half_bits_to_double(a_val[p]);
+            double a = a_val[p];
             for (int64_t q = b_row_ptr[k]; q < b_row_ptr[k + 1]; ++q) {
                 int64_t j = b_col[q];
-                double prod = a * half_bits_to_double(b_val[q]);
+                double prod = a * b_val[q];
                 if (mark[j] != i) {
                     mark[j] = i;
                     list[count++] = (int32_t)j;

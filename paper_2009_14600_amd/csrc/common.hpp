@@ -1,0 +1,158 @@
+// Internal declarations shared by the translation units of libtsp.so (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <cstring>
+#include <unordered_map>
+#include <vector>
+
+#include "tsp.h"
+
+namespace tsp {
+
+constexpr int T = 16;               // tile edge: one output tile = one 16x16 MFMA accumulator
+constexpr int kScalars = 32;        // device/host scalar slots of a handle
+
+// Slots of the handle's device scalar block (int64 each).
+enum Scalar {
+    S_INVALID = 0,       // != 0: an input CSR is not canonical
+    S_UNSUPPORTED = 1,   // != 0: a documented limit was exceeded on the device
+    S_TILES_A = 2,
+    S_TILES_B = 3,
+    S_C_TILES = 4,
+    S_PAIRS = 5,
+    S_CANDIDATES = 6,
+    S_MAX_ROW_C_TILES = 7,   // max over C tile-rows of the number of C tiles
+    S_MAX_ROW_WORDS = 8,     // max over C tile-rows of bitmap words needed
+    S_C_NNZ = 9,
+    S_MAX_ROW_A_TILES = 10,
+};
+
+struct Block {
+    void *ptr;
+    size_t bytes;
+};
+
+}  // namespace tsp
+
+struct tsp_context {
+    tsp_allocator allocator{};
+    bool user_allocator = false;
+    int device = 0;
+    std::vector<tsp::Block> cache;                 // free blocks, reusable
+    std::unordered_map<void *, size_t> live;       // blocks handed out
+    int64_t held_bytes = 0, peak_bytes = 0;
+    int validate = 1;
+    int timers = 0;
+    int last_hip = 0;
+    tsp_stats stats{};
+    int64_t *d_scalars = nullptr;                  // device, kScalars entries
+    int64_t *h_scalars = nullptr;                  // pinned host mirror
+    hipEvent_t ev[2 * TSP_PHASE_COUNT_ + 2]{};     // begin/end per phase, + total begin/end
+    bool ev_created = false;
+    bool ev_recorded[2 * TSP_PHASE_COUNT_ + 2]{};
+};
+
+struct tsp_tiles_s {
+    int64_t rows = 0, cols = 0, nnz = 0;
+    int64_t tile_rows = 0, tile_cols = 0;
+    int64_t ntiles = -1;                 // -1 until read back from the device
+    int64_t tile_capacity = 0;
+    int forms = 0;
+    int scalar_slot = 0;                 // S_TILES_A or S_TILES_B: where the device leaves ntiles
+    int32_t *tile_row_ptr = nullptr;
+    int32_t *tile_col = nullptr;
+    uint16_t *row_mask = nullptr;
+    uint32_t *lmask = nullptr, *rmask = nullptr;
+    uint32_t *loff = nullptr, *roff = nullptr;
+    uint4 *ldata = nullptr, *rdata = nullptr;
+    int64_t group_capacity = 0;
+};
+
+struct tsp_plan_s {
+    int64_t c_rows = 0, c_cols = 0, c_tile_rows = 0;
+    int64_t c_tiles = 0, pairs = 0, c_nnz = 0, candidates = 0;
+    int32_t *c_tile_row_ptr = nullptr;
+    int32_t *c_tile_row = nullptr, *c_tile_col = nullptr;
+    int64_t *pair_off = nullptr;
+    int32_t *pair_a = nullptr, *pair_b = nullptr;
+    uint16_t *c_row_mask = nullptr;
+    uint32_t *c_row_off = nullptr;
+    int64_t *c_row_ptr = nullptr;
+};
+
+namespace tsp {
+
+// ---- host helpers (context.hip) -------------------------------------------------------
+void *ctx_alloc(tsp_context *ctx, size_t bytes, hipStream_t s);          // NULL on failure
+void ctx_free(tsp_context *ctx, void *p, hipStream_t s);                 // back into the cache
+int hip_fail(tsp_context *ctx, hipError_t e);                            // records e, returns TSP_ERR_HIP
+int read_scalars(tsp_context *ctx, hipStream_t s);                       // d_scalars -> h_scalars, syncs
+void phase_begin(tsp_context *ctx, int phase, hipStream_t s);
+void phase_end(tsp_context *ctx, int phase, hipStream_t s);
+void total_begin(tsp_context *ctx, hipStream_t s);
+void total_end(tsp_context *ctx, hipStream_t s);
+void collect_timers(tsp_context *ctx);                                   // after a sync
+
+template <typename Tp>
+inline Tp *ctx_alloc_n(tsp_context *ctx, size_t n, hipStream_t s) {
+    return static_cast<Tp *>(ctx_alloc(ctx, (n ? n : 1) * sizeof(Tp), s));
+}
+
+#define TSP_HIP_CHECK(ctx, expr)                                   \
+    do {                                                           \
+        hipError_t e_ = (expr);                                    \
+        if (e_ != hipSuccess) return ::tsp::hip_fail((ctx), e_);   \
+    } while (0)
+
+// ---- scans (scan.hip) -----------------------------------------------------------------
+// out[i] = sum of in[0..i), i = 0..n (n+1 entries).  If d_total != nullptr, *d_total = out[n]
+// as int64; if d_max != nullptr, *d_max = max(in) as int64 (0 for n = 0).
+// tmp: workspace of scan_tmp_entries(n) int64.
+size_t scan_tmp_entries(int64_t n);
+int scan_exclusive_i32_to_i32(tsp_context *ctx, const int32_t *in, int32_t *out, int64_t n,
+                              int64_t *d_total, int64_t *d_max, int64_t *tmp, hipStream_t s);
+int scan_exclusive_i32_to_i64(tsp_context *ctx, const int32_t *in, int64_t *out, int64_t n,
+                              int64_t *d_total, int64_t *d_max, int64_t *tmp, hipStream_t s);
+
+// ---- phases (internal forms; the C ABI wraps them) -------------------------------------
+int convert_enqueue(tsp_context *ctx, const tsp_csr *A, int forms, int scalar_slot, tsp_tiles_s **out,
+                    hipStream_t s);
+void tiles_release(tsp_context *ctx, tsp_tiles_s *t, hipStream_t s);
+int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **out, hipStream_t s);
+void plan_release(tsp_context *ctx, tsp_plan_s *p, hipStream_t s);
+int numeric_enqueue(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s *plan, tsp_csr *C,
+                    hipStream_t s);
+
+#ifdef __HIPCC__
+// ---- device helpers -------------------------------------------------------------------
+__device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
+
+// Orders LDS traffic between the lanes of one wave (no block barrier needed).
+__device__ __forceinline__ void wave_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+__device__ __forceinline__ int group16_min(int v) {
+#pragma unroll
+    for (int o = 8; o >= 1; o >>= 1) v = min(v, __shfl_xor(v, o, 16));
+    return v;
+}
+__device__ __forceinline__ uint32_t group16_or(uint32_t v) {
+#pragma unroll
+    for (int o = 8; o >= 1; o >>= 1) v |= (uint32_t)__shfl_xor((int)v, o, 16);
+    return v;
+}
+// 16-bit slice of a wave ballot that belongs to this lane's 16-lane group.
+__device__ __forceinline__ uint32_t group16_ballot(bool pred) {
+    unsigned long long b = __ballot(pred);
+    return (uint32_t)(b >> (lane_id() & 48)) & 0xFFFFu;
+}
+__device__ __forceinline__ uint32_t fold16(uint32_t m) { return (m | (m >> 16)) & 0xFFFFu; }
+#endif
+
+}  // namespace tsp

@@ -1,0 +1,216 @@
+// Handle, device-memory cache, options, statistics, error strings.
+#include "common.hpp"
+
+#include <algorithm>
+#include <new>
+
+namespace tsp {
+
+static void *default_alloc(void *, size_t bytes, void *) {
+    void *p = nullptr;
+    if (hipMalloc(&p, bytes) != hipSuccess) {
+        (void)hipGetLastError();
+        return nullptr;
+    }
+    return p;
+}
+static void default_free(void *, void *p, void *) { (void)hipFree(p); }
+
+int hip_fail(tsp_context *ctx, hipError_t e) {
+    if (ctx) ctx->last_hip = (int)e;
+    (void)hipGetLastError();
+    return TSP_ERR_HIP;
+}
+
+// Best fit from the cache; a cached block is taken only if it wastes at most half of itself.
+void *ctx_alloc(tsp_context *ctx, size_t bytes, hipStream_t s) {
+    bytes = (bytes + 255) & ~size_t(255);
+    if (bytes == 0) bytes = 256;
+    int best = -1;
+    for (int i = 0; i < (int)ctx->cache.size(); ++i) {
+        size_t b = ctx->cache[i].bytes;
+        if (b >= bytes && b <= 2 * bytes + 4096 && (best < 0 || b < ctx->cache[best].bytes)) best = i;
+    }
+    void *p;
+    size_t got;
+    if (best >= 0) {
+        p = ctx->cache[best].ptr;
+        got = ctx->cache[best].bytes;
+        ctx->cache[best] = ctx->cache.back();
+        ctx->cache.pop_back();
+    } else {
+        p = ctx->allocator.alloc(ctx->allocator.user, bytes, (void *)s);
+        if (!p) {
+            // give cached memory back and retry once
+            for (auto &b : ctx->cache) {
+                ctx->allocator.free(ctx->allocator.user, b.ptr, (void *)s);
+                ctx->held_bytes -= (int64_t)b.bytes;
+            }
+            ctx->cache.clear();
+            p = ctx->allocator.alloc(ctx->allocator.user, bytes, (void *)s);
+            if (!p) return nullptr;
+        }
+        got = bytes;
+        ctx->held_bytes += (int64_t)got;
+        ctx->peak_bytes = std::max(ctx->peak_bytes, ctx->held_bytes);
+    }
+    ctx->live.emplace(p, got);
+    return p;
+}
+
+void ctx_free(tsp_context *ctx, void *p, hipStream_t) {
+    if (!p) return;
+    auto it = ctx->live.find(p);
+    if (it == ctx->live.end()) return;   // not ours: ignore
+    ctx->cache.push_back({p, it->second});
+    ctx->live.erase(it);
+}
+
+int read_scalars(tsp_context *ctx, hipStream_t s) {
+    TSP_HIP_CHECK(ctx, hipMemcpyAsync(ctx->h_scalars, ctx->d_scalars, sizeof(int64_t) * kScalars,
+                                      hipMemcpyDeviceToHost, s));
+    TSP_HIP_CHECK(ctx, hipStreamSynchronize(s));
+    return TSP_OK;
+}
+
+static void ensure_events(tsp_context *ctx) {
+    if (ctx->ev_created) return;
+    for (auto &e : ctx->ev) (void)hipEventCreate(&e);
+    ctx->ev_created = true;
+}
+void phase_begin(tsp_context *ctx, int phase, hipStream_t s) {
+    if (!ctx->timers) return;
+    ensure_events(ctx);
+    // a phase entered more than once in a call (conversion of A, then of B) keeps its first begin
+    if (!ctx->ev_recorded[2 * phase]) {
+        (void)hipEventRecord(ctx->ev[2 * phase], s);
+        ctx->ev_recorded[2 * phase] = true;
+    }
+}
+void phase_end(tsp_context *ctx, int phase, hipStream_t s) {
+    if (!ctx->timers) return;
+    ensure_events(ctx);
+    (void)hipEventRecord(ctx->ev[2 * phase + 1], s);
+    ctx->ev_recorded[2 * phase + 1] = true;
+}
+void total_begin(tsp_context *ctx, hipStream_t s) {
+    if (!ctx->timers) return;
+    ensure_events(ctx);
+    for (auto &r : ctx->ev_recorded) r = false;
+    (void)hipEventRecord(ctx->ev[2 * TSP_PHASE_COUNT_], s);
+    ctx->ev_recorded[2 * TSP_PHASE_COUNT_] = true;
+}
+void total_end(tsp_context *ctx, hipStream_t s) {
+    if (!ctx->timers) return;
+    (void)hipEventRecord(ctx->ev[2 * TSP_PHASE_COUNT_ + 1], s);
+    ctx->ev_recorded[2 * TSP_PHASE_COUNT_ + 1] = true;
+}
+void collect_timers(tsp_context *ctx) {
+    if (!ctx->timers || !ctx->ev_created) return;
+    for (int p = 0; p <= TSP_PHASE_COUNT_; ++p) {
+        float ms = 0.f;
+        float *dst = p < TSP_PHASE_COUNT_ ? &ctx->stats.phase_us[p] : &ctx->stats.total_us;
+        *dst = 0.f;
+        if (ctx->ev_recorded[2 * p] && ctx->ev_recorded[2 * p + 1] &&
+            hipEventElapsedTime(&ms, ctx->ev[2 * p], ctx->ev[2 * p + 1]) == hipSuccess)
+            *dst = ms * 1000.f;
+        else
+            (void)hipGetLastError();
+    }
+}
+
+}  // namespace tsp
+
+using namespace tsp;
+
+extern "C" int tsp_create(tsp_handle *handle, const tsp_allocator *allocator) {
+    if (!handle) return TSP_ERR_INVALID_ARG;
+    *handle = nullptr;
+    if (allocator && (!allocator->alloc || !allocator->free)) return TSP_ERR_INVALID_ARG;
+    tsp_context *ctx = new (std::nothrow) tsp_context();
+    if (!ctx) return TSP_ERR_ALLOC_FAILED;
+    if (allocator) {
+        ctx->allocator = *allocator;
+        ctx->user_allocator = true;
+    } else {
+        ctx->allocator = {default_alloc, default_free, nullptr};
+    }
+    hipError_t e = hipGetDevice(&ctx->device);
+    if (e == hipSuccess) e = hipMalloc((void **)&ctx->d_scalars, sizeof(int64_t) * kScalars);
+    if (e == hipSuccess) e = hipHostMalloc((void **)&ctx->h_scalars, sizeof(int64_t) * kScalars, hipHostMallocDefault);
+    if (e != hipSuccess) {
+        if (ctx->d_scalars) (void)hipFree(ctx->d_scalars);
+        (void)hipGetLastError();
+        delete ctx;
+        return TSP_ERR_HIP;
+    }
+    *handle = ctx;
+    return TSP_OK;
+}
+
+extern "C" int tsp_destroy(tsp_handle ctx) {
+    if (!ctx) return TSP_ERR_INVALID_ARG;
+    (void)hipDeviceSynchronize();
+    for (auto &b : ctx->cache) ctx->allocator.free(ctx->allocator.user, b.ptr, nullptr);
+    for (auto &kv : ctx->live) ctx->allocator.free(ctx->allocator.user, kv.first, nullptr);
+    if (ctx->ev_created)
+        for (auto &e : ctx->ev) (void)hipEventDestroy(e);
+    (void)hipFree(ctx->d_scalars);
+    (void)hipHostFree(ctx->h_scalars);
+    delete ctx;
+    return TSP_OK;
+}
+
+extern "C" int tsp_set_option(tsp_handle ctx, int key, int64_t value) {
+    if (!ctx) return TSP_ERR_INVALID_ARG;
+    switch (key) {
+        case TSP_OPT_VALIDATE: ctx->validate = value != 0; return TSP_OK;
+        case TSP_OPT_PHASE_TIMERS: ctx->timers = value != 0; return TSP_OK;
+        default: return TSP_ERR_INVALID_ARG;
+    }
+}
+
+extern "C" int tsp_trim(tsp_handle ctx, void *stream) {
+    if (!ctx) return TSP_ERR_INVALID_ARG;
+    TSP_HIP_CHECK(ctx, hipStreamSynchronize((hipStream_t)stream));
+    for (auto &b : ctx->cache) {
+        ctx->allocator.free(ctx->allocator.user, b.ptr, stream);
+        ctx->held_bytes -= (int64_t)b.bytes;
+    }
+    ctx->cache.clear();
+    return TSP_OK;
+}
+
+extern "C" int tsp_get_stats(tsp_handle ctx, tsp_stats *out) {
+    if (!ctx || !out) return TSP_ERR_INVALID_ARG;
+    ctx->stats.workspace_bytes = ctx->held_bytes;
+    ctx->stats.workspace_peak_bytes = ctx->peak_bytes;
+    *out = ctx->stats;
+    return TSP_OK;
+}
+
+extern "C" int tsp_last_hip_error(tsp_handle ctx) { return ctx ? ctx->last_hip : 0; }
+
+extern "C" const char *tsp_strerror(int status) {
+    switch (status) {
+        case TSP_OK: return "success";
+        case TSP_ERR_INVALID_ARG: return "invalid argument";
+        case TSP_ERR_SHAPE_MISMATCH: return "inner dimensions differ (A.cols != B.rows)";
+        case TSP_ERR_NOT_CANONICAL: return "input CSR is not canonical";
+        case TSP_ERR_ALLOC_FAILED: return "device allocation failed";
+        case TSP_ERR_INDEX_OVERFLOW: return "a size exceeds the index width of the format";
+        case TSP_ERR_HIP: return "HIP runtime error";
+        case TSP_ERR_UNSUPPORTED: return "a limit of this build is exceeded";
+        default: return "unknown status";
+    }
+}
+
+extern "C" int tsp_csr_free(tsp_handle ctx, tsp_csr *C, void *stream) {
+    if (!ctx || !C) return TSP_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    ctx_free(ctx, C->row_ptr, s);
+    ctx_free(ctx, C->col_idx, s);
+    ctx_free(ctx, C->val, s);
+    std::memset(C, 0, sizeof(*C));
+    return TSP_OK;
+}

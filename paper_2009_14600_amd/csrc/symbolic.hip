@@ -1,0 +1,530 @@
+// Tile-level symbolic phase and counting pass (paper Sections 4.1 and 4.2, Algorithm 1 lines 1-17).
+//
+// The paper expands every (A tile, B tile) correspondence into a global list, culls it, sorts it
+// twice and reduces it by key.  Here one workgroup owns one tile-row I of C and never leaves LDS:
+//   1. candidates: for each tile A[I,K], each tile B[K,J] (tile correspondence);
+//   2. cull: the pair survives iff some inner index k has a non-empty column k in the A tile and a
+//      non-empty row k in the B tile (the boolean test on the occupancy words; a surviving pair
+//      contributes at least one structural entry, so no listed C tile is empty);
+//   3. the surviving J of the tile-row are marked in an LDS bitmap over tile columns; its popcount
+//      is the number of C tiles of the row and the rank of a bit is the C tile's position, which
+//      sorts the row by J without a sort;
+//   4. per C tile a word records which A tiles (by position in the tile-row, 32 at a time)
+//      contribute: bitwise OR is order independent, so the pair count (popcount) and each pair's
+//      position inside its segment (popcount of the lower bits = ascending inner index K) are
+//      deterministic although the candidates are visited in parallel.
+// Prefix sums over the tile-rows give the C tile offsets and the task-list offsets.
+// The counting pass then forms, per C tile, the boolean product of the bitmaps of its pairs
+// (Section 4.2: "simulates" the multiplication on 0/1 tiles; here with integer bit operations on
+// the 16-bit row masks, which gives the same pattern), and the per-row counts give row_ptr of C.
+#include "common.hpp"
+
+#include <climits>
+#include <new>
+
+namespace tsp {
+
+constexpr int kSymThreads = 256;
+constexpr int kMaxWords = 4096;        // LDS bitmap words per tile-row: span of 131072 tile columns
+constexpr int kWindow = 2048;          // C tiles of one tile-row handled per LDS window
+
+struct TileRefs {
+    const int32_t *trp;      // tile_row_ptr
+    const int32_t *tcol;     // tile_col
+    const uint32_t *lmask;   // left group mask  -> row occupancy
+    const uint32_t *rmask;   // right group mask -> column occupancy
+    int32_t tile_rows;
+};
+
+__device__ __forceinline__ uint32_t block_sum_u32(uint32_t v, uint32_t *lds /*[>=16]*/) {
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) v += (uint32_t)__shfl_xor((int)v, o, 64);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) lds[threadIdx.x >> 6] = v;
+    __syncthreads();
+    uint32_t s = 0;
+    for (int w = 0; w < (int)(blockDim.x >> 6); ++w) s += lds[w];
+    return s;
+}
+
+// In-place exclusive scan of arr[0..n) by the whole block; returns the total.
+__device__ __forceinline__ uint32_t block_exclusive_scan_lds(uint32_t *arr, int n, uint32_t *lds /*[>=17]*/) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+    uint32_t carry = 0;
+    for (int base = 0; base < n; base += blockDim.x) {
+        const int i = base + threadIdx.x;
+        const uint32_t x = i < n ? arr[i] : 0;
+        uint32_t v = x;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            uint32_t u = (uint32_t)__shfl_up((int)v, o, 64);
+            if (lane >= o) v += u;
+        }
+        __syncthreads();
+        if (lane == 63) lds[wave] = v;
+        __syncthreads();
+        uint32_t before = 0, all = 0;
+        for (int w = 0; w < nw; ++w) {
+            uint32_t y = lds[w];
+            if (w < wave) before += y;
+            all += y;
+        }
+        if (i < n) arr[i] = carry + before + v - x;
+        carry += all;
+    }
+    __syncthreads();
+    return carry;
+}
+
+// Visits every surviving candidate pair of tile-row I whose A tile index lies in [a_begin,a_end).
+// `lanes_per_a` lanes share one A tile and stride over the tiles of B's tile-row K.
+// f(a, b, J) is called once per survivor; *candidates counts all candidates visited by this thread.
+template <class F>
+__device__ __forceinline__ void for_each_survivor(const TileRefs &A, const TileRefs &B, int a_begin, int a_end,
+                                                  int lanes_per_a, uint32_t *candidates, F f) {
+    const int sub = threadIdx.x / lanes_per_a, l = threadIdx.x % lanes_per_a;
+    const int nsub = blockDim.x / lanes_per_a;
+    for (int a = a_begin + sub; a < a_end; a += nsub) {
+        const uint32_t K = (uint32_t)A.tcol[a];
+        if (K >= (uint32_t)B.tile_rows) continue;            // only possible for a non-canonical input
+        const uint32_t col_occ = fold16(A.rmask[a]);
+        const int b0 = B.trp[K], b1 = B.trp[K + 1];
+        for (int b = b0 + l; b < b1; b += lanes_per_a) {
+            ++*candidates;
+            if (col_occ & fold16(B.lmask[b])) f(a, b, B.tcol[b]);
+        }
+    }
+}
+
+// Pass 1 per tile-row: span of candidate tile columns, number of C tiles, of surviving pairs, of
+// candidates.  Dynamic LDS: max_words words.
+__global__ __launch_bounds__(kSymThreads) void k_sym_count(TileRefs A, TileRefs B, int lanes_per_a, int max_words,
+                                                           int32_t *__restrict__ row_jmin,
+                                                           int32_t *__restrict__ row_c_tiles,
+                                                           int32_t *__restrict__ row_pairs,
+                                                           int64_t *__restrict__ d_scalars) {
+    extern __shared__ uint32_t lds_dyn[];
+    __shared__ uint32_t red[32];
+    __shared__ int s_jmin, s_jmax;
+    uint32_t *bm = lds_dyn;
+    const int I = blockIdx.x;
+    const int a0 = A.trp[I], a1 = A.trp[I + 1];
+    if (threadIdx.x == 0) {
+        s_jmin = INT_MAX;
+        s_jmax = -1;
+    }
+    __syncthreads();
+    int jmin = INT_MAX, jmax = -1;
+    for (int a = a0 + threadIdx.x; a < a1; a += blockDim.x) {
+        const uint32_t K = (uint32_t)A.tcol[a];
+        if (K >= (uint32_t)B.tile_rows) continue;
+        const int b0 = B.trp[K], b1 = B.trp[K + 1];
+        if (b0 < b1) {
+            jmin = min(jmin, B.tcol[b0]);
+            jmax = max(jmax, B.tcol[b1 - 1]);
+        }
+    }
+    if (jmax >= 0) {
+        atomicMin(&s_jmin, jmin);
+        atomicMax(&s_jmax, jmax);
+    }
+    __syncthreads();
+    jmin = s_jmin;
+    jmax = s_jmax;
+    if (jmax < 0 || jmin < 0) {       // no candidates in this tile-row
+        if (threadIdx.x == 0) {
+            row_jmin[I] = 0;
+            row_c_tiles[I] = 0;
+            row_pairs[I] = 0;
+        }
+        return;
+    }
+    const int64_t span = (int64_t)jmax - jmin + 1;
+    const int words = (int)((span + 31) >> 5);
+    if (words > max_words) {
+        if (threadIdx.x == 0) {
+            d_scalars[S_UNSUPPORTED] = 1;
+            row_jmin[I] = 0;
+            row_c_tiles[I] = 0;
+            row_pairs[I] = 0;
+        }
+        return;
+    }
+    for (int w = threadIdx.x; w < words; w += blockDim.x) bm[w] = 0;
+    __syncthreads();
+    uint32_t cand = 0, surv = 0;
+    for_each_survivor(A, B, a0, a1, lanes_per_a, &cand, [&](int, int, int J) {
+        const uint32_t j = (uint32_t)(J - jmin);
+        if (j < (uint32_t)span) {
+            atomicOr(&bm[j >> 5], 1u << (j & 31));
+            ++surv;
+        }
+    });
+    __syncthreads();
+    uint32_t cnt = 0;
+    for (int w = threadIdx.x; w < words; w += blockDim.x) cnt += __popc(bm[w]);
+    cnt = block_sum_u32(cnt, red);
+    surv = block_sum_u32(surv, red);
+    cand = block_sum_u32(cand, red);
+    if (threadIdx.x == 0) {
+        row_jmin[I] = jmin;
+        row_c_tiles[I] = (int32_t)cnt;
+        row_pairs[I] = (int32_t)surv;
+        atomicAdd((unsigned long long *)&d_scalars[S_CANDIDATES], (unsigned long long)cand);
+        atomicMax((unsigned long long *)&d_scalars[S_MAX_ROW_WORDS], (unsigned long long)words);
+        atomicMax((unsigned long long *)&d_scalars[S_MAX_ROW_A_TILES], (unsigned long long)(a1 - a0));
+    }
+}
+
+// Pass 2 per tile-row: C tile coordinates, task-list offsets, task list.
+// Dynamic LDS: 2*words_cap + 2*window words.
+__global__ __launch_bounds__(kSymThreads) void k_sym_emit(
+    TileRefs A, TileRefs B, int lanes_per_a, int words_cap, int window, const int32_t *__restrict__ row_jmin,
+    const int32_t *__restrict__ c_tile_row_ptr, const int64_t *__restrict__ row_pair_ptr,
+    int32_t *__restrict__ c_tile_row, int32_t *__restrict__ c_tile_col, int64_t *__restrict__ pair_off,
+    int32_t *__restrict__ pair_a, int32_t *__restrict__ pair_b) {
+    extern __shared__ uint32_t lds_dyn[];
+    __shared__ uint32_t red[32];
+    uint32_t *bm = lds_dyn;
+    uint32_t *wpre = bm + words_cap;
+    uint32_t *contrib = wpre + words_cap;
+    uint32_t *cnt = contrib + window;
+    const int I = blockIdx.x;
+    const int c0 = c_tile_row_ptr[I], nC = c_tile_row_ptr[I + 1] - c0;
+    if (I == (int)gridDim.x - 1 && threadIdx.x == 0) pair_off[c_tile_row_ptr[gridDim.x]] = row_pair_ptr[gridDim.x];
+    if (nC <= 0) return;
+    const int a0 = A.trp[I], a1 = A.trp[I + 1];
+    const int jmin = row_jmin[I];
+    // the span is recomputed from the bitmap extent the first pass used: highest J over the row
+    int jmax = -1;
+    for (int a = a0 + threadIdx.x; a < a1; a += blockDim.x) {
+        const uint32_t K = (uint32_t)A.tcol[a];
+        if (K >= (uint32_t)B.tile_rows) continue;
+        const int b0 = B.trp[K], b1 = B.trp[K + 1];
+        if (b0 < b1) jmax = max(jmax, B.tcol[b1 - 1]);
+    }
+    __shared__ int s_jmax;
+    if (threadIdx.x == 0) s_jmax = -1;
+    __syncthreads();
+    if (jmax >= 0) atomicMax(&s_jmax, jmax);
+    __syncthreads();
+    jmax = s_jmax;
+    const int64_t span = (int64_t)jmax - jmin + 1;
+    const int words = (int)((span + 31) >> 5);       // <= words_cap: rows over the limit have nC = 0
+    for (int w = threadIdx.x; w < words; w += blockDim.x) bm[w] = 0;
+    __syncthreads();
+    uint32_t dummy = 0;
+    for_each_survivor(A, B, a0, a1, lanes_per_a, &dummy, [&](int, int, int J) {
+        const uint32_t j = (uint32_t)(J - jmin);
+        if (j < (uint32_t)span) atomicOr(&bm[j >> 5], 1u << (j & 31));
+    });
+    __syncthreads();
+    for (int w = threadIdx.x; w < words; w += blockDim.x) wpre[w] = __popc(bm[w]);
+    __syncthreads();
+    block_exclusive_scan_lds(wpre, words, red);
+    // C tile coordinates, ascending J
+    for (int w = threadIdx.x; w < words; w += blockDim.x) {
+        uint32_t bits = bm[w];
+        int c = c0 + (int)wpre[w];
+        while (bits) {
+            const int bit = __ffs(bits) - 1;
+            bits &= bits - 1;
+            c_tile_row[c] = I;
+            c_tile_col[c] = jmin + w * 32 + bit;
+            ++c;
+        }
+    }
+    const int64_t row_base = row_pair_ptr[I];
+    const bool one_chunk = (a1 - a0) <= 32;
+    uint32_t win_base = 0;
+    for (int win0 = 0; win0 < nC; win0 += window) {
+        const int nw = min(window, nC - win0);
+        auto rank_in_window = [&](int J) -> int {
+            const uint32_t j = (uint32_t)(J - jmin);
+            if (j >= (uint32_t)span) return -1;
+            const uint32_t word = bm[j >> 5];
+            const int c = (int)wpre[j >> 5] + __popc(word & ((1u << (j & 31)) - 1u)) - win0;
+            return (c >= 0 && c < nw) ? c : -1;
+        };
+        for (int c = threadIdx.x; c < nw; c += blockDim.x) cnt[c] = 0;
+        // count pass: 32 A tiles at a time
+        for (int ch = a0; ch < a1; ch += 32) {
+            for (int c = threadIdx.x; c < nw; c += blockDim.x) contrib[c] = 0;
+            __syncthreads();
+            for_each_survivor(A, B, ch, min(ch + 32, a1), lanes_per_a, &dummy, [&](int a, int, int J) {
+                const int c = rank_in_window(J);
+                if (c >= 0) atomicOr(&contrib[c], 1u << (a - ch));
+            });
+            __syncthreads();
+            for (int c = threadIdx.x; c < nw; c += blockDim.x) cnt[c] += __popc(contrib[c]);
+            __syncthreads();
+        }
+        const uint32_t win_total = block_exclusive_scan_lds(cnt, nw, red);
+        for (int c = threadIdx.x; c < nw; c += blockDim.x)
+            pair_off[c0 + win0 + c] = row_base + (int64_t)win_base + (int64_t)cnt[c];
+        // emit pass
+        for (int ch = a0; ch < a1; ch += 32) {
+            if (!one_chunk) {
+                for (int c = threadIdx.x; c < nw; c += blockDim.x) contrib[c] = 0;
+                __syncthreads();
+                for_each_survivor(A, B, ch, min(ch + 32, a1), lanes_per_a, &dummy, [&](int a, int, int J) {
+                    const int c = rank_in_window(J);
+                    if (c >= 0) atomicOr(&contrib[c], 1u << (a - ch));
+                });
+                __syncthreads();
+            }
+            for_each_survivor(A, B, ch, min(ch + 32, a1), lanes_per_a, &dummy, [&](int a, int b, int J) {
+                const int c = rank_in_window(J);
+                if (c >= 0) {
+                    const int64_t pos = row_base + (int64_t)win_base + (int64_t)cnt[c] +
+                                        __popc(contrib[c] & ((1u << (a - ch)) - 1u));
+                    pair_a[pos] = a;
+                    pair_b[pos] = b;
+                }
+            });
+            __syncthreads();
+            if (!one_chunk) {
+                for (int c = threadIdx.x; c < nw; c += blockDim.x) cnt[c] += __popc(contrib[c]);
+                __syncthreads();
+            }
+        }
+        win_base += win_total;
+        __syncthreads();
+    }
+}
+
+// Counting pass: 16 lanes per C tile, lane r owns row r of the tile.  For each pair of the tile's
+// segment: c_mask[r] |= OR over the set bits k of the A tile's row mask r of the B tile's row mask k.
+__global__ __launch_bounds__(256) void k_count_masks(int64_t c_tiles, const int64_t *__restrict__ pair_off,
+                                                     const int32_t *__restrict__ pair_a,
+                                                     const int32_t *__restrict__ pair_b,
+                                                     const uint16_t *__restrict__ a_row_mask,
+                                                     const uint16_t *__restrict__ b_row_mask,
+                                                     uint16_t *__restrict__ c_row_mask) {
+    const int64_t c = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 4;
+    const int r = threadIdx.x & 15;
+    if (c >= c_tiles) return;
+    const int64_t s0 = pair_off[c], s1 = pair_off[c + 1];
+    uint32_t acc = 0;
+    for (int64_t p = s0; p < s1; ++p) {
+        const int64_t a = pair_a[p], b = pair_b[p];
+        const uint32_t am = a_row_mask[a * T + r];
+        const uint4 *bp = reinterpret_cast<const uint4 *>(b_row_mask + b * T);
+        const uint4 x = bp[0], y = bp[1];
+        const uint32_t w[8] = {x.x, x.y, x.z, x.w, y.x, y.y, y.z, y.w};   // masks of rows 2i (low) and 2i+1 (high)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const uint32_t lo = (uint32_t)(-(int32_t)((am >> (2 * i)) & 1u)) & 0x0000FFFFu;
+            const uint32_t hi = (uint32_t)(-(int32_t)((am >> (2 * i + 1)) & 1u)) & 0xFFFF0000u;
+            acc |= w[i] & (lo | hi);
+        }
+    }
+    c_row_mask[c * T + r] = (uint16_t)((acc | (acc >> 16)) & 0xFFFFu);
+}
+
+// Per tile-row of C (16 lanes, lane r = row r): running count of entries of CSR row 16I+r in the
+// tiles to the left, and the row's total.
+__global__ __launch_bounds__(256) void k_row_offsets(int64_t c_tile_rows, int64_t c_rows,
+                                                     const int32_t *__restrict__ c_tile_row_ptr,
+                                                     const uint16_t *__restrict__ c_row_mask,
+                                                     uint32_t *__restrict__ c_row_off,
+                                                     int32_t *__restrict__ row_nnz) {
+    const int64_t I = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 4;
+    const int r = threadIdx.x & 15;
+    if (I >= c_tile_rows) return;
+    const int64_t c0 = c_tile_row_ptr[I], c1 = c_tile_row_ptr[I + 1];
+    uint32_t run = 0;
+    for (int64_t c = c0; c < c1; ++c) {
+        const uint32_t m = c_row_mask[c * T + r];
+        c_row_off[c * T + r] = run;
+        run += __popc(m);
+    }
+    const int64_t row = I * T + r;
+    if (row < c_rows) row_nnz[row] = (int32_t)run;
+}
+
+void plan_release(tsp_context *ctx, tsp_plan_s *p, hipStream_t s) {
+    if (!p) return;
+    ctx_free(ctx, p->c_tile_row_ptr, s);
+    ctx_free(ctx, p->c_tile_row, s);
+    ctx_free(ctx, p->c_tile_col, s);
+    ctx_free(ctx, p->pair_off, s);
+    ctx_free(ctx, p->pair_a, s);
+    ctx_free(ctx, p->pair_b, s);
+    ctx_free(ctx, p->c_row_mask, s);
+    ctx_free(ctx, p->c_row_off, s);
+    ctx_free(ctx, p->c_row_ptr, s);
+    delete p;
+}
+
+static int lanes_per_a_tile(const tsp_tiles_s *B) {
+    // lanes that share one A tile stride over the tiles of one tile-row of B: match its mean length
+    const double mean = B->tile_rows > 0 && B->ntiles > 0 ? (double)B->ntiles / (double)B->tile_rows : 1.0;
+    int l = 4;
+    while (l < 64 && l < mean) l <<= 1;
+    return l;
+}
+
+int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **out, hipStream_t s) {
+    *out = nullptr;
+    if (A->cols != B->rows) return TSP_ERR_SHAPE_MISMATCH;
+    tsp_plan_s *P = new (std::nothrow) tsp_plan_s();
+    if (!P) return TSP_ERR_ALLOC_FAILED;
+    P->c_rows = A->rows;
+    P->c_cols = B->cols;
+    P->c_tile_rows = A->tile_rows;
+    const int64_t ntr = A->tile_rows;
+    int rc = TSP_OK;
+    int32_t *row_jmin = nullptr, *row_c_tiles = nullptr, *row_pairs = nullptr, *row_nnz = nullptr;
+    int64_t *row_pair_ptr = nullptr, *tmp = nullptr;
+    auto cleanup = [&](int code) {
+        ctx_free(ctx, row_jmin, s);
+        ctx_free(ctx, row_c_tiles, s);
+        ctx_free(ctx, row_pairs, s);
+        ctx_free(ctx, row_nnz, s);
+        ctx_free(ctx, row_pair_ptr, s);
+        ctx_free(ctx, tmp, s);
+        if (code) plan_release(ctx, P, s);
+        return code;
+    };
+
+    phase_begin(ctx, TSP_PHASE_SYMBOLIC, s);
+    row_jmin = ctx_alloc_n<int32_t>(ctx, (size_t)ntr + 1, s);
+    row_c_tiles = ctx_alloc_n<int32_t>(ctx, (size_t)ntr + 1, s);
+    row_pairs = ctx_alloc_n<int32_t>(ctx, (size_t)ntr + 1, s);
+    row_pair_ptr = ctx_alloc_n<int64_t>(ctx, (size_t)ntr + 1, s);
+    P->c_tile_row_ptr = ctx_alloc_n<int32_t>(ctx, (size_t)ntr + 1, s);
+    const int64_t scan_n = ntr > P->c_rows ? ntr : P->c_rows;
+    tmp = ctx_alloc_n<int64_t>(ctx, scan_tmp_entries(scan_n), s);
+    if (!row_jmin || !row_c_tiles || !row_pairs || !row_pair_ptr || !P->c_tile_row_ptr || !tmp)
+        return cleanup(TSP_ERR_ALLOC_FAILED);
+
+    TileRefs ra{A->tile_row_ptr, A->tile_col, A->lmask, A->rmask, (int32_t)A->tile_rows};
+    TileRefs rb{B->tile_row_ptr, B->tile_col, B->lmask, B->rmask, (int32_t)B->tile_rows};
+    // tiles-per-tile-row of B is not known on the host before the first read-back: estimate the
+    // sharing width from the bound nnz/tile_rows (an upper bound on the mean), capped
+    int lanes = 4;
+    {
+        const double mean_bound = B->tile_rows > 0 ? (double)B->nnz / (double)B->tile_rows : 1.0;
+        while (lanes < 32 && lanes * 4 < mean_bound) lanes <<= 1;
+        if (B->ntiles >= 0) lanes = lanes_per_a_tile(B);
+    }
+    if (ntr > 0) {
+        hipLaunchKernelGGL(k_sym_count, dim3((unsigned)ntr), dim3(kSymThreads), kMaxWords * sizeof(uint32_t), s, ra,
+                           rb, lanes, kMaxWords, row_jmin, row_c_tiles, row_pairs, ctx->d_scalars);
+        TSP_HIP_CHECK(ctx, hipGetLastError());
+    }
+    rc = scan_exclusive_i32_to_i32(ctx, row_c_tiles, P->c_tile_row_ptr, ntr, ctx->d_scalars + S_C_TILES,
+                                   ctx->d_scalars + S_MAX_ROW_C_TILES, tmp, s);
+    if (!rc)
+        rc = scan_exclusive_i32_to_i64(ctx, row_pairs, row_pair_ptr, ntr, ctx->d_scalars + S_PAIRS, nullptr, tmp, s);
+    if (!rc) rc = read_scalars(ctx, s);                                    // ---- sync 1: sizes of the task list
+    if (rc) return cleanup(rc);
+    const int64_t *h = ctx->h_scalars;
+    if (h[S_INVALID]) return cleanup(TSP_ERR_NOT_CANONICAL);
+    if (h[S_UNSUPPORTED]) return cleanup(TSP_ERR_UNSUPPORTED);
+    if (A->ntiles < 0) A->ntiles = h[A->scalar_slot];
+    if (B->ntiles < 0) B->ntiles = h[B->scalar_slot];
+    P->c_tiles = h[S_C_TILES];
+    P->pairs = h[S_PAIRS];
+    P->candidates = h[S_CANDIDATES];
+    if (P->c_tiles >= INT32_MAX) return cleanup(TSP_ERR_INDEX_OVERFLOW);
+
+    P->c_tile_row = ctx_alloc_n<int32_t>(ctx, (size_t)P->c_tiles, s);
+    P->c_tile_col = ctx_alloc_n<int32_t>(ctx, (size_t)P->c_tiles, s);
+    P->pair_off = ctx_alloc_n<int64_t>(ctx, (size_t)P->c_tiles + 1, s);
+    P->pair_a = ctx_alloc_n<int32_t>(ctx, (size_t)P->pairs, s);
+    P->pair_b = ctx_alloc_n<int32_t>(ctx, (size_t)P->pairs, s);
+    P->c_row_mask = ctx_alloc_n<uint16_t>(ctx, (size_t)P->c_tiles * T, s);
+    P->c_row_off = ctx_alloc_n<uint32_t>(ctx, (size_t)P->c_tiles * T, s);
+    P->c_row_ptr = ctx_alloc_n<int64_t>(ctx, (size_t)P->c_rows + 1, s);
+    row_nnz = ctx_alloc_n<int32_t>(ctx, (size_t)P->c_rows + 1, s);
+    if (!P->c_tile_row || !P->c_tile_col || !P->pair_off || !P->pair_a || !P->pair_b || !P->c_row_mask ||
+        !P->c_row_off || !P->c_row_ptr || !row_nnz)
+        return cleanup(TSP_ERR_ALLOC_FAILED);
+
+    if (ntr > 0) {
+        const int words_cap = (int)(h[S_MAX_ROW_WORDS] > 0 ? h[S_MAX_ROW_WORDS] : 1);
+        int window = (int)(h[S_MAX_ROW_C_TILES] < kWindow ? h[S_MAX_ROW_C_TILES] : kWindow);
+        if (window < 1) window = 1;
+        const size_t lds = (size_t)(2 * words_cap + 2 * window) * sizeof(uint32_t);
+        lanes = lanes_per_a_tile(B);
+        hipLaunchKernelGGL(k_sym_emit, dim3((unsigned)ntr), dim3(kSymThreads), lds, s, ra, rb, lanes, words_cap,
+                           window, row_jmin, P->c_tile_row_ptr, row_pair_ptr, P->c_tile_row, P->c_tile_col,
+                           P->pair_off, P->pair_a, P->pair_b);
+        TSP_HIP_CHECK(ctx, hipGetLastError());
+    } else {
+        TSP_HIP_CHECK(ctx, hipMemsetAsync(P->pair_off, 0, sizeof(int64_t), s));
+    }
+    phase_end(ctx, TSP_PHASE_SYMBOLIC, s);
+
+    phase_begin(ctx, TSP_PHASE_COUNT, s);
+    if (P->c_tiles > 0) {
+        const unsigned grid = (unsigned)((P->c_tiles * 16 + 255) / 256);
+        hipLaunchKernelGGL(k_count_masks, dim3(grid), dim3(256), 0, s, P->c_tiles, P->pair_off, P->pair_a, P->pair_b,
+                           A->row_mask, B->row_mask, P->c_row_mask);
+    }
+    if (ntr > 0) {
+        const unsigned grid = (unsigned)((ntr * 16 + 255) / 256);
+        hipLaunchKernelGGL(k_row_offsets, dim3(grid), dim3(256), 0, s, ntr, P->c_rows, P->c_tile_row_ptr,
+                           P->c_row_mask, P->c_row_off, row_nnz);
+    }
+    TSP_HIP_CHECK(ctx, hipGetLastError());
+    rc = scan_exclusive_i32_to_i64(ctx, row_nnz, P->c_row_ptr, P->c_rows, ctx->d_scalars + S_C_NNZ, nullptr, tmp, s);
+    phase_end(ctx, TSP_PHASE_COUNT, s);
+    if (!rc) rc = read_scalars(ctx, s);                                    // ---- sync 2: nnz(C)
+    if (rc) return cleanup(rc);
+    P->c_nnz = ctx->h_scalars[S_C_NNZ];
+    ctx->stats.a_tiles = A->ntiles;
+    ctx->stats.b_tiles = B->ntiles;
+    ctx->stats.candidate_pairs = P->candidates;
+    ctx->stats.pairs = P->pairs;
+    ctx->stats.c_tiles = P->c_tiles;
+    ctx->stats.c_nnz = P->c_nnz;
+    *out = P;
+    return cleanup(TSP_OK);
+}
+
+}  // namespace tsp
+
+using namespace tsp;
+
+namespace tsp {
+__global__ void k_clear_scalars_sym(int64_t *d_scalars) {
+    if (threadIdx.x < kScalars) d_scalars[threadIdx.x] = 0;
+}
+}  // namespace tsp
+
+extern "C" int tsp_symbolic(tsp_handle ctx, tsp_tiles A, tsp_tiles B, tsp_plan *out, void *stream) {
+    if (!ctx || !A || !B || !out) return TSP_ERR_INVALID_ARG;
+    if (A->ntiles < 0 || B->ntiles < 0) return TSP_ERR_INVALID_ARG;   // tiles must come from tsp_convert
+    hipLaunchKernelGGL(k_clear_scalars_sym, dim3(1), dim3(64), 0, (hipStream_t)stream, ctx->d_scalars);
+    return symbolic_run(ctx, A, B, out, (hipStream_t)stream);
+}
+
+extern "C" int tsp_plan_free(tsp_handle ctx, tsp_plan plan, void *stream) {
+    if (!ctx) return TSP_ERR_INVALID_ARG;
+    plan_release(ctx, plan, (hipStream_t)stream);
+    return TSP_OK;
+}
+
+extern "C" int tsp_plan_get_view(tsp_plan p, tsp_plan_view *v) {
+    if (!p || !v) return TSP_ERR_INVALID_ARG;
+    v->c_rows = p->c_rows;
+    v->c_cols = p->c_cols;
+    v->c_tile_rows = p->c_tile_rows;
+    v->c_tiles = p->c_tiles;
+    v->pairs = p->pairs;
+    v->c_nnz = p->c_nnz;
+    v->candidate_pairs = p->candidates;
+    v->c_tile_row_ptr = p->c_tile_row_ptr;
+    v->c_tile_row = p->c_tile_row;
+    v->c_tile_col = p->c_tile_col;
+    v->pair_off = p->pair_off;
+    v->pair_a = p->pair_a;
+    v->pair_b = p->pair_b;
+    v->c_row_mask = p->c_row_mask;
+    v->c_row_off = p->c_row_off;
+    v->c_row_ptr = p->c_row_ptr;
+    return TSP_OK;
+}

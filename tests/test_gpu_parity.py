@@ -1,0 +1,246 @@
+"""Parity of the HIP path (through the C ABI) against the CPU oracle.  Needs an MI355X.
+
+Bar: row_ptr and col_idx bit-exact; |c - c_ref| <= 1e-5 * sum_k|a_ik||b_kj| + 1e-7 per entry.
+"""
+import numpy as np
+import pytest
+
+from paper_2009_14600_amd import inputs
+
+pytestmark = pytest.mark.gpu
+
+RTOL_S, ATOL = 1e-5, 1e-7
+
+
+@pytest.fixture(scope="module")
+def tsp():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2009_14600_amd import tsp as binding
+    binding.load_library()
+    return binding
+
+
+@pytest.fixture(scope="module")
+def handle(tsp):
+    h = tsp.Handle(validate=True)
+    yield h
+    h.close()
+
+
+def assert_matches_oracle(C, ref, what=""):
+    row_ptr, col, val = C.to_host()
+    assert np.array_equal(row_ptr, ref.row_ptr), f"{what}: row_ptr differs"
+    assert np.array_equal(col, ref.col), f"{what}: col_idx differs"
+    err = np.abs(val.astype(np.float64) - ref.val)
+    bound = RTOL_S * ref.mag + ATOL
+    bad = np.nonzero(err > bound)[0]
+    assert bad.size == 0, (f"{what}: {bad.size} values out of tolerance, first at {bad[:5]}: "
+                           f"got {val[bad[:5]]}, want {ref.val[bad[:5]]}, bound {bound[bad[:5]]}")
+
+
+def run_and_check(tsp, handle, oracle, A, B=None, **upload):
+    dA = tsp.to_device(A, **upload)
+    dB = dA if B is None else tsp.to_device(B, **upload)
+    C = handle.spgemm(dA, dB)
+    try:
+        ref = oracle.spgemm(A, A if B is None else B, threads=4)
+        assert (C.rows, C.cols) == (A.rows, (A if B is None else B).cols)
+        assert_matches_oracle(C, ref, A.name)
+        return C.nnz, ref
+    finally:
+        C.free()
+
+
+# ------------------------------------------------------------------ small instances of the five workloads
+@pytest.mark.parametrize("index", [1, 2, 3, 4, 5])
+def test_small_configs(tsp, handle, oracle, index):
+    A = inputs.config(index, small=True)
+    print(f"config {index} small: {A.name} rows={A.rows} nnz={A.nnz}", flush=True)
+    run_and_check(tsp, handle, oracle, A)
+
+
+# ------------------------------------------------------------------ rectangular, ragged, degenerate
+@pytest.mark.parametrize("M,K,N,density,seed,kind", [
+    (1, 1, 1, 1.0, 1, "uniform"),
+    (15, 17, 33, 0.3, 2, "uniform"),
+    (100, 37, 250, 0.08, 3, "uniform"),
+    (257, 129, 65, 0.05, 4, "smallint"),
+    (64, 640, 64, 0.02, 5, "uniform"),
+    (500, 500, 500, 0.01, 6, "uniform"),
+    (33, 1000, 47, 0.2, 7, "ones"),
+    (200, 200, 200, 0.25, 8, "uniform"),      # dense tiles, long segments
+])
+def test_random_rectangular(tsp, handle, oracle, M, K, N, density, seed, kind):
+    A = inputs.random_sparse(M, K, density, seed, empty_row_fraction=0.15, values=kind)
+    B = inputs.random_sparse(K, N, density, seed + 50, empty_row_fraction=0.15, values=kind)
+    print(f"random {M}x{K}x{N} d={density} {kind}", flush=True)
+    run_and_check(tsp, handle, oracle, A, B)
+
+
+def test_empty_operands(tsp, handle, oracle):
+    for M, K, N in [(0, 5, 7), (5, 0, 7), (5, 7, 0), (20, 30, 40)]:
+        A = inputs.random_sparse(M, K, 0.0, 1)
+        B = inputs.random_sparse(K, N, 0.3 if M == 20 else 0.0, 2)
+        nnz, _ = run_and_check(tsp, handle, oracle, A, B)
+        assert nnz == 0
+
+
+def test_cancellation_and_stored_zeros_keep_their_positions(tsp, handle, oracle):
+    A = inputs.from_coo(2, 2, [0, 0, 1], [0, 1, 1], [1.0, 1.0, 2.0])
+    B = inputs.from_coo(2, 3, [0, 1, 1], [0, 0, 2], [1.0, -1.0, 0.0])
+    nnz, _ = run_and_check(tsp, handle, oracle, A, B)
+    assert nnz == 4
+
+
+def test_fp16_subnormal_inputs_are_not_flushed(tsp, handle, oracle):
+    """Products of fp16 subnormals with ordinary values are far above the 1e-7 absolute term,
+    so a matrix unit that flushed subnormal inputs would fail here."""
+    A = inputs.random_sparse(64, 64, 0.2, 31, values="tiny")
+    B = inputs.random_sparse(64, 64, 0.2, 32, values="smallint")
+    _, ref = run_and_check(tsp, handle, oracle, A, B)
+    assert (ref.mag > 1e-6).sum() > 100
+
+
+def test_zero_one_inputs_are_exact(tsp, handle, oracle):
+    G = inputs.rmat(10, 16, seed=5)
+    dG = tsp.to_device(G)
+    C = handle.spgemm(dG, dG)
+    ref = oracle.spgemm(G, G)
+    _, _, val = C.to_host()
+    assert np.array_equal(val.astype(np.float64), ref.val)         # integers: no rounding at all
+    assert oracle.smape_percent(ref.val, val) == 0.0
+    C.free()
+
+
+def test_fp32_and_int64_inputs(tsp, handle, oracle):
+    A = inputs.config(3, small=True)
+    run_and_check(tsp, handle, oracle, A, value_dtype="f32", row_ptr_dtype="i64")
+    # values that are not fp16 numbers are rounded to nearest even on the device
+    import torch
+    rng = np.random.default_rng(3)
+    A = inputs.random_sparse(90, 70, 0.1, 41)
+    v32 = rng.uniform(-2, 2, A.nnz).astype(np.float32)
+    dA = tsp.to_device(A, value_dtype="f32")
+    dA.val = torch.from_numpy(v32).cuda()
+    B = inputs.random_sparse(70, 50, 0.1, 42)
+    C = handle.spgemm(dA, tsp.to_device(B))
+    A.val = v32.astype(np.float16)
+    assert_matches_oracle(C, oracle.spgemm(A, B), "fp32 inputs")
+    C.free()
+
+
+def test_runs_are_bit_identical(tsp, handle):
+    A = inputs.config(4, small=True)
+    dA = tsp.to_device(A)
+    outs = []
+    for _ in range(3):
+        C = handle.spgemm(dA, dA)
+        outs.append(C.to_host())
+        C.free()
+    for o in outs[1:]:
+        assert all(np.array_equal(x, y) for x, y in zip(o, outs[0]))
+
+
+# ------------------------------------------------------------------ error paths (forced from the host)
+def test_error_codes(tsp, handle):
+    import torch
+    A = tsp.to_device(inputs.random_sparse(20, 30, 0.2, 1))
+    B = tsp.to_device(inputs.random_sparse(31, 10, 0.2, 2))
+    with pytest.raises(tsp.TspError) as e:
+        handle.spgemm(A, B)
+    assert e.value.status == -2
+    bad = tsp.to_device(inputs.random_sparse(40, 40, 0.2, 3))
+    cols = bad.col_idx.clone()
+    bad.col_idx = torch.flip(cols, dims=[0]).contiguous()           # descending columns
+    with pytest.raises(tsp.TspError) as e:
+        handle.spgemm(bad, bad)
+    assert e.value.status == -3
+    bad.col_idx = cols.clone()
+    bad.col_idx[5] = 4000                                           # out of range column
+    with pytest.raises(tsp.TspError) as e:
+        handle.spgemm(bad, bad)
+    assert e.value.status == -3
+    bad.col_idx = cols
+    rp = bad.row_ptr.clone()
+    bad.row_ptr[3] = rp[4] + 1                                      # non-monotone row_ptr
+    with pytest.raises(tsp.TspError) as e:
+        handle.spgemm(bad, bad)
+    assert e.value.status == -3
+    bad.row_ptr = rp
+    C = handle.spgemm(bad, bad)                                     # the handle still works afterwards
+    assert C.nnz > 0
+    C.free()
+
+
+# ------------------------------------------------------------------ phase by phase against the paper's objects
+def _decode_groups(view, form, t):
+    """Dense 16x16 image (values, occupancy) of tile t from the group storage of one form."""
+    mask = int(view[f"{form}_group_mask"][t]) & 0xFFFFFFFF
+    off = int(view[f"{form}_group_off"][t]) & 0xFFFFFFFF
+    el = view[f"{form}_elements"]
+    dense = np.zeros((16, 16), dtype=np.float16)
+    stored = 0
+    for g in range(32):
+        if (mask >> g) & 1:
+            vals = el[(off + stored) * 8:(off + stored + 1) * 8]
+            h, x = g // 16, g % 16
+            if form == "left":
+                dense[x, 8 * h:8 * h + 8] = vals
+            else:
+                dense[8 * h:8 * h + 8, x] = vals
+            stored += 1
+    return dense
+
+
+@pytest.mark.parametrize("maker", [
+    lambda: (inputs.random_sparse(70, 45, 0.1, 61, empty_row_fraction=0.2), inputs.random_sparse(45, 90, 0.1, 62)),
+    lambda: (inputs.config(2, small=True),) * 2,
+    lambda: (inputs.config(5, small=True),) * 2,
+    lambda: (inputs.config(1, small=True),) * 2,
+])
+def test_phases_against_paper_objects(tsp, handle, oracle, maker):
+    A, B = maker()
+    same = A is B
+    dA = tsp.to_device(A)
+    dB = dA if same else tsp.to_device(B)
+    tA = handle.convert(dA)
+    tB = tA if same else handle.convert(dB)
+    refs = []
+    for M, tiles in ((A, tA), (B, tB)):
+        bm = oracle.bitmap_format(M, 16)
+        refs.append(bm)
+        v = {k: (x.cpu().numpy() if hasattr(x, "cpu") else x) for k, x in tiles.view().items()}
+        n = bm.tile_row.shape[0]
+        assert v["ntiles"] == n and v["tile_rows"] == bm.tile_rows and v["tile_cols"] == bm.tile_cols
+        assert np.array_equal(np.repeat(np.arange(bm.tile_rows), np.diff(v["tile_row_ptr"])), bm.tile_row)
+        assert np.array_equal(v["tile_col"], bm.tile_col)
+        assert np.array_equal(v["row_mask"].view(np.uint16).reshape(n, 16), bm.row_mask.astype(np.uint16))
+        for t in range(n):
+            occ = np.array([[(int(bm.row_mask[t, r]) >> c) & 1 for c in range(16)] for r in range(16)], dtype=bool)
+            want = np.zeros((16, 16), dtype=np.float16)
+            want[occ] = bm.elements[bm.index[t]:bm.index[t + 1]]      # ascending slot order = row-major
+            for form in ("left", "right"):
+                got = _decode_groups(v, form, t)
+                assert np.array_equal(got.view(np.uint16), want.view(np.uint16)), (t, form)
+    plan = handle.symbolic(tA, tB)
+    pv = {k: (x.cpu().numpy() if hasattr(x, "cpu") else x) for k, x in plan.view().items()}
+    tl = oracle.task_list(refs[0], refs[1])
+    masks, counts = oracle.counting(refs[0], refs[1], tl)
+    assert pv["pairs"] == tl.a_tile.shape[0] and pv["c_tiles"] == tl.c_tile_row.shape[0]
+    assert pv["candidate_pairs"] == tl.candidates
+    assert np.array_equal(pv["pair_off"], tl.offsets)
+    assert np.array_equal(pv["pair_a"], tl.a_tile) and np.array_equal(pv["pair_b"], tl.b_tile)
+    assert np.array_equal(pv["c_tile_row"], tl.c_tile_row) and np.array_equal(pv["c_tile_col"], tl.c_tile_col)
+    assert np.array_equal(pv["c_row_mask"].view(np.uint16).reshape(-1, 16), masks.astype(np.uint16))
+    assert pv["c_nnz"] == counts.sum()
+    ref = oracle.spgemm(A, B)
+    assert np.array_equal(pv["c_row_ptr"], ref.row_ptr)
+    C = handle.numeric(tA, tB, plan)
+    assert_matches_oracle(C, ref, "numeric phase")
+    C2 = handle.numeric(tA, tB, plan)                                   # a plan can be reused
+    assert_matches_oracle(C2, ref, "numeric phase, second use of the plan")
+    C.free(); C2.free(); plan.free(); tA.free()
+    if not same:
+        tB.free()
