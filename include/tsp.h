@@ -98,6 +98,22 @@ enum {
     TSP_PHASE_COUNT_ = 4
 };
 
+/* Kernels reported in tsp_stats.kernel_us (a prefix sum is three small launches, timed together). */
+enum {
+    TSP_KERNEL_VALIDATE = 0,
+    TSP_KERNEL_COUNT_TILES = 1,
+    TSP_KERNEL_SCAN_TILES = 2,
+    TSP_KERNEL_FILL_TILES = 3,
+    TSP_KERNEL_SYM_COUNT = 4,
+    TSP_KERNEL_SCAN_SYM = 5,
+    TSP_KERNEL_SYM_EMIT = 6,
+    TSP_KERNEL_COUNT_MASKS = 7,
+    TSP_KERNEL_ROW_OFFSETS = 8,
+    TSP_KERNEL_SCAN_ROWS = 9,
+    TSP_KERNEL_NUMERIC = 10,
+    TSP_KERNEL_COUNT_ = 11
+};
+
 /* Counters and timings of the most recent tsp_spgemm / phase calls on a handle. */
 typedef struct {
     int64_t a_tiles, b_tiles;        /* non-empty tiles of the operands                              */
@@ -109,6 +125,8 @@ typedef struct {
     int64_t workspace_peak_bytes;    /* high-water mark of the above                                  */
     float phase_us[TSP_PHASE_COUNT_];/* device time per phase of the last call, if timers are on      */
     float total_us;                  /* first event to last event of the last tsp_spgemm, if timers on */
+    float kernel_us[TSP_KERNEL_COUNT_]; /* device time per kernel of the last tsp_spgemm, if timers on  */
+                                     /* (when B is not A, the conversion entries describe B's)        */
 } tsp_stats;
 
 /* Create a handle on the current HIP device.  allocator == NULL selects hipMalloc/hipFree. */

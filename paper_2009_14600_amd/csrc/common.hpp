@@ -53,6 +53,8 @@ struct tsp_context {
     hipEvent_t ev[2 * TSP_PHASE_COUNT_ + 2]{};     // begin/end per phase, + total begin/end
     bool ev_created = false;
     bool ev_recorded[2 * TSP_PHASE_COUNT_ + 2]{};
+    hipEvent_t kev[2 * TSP_KERNEL_COUNT_]{};       // begin/end per kernel
+    bool kev_recorded[TSP_KERNEL_COUNT_]{};
 };
 
 struct tsp_tiles_s {
@@ -95,6 +97,15 @@ void phase_end(tsp_context *ctx, int phase, hipStream_t s);
 void total_begin(tsp_context *ctx, hipStream_t s);
 void total_end(tsp_context *ctx, hipStream_t s);
 void collect_timers(tsp_context *ctx);                                   // after a sync
+
+// Brackets the kernel launches inside its scope with events when the handle's timers are on.
+struct KernelTimer {
+    tsp_context *ctx;
+    int id;
+    hipStream_t s;
+    KernelTimer(tsp_context *c, int kernel_id, hipStream_t stream);
+    ~KernelTimer();
+};
 
 template <typename Tp>
 inline Tp *ctx_alloc_n(tsp_context *ctx, size_t n, hipStream_t s) {

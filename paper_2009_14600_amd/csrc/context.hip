@@ -76,6 +76,7 @@ int read_scalars(tsp_context *ctx, hipStream_t s) {
 static void ensure_events(tsp_context *ctx) {
     if (ctx->ev_created) return;
     for (auto &e : ctx->ev) (void)hipEventCreate(&e);
+    for (auto &e : ctx->kev) (void)hipEventCreate(&e);
     ctx->ev_created = true;
 }
 void phase_begin(tsp_context *ctx, int phase, hipStream_t s) {
@@ -97,6 +98,7 @@ void total_begin(tsp_context *ctx, hipStream_t s) {
     if (!ctx->timers) return;
     ensure_events(ctx);
     for (auto &r : ctx->ev_recorded) r = false;
+    for (auto &r : ctx->kev_recorded) r = false;
     (void)hipEventRecord(ctx->ev[2 * TSP_PHASE_COUNT_], s);
     ctx->ev_recorded[2 * TSP_PHASE_COUNT_] = true;
 }
@@ -117,6 +119,25 @@ void collect_timers(tsp_context *ctx) {
         else
             (void)hipGetLastError();
     }
+    for (int k = 0; k < TSP_KERNEL_COUNT_; ++k) {
+        float ms = 0.f;
+        ctx->stats.kernel_us[k] = 0.f;
+        if (ctx->kev_recorded[k] && hipEventElapsedTime(&ms, ctx->kev[2 * k], ctx->kev[2 * k + 1]) == hipSuccess)
+            ctx->stats.kernel_us[k] = ms * 1000.f;
+        else
+            (void)hipGetLastError();
+    }
+}
+
+KernelTimer::KernelTimer(tsp_context *c, int kernel_id, hipStream_t stream) : ctx(c), id(kernel_id), s(stream) {
+    if (!ctx->timers) return;
+    ensure_events(ctx);
+    (void)hipEventRecord(ctx->kev[2 * id], s);
+}
+KernelTimer::~KernelTimer() {
+    if (!ctx->timers) return;
+    (void)hipEventRecord(ctx->kev[2 * id + 1], s);
+    ctx->kev_recorded[id] = true;
 }
 
 }  // namespace tsp
@@ -154,7 +175,10 @@ extern "C" int tsp_destroy(tsp_handle ctx) {
     for (auto &b : ctx->cache) ctx->allocator.free(ctx->allocator.user, b.ptr, nullptr);
     for (auto &kv : ctx->live) ctx->allocator.free(ctx->allocator.user, kv.first, nullptr);
     if (ctx->ev_created)
+    {
         for (auto &e : ctx->ev) (void)hipEventDestroy(e);
+        for (auto &e : ctx->kev) (void)hipEventDestroy(e);
+    }
     (void)hipFree(ctx->d_scalars);
     (void)hipHostFree(ctx->h_scalars);
     delete ctx;

@@ -168,16 +168,24 @@ static int launch_convert_rp(tsp_context *ctx, const tsp_csr *A, tsp_tiles_s *t,
     const RP *rp = static_cast<const RP *>(A->row_ptr);
     const unsigned grid = (unsigned)((t->tile_rows + kGroupsPerBlock - 1) / kGroupsPerBlock);
     if (ctx->validate && A->rows > 0) {
+        KernelTimer kt(ctx, TSP_KERNEL_VALIDATE, s);
         hipLaunchKernelGGL(k_validate_csr<RP>, dim3((unsigned)((A->rows + kConvThreads - 1) / kConvThreads)),
                            dim3(kConvThreads), 0, s, rp, A->col_idx, A->rows, A->cols, A->nnz, ctx->d_scalars);
     }
-    if (grid)
+    if (grid) {
+        KernelTimer kt(ctx, TSP_KERNEL_COUNT_TILES, s);
         hipLaunchKernelGGL(k_count_tiles<RP>, dim3(grid), dim3(kConvThreads), 0, s, rp, A->col_idx, A->rows, A->nnz,
                            t->tile_rows, counts);
-    int rc = scan_exclusive_i32_to_i32(ctx, counts, t->tile_row_ptr, t->tile_rows,
-                                       ctx->d_scalars + t->scalar_slot, nullptr, tmp, s);
+    }
+    int rc;
+    {
+        KernelTimer kt(ctx, TSP_KERNEL_SCAN_TILES, s);
+        rc = scan_exclusive_i32_to_i32(ctx, counts, t->tile_row_ptr, t->tile_rows, ctx->d_scalars + t->scalar_slot,
+                                       nullptr, tmp, s);
+    }
     if (rc) return rc;
     if (grid) {
+        KernelTimer kt(ctx, TSP_KERNEL_FILL_TILES, s);
         if (A->val_type == TSP_F16)
             hipLaunchKernelGGL((k_fill_tiles<RP, uint16_t>), dim3(grid), dim3(kConvThreads), 0, s, rp, A->col_idx,
                                static_cast<const uint16_t *>(A->val), A->rows, A->nnz, t->tile_rows, t->tile_row_ptr,

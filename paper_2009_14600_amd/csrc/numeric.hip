@@ -91,6 +91,7 @@ int numeric_enqueue(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s
     hipError_t e = hipMemcpyAsync(row_ptr, P->c_row_ptr, sizeof(int64_t) * (size_t)(P->c_rows + 1),
                                   hipMemcpyDeviceToDevice, s);
     if (e == hipSuccess && P->c_tiles > 0) {
+        KernelTimer kt(ctx, TSP_KERNEL_NUMERIC, s);
         const unsigned grid = (unsigned)((P->c_tiles + kNumThreads / 64 - 1) / (kNumThreads / 64));
         hipLaunchKernelGGL(k_numeric, dim3(grid), dim3(kNumThreads), 0, s, P->c_tiles, P->pair_off, P->pair_a,
                            P->pair_b, A->lmask, A->loff, A->ldata, B->rmask, B->roff, B->rdata, P->c_tile_row,

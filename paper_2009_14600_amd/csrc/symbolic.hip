@@ -410,14 +410,19 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
         if (B->ntiles >= 0) lanes = lanes_per_a_tile(B);
     }
     if (ntr > 0) {
+        KernelTimer kt(ctx, TSP_KERNEL_SYM_COUNT, s);
         hipLaunchKernelGGL(k_sym_count, dim3((unsigned)ntr), dim3(kSymThreads), kMaxWords * sizeof(uint32_t), s, ra,
                            rb, lanes, kMaxWords, row_jmin, row_c_tiles, row_pairs, ctx->d_scalars);
         TSP_HIP_CHECK(ctx, hipGetLastError());
     }
-    rc = scan_exclusive_i32_to_i32(ctx, row_c_tiles, P->c_tile_row_ptr, ntr, ctx->d_scalars + S_C_TILES,
-                                   ctx->d_scalars + S_MAX_ROW_C_TILES, tmp, s);
-    if (!rc)
-        rc = scan_exclusive_i32_to_i64(ctx, row_pairs, row_pair_ptr, ntr, ctx->d_scalars + S_PAIRS, nullptr, tmp, s);
+    {
+        KernelTimer kt(ctx, TSP_KERNEL_SCAN_SYM, s);
+        rc = scan_exclusive_i32_to_i32(ctx, row_c_tiles, P->c_tile_row_ptr, ntr, ctx->d_scalars + S_C_TILES,
+                                       ctx->d_scalars + S_MAX_ROW_C_TILES, tmp, s);
+        if (!rc)
+            rc = scan_exclusive_i32_to_i64(ctx, row_pairs, row_pair_ptr, ntr, ctx->d_scalars + S_PAIRS, nullptr, tmp,
+                                           s);
+    }
     if (!rc) rc = read_scalars(ctx, s);                                    // ---- sync 1: sizes of the task list
     if (rc) return cleanup(rc);
     const int64_t *h = ctx->h_scalars;
@@ -449,6 +454,7 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
         if (window < 1) window = 1;
         const size_t lds = (size_t)(2 * words_cap + 2 * window) * sizeof(uint32_t);
         lanes = lanes_per_a_tile(B);
+        KernelTimer kt(ctx, TSP_KERNEL_SYM_EMIT, s);
         hipLaunchKernelGGL(k_sym_emit, dim3((unsigned)ntr), dim3(kSymThreads), lds, s, ra, rb, lanes, words_cap,
                            window, row_jmin, P->c_tile_row_ptr, row_pair_ptr, P->c_tile_row, P->c_tile_col,
                            P->pair_off, P->pair_a, P->pair_b);
@@ -461,16 +467,22 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
     phase_begin(ctx, TSP_PHASE_COUNT, s);
     if (P->c_tiles > 0) {
         const unsigned grid = (unsigned)((P->c_tiles * 16 + 255) / 256);
+        KernelTimer kt(ctx, TSP_KERNEL_COUNT_MASKS, s);
         hipLaunchKernelGGL(k_count_masks, dim3(grid), dim3(256), 0, s, P->c_tiles, P->pair_off, P->pair_a, P->pair_b,
                            A->row_mask, B->row_mask, P->c_row_mask);
     }
     if (ntr > 0) {
         const unsigned grid = (unsigned)((ntr * 16 + 255) / 256);
+        KernelTimer kt(ctx, TSP_KERNEL_ROW_OFFSETS, s);
         hipLaunchKernelGGL(k_row_offsets, dim3(grid), dim3(256), 0, s, ntr, P->c_rows, P->c_tile_row_ptr,
                            P->c_row_mask, P->c_row_off, row_nnz);
     }
     TSP_HIP_CHECK(ctx, hipGetLastError());
-    rc = scan_exclusive_i32_to_i64(ctx, row_nnz, P->c_row_ptr, P->c_rows, ctx->d_scalars + S_C_NNZ, nullptr, tmp, s);
+    {
+        KernelTimer kt(ctx, TSP_KERNEL_SCAN_ROWS, s);
+        rc = scan_exclusive_i32_to_i64(ctx, row_nnz, P->c_row_ptr, P->c_rows, ctx->d_scalars + S_C_NNZ, nullptr, tmp,
+                                       s);
+    }
     phase_end(ctx, TSP_PHASE_COUNT, s);
     if (!rc) rc = read_scalars(ctx, s);                                    // ---- sync 2: nnz(C)
     if (rc) return cleanup(rc);

@@ -19,6 +19,8 @@ TSP_F16, TSP_F32 = 0, 1
 FORM_LEFT, FORM_RIGHT = 1, 2
 OPT_VALIDATE, OPT_PHASE_TIMERS = 1, 2
 PHASES = ("convert", "symbolic", "count", "numeric")
+KERNELS = ("validate", "count_tiles", "scan_tiles", "fill_tiles", "sym_count", "scan_sym", "sym_emit",
+           "count_masks", "row_offsets", "scan_rows", "numeric")
 
 EXPORTS = [
     "tsp_create", "tsp_destroy", "tsp_set_option", "tsp_trim", "tsp_spgemm", "tsp_csr_free",
@@ -51,7 +53,8 @@ class _Stats(ctypes.Structure):
     _fields_ = [("a_tiles", ctypes.c_int64), ("b_tiles", ctypes.c_int64), ("candidate_pairs", ctypes.c_int64),
                 ("pairs", ctypes.c_int64), ("c_tiles", ctypes.c_int64), ("c_nnz", ctypes.c_int64),
                 ("workspace_bytes", ctypes.c_int64), ("workspace_peak_bytes", ctypes.c_int64),
-                ("phase_us", ctypes.c_float * 4), ("total_us", ctypes.c_float)]
+                ("phase_us", ctypes.c_float * 4), ("total_us", ctypes.c_float),
+                ("kernel_us", ctypes.c_float * 11)]
 
 
 class _TilesView(ctypes.Structure):
@@ -240,8 +243,9 @@ class Handle:
     def stats(self) -> dict:
         st = _Stats()
         _check(self._lib.tsp_get_stats(self._h, ctypes.byref(st)))
-        out = {k: getattr(st, k) for k, _ in _Stats._fields_ if k not in ("phase_us",)}
+        out = {k: getattr(st, k) for k, _ in _Stats._fields_ if k not in ("phase_us", "kernel_us")}
         out["phase_us"] = {name: st.phase_us[i] for i, name in enumerate(PHASES)}
+        out["kernel_us"] = {name: st.kernel_us[i] for i, name in enumerate(KERNELS)}
         return out
 
     def _wrap_output(self, raw: _Csr) -> DeviceCSR:
