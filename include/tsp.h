@@ -85,8 +85,10 @@ typedef struct tsp_plan_s *tsp_plan;     /* task list + output pattern of one pr
 /* Option keys for tsp_set_option. */
 enum {
     TSP_OPT_VALIDATE = 1,      /* 1 (default): check that CSR inputs are canonical                 */
-    TSP_OPT_PHASE_TIMERS = 2   /* 1: bracket every phase with HIP events on the call's stream and   */
+    TSP_OPT_PHASE_TIMERS = 2,  /* 1: bracket every phase with HIP events on the call's stream and   */
                                /*    report the durations in tsp_stats; 0 (default): no events      */
+    TSP_OPT_WIDE_INDEX = 3     /* 1: always use the kernels that address arrays of 4 GiB and more   */
+                               /*    through 64-bit pointers; 0 (default): chosen from the sizes    */
 };
 
 /* Phases reported in tsp_stats.phase_us, in pipeline order. */

@@ -14,7 +14,7 @@ LIB = os.path.join(HERE, "libtsp.so")
 SOURCES = ["context.hip", "scan.hip", "convert.hip", "symbolic.hip", "numeric.hip", "spgemm.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         "-I", os.path.join(ROOT, "include"), "-I", CSRC]
+         "-I", os.path.join(ROOT, "include"), "-I", CSRC] + os.environ.get("TSP_EXTRA_FLAGS", "").split()
 
 
 def _hipcc() -> str:

@@ -46,6 +46,7 @@ struct tsp_context {
     int64_t held_bytes = 0, peak_bytes = 0;
     int validate = 1;
     int timers = 0;
+    int force_wide = 0;                            // use the 64-bit-pointer kernels whatever the sizes
     int last_hip = 0;
     tsp_stats stats{};
     int64_t *d_scalars = nullptr;                  // device, kScalars entries

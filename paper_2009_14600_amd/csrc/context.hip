@@ -190,6 +190,7 @@ extern "C" int tsp_set_option(tsp_handle ctx, int key, int64_t value) {
     switch (key) {
         case TSP_OPT_VALIDATE: ctx->validate = value != 0; return TSP_OK;
         case TSP_OPT_PHASE_TIMERS: ctx->timers = value != 0; return TSP_OK;
+        case TSP_OPT_WIDE_INDEX: ctx->force_wide = value != 0; return TSP_OK;
         default: return TSP_ERR_INVALID_ARG;
     }
 }

@@ -1,7 +1,7 @@
 // Multiplication pass and CSR emission (paper Sections 4.3 and 4.4, Algorithm 1 line 18).
 //
-// One wave owns one output tile and walks the tile's task-list segment, two pairs per step: the
-// pairs of a C tile form one 16 x 16p by 16p x 16 product, so the inner (K) dimension of
+// One wave owns one output tile at a time and walks the tile's task-list segment: the pairs of a C
+// tile form one 16 x 16p by 16p x 16 product, so the inner (K) dimension of
 // v_mfma_f32_16x16x32_f16 is filled with the inner indices of two consecutive pairs
 // (lanes 0-31 feed pair p, lanes 32-63 feed pair p+1) and the four fp32 accumulator registers
 // of a lane carry the tile through the whole segment: the segmented reduction happens in
@@ -13,6 +13,15 @@
 // format stores exactly those 8-value groups (see tsp.h), so an operand is one 16-byte load, or
 // zero when the group mask says the group is empty: nothing is "placed by bitmap" at run time.
 // The accumulator of lane l holds column l%16, rows 4*(l/16)..+3 of the output tile.
+//
+// The paper notes that this kernel is bound by the scattered tile reads behind the task list
+// (Section 6.2).  The chain task-list entry -> tile header -> tile elements is three dependent
+// memory accesses, so a wave takes a run of consecutive output tiles and software-pipelines them:
+// while tile c is multiplied, the tile headers of c+1 and the task-list entries of c+2 are in flight.  A
+// segment's entries are read 64 at a time, one per lane, and handed to the two half-waves with
+// cross-lane reads.  All gathers go through buffer descriptors whose range check returns zeros
+// for masked-off lanes (no branches, no zero-filled registers).  Workgroup ids are remapped so
+// that consecutive runs of output tiles execute on the same XCD and share its L2.
 //
 // Emission: the counting pass left, per C tile, the 16 row masks of its structural pattern and
 // the number of entries each CSR row has to the left of the tile; the lane that holds element
@@ -31,46 +40,163 @@ union Group {
     half8 h;
 };
 
-constexpr int kNumThreads = 256;   // 4 waves = 4 output tiles per block
+constexpr int kNumThreads = 256;       // 4 waves per block
+constexpr int kTilesPerWave = 8;       // consecutive output tiles one wave pipelines through
+constexpr int kXcds = 8;
 
+struct Header {          // tile headers of one task-list entry, held by the lane that read the entry
+    uint32_t lm, lo, rm, ro;
+};
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// Read-only array behind a buffer descriptor: a lane that passes valid = false (or an index past the
+// end) gets zeros back from the hardware range check, so predicated loads need neither branches nor
+// zero-initialised registers.  Offsets are 32-bit: the array must be smaller than 4 GiB.
+struct BufferArray {
+    __amdgpu_buffer_rsrc_t rsrc;
+    __device__ __forceinline__ BufferArray(const void *base, uint64_t bytes)
+        : rsrc(__builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (uint32_t)bytes, 0x00020000)) {}
+    __device__ __forceinline__ uint32_t u32(uint32_t index, bool valid) const {
+        return __builtin_amdgcn_raw_buffer_load_b32(rsrc, valid ? index * 4u : 0xFFFFFFFFu, 0, 0);
+    }
+    __device__ __forceinline__ uint4 group(uint32_t index, bool valid) const {
+        const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, valid ? index * 16u : 0xFFFFFFFFu, 0, 0);
+        return make_uint4(v.x, v.y, v.z, v.w);
+    }
+};
+// Same interface on plain pointers, for arrays of 4 GiB and more.
+struct PointerArray {
+    const void *base;
+    __device__ __forceinline__ PointerArray(const void *b, uint64_t) : base(b) {}
+    __device__ __forceinline__ uint32_t u32(uint32_t index, bool valid) const {
+        return valid ? static_cast<const uint32_t *>(base)[index] : 0u;
+    }
+    __device__ __forceinline__ uint4 group(uint32_t index, bool valid) const {
+        return valid ? static_cast<const uint4 *>(base)[index] : make_uint4(0, 0, 0, 0);
+    }
+};
+
+struct NumericSizes {
+    uint64_t pairs, a_tiles, b_tiles, a_groups, b_groups;   // element counts of the arrays
+};
+
+template <class Array>
 __global__ __launch_bounds__(kNumThreads) void k_numeric(
-    int64_t c_tiles, const int64_t *__restrict__ pair_off, const int32_t *__restrict__ pair_a,
-    const int32_t *__restrict__ pair_b, const uint32_t *__restrict__ a_lmask, const uint32_t *__restrict__ a_loff,
-    const uint4 *__restrict__ a_ldata, const uint32_t *__restrict__ b_rmask, const uint32_t *__restrict__ b_roff,
-    const uint4 *__restrict__ b_rdata, const int32_t *__restrict__ c_tile_row, const int32_t *__restrict__ c_tile_col,
-    const uint16_t *__restrict__ c_row_mask, const uint32_t *__restrict__ c_row_off,
-    const int64_t *__restrict__ c_row_ptr, int32_t *__restrict__ c_col, float *__restrict__ c_val) {
-    const int64_t c = (int64_t)blockIdx.x * (kNumThreads / 64) + (threadIdx.x >> 6);
-    if (c >= c_tiles) return;                       // uniform per wave
+    const int64_t c_tiles, const NumericSizes z, const int64_t *__restrict__ pair_off,
+    const int32_t *__restrict__ pair_a_, const int32_t *__restrict__ pair_b_, const uint32_t *__restrict__ a_lmask_,
+    const uint32_t *__restrict__ a_loff_, const uint4 *__restrict__ a_ldata_, const uint32_t *__restrict__ b_rmask_,
+    const uint32_t *__restrict__ b_roff_, const uint4 *__restrict__ b_rdata_, const int32_t *__restrict__ c_tile_row,
+    const int32_t *__restrict__ c_tile_col, const uint16_t *__restrict__ c_row_mask,
+    const uint32_t *__restrict__ c_row_off, const int64_t *__restrict__ c_row_ptr, int32_t *__restrict__ c_col,
+    float *__restrict__ c_val) {
+    // consecutive logical blocks on the same XCD (workgroups are dealt to the XCDs round-robin)
+    const int per_xcd = gridDim.x / kXcds;
+    const int logical = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
+    // wave-uniform values are kept in scalar registers; their loads become scalar loads
+    const int64_t wave = (int64_t)logical * (kNumThreads / 64) + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t c_begin = wave * kTilesPerWave;
+    if (c_begin >= c_tiles) return;
+    const int64_t c_end = min(c_begin + kTilesPerWave, c_tiles);
     const int lane = threadIdx.x & 63;
     const int hl = lane & 31, upper = lane >> 5;
     const uint32_t bit = 1u << hl, below = bit - 1u;
-    const int64_t s0 = pair_off[c], s1 = pair_off[c + 1];
-    float4v acc = {0.f, 0.f, 0.f, 0.f};
-    for (int64_t p = s0; p < s1; p += 2) {
-        const int64_t q = p + upper;
-        Group av, bv;
-        av.u = make_uint4(0, 0, 0, 0);
-        bv.u = make_uint4(0, 0, 0, 0);
-        if (q < s1) {
-            const int64_t a = pair_a[q], b = pair_b[q];
-            const uint32_t lm = a_lmask[a], rm = b_rmask[b];
-            if (lm & bit) av.u = a_ldata[(int64_t)a_loff[a] + __popc(lm & below)];
-            if (rm & bit) bv.u = b_rdata[(int64_t)b_roff[b] + __popc(rm & below)];
-        }
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(av.h, bv.h, acc, 0, 0, 0);
-    }
-    const int64_t I = c_tile_row[c], J = c_tile_col[c];
     const int j = lane & 15, ig = lane >> 4;
-#pragma unroll
-    for (int v = 0; v < 4; ++v) {
-        const int i = 4 * ig + v;
-        const uint32_t cm = c_row_mask[c * T + i];
-        if ((cm >> j) & 1u) {
-            const int64_t pos = c_row_ptr[I * T + i] + (int64_t)c_row_off[c * T + i] + __popc(cm & ((1u << j) - 1u));
-            c_col[pos] = (int32_t)(J * T + j);
-            c_val[pos] = acc[v];
+    const Array pair_a(pair_a_, z.pairs * 4), pair_b(pair_b_, z.pairs * 4);
+    const Array a_lmask(a_lmask_, z.a_tiles * 4), a_loff(a_loff_, z.a_tiles * 4);
+    const Array b_rmask(b_rmask_, z.b_tiles * 4), b_roff(b_roff_, z.b_tiles * 4);
+    const Array a_ldata(a_ldata_, z.a_groups * 16), b_rdata(b_rdata_, z.b_groups * 16);
+
+    // one task-list entry per lane: 64 entries from position s0 of the segment [.., s1)
+    struct Entries {
+        uint32_t a, b;
+        bool valid;
+    };
+    auto load_entries = [&](int64_t s0, int64_t s1) {
+        const bool valid = s0 + lane < s1;
+        const uint32_t e = (uint32_t)(s0 + lane);
+        return Entries{pair_a.u32(e, valid), pair_b.u32(e, valid), valid};
+    };
+    auto load_headers = [&](const Entries &e) {
+        return Header{a_lmask.u32(e.a, e.valid), a_loff.u32(e.a, e.valid), b_rmask.u32(e.b, e.valid),
+                      b_roff.u32(e.b, e.valid)};
+    };
+    // operands of entry `src` (index into the 64 entries the lanes hold) for this lane, or zeros:
+    // lanes past the end of the segment hold all-zero headers
+    auto load_operands = [&](const Header &h, int src, Group &av, Group &bv) {
+        const uint32_t lm = (uint32_t)__shfl((int)h.lm, src, 64), lo = (uint32_t)__shfl((int)h.lo, src, 64);
+        const uint32_t rm = (uint32_t)__shfl((int)h.rm, src, 64), ro = (uint32_t)__shfl((int)h.ro, src, 64);
+        av.u = a_ldata.group(lo + __popc(lm & below), (lm & bit) != 0);
+        bv.u = b_rdata.group(ro + __popc(rm & below), (rm & bit) != 0);
+    };
+
+    // pipeline registers: headers of tile c, entries of tile c+1; entries of c+2 are requested first
+    // in every step so that the three dependent accesses of consecutive tiles overlap
+    int64_t s0_cur = pair_off[c_begin], s1_cur = pair_off[c_begin + 1];
+    int64_t s1_nxt = c_begin + 1 < c_end ? pair_off[c_begin + 2] : s1_cur;
+    Header h_cur;
+    Entries e_nxt;
+    {
+        const Entries e_cur = load_entries(s0_cur, s1_cur);
+        e_nxt = load_entries(s1_cur, s1_nxt);
+        h_cur = load_headers(e_cur);
+    }
+    for (int64_t c = c_begin; c < c_end; ++c) {
+        const int64_t s1_far = c + 2 < c_end ? pair_off[c + 3] : s1_nxt;
+        const Entries e_far = load_entries(s1_nxt, s1_far);
+        const Header h_nxt = load_headers(e_nxt);
+        // what the emission needs, requested before the multiplication: row masks (4 x 16 bit), the
+        // rows' entry counts left of the tile (4 x 32 bit) and the rows' starts (4 x 64 bit; the plan
+        // pads row_ptr to whole tile-rows, so rows past the matrix edge read valid memory)
+        const int64_t I = c_tile_row[c], J = c_tile_col[c];
+        const uint2 cm2 = *reinterpret_cast<const uint2 *>(c_row_mask + c * T + 4 * ig);
+        const uint4 coff4 = *reinterpret_cast<const uint4 *>(c_row_off + c * T + 4 * ig);
+        const longlong2 rb01 = *reinterpret_cast<const longlong2 *>(c_row_ptr + I * T + 4 * ig);
+        const longlong2 rb23 = *reinterpret_cast<const longlong2 *>(c_row_ptr + I * T + 4 * ig + 2);
+        float4v acc = {0.f, 0.f, 0.f, 0.f};
+        const int count = (int)min(s1_cur - s0_cur, (int64_t)64);
+        for (int it = 0; it < count; it += 8) {
+            Group a0, b0, a1, b1, a2, b2, a3, b3;
+            // the cross-lane reads stay in range through & 63; lanes past count hold zero headers
+            load_operands(h_cur, (it + upper) & 63, a0, b0);
+            load_operands(h_cur, (it + 2 + upper) & 63, a1, b1);
+            load_operands(h_cur, (it + 4 + upper) & 63, a2, b2);
+            load_operands(h_cur, (it + 6 + upper) & 63, a3, b3);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a0.h, b0.h, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1.h, b1.h, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a2.h, b2.h, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a3.h, b3.h, acc, 0, 0, 0);
         }
+        // segments longer than 64 entries: the rest, 64 at a time, without the cross-tile pipeline
+        for (int64_t s = s0_cur + 64; s < s1_cur; s += 64) {
+            const Header h = load_headers(load_entries(s, s1_cur));
+            const int cnt = (int)min(s1_cur - s, (int64_t)64);
+            for (int it = 0; it < cnt; it += 4) {
+                Group a0, b0, a1, b1;
+                load_operands(h, (it + upper) & 63, a0, b0);
+                load_operands(h, (it + 2 + upper) & 63, a1, b1);
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a0.h, b0.h, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1.h, b1.h, acc, 0, 0, 0);
+            }
+        }
+        // emission
+        const uint32_t cm[4] = {cm2.x & 0xFFFFu, cm2.x >> 16, cm2.y & 0xFFFFu, cm2.y >> 16};
+        const uint32_t coff[4] = {coff4.x, coff4.y, coff4.z, coff4.w};
+        const int64_t rbase[4] = {rb01.x, rb01.y, rb23.x, rb23.y};
+        const int32_t col = (int32_t)(J * T + j);
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            if ((cm[v] >> j) & 1u) {
+                const int64_t pos = rbase[v] + (int64_t)(coff[v] + __popc(cm[v] & ((1u << j) - 1u)));
+                c_col[pos] = col;
+                c_val[pos] = acc[v];
+            }
+        }
+        s0_cur = s1_cur;
+        s1_cur = s1_nxt;
+        s1_nxt = s1_far;
+        h_cur = h_nxt;
+        e_nxt = e_far;
     }
 }
 
@@ -92,10 +218,18 @@ int numeric_enqueue(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s
                                   hipMemcpyDeviceToDevice, s);
     if (e == hipSuccess && P->c_tiles > 0) {
         KernelTimer kt(ctx, TSP_KERNEL_NUMERIC, s);
-        const unsigned grid = (unsigned)((P->c_tiles + kNumThreads / 64 - 1) / (kNumThreads / 64));
-        hipLaunchKernelGGL(k_numeric, dim3(grid), dim3(kNumThreads), 0, s, P->c_tiles, P->pair_off, P->pair_a,
-                           P->pair_b, A->lmask, A->loff, A->ldata, B->rmask, B->roff, B->rdata, P->c_tile_row,
-                           P->c_tile_col, P->c_row_mask, P->c_row_off, P->c_row_ptr, col, val);
+        const int64_t tiles_per_block = (int64_t)(kNumThreads / 64) * kTilesPerWave;
+        int64_t blocks = (P->c_tiles + tiles_per_block - 1) / tiles_per_block;
+        blocks = (blocks + kXcds - 1) / kXcds * kXcds;             // the XCD remap needs a multiple of 8
+        const NumericSizes z{(uint64_t)P->pairs, (uint64_t)A->tile_capacity, (uint64_t)B->tile_capacity,
+                             (uint64_t)A->group_capacity, (uint64_t)B->group_capacity};
+        const uint64_t limit = (1ull << 32) - 64;
+        const bool narrow = z.pairs * 4 < limit && z.a_groups * 16 < limit && z.b_groups * 16 < limit &&
+                            z.a_tiles * 4 < limit && z.b_tiles * 4 < limit && !ctx->force_wide;
+        auto kernel = narrow ? k_numeric<BufferArray> : k_numeric<PointerArray>;
+        hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(kNumThreads), 0, s, P->c_tiles, z, P->pair_off,
+                           P->pair_a, P->pair_b, A->lmask, A->loff, A->ldata, B->rmask, B->roff, B->rdata,
+                           P->c_tile_row, P->c_tile_col, P->c_row_mask, P->c_row_off, P->c_row_ptr, col, val);
         e = hipGetLastError();
     }
     phase_end(ctx, TSP_PHASE_NUMERIC, s);

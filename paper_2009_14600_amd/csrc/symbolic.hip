@@ -102,6 +102,8 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_count(TileRefs A, TileRefs 
                                                            int32_t *__restrict__ row_jmin,
                                                            int32_t *__restrict__ row_c_tiles,
                                                            int32_t *__restrict__ row_pairs,
+                                                           int32_t *__restrict__ row_words,
+                                                           int32_t *__restrict__ row_cand,
                                                            int64_t *__restrict__ d_scalars) {
     extern __shared__ uint32_t lds_dyn[];
     __shared__ uint32_t red[32];
@@ -136,6 +138,8 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_count(TileRefs A, TileRefs 
             row_jmin[I] = 0;
             row_c_tiles[I] = 0;
             row_pairs[I] = 0;
+            row_words[I] = 0;
+            row_cand[I] = 0;
         }
         return;
     }
@@ -147,6 +151,8 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_count(TileRefs A, TileRefs 
             row_jmin[I] = 0;
             row_c_tiles[I] = 0;
             row_pairs[I] = 0;
+            row_words[I] = 0;
+            row_cand[I] = 0;
         }
         return;
     }
@@ -170,9 +176,106 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_count(TileRefs A, TileRefs 
         row_jmin[I] = jmin;
         row_c_tiles[I] = (int32_t)cnt;
         row_pairs[I] = (int32_t)surv;
-        atomicAdd((unsigned long long *)&d_scalars[S_CANDIDATES], (unsigned long long)cand);
-        atomicMax((unsigned long long *)&d_scalars[S_MAX_ROW_WORDS], (unsigned long long)words);
-        atomicMax((unsigned long long *)&d_scalars[S_MAX_ROW_A_TILES], (unsigned long long)(a1 - a0));
+        row_words[I] = words;
+        row_cand[I] = (int32_t)cand;
+    }
+}
+
+// Prefix sums over the tile-rows (Algorithm 1 lines 9-15: counts -> offsets and total sizes), one
+// block: C tiles per row -> c_tile_row_ptr, pairs per row -> row_pair_ptr, plus the totals and maxima
+// the host needs to size the task list.
+constexpr int kRowScanThreads = 1024;
+constexpr int kRowScanItems = 4;
+__global__ __launch_bounds__(kRowScanThreads) void k_sym_row_scan(
+    int64_t ntr, const int32_t *__restrict__ row_c_tiles, const int32_t *__restrict__ row_pairs,
+    const int32_t *__restrict__ row_words, const int32_t *__restrict__ row_cand,
+    int32_t *__restrict__ c_tile_row_ptr, int64_t *__restrict__ row_pair_ptr, int64_t *__restrict__ d_scalars) {
+    __shared__ int64_t lds_c[kRowScanThreads / 64], lds_p[kRowScanThreads / 64], lds_m[4][kRowScanThreads / 64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int64_t carry_c = 0, carry_p = 0, max_c = 0, max_w = 0, sum_cand = 0;
+    for (int64_t base = 0; base < ntr; base += kRowScanThreads * kRowScanItems) {
+        const int64_t i0 = base + (int64_t)threadIdx.x * kRowScanItems;
+        int64_t xc[kRowScanItems], xp[kRowScanItems], sc = 0, sp = 0;
+#pragma unroll
+        for (int k = 0; k < kRowScanItems; ++k) {
+            const bool in = i0 + k < ntr;
+            xc[k] = in ? row_c_tiles[i0 + k] : 0;
+            xp[k] = in ? row_pairs[i0 + k] : 0;
+            sc += xc[k];
+            sp += xp[k];
+            max_c = max(max_c, xc[k]);
+            if (in) {
+                max_w = max(max_w, (int64_t)row_words[i0 + k]);
+                sum_cand += row_cand[i0 + k];
+            }
+        }
+        int64_t vc = sc, vp = sp;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int64_t uc = __shfl_up(vc, o, 64), up = __shfl_up(vp, o, 64);
+            if (lane >= o) {
+                vc += uc;
+                vp += up;
+            }
+        }
+        __syncthreads();
+        if (lane == 63) {
+            lds_c[wave] = vc;
+            lds_p[wave] = vp;
+        }
+        __syncthreads();
+        int64_t before_c = 0, before_p = 0, all_c = 0, all_p = 0;
+#pragma unroll
+        for (int w = 0; w < kRowScanThreads / 64; ++w) {
+            const int64_t yc = lds_c[w], yp = lds_p[w];
+            if (w < wave) {
+                before_c += yc;
+                before_p += yp;
+            }
+            all_c += yc;
+            all_p += yp;
+        }
+        int64_t run_c = carry_c + before_c + vc - sc, run_p = carry_p + before_p + vp - sp;
+#pragma unroll
+        for (int k = 0; k < kRowScanItems; ++k) {
+            if (i0 + k < ntr) {
+                c_tile_row_ptr[i0 + k] = (int32_t)run_c;
+                row_pair_ptr[i0 + k] = run_p;
+            }
+            run_c += xc[k];
+            run_p += xp[k];
+        }
+        carry_c += all_c;
+        carry_p += all_p;
+    }
+    // block-wide maxima and the candidate total
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) {
+        max_c = max(max_c, (int64_t)__shfl_xor(max_c, o, 64));
+        max_w = max(max_w, (int64_t)__shfl_xor(max_w, o, 64));
+        sum_cand += __shfl_xor(sum_cand, o, 64);
+    }
+    __syncthreads();
+    if (lane == 0) {
+        lds_m[0][wave] = max_c;
+        lds_m[1][wave] = max_w;
+        lds_m[2][wave] = sum_cand;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int64_t mc = 0, mw = 0, sc = 0;
+        for (int w = 0; w < kRowScanThreads / 64; ++w) {
+            mc = max(mc, lds_m[0][w]);
+            mw = max(mw, lds_m[1][w]);
+            sc += lds_m[2][w];
+        }
+        c_tile_row_ptr[ntr] = (int32_t)carry_c;
+        row_pair_ptr[ntr] = carry_p;
+        d_scalars[S_C_TILES] = carry_c;
+        d_scalars[S_PAIRS] = carry_p;
+        d_scalars[S_MAX_ROW_C_TILES] = mc;
+        d_scalars[S_MAX_ROW_WORDS] = mw;
+        d_scalars[S_CANDIDATES] = sc;
     }
 }
 
@@ -295,31 +398,61 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_emit(
 
 // Counting pass: 16 lanes per C tile, lane r owns row r of the tile.  For each pair of the tile's
 // segment: c_mask[r] |= OR over the set bits k of the A tile's row mask r of the B tile's row mask k.
+// The segment's entries are read 16 at a time, one per lane, and the bitmaps of four pairs are
+// requested together so that their latencies overlap.
+__device__ __forceinline__ uint32_t boolean_row_product(uint32_t am, const uint4 &x, const uint4 &y) {
+    const uint32_t w[8] = {x.x, x.y, x.z, x.w, y.x, y.y, y.z, y.w};   // masks of rows 2i (low half) and 2i+1 (high)
+    uint32_t acc = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const uint32_t lo = (uint32_t)(-(int32_t)((am >> (2 * i)) & 1u)) & 0x0000FFFFu;
+        const uint32_t hi = (uint32_t)(-(int32_t)((am >> (2 * i + 1)) & 1u)) & 0xFFFF0000u;
+        acc |= w[i] & (lo | hi);
+    }
+    return acc;
+}
+
 __global__ __launch_bounds__(256) void k_count_masks(int64_t c_tiles, const int64_t *__restrict__ pair_off,
                                                      const int32_t *__restrict__ pair_a,
                                                      const int32_t *__restrict__ pair_b,
                                                      const uint16_t *__restrict__ a_row_mask,
                                                      const uint16_t *__restrict__ b_row_mask,
                                                      uint16_t *__restrict__ c_row_mask) {
-    const int64_t c = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 4;
+    const int per_xcd = gridDim.x / 8;
+    const int64_t logical = (int64_t)(blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+    const int64_t c = (logical * blockDim.x + threadIdx.x) >> 4;
     const int r = threadIdx.x & 15;
-    if (c >= c_tiles) return;
-    const int64_t s0 = pair_off[c], s1 = pair_off[c + 1];
+    const bool in = c < c_tiles;
+    const int64_t s0 = in ? pair_off[c] : 0, s1 = in ? pair_off[c + 1] : 0;
     uint32_t acc = 0;
-    for (int64_t p = s0; p < s1; ++p) {
-        const int64_t a = pair_a[p], b = pair_b[p];
-        const uint32_t am = a_row_mask[a * T + r];
-        const uint4 *bp = reinterpret_cast<const uint4 *>(b_row_mask + b * T);
-        const uint4 x = bp[0], y = bp[1];
-        const uint32_t w[8] = {x.x, x.y, x.z, x.w, y.x, y.y, y.z, y.w};   // masks of rows 2i (low) and 2i+1 (high)
+    // the 16-lane groups of a wave run different trip counts; the cross-lane reads stay inside a group
+    for (int64_t base = s0; __any(base < s1); base += 16) {
+        int a_mine = 0, b_mine = 0;
+        if (base + r < s1) {
+            a_mine = pair_a[base + r];
+            b_mine = pair_b[base + r];
+        }
+        const int cnt = (int)max((int64_t)0, min((int64_t)16, s1 - base));
+        for (int i = 0; __any(i < cnt); i += 4) {
+            uint32_t am[4];
+            uint4 x[4], y[4];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const uint32_t lo = (uint32_t)(-(int32_t)((am >> (2 * i)) & 1u)) & 0x0000FFFFu;
-            const uint32_t hi = (uint32_t)(-(int32_t)((am >> (2 * i + 1)) & 1u)) & 0xFFFF0000u;
-            acc |= w[i] & (lo | hi);
+            for (int u = 0; u < 4; ++u) {
+                const int a = __shfl(a_mine, (i + u) & 15, 16), b = __shfl(b_mine, (i + u) & 15, 16);
+                am[u] = 0;
+                x[u] = y[u] = make_uint4(0, 0, 0, 0);
+                if (i + u < cnt) {
+                    am[u] = a_row_mask[(int64_t)a * T + r];
+                    const uint4 *bp = reinterpret_cast<const uint4 *>(b_row_mask + (int64_t)b * T);
+                    x[u] = bp[0];
+                    y[u] = bp[1];
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) acc |= boolean_row_product(am[u], x[u], y[u]);
         }
     }
-    c_row_mask[c * T + r] = (uint16_t)((acc | (acc >> 16)) & 0xFFFFu);
+    if (in) c_row_mask[c * T + r] = (uint16_t)((acc | (acc >> 16)) & 0xFFFFu);
 }
 
 // Per tile-row of C (16 lanes, lane r = row r): running count of entries of CSR row 16I+r in the
@@ -376,11 +509,14 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
     const int64_t ntr = A->tile_rows;
     int rc = TSP_OK;
     int32_t *row_jmin = nullptr, *row_c_tiles = nullptr, *row_pairs = nullptr, *row_nnz = nullptr;
+    int32_t *row_words = nullptr, *row_cand = nullptr;
     int64_t *row_pair_ptr = nullptr, *tmp = nullptr;
     auto cleanup = [&](int code) {
         ctx_free(ctx, row_jmin, s);
         ctx_free(ctx, row_c_tiles, s);
         ctx_free(ctx, row_pairs, s);
+        ctx_free(ctx, row_words, s);
+        ctx_free(ctx, row_cand, s);
         ctx_free(ctx, row_nnz, s);
         ctx_free(ctx, row_pair_ptr, s);
         ctx_free(ctx, tmp, s);
@@ -392,11 +528,13 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
     row_jmin = ctx_alloc_n<int32_t>(ctx, (size_t)ntr + 1, s);
     row_c_tiles = ctx_alloc_n<int32_t>(ctx, (size_t)ntr + 1, s);
     row_pairs = ctx_alloc_n<int32_t>(ctx, (size_t)ntr + 1, s);
+    row_words = ctx_alloc_n<int32_t>(ctx, (size_t)ntr + 1, s);
+    row_cand = ctx_alloc_n<int32_t>(ctx, (size_t)ntr + 1, s);
     row_pair_ptr = ctx_alloc_n<int64_t>(ctx, (size_t)ntr + 1, s);
     P->c_tile_row_ptr = ctx_alloc_n<int32_t>(ctx, (size_t)ntr + 1, s);
     const int64_t scan_n = ntr > P->c_rows ? ntr : P->c_rows;
     tmp = ctx_alloc_n<int64_t>(ctx, scan_tmp_entries(scan_n), s);
-    if (!row_jmin || !row_c_tiles || !row_pairs || !row_pair_ptr || !P->c_tile_row_ptr || !tmp)
+    if (!row_jmin || !row_c_tiles || !row_pairs || !row_words || !row_cand || !row_pair_ptr || !P->c_tile_row_ptr || !tmp)
         return cleanup(TSP_ERR_ALLOC_FAILED);
 
     TileRefs ra{A->tile_row_ptr, A->tile_col, A->lmask, A->rmask, (int32_t)A->tile_rows};
@@ -412,16 +550,14 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
     if (ntr > 0) {
         KernelTimer kt(ctx, TSP_KERNEL_SYM_COUNT, s);
         hipLaunchKernelGGL(k_sym_count, dim3((unsigned)ntr), dim3(kSymThreads), kMaxWords * sizeof(uint32_t), s, ra,
-                           rb, lanes, kMaxWords, row_jmin, row_c_tiles, row_pairs, ctx->d_scalars);
+                           rb, lanes, kMaxWords, row_jmin, row_c_tiles, row_pairs, row_words, row_cand, ctx->d_scalars);
         TSP_HIP_CHECK(ctx, hipGetLastError());
     }
     {
         KernelTimer kt(ctx, TSP_KERNEL_SCAN_SYM, s);
-        rc = scan_exclusive_i32_to_i32(ctx, row_c_tiles, P->c_tile_row_ptr, ntr, ctx->d_scalars + S_C_TILES,
-                                       ctx->d_scalars + S_MAX_ROW_C_TILES, tmp, s);
-        if (!rc)
-            rc = scan_exclusive_i32_to_i64(ctx, row_pairs, row_pair_ptr, ntr, ctx->d_scalars + S_PAIRS, nullptr, tmp,
-                                           s);
+        hipLaunchKernelGGL(k_sym_row_scan, dim3(1), dim3(kRowScanThreads), 0, s, ntr, row_c_tiles, row_pairs, row_words,
+                           row_cand, P->c_tile_row_ptr, row_pair_ptr, ctx->d_scalars);
+        TSP_HIP_CHECK(ctx, hipGetLastError());
     }
     if (!rc) rc = read_scalars(ctx, s);                                    // ---- sync 1: sizes of the task list
     if (rc) return cleanup(rc);
@@ -442,7 +578,8 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
     P->pair_b = ctx_alloc_n<int32_t>(ctx, (size_t)P->pairs, s);
     P->c_row_mask = ctx_alloc_n<uint16_t>(ctx, (size_t)P->c_tiles * T, s);
     P->c_row_off = ctx_alloc_n<uint32_t>(ctx, (size_t)P->c_tiles * T, s);
-    P->c_row_ptr = ctx_alloc_n<int64_t>(ctx, (size_t)P->c_rows + 1, s);
+    // padded to whole tile-rows: the numeric pass reads the 16 row starts of a tile-row unconditionally
+    P->c_row_ptr = ctx_alloc_n<int64_t>(ctx, (size_t)P->c_tile_rows * T + T + 1, s);
     row_nnz = ctx_alloc_n<int32_t>(ctx, (size_t)P->c_rows + 1, s);
     if (!P->c_tile_row || !P->c_tile_col || !P->pair_off || !P->pair_a || !P->pair_b || !P->c_row_mask ||
         !P->c_row_off || !P->c_row_ptr || !row_nnz)
@@ -466,7 +603,7 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
 
     phase_begin(ctx, TSP_PHASE_COUNT, s);
     if (P->c_tiles > 0) {
-        const unsigned grid = (unsigned)((P->c_tiles * 16 + 255) / 256);
+        const unsigned grid = (unsigned)(((P->c_tiles * 16 + 255) / 256 + 7) / 8 * 8);   // multiple of 8: XCD remap
         KernelTimer kt(ctx, TSP_KERNEL_COUNT_MASKS, s);
         hipLaunchKernelGGL(k_count_masks, dim3(grid), dim3(256), 0, s, P->c_tiles, P->pair_off, P->pair_a, P->pair_b,
                            A->row_mask, B->row_mask, P->c_row_mask);
