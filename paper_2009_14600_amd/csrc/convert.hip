@@ -1,15 +1,24 @@
 // CSR -> tile ("bitmap") format, paper Section 2.1.2 with 16x16 tiles: a tile occupancy scan
-// (how many non-empty tiles each tile-row has), a prefix sum, and a packing pass that writes, per
-// non-empty tile, its tile column, its bitmap (16 row masks) and its elements.
+// (how many non-empty tiles, and how many element groups, each tile-row has), a prefix sum, and a
+// packing pass that writes, per non-empty tile, its tile column, its bitmap (16 row masks) and its
+// elements.
 //
-// Work decomposition: 16 lanes own one tile-row, one lane per CSR row.  Because the columns of a
-// CSR row ascend, so do its tile columns, and the distinct tile columns of the tile-row come out
-// of a 16-way merge: every step takes the smallest pending tile column over the 16 lanes; the
-// lanes whose row has entries in that tile consume them.  The element storage is laid out for
-// the matrix-core operand registers (see tsp_tiles_view in tsp.h): 16-byte groups of 8 fp16,
-// row-wise groups for a left operand, column-wise groups for a right operand, empty groups
-// skipped.  A tile-row can hold at most as many groups as it has stored entries, so group
-// offsets start at row_ptr[16*I] and no second prefix sum is needed.
+// A group of G threads (one wave, or one 256-thread block for long tile-rows) owns one tile-row,
+// i.e. 16 CSR rows whose entries are one contiguous stretch of the CSR arrays, and visits the
+// entries in parallel:
+//   1. every entry marks its tile column in an LDS bitmap that spans the tile-row's first to last
+//      tile column; the popcount is the number of tiles and the rank of a bit is the tile's
+//      position inside the tile-row, so the tiles come out sorted by column without a sort;
+//   2. every entry ORs its bit into its tile's row masks (LDS); from the 16 row masks of a tile
+//      follow the two group masks (which 8-element row pieces / column pieces are non-empty);
+//   3. (packing pass) every entry stores its value into its slot of the left-form and of the
+//      right-form group of its tile; the groups were zeroed first.
+// The element storage is laid out for the matrix-core operand registers (see tsp_tiles_view in
+// tsp.h).  Group offsets come from the prefix sum of the per-tile-row group counts, so the stored
+// groups are contiguous from the start of the element arrays.
+// Tile-rows whose tile columns span more than the LDS bitmap take a second path: 16 lanes merge
+// the 16 sorted rows, one tile per step (any span, one tile at a time).
+// The occupancy pass also checks that the input is canonical (it reads every index anyway).
 #include "common.hpp"
 
 #include <hip/hip_fp16.h>
@@ -19,140 +28,412 @@
 
 namespace tsp {
 
-constexpr int kConvThreads = 256;                 // 16 tile-rows per block
-constexpr int kGroupsPerBlock = kConvThreads / 16;
+constexpr int kConvThreads = 256;
+enum : int32_t { ROW_FAST = 0, ROW_MERGE = 1 };
+
+template <int G> struct ConvCfg;
+template <> struct ConvCfg<64> {                  // one wave per tile-row, four tile-rows per block
+    static constexpr int kWords = 768;            // bitmap words: tile columns may span 24576
+    static constexpr int kWindow = 64;            // tiles handled per pass over the entries
+};
+template <> struct ConvCfg<256> {                 // one block per tile-row
+    static constexpr int kWords = 4096;           // span of 131072 tile columns
+    static constexpr int kWindow = 512;
+};
 
 __device__ __forceinline__ uint16_t to_half_bits(uint16_t v) { return v; }
 __device__ __forceinline__ uint16_t to_half_bits(float v) { return __half_as_ushort(__float2half_rn(v)); }
 
-template <typename RP>
-__global__ __launch_bounds__(kConvThreads) void k_validate_csr(const RP *__restrict__ row_ptr,
-                                                               const int32_t *__restrict__ col, int64_t rows,
-                                                               int64_t cols, int64_t nnz,
-                                                               int64_t *__restrict__ d_scalars) {
-    const int64_t row = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (row >= rows) return;
-    const int64_t p = (int64_t)row_ptr[row], e = (int64_t)row_ptr[row + 1];
-    bool bad = (row == 0 && p != 0) || (row == rows - 1 && e != nnz) || p < 0 || e > nnz || p > e;
-    if (!bad) {
-        int64_t prev = -1;
-        for (int64_t q = p; q < e; ++q) {
-            const int64_t c = col[q];
-            bad |= (c <= prev) | (c >= cols);
-            prev = c;
+template <typename RP, typename VT>
+struct ConvArgs {
+    const RP *row_ptr;
+    const int32_t *col;
+    const VT *val;
+    int64_t rows, cols, nnz, tile_rows, tile_capacity, group_capacity;
+    int forms, validate;
+    // occupancy pass outputs / packing pass inputs, one entry per tile-row
+    int32_t *row_tiles, *row_lgroups, *row_rgroups, *row_class;
+    const int32_t *tile_row_ptr;
+    const uint32_t *row_lbase, *row_rbase;
+    // tile arrays
+    int32_t *tile_col;
+    uint16_t *row_mask;
+    uint32_t *lmask, *rmask, *loff, *roff;
+    uint4 *ldata, *rdata;
+    int64_t *d_scalars;
+};
+
+template <int G>
+__device__ __forceinline__ void group_sync() {
+    if (G == 64) wave_sync(); else __syncthreads();
+}
+
+// Reductions over the G threads of a group.  red: LDS scratch of 8 words per group (G = 256 only).
+template <int G>
+__device__ __forceinline__ int group_max(int v, int *red) {
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) v = max(v, __shfl_xor(v, o, 64));
+    if (G > 64) {
+        __syncthreads();
+        if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+        __syncthreads();
+        v = max(max(red[0], red[1]), max(red[2], red[3]));
+    }
+    return v;
+}
+template <int G>
+__device__ __forceinline__ uint32_t group_sum(uint32_t v, int *red) {
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) v += (uint32_t)__shfl_xor((int)v, o, 64);
+    if (G > 64) {
+        __syncthreads();
+        if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = (int)v;
+        __syncthreads();
+        v = (uint32_t)red[0] + (uint32_t)red[1] + (uint32_t)red[2] + (uint32_t)red[3];
+    }
+    return v;
+}
+// In-place exclusive scan of arr[0..n) by the group; returns the total.
+template <int G>
+__device__ __forceinline__ uint32_t group_exclusive_scan(uint32_t *arr, int n, int *red) {
+    const int gt = threadIdx.x % G, lane = threadIdx.x & 63, wave = (threadIdx.x % G) >> 6;
+    uint32_t carry = 0;
+    for (int base = 0; base < n; base += G) {
+        const int i = base + gt;
+        const uint32_t x = i < n ? arr[i] : 0;
+        uint32_t v = x;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const uint32_t u = (uint32_t)__shfl_up((int)v, o, 64);
+            if (lane >= o) v += u;
         }
-    }
-    if (bad) d_scalars[S_INVALID] = 1;
-}
-
-template <typename RP>
-__device__ __forceinline__ void row_range(const RP *row_ptr, int64_t row, int64_t rows, int64_t nnz, bool in_grid,
-                                          int64_t &p, int64_t &e) {
-    p = e = 0;
-    if (in_grid && row < rows) {
-        p = (int64_t)row_ptr[row];
-        e = (int64_t)row_ptr[row + 1];
-        p = min(max(p, (int64_t)0), nnz);      // never read col[] outside the array, whatever row_ptr holds
-        e = min(max(e, p), nnz);
-    }
-}
-
-// Occupancy scan: number of non-empty tiles per tile-row.
-template <typename RP>
-__global__ __launch_bounds__(kConvThreads) void k_count_tiles(const RP *__restrict__ row_ptr,
-                                                              const int32_t *__restrict__ col, int64_t rows,
-                                                              int64_t nnz, int64_t tile_rows,
-                                                              int32_t *__restrict__ tiles_per_row) {
-    const int64_t I = (int64_t)blockIdx.x * kGroupsPerBlock + (threadIdx.x >> 4);
-    const int r = threadIdx.x & 15;
-    int64_t p, e;
-    row_range(row_ptr, I * T + r, rows, nnz, I < tile_rows, p, e);
-    int cur = p < e ? (col[p] >> 4) : INT_MAX;
-    int count = 0;
-    for (;;) {
-        const int m = group16_min(cur);
-        if (__all(m == INT_MAX)) break;
-        if (m != INT_MAX) {
-            ++count;
-            if (cur == m) {
-                do { ++p; } while (p < e && (col[p] >> 4) == m);
-                cur = p < e ? (col[p] >> 4) : INT_MAX;
+        uint32_t before = 0, all = (uint32_t)__shfl((int)v, 63, 64);
+        if (G > 64) {
+            __syncthreads();
+            if (lane == 63) red[wave] = (int)v;
+            __syncthreads();
+            all = 0;
+#pragma unroll
+            for (int w = 0; w < G / 64; ++w) {
+                const uint32_t y = (uint32_t)red[w];
+                if (w < wave) before += y;
+                all += y;
             }
         }
+        if (i < n) arr[i] = carry + before + v - x;
+        carry += all;
     }
-    if (r == 0 && I < tile_rows) tiles_per_row[I] = count;
+    group_sync<G>();
+    return carry;
 }
 
-// Packing pass.
-template <typename RP, typename VT>
-__global__ __launch_bounds__(kConvThreads) void k_fill_tiles(
-    const RP *__restrict__ row_ptr, const int32_t *__restrict__ col, const VT *__restrict__ val, int64_t rows,
-    int64_t nnz, int64_t tile_rows, const int32_t *__restrict__ tile_row_ptr, int64_t tile_capacity,
-    int64_t group_capacity, int forms,
-    int32_t *__restrict__ tile_col, uint16_t *__restrict__ row_mask, uint32_t *__restrict__ lmask,
-    uint32_t *__restrict__ rmask, uint32_t *__restrict__ loff, uint32_t *__restrict__ roff,
-    uint4 *__restrict__ ldata, uint4 *__restrict__ rdata) {
-    __shared__ __align__(16) uint16_t dense_all[kGroupsPerBlock][T * T];
+// ------------------------------------------------------------------------------------------------
+// Fast path: LDS bitmap over the tile-row's span of tile columns.
+// ------------------------------------------------------------------------------------------------
+template <int G, bool FILL, typename RP, typename VT>
+__global__ __launch_bounds__(kConvThreads) void k_convert_rows(const ConvArgs<RP, VT> a) {
+    constexpr int kWords = ConvCfg<G>::kWords, kWindow = ConvCfg<G>::kWindow, kGroups = kConvThreads / G;
+    __shared__ int64_t s_rp_all[kGroups][17];
+    __shared__ uint32_t s_bm_all[kGroups][kWords], s_pre_all[kGroups][kWords];
+    __shared__ uint32_t s_mask_all[kGroups][kWindow * 8];
+    __shared__ uint32_t s_lm_all[kGroups][kWindow], s_rm_all[kGroups][kWindow];
+    __shared__ uint32_t s_lo_all[kGroups][kWindow], s_ro_all[kGroups][kWindow];
+    __shared__ int s_red_all[kGroups][8];
+    const int gi = threadIdx.x / G, gt = threadIdx.x % G;
+    int64_t *s_rp = s_rp_all[gi];
+    uint32_t *s_bm = s_bm_all[gi], *s_pre = s_pre_all[gi], *s_mask = s_mask_all[gi];
+    uint32_t *s_lm = s_lm_all[gi], *s_rm = s_rm_all[gi], *s_lo = s_lo_all[gi], *s_ro = s_ro_all[gi];
+    int *s_red = s_red_all[gi];
+    const int64_t I = (int64_t)blockIdx.x * kGroups + gi;
+    if (I >= a.tile_rows) return;                 // whole group (G = 256: whole block)
+    bool bad = false;
+
+    // the 17 row pointers of the tile-row, clamped so that whatever they hold the entry ranges are
+    // disjoint stretches inside the arrays
+    if (gt == 0) {
+        int64_t prev = 0;
+        for (int k = 0; k <= 16; ++k) {
+            const int64_t row = min(I * T + k, a.rows);
+            const int64_t v = (int64_t)a.row_ptr[row];
+            const int64_t lo = k == 0 ? 0 : prev;
+            bad |= v < lo || v > a.nnz || (row == 0 && v != 0) || (row == a.rows && v != a.nnz);
+            prev = min(max(v, lo), a.nnz);
+            s_rp[k] = prev;
+        }
+    }
+    group_sync<G>();
+    const int64_t e0 = s_rp[0], e1 = s_rp[16];
+    if (FILL && a.row_class[I] != ROW_FAST) return;
+    if (e0 == e1) {
+        if (!FILL && gt == 0) {
+            a.row_tiles[I] = 0;
+            a.row_lgroups[I] = 0;
+            a.row_rgroups[I] = 0;
+            a.row_class[I] = ROW_FAST;
+            if (bad && a.validate) a.d_scalars[S_INVALID] = 1;
+        }
+        return;
+    }
+    // span of tile columns: first and last entry of every non-empty row
+    int jmin = INT_MAX, jmax = -1;
+    if (gt < 16) {
+        const int64_t p = s_rp[gt], e = s_rp[gt + 1];
+        if (p < e) {
+            jmin = a.col[p] >> 4;
+            jmax = a.col[e - 1] >> 4;
+        }
+    }
+    jmin = -group_max<G>(-jmin, s_red);
+    jmax = group_max<G>(jmax, s_red);
+    const int64_t span = (int64_t)jmax - jmin + 1;
+    const int words = (int)((span + 31) >> 5);
+    if (jmin < 0 || span <= 0 || words > kWords) {
+        if (!FILL && gt == 0) {                   // the merge path takes this tile-row (and validates it)
+            // (a span that cannot occur in a matrix of this width means the indices are out of range)
+            if (a.validate && (bad || jmin < 0 || jmax >= (a.cols + T - 1) / T)) a.d_scalars[S_INVALID] = 1;
+            a.row_tiles[I] = 0;
+            a.row_lgroups[I] = 0;
+            a.row_rgroups[I] = 0;
+            a.row_class[I] = ROW_MERGE;
+        }
+        return;
+    }
+    auto row_of = [&](int64_t e) {
+        int r = e >= s_rp[8] ? 8 : 0;
+        r += e >= s_rp[r + 4] ? 4 : 0;
+        r += e >= s_rp[r + 2] ? 2 : 0;
+        r += e >= s_rp[r + 1] ? 1 : 0;
+        return r;
+    };
+
+    // 1. tile columns -> bitmap
+    for (int w = gt; w < words; w += G) s_bm[w] = 0;
+    group_sync<G>();
+    for (int64_t e = e0 + gt; e < e1; e += G) {
+        const int c = a.col[e];
+        const uint32_t j = (uint32_t)((c >> 4) - jmin);
+        if (j < (uint32_t)span) atomicOr(&s_bm[j >> 5], 1u << (j & 31));
+        if (!FILL && a.validate) {
+            bad |= c < 0 || c >= a.cols || j >= (uint32_t)span;
+            if (e > s_rp[row_of(e)]) bad |= c <= a.col[e - 1];
+        }
+    }
+    group_sync<G>();
+    for (int w = gt; w < words; w += G) s_pre[w] = __popc(s_bm[w]);
+    group_sync<G>();
+    const int ntiles = (int)group_exclusive_scan<G>(s_pre, words, s_red);
+    auto tile_rank = [&](int c) -> int {          // position of the entry's tile inside the tile-row, or -1
+        const uint32_t j = (uint32_t)((c >> 4) - jmin);
+        if (j >= (uint32_t)span) return -1;
+        return (int)s_pre[j >> 5] + __popc(s_bm[j >> 5] & ((1u << (j & 31)) - 1u));
+    };
+
+    int64_t t0 = 0;
+    uint32_t lrun = 0, rrun = 0;
+    uint16_t *const l16 = reinterpret_cast<uint16_t *>(a.ldata), *const r16 = reinterpret_cast<uint16_t *>(a.rdata);
+    if (FILL) {
+        t0 = a.tile_row_ptr[I];
+        lrun = a.row_lbase[I];
+        rrun = a.row_rbase[I];
+        // tile columns, ascending
+        for (int w = gt; w < words; w += G) {
+            uint32_t bits = s_bm[w];
+            int64_t t = t0 + s_pre[w];
+            while (bits) {
+                const int b = __ffs(bits) - 1;
+                bits &= bits - 1;
+                if (t < a.tile_capacity) a.tile_col[t] = jmin + w * 32 + b;
+                ++t;
+            }
+        }
+        // zero the tile-row's groups; the entries then drop their values into their slots
+        const uint4 zero = make_uint4(0, 0, 0, 0);
+        if (a.forms & TSP_FORM_LEFT)
+            for (int64_t g = (int64_t)lrun + gt, end = min((int64_t)a.row_lbase[I + 1], a.group_capacity); g < end; g += G)
+                a.ldata[g] = zero;
+        if (a.forms & TSP_FORM_RIGHT)
+            for (int64_t g = (int64_t)rrun + gt, end = min((int64_t)a.row_rbase[I + 1], a.group_capacity); g < end; g += G)
+                a.rdata[g] = zero;
+        __builtin_amdgcn_s_waitcnt(0x0F70);       // vmcnt(0): the zeros are in L2 before any value is stored
+    }
+    uint32_t lcount = 0, rcount = 0;
+    for (int win0 = 0; win0 < ntiles; win0 += kWindow) {
+        const int nw = min(kWindow, ntiles - win0);
+        // 2. row masks of the tiles of this window
+        for (int k = gt; k < nw * 8; k += G) s_mask[k] = 0;
+        group_sync<G>();
+        for (int64_t e = e0 + gt; e < e1; e += G) {
+            const int c = a.col[e];
+            const int t = tile_rank(c) - win0;
+            if (t >= 0 && t < nw) {
+                const int r = row_of(e);
+                atomicOr(&s_mask[t * 8 + (r >> 1)], 1u << ((r & 1) * 16 + (c & 15)));
+            }
+        }
+        group_sync<G>();
+        for (int t = gt; t < nw; t += G) {
+            uint32_t lm = 0, rm = 0;
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const uint32_t m2 = s_mask[t * 8 + k];              // rows 2k (low half) and 2k+1 (high half)
+                lm |= ((m2 & 0x000000FFu) ? 1u << (2 * k) : 0u) | ((m2 & 0x0000FF00u) ? 1u << (16 + 2 * k) : 0u) |
+                      ((m2 & 0x00FF0000u) ? 1u << (2 * k + 1) : 0u) | ((m2 & 0xFF000000u) ? 1u << (17 + 2 * k) : 0u);
+                const uint32_t cols = (m2 | (m2 >> 16)) & 0xFFFFu;  // columns present in rows 2k, 2k+1
+                rm |= k < 4 ? cols : cols << 16;
+            }
+            s_lm[t] = lm;
+            s_rm[t] = rm;
+            lcount += __popc(lm);
+            rcount += __popc(rm);
+            if (FILL) {
+                s_lo[t] = __popc(lm);
+                s_ro[t] = __popc(rm);
+            }
+        }
+        group_sync<G>();
+        if (FILL) {
+            const uint32_t ltot = group_exclusive_scan<G>(s_lo, nw, s_red);
+            const uint32_t rtot = group_exclusive_scan<G>(s_ro, nw, s_red);
+            // tile headers and bitmaps
+            for (int t = gt; t < nw; t += G) {
+                const int64_t tg = t0 + win0 + t;
+                if (tg < a.tile_capacity) {
+                    uint4 *dst = reinterpret_cast<uint4 *>(a.row_mask + tg * T);
+                    dst[0] = make_uint4(s_mask[t * 8 + 0], s_mask[t * 8 + 1], s_mask[t * 8 + 2], s_mask[t * 8 + 3]);
+                    dst[1] = make_uint4(s_mask[t * 8 + 4], s_mask[t * 8 + 5], s_mask[t * 8 + 6], s_mask[t * 8 + 7]);
+                    a.lmask[tg] = s_lm[t];
+                    a.rmask[tg] = s_rm[t];
+                    if (a.forms & TSP_FORM_LEFT) a.loff[tg] = lrun + s_lo[t];
+                    if (a.forms & TSP_FORM_RIGHT) a.roff[tg] = rrun + s_ro[t];
+                }
+            }
+            // 3. values
+            for (int64_t e = e0 + gt; e < e1; e += G) {
+                const int c = a.col[e];
+                const int t = tile_rank(c) - win0;
+                if (t >= 0 && t < nw) {
+                    const int r = row_of(e), cc = c & 15;
+                    const uint16_t v = to_half_bits(a.val[e]);
+                    if (a.forms & TSP_FORM_LEFT) {
+                        const int g = (cc >> 3) * 16 + r;
+                        const int64_t idx = (int64_t)lrun + s_lo[t] + __popc(s_lm[t] & ((1u << g) - 1u));
+                        if (idx < a.group_capacity) l16[idx * 8 + (cc & 7)] = v;
+                    }
+                    if (a.forms & TSP_FORM_RIGHT) {
+                        const int g = (r >> 3) * 16 + cc;
+                        const int64_t idx = (int64_t)rrun + s_ro[t] + __popc(s_rm[t] & ((1u << g) - 1u));
+                        if (idx < a.group_capacity) r16[idx * 8 + (r & 7)] = v;
+                    }
+                }
+            }
+            lrun += ltot;
+            rrun += rtot;
+            group_sync<G>();
+        }
+    }
+    if (!FILL) {
+        lcount = group_sum<G>(lcount, s_red);
+        rcount = group_sum<G>(rcount, s_red);
+        const bool any_bad = group_max<G>(bad ? 1 : 0, s_red) != 0;
+        if (gt == 0) {
+            a.row_tiles[I] = ntiles;
+            a.row_lgroups[I] = (int32_t)lcount;
+            a.row_rgroups[I] = (int32_t)rcount;
+            a.row_class[I] = ROW_FAST;
+            if (any_bad && a.validate) a.d_scalars[S_INVALID] = 1;
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Merge path for tile-rows whose span does not fit the bitmap: 16 lanes own one tile-row, one lane
+// per CSR row.  The columns of a CSR row ascend, so do its tile columns, and the distinct tile
+// columns of the tile-row come out of a 16-way merge: every step takes the smallest pending tile
+// column over the 16 lanes; the lanes whose row has entries in that tile consume them.
+// ------------------------------------------------------------------------------------------------
+constexpr int kMergeGroupsPerBlock = kConvThreads / 16;
+
+template <bool FILL, typename RP, typename VT>
+__global__ __launch_bounds__(kConvThreads) void k_convert_merge(const ConvArgs<RP, VT> a) {
+    __shared__ __align__(16) uint16_t dense_all[kMergeGroupsPerBlock][T * T];
     const int g = threadIdx.x >> 4, r = threadIdx.x & 15;
     uint16_t *dense = dense_all[g];
-    const int64_t I = (int64_t)blockIdx.x * kGroupsPerBlock + g;
-    int64_t p, e;
-    row_range(row_ptr, I * T + r, rows, nnz, I < tile_rows, p, e);
+    const int64_t I = (int64_t)blockIdx.x * kMergeGroupsPerBlock + g;
+    const bool mine = I < a.tile_rows && a.row_class[I] == ROW_MERGE;
+    bool bad = false;
+    int64_t p = 0, e = 0;
+    if (mine && I * T + r < a.rows) {
+        const int64_t row = I * T + r;
+        p = (int64_t)a.row_ptr[row];
+        e = (int64_t)a.row_ptr[row + 1];
+        bad |= p < 0 || e > a.nnz || p > e || (row == 0 && p != 0) || (row == a.rows - 1 && e != a.nnz);
+        p = min(max(p, (int64_t)0), a.nnz);      // never read outside the arrays, whatever row_ptr holds
+        e = min(max(e, p), a.nnz);
+    }
     int64_t t = 0;
     uint32_t lrun = 0, rrun = 0;
-    if (I < tile_rows) {
-        t = tile_row_ptr[I];
-        int64_t b = (int64_t)row_ptr[min(I * T, rows)];
-        lrun = rrun = (uint32_t)min(max(b, (int64_t)0), nnz);
+    if (FILL && mine) {
+        t = a.tile_row_ptr[I];
+        lrun = a.row_lbase[I];
+        rrun = a.row_rbase[I];
     }
-    int cur = p < e ? (col[p] >> 4) : INT_MAX;
+    int ntiles = 0;
+    uint32_t lcount = 0, rcount = 0;
+    int cur = p < e ? (a.col[p] >> 4) : INT_MAX;
+    int prev_col = -1;
     const uint32_t below_lo = (1u << r) - 1u, below_hi = (1u << (16 + r)) - 1u;
     for (;;) {
         const int m = group16_min(cur);
         if (__all(m == INT_MAX)) break;
         const bool active = m != INT_MAX;
-        // dense image of the tile in LDS; every lane clears and fills its own row
         uint4 *myrow = reinterpret_cast<uint4 *>(dense + r * T);
-        myrow[0] = make_uint4(0, 0, 0, 0);
-        myrow[1] = make_uint4(0, 0, 0, 0);
+        if (FILL) {                               // dense image of the tile in LDS; every lane fills its own row
+            myrow[0] = make_uint4(0, 0, 0, 0);
+            myrow[1] = make_uint4(0, 0, 0, 0);
+        }
         uint32_t mask = 0;
         if (active && cur == m) {
             do {
-                const int c = col[p] & 15;
-                mask |= 1u << c;
-                dense[r * T + c] = to_half_bits(val[p]);
+                const int c = a.col[p];
+                bad |= c <= prev_col || c >= a.cols;
+                prev_col = c;
+                mask |= 1u << (c & 15);
+                if (FILL) dense[r * T + (c & 15)] = to_half_bits(a.val[p]);
                 ++p;
-            } while (p < e && (col[p] >> 4) == m);
-            cur = p < e ? (col[p] >> 4) : INT_MAX;
+            } while (p < e && (a.col[p] >> 4) == m);
+            cur = p < e ? (a.col[p] >> 4) : INT_MAX;
         }
         wave_sync();
         // group masks: left form g = h*16 + row, right form g = h*16 + column
         const uint32_t lm = group16_ballot((mask & 0xFFu) != 0) | (group16_ballot((mask >> 8) != 0) << 16);
         const uint32_t rm = group16_or(r < 8 ? mask : (mask << 16));
-        if (active && t < tile_capacity) {
-            if (forms & TSP_FORM_LEFT) {
-                const int64_t g0 = (int64_t)lrun + __popc(lm & below_lo), g1 = (int64_t)lrun + __popc(lm & below_hi);
-                if ((mask & 0xFFu) && g0 < group_capacity) ldata[g0] = myrow[0];
-                if ((mask >> 8) && g1 < group_capacity) ldata[g1] = myrow[1];
-            }
-            if (forms & TSP_FORM_RIGHT) {
-                // lane r gathers column r of the tile
-                uint32_t w[8];
+        if (active) {
+            ++ntiles;
+            lcount += __popc(lm);
+            rcount += __popc(rm);
+            if (FILL && t < a.tile_capacity) {
+                if (a.forms & TSP_FORM_LEFT) {
+                    const int64_t g0 = (int64_t)lrun + __popc(lm & below_lo), g1 = (int64_t)lrun + __popc(lm & below_hi);
+                    if ((mask & 0xFFu) && g0 < a.group_capacity) a.ldata[g0] = myrow[0];
+                    if ((mask >> 8) && g1 < a.group_capacity) a.ldata[g1] = myrow[1];
+                }
+                if (a.forms & TSP_FORM_RIGHT) {
+                    uint32_t w[8];                 // lane r gathers column r of the tile
 #pragma unroll
-                for (int k = 0; k < 8; ++k)
-                    w[k] = (uint32_t)dense[(2 * k) * T + r] | ((uint32_t)dense[(2 * k + 1) * T + r] << 16);
-                const int64_t g0 = (int64_t)rrun + __popc(rm & below_lo), g1 = (int64_t)rrun + __popc(rm & below_hi);
-                // (the capacity tests can only fail for a non-canonical input)
-                if (((rm >> r) & 1u) && g0 < group_capacity) rdata[g0] = make_uint4(w[0], w[1], w[2], w[3]);
-                if (((rm >> (16 + r)) & 1u) && g1 < group_capacity) rdata[g1] = make_uint4(w[4], w[5], w[6], w[7]);
-            }
-            row_mask[t * T + r] = (uint16_t)mask;
-            if (r == 0) {
-                tile_col[t] = m;
-                lmask[t] = lm;
-                rmask[t] = rm;
-                if (forms & TSP_FORM_LEFT) loff[t] = lrun;
-                if (forms & TSP_FORM_RIGHT) roff[t] = rrun;
+                    for (int k = 0; k < 8; ++k)
+                        w[k] = (uint32_t)dense[(2 * k) * T + r] | ((uint32_t)dense[(2 * k + 1) * T + r] << 16);
+                    const int64_t g0 = (int64_t)rrun + __popc(rm & below_lo), g1 = (int64_t)rrun + __popc(rm & below_hi);
+                    if (((rm >> r) & 1u) && g0 < a.group_capacity) a.rdata[g0] = make_uint4(w[0], w[1], w[2], w[3]);
+                    if (((rm >> (16 + r)) & 1u) && g1 < a.group_capacity) a.rdata[g1] = make_uint4(w[4], w[5], w[6], w[7]);
+                }
+                a.row_mask[t * T + r] = (uint16_t)mask;
+                if (r == 0) {
+                    a.tile_col[t] = m;
+                    a.lmask[t] = lm;
+                    a.rmask[t] = rm;
+                    if (a.forms & TSP_FORM_LEFT) a.loff[t] = lrun;
+                    if (a.forms & TSP_FORM_RIGHT) a.roff[t] = rrun;
+                }
             }
             lrun += __popc(lm);
             rrun += __popc(rm);
@@ -160,42 +441,147 @@ __global__ __launch_bounds__(kConvThreads) void k_fill_tiles(
         }
         wave_sync();   // column reads above finish before the rows are cleared again
     }
+    if (!FILL) {
+        const bool any_bad = group16_or(bad ? 1u : 0u) != 0;
+        if (mine && r == 0) {
+            a.row_tiles[I] = ntiles;
+            a.row_lgroups[I] = (int32_t)lcount;
+            a.row_rgroups[I] = (int32_t)rcount;
+            if (any_bad && a.validate) a.d_scalars[S_INVALID] = 1;
+        }
+    }
 }
 
-template <typename RP>
-static int launch_convert_rp(tsp_context *ctx, const tsp_csr *A, tsp_tiles_s *t, int32_t *counts, int64_t *tmp,
-                             hipStream_t s) {
-    const RP *rp = static_cast<const RP *>(A->row_ptr);
-    const unsigned grid = (unsigned)((t->tile_rows + kGroupsPerBlock - 1) / kGroupsPerBlock);
-    if (ctx->validate && A->rows > 0) {
-        KernelTimer kt(ctx, TSP_KERNEL_VALIDATE, s);
-        hipLaunchKernelGGL(k_validate_csr<RP>, dim3((unsigned)((A->rows + kConvThreads - 1) / kConvThreads)),
-                           dim3(kConvThreads), 0, s, rp, A->col_idx, A->rows, A->cols, A->nnz, ctx->d_scalars);
+// Prefix sums over the tile-rows, one block: tiles, left groups, right groups.
+constexpr int kRowScanThreads = 1024, kRowScanItems = 4;
+__global__ __launch_bounds__(kRowScanThreads) void k_convert_scan(int64_t ntr, const int32_t *__restrict__ row_tiles,
+                                                                const int32_t *__restrict__ row_lg,
+                                                                const int32_t *__restrict__ row_rg,
+                                                                int32_t *__restrict__ tile_row_ptr,
+                                                                uint32_t *__restrict__ row_lbase,
+                                                                uint32_t *__restrict__ row_rbase,
+                                                                int64_t *__restrict__ d_total_tiles) {
+    __shared__ int64_t lds[3][kRowScanThreads / 64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int64_t carry[3] = {0, 0, 0};
+    for (int64_t base = 0; base < ntr; base += kRowScanThreads * kRowScanItems) {
+        const int64_t i0 = base + (int64_t)threadIdx.x * kRowScanItems;
+        int64_t x[3][kRowScanItems], sum[3] = {0, 0, 0};
+#pragma unroll
+        for (int k = 0; k < kRowScanItems; ++k) {
+            const bool in = i0 + k < ntr;
+            x[0][k] = in ? row_tiles[i0 + k] : 0;
+            x[1][k] = in ? row_lg[i0 + k] : 0;
+            x[2][k] = in ? row_rg[i0 + k] : 0;
+#pragma unroll
+            for (int q = 0; q < 3; ++q) sum[q] += x[q][k];
+        }
+        int64_t v[3] = {sum[0], sum[1], sum[2]};
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+#pragma unroll
+            for (int q = 0; q < 3; ++q) {
+                const int64_t u = __shfl_up(v[q], o, 64);
+                if (lane >= o) v[q] += u;
+            }
+        }
+        __syncthreads();
+        if (lane == 63)
+            for (int q = 0; q < 3; ++q) lds[q][wave] = v[q];
+        __syncthreads();
+        int64_t run[3];
+#pragma unroll
+        for (int q = 0; q < 3; ++q) {
+            int64_t before = 0, all = 0;
+            for (int w = 0; w < kRowScanThreads / 64; ++w) {
+                const int64_t y = lds[q][w];
+                if (w < wave) before += y;
+                all += y;
+            }
+            run[q] = carry[q] + before + v[q] - sum[q];
+            carry[q] += all;
+        }
+#pragma unroll
+        for (int k = 0; k < kRowScanItems; ++k) {
+            if (i0 + k < ntr) {
+                tile_row_ptr[i0 + k] = (int32_t)run[0];
+                row_lbase[i0 + k] = (uint32_t)run[1];
+                row_rbase[i0 + k] = (uint32_t)run[2];
+            }
+#pragma unroll
+            for (int q = 0; q < 3; ++q) run[q] += x[q][k];
+        }
     }
-    if (grid) {
+    if (threadIdx.x == 0) {
+        tile_row_ptr[ntr] = (int32_t)carry[0];
+        row_lbase[ntr] = (uint32_t)carry[1];
+        row_rbase[ntr] = (uint32_t)carry[2];
+        *d_total_tiles = carry[0];
+    }
+}
+
+template <typename RP, typename VT>
+static int launch_convert(tsp_context *ctx, const tsp_csr *A, tsp_tiles_s *t, int32_t *scratch, hipStream_t s) {
+    const int64_t ntr = t->tile_rows;
+    ConvArgs<RP, VT> a{};
+    a.row_ptr = static_cast<const RP *>(A->row_ptr);
+    a.col = A->col_idx;
+    a.val = static_cast<const VT *>(A->val);
+    a.rows = A->rows;
+    a.cols = A->cols;
+    a.nnz = A->nnz;
+    a.tile_rows = ntr;
+    a.tile_capacity = t->tile_capacity;
+    a.group_capacity = t->group_capacity;
+    a.forms = t->forms;
+    a.validate = ctx->validate;
+    a.row_tiles = scratch;
+    a.row_lgroups = scratch + (ntr + 1);
+    a.row_rgroups = scratch + 2 * (ntr + 1);
+    a.row_class = scratch + 3 * (ntr + 1);
+    uint32_t *lbase = reinterpret_cast<uint32_t *>(scratch + 4 * (ntr + 1));
+    uint32_t *rbase = reinterpret_cast<uint32_t *>(scratch + 5 * (ntr + 1));
+    a.tile_row_ptr = t->tile_row_ptr;
+    a.row_lbase = lbase;
+    a.row_rbase = rbase;
+    a.tile_col = t->tile_col;
+    a.row_mask = t->row_mask;
+    a.lmask = t->lmask;
+    a.rmask = t->rmask;
+    a.loff = t->loff;
+    a.roff = t->roff;
+    a.ldata = t->ldata;
+    a.rdata = t->rdata;
+    a.d_scalars = ctx->d_scalars;
+    // a wave per tile-row unless the tile-rows are long; the merge path only when a tile-row could
+    // span more tile columns than the bitmap of the chosen kernel holds
+    const bool wide_groups = ntr > 0 && A->nnz / ntr > 1024;
+    const int64_t bitmap_span = 32ll * (wide_groups ? ConvCfg<256>::kWords : ConvCfg<64>::kWords);
+    const bool may_merge = t->tile_cols > bitmap_span;
+    const unsigned grid_fast = (unsigned)(wide_groups ? ntr : (ntr + 3) / 4);
+    const unsigned grid_merge = (unsigned)((ntr + kMergeGroupsPerBlock - 1) / kMergeGroupsPerBlock);
+    if (ntr > 0) {
         KernelTimer kt(ctx, TSP_KERNEL_COUNT_TILES, s);
-        hipLaunchKernelGGL(k_count_tiles<RP>, dim3(grid), dim3(kConvThreads), 0, s, rp, A->col_idx, A->rows, A->nnz,
-                           t->tile_rows, counts);
+        if (wide_groups)
+            hipLaunchKernelGGL((k_convert_rows<256, false, RP, VT>), dim3(grid_fast), dim3(kConvThreads), 0, s, a);
+        else
+            hipLaunchKernelGGL((k_convert_rows<64, false, RP, VT>), dim3(grid_fast), dim3(kConvThreads), 0, s, a);
+        if (may_merge)
+            hipLaunchKernelGGL((k_convert_merge<false, RP, VT>), dim3(grid_merge), dim3(kConvThreads), 0, s, a);
     }
-    int rc;
     {
         KernelTimer kt(ctx, TSP_KERNEL_SCAN_TILES, s);
-        rc = scan_exclusive_i32_to_i32(ctx, counts, t->tile_row_ptr, t->tile_rows, ctx->d_scalars + t->scalar_slot,
-                                       nullptr, tmp, s);
+        hipLaunchKernelGGL(k_convert_scan, dim3(1), dim3(kRowScanThreads), 0, s, ntr, a.row_tiles, a.row_lgroups,
+                           a.row_rgroups, t->tile_row_ptr, lbase, rbase, ctx->d_scalars + t->scalar_slot);
     }
-    if (rc) return rc;
-    if (grid) {
+    if (ntr > 0) {
         KernelTimer kt(ctx, TSP_KERNEL_FILL_TILES, s);
-        if (A->val_type == TSP_F16)
-            hipLaunchKernelGGL((k_fill_tiles<RP, uint16_t>), dim3(grid), dim3(kConvThreads), 0, s, rp, A->col_idx,
-                               static_cast<const uint16_t *>(A->val), A->rows, A->nnz, t->tile_rows, t->tile_row_ptr,
-                               t->tile_capacity, t->group_capacity, t->forms, t->tile_col, t->row_mask, t->lmask, t->rmask, t->loff,
-                               t->roff, t->ldata, t->rdata);
+        if (wide_groups)
+            hipLaunchKernelGGL((k_convert_rows<256, true, RP, VT>), dim3(grid_fast), dim3(kConvThreads), 0, s, a);
         else
-            hipLaunchKernelGGL((k_fill_tiles<RP, float>), dim3(grid), dim3(kConvThreads), 0, s, rp, A->col_idx,
-                               static_cast<const float *>(A->val), A->rows, A->nnz, t->tile_rows, t->tile_row_ptr,
-                               t->tile_capacity, t->group_capacity, t->forms, t->tile_col, t->row_mask, t->lmask, t->rmask, t->loff,
-                               t->roff, t->ldata, t->rdata);
+            hipLaunchKernelGGL((k_convert_rows<64, true, RP, VT>), dim3(grid_fast), dim3(kConvThreads), 0, s, a);
+        if (may_merge)
+            hipLaunchKernelGGL((k_convert_merge<true, RP, VT>), dim3(grid_merge), dim3(kConvThreads), 0, s, a);
     }
     TSP_HIP_CHECK(ctx, hipGetLastError());
     return TSP_OK;
@@ -265,15 +651,17 @@ int convert_enqueue(tsp_context *ctx, const tsp_csr *A, int forms, int scalar_sl
         t->rdata = ctx_alloc_n<uint4>(ctx, (size_t)t->group_capacity, s);
         ok = ok && t->roff && t->rdata;
     }
-    int32_t *counts = ctx_alloc_n<int32_t>(ctx, (size_t)t->tile_rows + 1, s);
-    int64_t *tmp = ctx_alloc_n<int64_t>(ctx, scan_tmp_entries(t->tile_rows), s);
-    ok = ok && counts && tmp;
+    int32_t *scratch = ctx_alloc_n<int32_t>(ctx, 6 * ((size_t)t->tile_rows + 1), s);
+    ok = ok && scratch;
     rc = ok ? TSP_OK : TSP_ERR_ALLOC_FAILED;
-    if (!rc)
-        rc = A->row_ptr_type == TSP_I32 ? launch_convert_rp<int32_t>(ctx, A, t, counts, tmp, s)
-                                        : launch_convert_rp<int64_t>(ctx, A, t, counts, tmp, s);
-    ctx_free(ctx, counts, s);
-    ctx_free(ctx, tmp, s);
+    if (!rc) {
+        const bool i32 = A->row_ptr_type == TSP_I32, f16 = A->val_type == TSP_F16;
+        rc = i32 ? (f16 ? launch_convert<int32_t, uint16_t>(ctx, A, t, scratch, s)
+                        : launch_convert<int32_t, float>(ctx, A, t, scratch, s))
+                 : (f16 ? launch_convert<int64_t, uint16_t>(ctx, A, t, scratch, s)
+                        : launch_convert<int64_t, float>(ctx, A, t, scratch, s));
+    }
+    ctx_free(ctx, scratch, s);
     if (rc) {
         tiles_release(ctx, t, s);
         return rc;

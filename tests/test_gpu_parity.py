@@ -79,6 +79,30 @@ def test_random_rectangular(tsp, handle, oracle, M, K, N, density, seed, kind):
     run_and_check(tsp, handle, oracle, A, B)
 
 
+def test_very_wide_tile_rows_take_the_merge_path(tsp, handle, oracle):
+    """Tile-rows whose tile columns span more than the converter's LDS bitmap (24576 tile columns
+    for wave-sized groups, 131072 for block-sized ones) are converted by the 16-way merge."""
+    rng = np.random.default_rng(17)
+    n_wide = 2_000_000
+    rows = np.repeat(np.arange(40), 30)
+    cols = np.concatenate([np.sort(rng.choice(n_wide, 30, replace=False)) for _ in range(40)])
+    A = inputs.from_coo(40, n_wide, rows, cols, rng.uniform(-1, 1, rows.shape[0]))
+    brow = rng.choice(n_wide, 5000, replace=False)
+    B = inputs.from_coo(n_wide, 70, np.concatenate([brow, cols[::7]]),
+                        rng.integers(0, 70, brow.shape[0] + cols[::7].shape[0]),
+                        rng.uniform(-1, 1, brow.shape[0] + cols[::7].shape[0]))
+    nnz, _ = run_and_check(tsp, handle, oracle, A, B)
+    assert nnz > 0
+    At = inputs.from_coo(n_wide, 40, cols, rows, A.val)            # tall operand, wide inner dimension
+    run_and_check(tsp, handle, oracle, At, A)
+
+
+def test_long_tile_rows_use_block_sized_groups(tsp, handle, oracle):
+    A = inputs.random_sparse(64, 3000, 0.6, 71)                    # > 1024 entries per tile-row on average
+    B = inputs.random_sparse(3000, 48, 0.05, 72)
+    run_and_check(tsp, handle, oracle, A, B)
+
+
 def test_empty_operands(tsp, handle, oracle):
     for M, K, N in [(0, 5, 7), (5, 0, 7), (5, 7, 0), (20, 30, 40)]:
         A = inputs.random_sparse(M, K, 0.0, 1)
