@@ -28,6 +28,7 @@ enum Scalar {
     S_MAX_ROW_WORDS = 8,     // max over C tile-rows of bitmap words needed
     S_C_NNZ = 9,
     S_MAX_ROW_A_TILES = 10,
+    S_INTERNAL = 11,         // != 0: a bounded device-side wait ran out (should never happen)
 };
 
 struct Block {
@@ -49,6 +50,9 @@ struct tsp_context {
     int force_wide = 0;                            // use the 64-bit-pointer kernels whatever the sizes
     int last_hip = 0;
     tsp_stats stats{};
+    void *chain_slots = nullptr;                   // device, for the chained scans (chain.hpp)
+    int64_t chain_capacity = 0;                    // slots allocated
+    unsigned chain_epoch = 0;                      // tag of the last chained scan
     int64_t *d_scalars = nullptr;                  // device, kScalars entries
     int64_t *h_scalars = nullptr;                  // pinned host mirror
     hipEvent_t ev[2 * TSP_PHASE_COUNT_ + 2]{};     // begin/end per phase, + total begin/end
@@ -93,6 +97,8 @@ void *ctx_alloc(tsp_context *ctx, size_t bytes, hipStream_t s);          // NULL
 void ctx_free(tsp_context *ctx, void *p, hipStream_t s);                 // back into the cache
 int hip_fail(tsp_context *ctx, hipError_t e);                            // records e, returns TSP_ERR_HIP
 int read_scalars(tsp_context *ctx, hipStream_t s);                       // d_scalars -> h_scalars, syncs
+// Slots for a chained scan over `blocks` blocks and a fresh epoch tag; nullptr on failure.
+void *chain_prepare(tsp_context *ctx, int64_t blocks, unsigned *epoch, hipStream_t s);
 void phase_begin(tsp_context *ctx, int phase, hipStream_t s);
 void phase_end(tsp_context *ctx, int phase, hipStream_t s);
 void total_begin(tsp_context *ctx, hipStream_t s);
@@ -149,15 +155,73 @@ __device__ __forceinline__ void wave_sync() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-__device__ __forceinline__ int group16_min(int v) {
-#pragma unroll
-    for (int o = 8; o >= 1; o >>= 1) v = min(v, __shfl_xor(v, o, 16));
+// Cross-lane operations on the data-parallel-primitive path (VALU speed, no LDS round trips).
+// A "row" is 16 consecutive lanes; row_ror rotates inside a row, row_shr shifts inside a row,
+// row_bcast:15 / row_bcast:31 carry a row's (half-wave's) last lane into the following rows.
+#define TSP_DPP(old, src, ctrl, row_mask, bound) \
+    __builtin_amdgcn_update_dpp((old), (src), (ctrl), (row_mask), 0xf, (bound))
+
+__device__ __forceinline__ int group16_min(int v) {          // all 16 lanes of the row get the minimum
+    v = min(v, TSP_DPP(v, v, 0x128, 0xf, false));
+    v = min(v, TSP_DPP(v, v, 0x124, 0xf, false));
+    v = min(v, TSP_DPP(v, v, 0x122, 0xf, false));
+    v = min(v, TSP_DPP(v, v, 0x121, 0xf, false));
     return v;
 }
 __device__ __forceinline__ uint32_t group16_or(uint32_t v) {
-#pragma unroll
-    for (int o = 8; o >= 1; o >>= 1) v |= (uint32_t)__shfl_xor((int)v, o, 16);
+    v |= (uint32_t)TSP_DPP((int)v, (int)v, 0x128, 0xf, false);
+    v |= (uint32_t)TSP_DPP((int)v, (int)v, 0x124, 0xf, false);
+    v |= (uint32_t)TSP_DPP((int)v, (int)v, 0x122, 0xf, false);
+    v |= (uint32_t)TSP_DPP((int)v, (int)v, 0x121, 0xf, false);
     return v;
+}
+// Inclusive prefix sum over the 64 lanes of a wave.
+__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t x) {
+    int v = (int)x;
+    v += TSP_DPP(0, v, 0x111, 0xf, true);     // row_shr:1
+    v += TSP_DPP(0, v, 0x112, 0xf, true);     // row_shr:2
+    v += TSP_DPP(0, v, 0x114, 0xf, true);     // row_shr:4
+    v += TSP_DPP(0, v, 0x118, 0xf, true);     // row_shr:8
+    v += TSP_DPP(0, v, 0x142, 0xa, false);    // row_bcast:15 into rows 1 and 3
+    v += TSP_DPP(0, v, 0x143, 0xc, false);    // row_bcast:31 into rows 2 and 3
+    return (uint32_t)v;
+}
+// The same for 64-bit values below 2^46: the low 20 bits and the rest are scanned separately
+// (sums of 64 such parts fit 32 bits) and recombined; addition is linear, so this is exact.
+__device__ __forceinline__ uint64_t wave_inclusive_scan64(uint64_t x) {
+    const uint32_t lo = wave_inclusive_scan((uint32_t)x & 0xFFFFFu), hi = wave_inclusive_scan((uint32_t)(x >> 20));
+    return ((uint64_t)hi << 20) + lo;
+}
+// Exclusive prefix of one 64-bit value per thread over a block of kThreads threads (every thread
+// of the block calls it); *total receives the block total.  lds: kThreads/64 words of scratch.
+template <int kThreads>
+__device__ __forceinline__ uint64_t block_exclusive_scan64(uint64_t x, uint64_t *total, uint64_t *lds) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint64_t inc = wave_inclusive_scan64(x);
+    __syncthreads();                       // lds may still be in use by a previous call
+    if (lane == 63) lds[wave] = inc;
+    __syncthreads();
+    uint64_t before = 0, all = 0;
+#pragma unroll
+    for (int w = 0; w < kThreads / 64; ++w) {
+        const uint64_t y = lds[w];
+        if (w < wave) before += y;
+        all += y;
+    }
+    *total = all;
+    return before + inc - x;
+}
+__device__ __forceinline__ uint32_t wave_sum(uint32_t x) {   // total in every lane
+    return (uint32_t)__builtin_amdgcn_readlane((int)wave_inclusive_scan(x), 63);
+}
+__device__ __forceinline__ int wave_max(int v) {             // maximum in every lane
+    v = max(v, TSP_DPP(v, v, 0x111, 0xf, false));
+    v = max(v, TSP_DPP(v, v, 0x112, 0xf, false));
+    v = max(v, TSP_DPP(v, v, 0x114, 0xf, false));
+    v = max(v, TSP_DPP(v, v, 0x118, 0xf, false));
+    v = max(v, TSP_DPP(v, v, 0x142, 0xa, false));
+    v = max(v, TSP_DPP(v, v, 0x143, 0xc, false));
+    return __builtin_amdgcn_readlane(v, 63);
 }
 // 16-bit slice of a wave ballot that belongs to this lane's 16-lane group.
 __device__ __forceinline__ uint32_t group16_ballot(bool pred) {

@@ -1,5 +1,6 @@
 // Handle, device-memory cache, options, statistics, error strings.
 #include "common.hpp"
+#include "chain.hpp"
 
 #include <algorithm>
 #include <new>
@@ -71,6 +72,26 @@ int read_scalars(tsp_context *ctx, hipStream_t s) {
                                       hipMemcpyDeviceToHost, s));
     TSP_HIP_CHECK(ctx, hipStreamSynchronize(s));
     return TSP_OK;
+}
+
+void *chain_prepare(tsp_context *ctx, int64_t blocks, unsigned *epoch, hipStream_t s) {
+    if (blocks > ctx->chain_capacity || ctx->chain_epoch >= (1u << 29)) {
+        const int64_t want = blocks > ctx->chain_capacity ? (blocks < 1024 ? 1024 : 2 * blocks) : ctx->chain_capacity;
+        if (want != ctx->chain_capacity) {
+            if (ctx->chain_slots) ctx_free(ctx, ctx->chain_slots, s);
+            ctx->chain_slots = ctx_alloc(ctx, (size_t)want * sizeof(ChainSlot), s);
+            ctx->chain_capacity = ctx->chain_slots ? want : 0;
+            if (!ctx->chain_slots) return nullptr;
+        }
+        // all flags to "no epoch"; epochs restart at 1
+        if (hipMemsetAsync(ctx->chain_slots, 0, (size_t)ctx->chain_capacity * sizeof(ChainSlot), s) != hipSuccess) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        ctx->chain_epoch = 0;
+    }
+    *epoch = ++ctx->chain_epoch;
+    return ctx->chain_slots;
 }
 
 static void ensure_events(tsp_context *ctx) {

@@ -20,6 +20,7 @@
 // the 16 sorted rows, one tile per step (any span, one tile at a time).
 // The occupancy pass also checks that the input is canonical (it reads every index anyway).
 #include "common.hpp"
+#include "chain.hpp"
 
 #include <hip/hip_fp16.h>
 
@@ -71,8 +72,7 @@ __device__ __forceinline__ void group_sync() {
 // Reductions over the G threads of a group.  red: LDS scratch of 8 words per group (G = 256 only).
 template <int G>
 __device__ __forceinline__ int group_max(int v, int *red) {
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) v = max(v, __shfl_xor(v, o, 64));
+    v = wave_max(v);
     if (G > 64) {
         __syncthreads();
         if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
@@ -83,8 +83,7 @@ __device__ __forceinline__ int group_max(int v, int *red) {
 }
 template <int G>
 __device__ __forceinline__ uint32_t group_sum(uint32_t v, int *red) {
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) v += (uint32_t)__shfl_xor((int)v, o, 64);
+    v = wave_sum(v);
     if (G > 64) {
         __syncthreads();
         if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = (int)v;
@@ -96,21 +95,16 @@ __device__ __forceinline__ uint32_t group_sum(uint32_t v, int *red) {
 // In-place exclusive scan of arr[0..n) by the group; returns the total.
 template <int G>
 __device__ __forceinline__ uint32_t group_exclusive_scan(uint32_t *arr, int n, int *red) {
-    const int gt = threadIdx.x % G, lane = threadIdx.x & 63, wave = (threadIdx.x % G) >> 6;
+    const int gt = threadIdx.x % G, wave = (threadIdx.x % G) >> 6;
     uint32_t carry = 0;
     for (int base = 0; base < n; base += G) {
         const int i = base + gt;
         const uint32_t x = i < n ? arr[i] : 0;
-        uint32_t v = x;
-#pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-            const uint32_t u = (uint32_t)__shfl_up((int)v, o, 64);
-            if (lane >= o) v += u;
-        }
-        uint32_t before = 0, all = (uint32_t)__shfl((int)v, 63, 64);
+        const uint32_t v = wave_inclusive_scan(x);
+        uint32_t before = 0, all = (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
         if (G > 64) {
             __syncthreads();
-            if (lane == 63) red[wave] = (int)v;
+            if ((threadIdx.x & 63) == 63) red[wave] = (int)v;
             __syncthreads();
             all = 0;
 #pragma unroll
@@ -452,71 +446,55 @@ __global__ __launch_bounds__(kConvThreads) void k_convert_merge(const ConvArgs<R
     }
 }
 
-// Prefix sums over the tile-rows, one block: tiles, left groups, right groups.
-constexpr int kRowScanThreads = 1024, kRowScanItems = 4;
+// Prefix sums over the tile-rows (tiles, left groups, right groups) in one launch: a block scans
+// 1024 tile-rows (4 per thread, one 16-byte load per array) and the blocks are chained (chain.hpp).
+constexpr int kRowScanThreads = 256, kRowScanItems = 4, kRowScanBlock = kRowScanThreads * kRowScanItems;
 __global__ __launch_bounds__(kRowScanThreads) void k_convert_scan(int64_t ntr, const int32_t *__restrict__ row_tiles,
                                                                 const int32_t *__restrict__ row_lg,
                                                                 const int32_t *__restrict__ row_rg,
                                                                 int32_t *__restrict__ tile_row_ptr,
                                                                 uint32_t *__restrict__ row_lbase,
-                                                                uint32_t *__restrict__ row_rbase,
-                                                                int64_t *__restrict__ d_total_tiles) {
-    __shared__ int64_t lds[3][kRowScanThreads / 64];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    int64_t carry[3] = {0, 0, 0};
-    for (int64_t base = 0; base < ntr; base += kRowScanThreads * kRowScanItems) {
-        const int64_t i0 = base + (int64_t)threadIdx.x * kRowScanItems;
-        int64_t x[3][kRowScanItems], sum[3] = {0, 0, 0};
+                                                                uint32_t *__restrict__ row_rbase, ChainSlot *slots,
+                                                                unsigned epoch, int64_t *__restrict__ d_scalars,
+                                                                int total_slot) {
+    __shared__ uint64_t lds[kRowScanThreads / 64 + kChainValues];
+    const int32_t *in[3] = {row_tiles, row_lg, row_rg};
+    const int64_t i0 = (int64_t)blockIdx.x * kRowScanBlock + (int64_t)threadIdx.x * kRowScanItems;
+    int32_t x[3][kRowScanItems];
+    uint64_t sum[3] = {0, 0, 0}, local[3];
+    unsigned long long agg[kChainValues], prefix[kChainValues];
 #pragma unroll
-        for (int k = 0; k < kRowScanItems; ++k) {
-            const bool in = i0 + k < ntr;
-            x[0][k] = in ? row_tiles[i0 + k] : 0;
-            x[1][k] = in ? row_lg[i0 + k] : 0;
-            x[2][k] = in ? row_rg[i0 + k] : 0;
+    for (int q = 0; q < 3; ++q) {
+        if (i0 + kRowScanItems <= ntr) {                     // one aligned 16-byte load
+            const int4 v = *reinterpret_cast<const int4 *>(in[q] + i0);
+            x[q][0] = v.x, x[q][1] = v.y, x[q][2] = v.z, x[q][3] = v.w;
+        } else {
 #pragma unroll
-            for (int q = 0; q < 3; ++q) sum[q] += x[q][k];
-        }
-        int64_t v[3] = {sum[0], sum[1], sum[2]};
-#pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-#pragma unroll
-            for (int q = 0; q < 3; ++q) {
-                const int64_t u = __shfl_up(v[q], o, 64);
-                if (lane >= o) v[q] += u;
-            }
-        }
-        __syncthreads();
-        if (lane == 63)
-            for (int q = 0; q < 3; ++q) lds[q][wave] = v[q];
-        __syncthreads();
-        int64_t run[3];
-#pragma unroll
-        for (int q = 0; q < 3; ++q) {
-            int64_t before = 0, all = 0;
-            for (int w = 0; w < kRowScanThreads / 64; ++w) {
-                const int64_t y = lds[q][w];
-                if (w < wave) before += y;
-                all += y;
-            }
-            run[q] = carry[q] + before + v[q] - sum[q];
-            carry[q] += all;
+            for (int k = 0; k < kRowScanItems; ++k) x[q][k] = i0 + k < ntr ? in[q][i0 + k] : 0;
         }
 #pragma unroll
-        for (int k = 0; k < kRowScanItems; ++k) {
-            if (i0 + k < ntr) {
-                tile_row_ptr[i0 + k] = (int32_t)run[0];
-                row_lbase[i0 + k] = (uint32_t)run[1];
-                row_rbase[i0 + k] = (uint32_t)run[2];
-            }
-#pragma unroll
-            for (int q = 0; q < 3; ++q) run[q] += x[q][k];
-        }
+        for (int k = 0; k < kRowScanItems; ++k) sum[q] += (uint32_t)x[q][k];
+        uint64_t total;
+        local[q] = block_exclusive_scan64<kRowScanThreads>(sum[q], &total, lds);
+        agg[q] = total;
     }
-    if (threadIdx.x == 0) {
-        tile_row_ptr[ntr] = (int32_t)carry[0];
-        row_lbase[ntr] = (uint32_t)carry[1];
-        row_rbase[ntr] = (uint32_t)carry[2];
-        *d_total_tiles = carry[0];
+    chain_exclusive_prefix(slots, epoch, agg, prefix, lds + kRowScanThreads / 64, d_scalars + S_INTERNAL);
+    uint64_t run[3] = {prefix[0] + local[0], prefix[1] + local[1], prefix[2] + local[2]};
+#pragma unroll
+    for (int k = 0; k < kRowScanItems; ++k) {
+        if (i0 + k < ntr) {
+            tile_row_ptr[i0 + k] = (int32_t)run[0];
+            row_lbase[i0 + k] = (uint32_t)run[1];
+            row_rbase[i0 + k] = (uint32_t)run[2];
+        }
+#pragma unroll
+        for (int q = 0; q < 3; ++q) run[q] += (uint32_t)x[q][k];
+    }
+    if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) {
+        tile_row_ptr[ntr] = (int32_t)(prefix[0] + agg[0]);
+        row_lbase[ntr] = (uint32_t)(prefix[1] + agg[1]);
+        row_rbase[ntr] = (uint32_t)(prefix[2] + agg[2]);
+        d_scalars[total_slot] = (int64_t)(prefix[0] + agg[0]);
     }
 }
 
@@ -571,8 +549,13 @@ static int launch_convert(tsp_context *ctx, const tsp_csr *A, tsp_tiles_s *t, in
     }
     {
         KernelTimer kt(ctx, TSP_KERNEL_SCAN_TILES, s);
-        hipLaunchKernelGGL(k_convert_scan, dim3(1), dim3(kRowScanThreads), 0, s, ntr, a.row_tiles, a.row_lgroups,
-                           a.row_rgroups, t->tile_row_ptr, lbase, rbase, ctx->d_scalars + t->scalar_slot);
+        const int64_t blocks = ntr > 0 ? (ntr + kRowScanBlock - 1) / kRowScanBlock : 1;
+        unsigned epoch = 0;
+        ChainSlot *slots = static_cast<ChainSlot *>(chain_prepare(ctx, blocks, &epoch, s));
+        if (!slots) return TSP_ERR_ALLOC_FAILED;
+        hipLaunchKernelGGL(k_convert_scan, dim3((unsigned)blocks), dim3(kRowScanThreads), 0, s, ntr, a.row_tiles,
+                           a.row_lgroups, a.row_rgroups, t->tile_row_ptr, lbase, rbase, slots, epoch, ctx->d_scalars,
+                           t->scalar_slot);
     }
     if (ntr > 0) {
         KernelTimer kt(ctx, TSP_KERNEL_FILL_TILES, s);

@@ -18,6 +18,7 @@
 // (Section 4.2: "simulates" the multiplication on 0/1 tiles; here with integer bit operations on
 // the 16-bit row masks, which gives the same pattern), and the per-row counts give row_ptr of C.
 #include "common.hpp"
+#include "chain.hpp"
 
 #include <climits>
 #include <new>
@@ -37,8 +38,7 @@ struct TileRefs {
 };
 
 __device__ __forceinline__ uint32_t block_sum_u32(uint32_t v, uint32_t *lds /*[>=16]*/) {
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) v += (uint32_t)__shfl_xor((int)v, o, 64);
+    v = wave_sum(v);
     __syncthreads();
     if ((threadIdx.x & 63) == 0) lds[threadIdx.x >> 6] = v;
     __syncthreads();
@@ -54,12 +54,7 @@ __device__ __forceinline__ uint32_t block_exclusive_scan_lds(uint32_t *arr, int 
     for (int base = 0; base < n; base += blockDim.x) {
         const int i = base + threadIdx.x;
         const uint32_t x = i < n ? arr[i] : 0;
-        uint32_t v = x;
-#pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-            uint32_t u = (uint32_t)__shfl_up((int)v, o, 64);
-            if (lane >= o) v += u;
-        }
+        const uint32_t v = wave_inclusive_scan(x);
         __syncthreads();
         if (lane == 63) lds[wave] = v;
         __syncthreads();
@@ -181,101 +176,77 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_count(TileRefs A, TileRefs 
     }
 }
 
-// Prefix sums over the tile-rows (Algorithm 1 lines 9-15: counts -> offsets and total sizes), one
-// block: C tiles per row -> c_tile_row_ptr, pairs per row -> row_pair_ptr, plus the totals and maxima
-// the host needs to size the task list.
-constexpr int kRowScanThreads = 1024;
-constexpr int kRowScanItems = 4;
+// Prefix sums over the tile-rows (Algorithm 1 lines 9-15: counts -> offsets and total sizes) in one
+// launch: C tiles per row -> c_tile_row_ptr, pairs per row -> row_pair_ptr, plus the totals and maxima
+// the host needs to size the task list.  A block scans 1024 tile-rows; the blocks are chained.
+constexpr int kRowScanThreads = 256, kRowScanItems = 4, kRowScanBlock = kRowScanThreads * kRowScanItems;
 __global__ __launch_bounds__(kRowScanThreads) void k_sym_row_scan(
     int64_t ntr, const int32_t *__restrict__ row_c_tiles, const int32_t *__restrict__ row_pairs,
     const int32_t *__restrict__ row_words, const int32_t *__restrict__ row_cand,
-    int32_t *__restrict__ c_tile_row_ptr, int64_t *__restrict__ row_pair_ptr, int64_t *__restrict__ d_scalars) {
-    __shared__ int64_t lds_c[kRowScanThreads / 64], lds_p[kRowScanThreads / 64], lds_m[4][kRowScanThreads / 64];
+    int32_t *__restrict__ c_tile_row_ptr, int64_t *__restrict__ row_pair_ptr, ChainSlot *slots, unsigned epoch,
+    int64_t *__restrict__ d_scalars) {
+    __shared__ uint64_t lds[kRowScanThreads / 64 + kChainValues];
+    __shared__ int lds_m[2][kRowScanThreads / 64];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    int64_t carry_c = 0, carry_p = 0, max_c = 0, max_w = 0, sum_cand = 0;
-    for (int64_t base = 0; base < ntr; base += kRowScanThreads * kRowScanItems) {
-        const int64_t i0 = base + (int64_t)threadIdx.x * kRowScanItems;
-        int64_t xc[kRowScanItems], xp[kRowScanItems], sc = 0, sp = 0;
+    const int64_t i0 = (int64_t)blockIdx.x * kRowScanBlock + (int64_t)threadIdx.x * kRowScanItems;
+    int32_t xc[kRowScanItems], xp[kRowScanItems];
+    uint64_t sc = 0, sp = 0, cand = 0;
+    int max_c = 0, max_w = 0;
 #pragma unroll
-        for (int k = 0; k < kRowScanItems; ++k) {
-            const bool in = i0 + k < ntr;
-            xc[k] = in ? row_c_tiles[i0 + k] : 0;
-            xp[k] = in ? row_pairs[i0 + k] : 0;
-            sc += xc[k];
-            sp += xp[k];
-            max_c = max(max_c, xc[k]);
-            if (in) {
-                max_w = max(max_w, (int64_t)row_words[i0 + k]);
-                sum_cand += row_cand[i0 + k];
-            }
-        }
-        int64_t vc = sc, vp = sp;
-#pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-            const int64_t uc = __shfl_up(vc, o, 64), up = __shfl_up(vp, o, 64);
-            if (lane >= o) {
-                vc += uc;
-                vp += up;
-            }
-        }
-        __syncthreads();
-        if (lane == 63) {
-            lds_c[wave] = vc;
-            lds_p[wave] = vp;
-        }
-        __syncthreads();
-        int64_t before_c = 0, before_p = 0, all_c = 0, all_p = 0;
-#pragma unroll
-        for (int w = 0; w < kRowScanThreads / 64; ++w) {
-            const int64_t yc = lds_c[w], yp = lds_p[w];
-            if (w < wave) {
-                before_c += yc;
-                before_p += yp;
-            }
-            all_c += yc;
-            all_p += yp;
-        }
-        int64_t run_c = carry_c + before_c + vc - sc, run_p = carry_p + before_p + vp - sp;
-#pragma unroll
-        for (int k = 0; k < kRowScanItems; ++k) {
-            if (i0 + k < ntr) {
-                c_tile_row_ptr[i0 + k] = (int32_t)run_c;
-                row_pair_ptr[i0 + k] = run_p;
-            }
-            run_c += xc[k];
-            run_p += xp[k];
-        }
-        carry_c += all_c;
-        carry_p += all_p;
+    for (int k = 0; k < kRowScanItems; ++k) {
+        const bool in = i0 + k < ntr;
+        xc[k] = in ? row_c_tiles[i0 + k] : 0;
+        xp[k] = in ? row_pairs[i0 + k] : 0;
+        sc += (uint32_t)xc[k];
+        sp += (uint32_t)xp[k];
+        max_c = max(max_c, xc[k]);
+        max_w = max(max_w, in ? row_words[i0 + k] : 0);
+        cand += in ? (uint32_t)row_cand[i0 + k] : 0u;
     }
-    // block-wide maxima and the candidate total
+    unsigned long long agg[kChainValues], prefix[kChainValues];
+    uint64_t total, unused;
+    const uint64_t local_c = block_exclusive_scan64<kRowScanThreads>(sc, &total, lds);
+    agg[0] = total;
+    const uint64_t local_p = block_exclusive_scan64<kRowScanThreads>(sp, &total, lds);
+    agg[1] = total;
+    (void)block_exclusive_scan64<kRowScanThreads>(cand, &total, lds);
+    agg[2] = total;
+    (void)unused;
+    chain_exclusive_prefix(slots, epoch, agg, prefix, lds + kRowScanThreads / 64, d_scalars + S_INTERNAL);
+    uint64_t run_c = prefix[0] + local_c, run_p = prefix[1] + local_p;
 #pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) {
-        max_c = max(max_c, (int64_t)__shfl_xor(max_c, o, 64));
-        max_w = max(max_w, (int64_t)__shfl_xor(max_w, o, 64));
-        sum_cand += __shfl_xor(sum_cand, o, 64);
+    for (int k = 0; k < kRowScanItems; ++k) {
+        if (i0 + k < ntr) {
+            c_tile_row_ptr[i0 + k] = (int32_t)run_c;
+            row_pair_ptr[i0 + k] = (int64_t)run_p;
+        }
+        run_c += (uint32_t)xc[k];
+        run_p += (uint32_t)xp[k];
     }
+    // maxima: one atomic per block (a few dozen blocks at most per million rows)
+    max_c = wave_max(max_c);
+    max_w = wave_max(max_w);
     __syncthreads();
     if (lane == 0) {
         lds_m[0][wave] = max_c;
         lds_m[1][wave] = max_w;
-        lds_m[2][wave] = sum_cand;
     }
     __syncthreads();
     if (threadIdx.x == 0) {
-        int64_t mc = 0, mw = 0, sc = 0;
+        int mc = 0, mw = 0;
         for (int w = 0; w < kRowScanThreads / 64; ++w) {
             mc = max(mc, lds_m[0][w]);
             mw = max(mw, lds_m[1][w]);
-            sc += lds_m[2][w];
         }
-        c_tile_row_ptr[ntr] = (int32_t)carry_c;
-        row_pair_ptr[ntr] = carry_p;
-        d_scalars[S_C_TILES] = carry_c;
-        d_scalars[S_PAIRS] = carry_p;
-        d_scalars[S_MAX_ROW_C_TILES] = mc;
-        d_scalars[S_MAX_ROW_WORDS] = mw;
-        d_scalars[S_CANDIDATES] = sc;
+        atomicMax((unsigned long long *)&d_scalars[S_MAX_ROW_C_TILES], (unsigned long long)mc);
+        atomicMax((unsigned long long *)&d_scalars[S_MAX_ROW_WORDS], (unsigned long long)mw);
+        if (blockIdx.x == gridDim.x - 1) {
+            c_tile_row_ptr[ntr] = (int32_t)(prefix[0] + agg[0]);
+            row_pair_ptr[ntr] = (int64_t)(prefix[1] + agg[1]);
+            d_scalars[S_C_TILES] = (int64_t)(prefix[0] + agg[0]);
+            d_scalars[S_PAIRS] = (int64_t)(prefix[1] + agg[1]);
+            d_scalars[S_CANDIDATES] = (int64_t)(prefix[2] + agg[2]);
+        }
     }
 }
 
@@ -555,8 +526,13 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
     }
     {
         KernelTimer kt(ctx, TSP_KERNEL_SCAN_SYM, s);
-        hipLaunchKernelGGL(k_sym_row_scan, dim3(1), dim3(kRowScanThreads), 0, s, ntr, row_c_tiles, row_pairs, row_words,
-                           row_cand, P->c_tile_row_ptr, row_pair_ptr, ctx->d_scalars);
+        const int64_t blocks = ntr > 0 ? (ntr + kRowScanBlock - 1) / kRowScanBlock : 1;
+        unsigned epoch = 0;
+        ChainSlot *slots = static_cast<ChainSlot *>(chain_prepare(ctx, blocks, &epoch, s));
+        if (!slots) return cleanup(TSP_ERR_ALLOC_FAILED);
+        hipLaunchKernelGGL(k_sym_row_scan, dim3((unsigned)blocks), dim3(kRowScanThreads), 0, s, ntr, row_c_tiles,
+                           row_pairs, row_words, row_cand, P->c_tile_row_ptr, row_pair_ptr, slots, epoch,
+                           ctx->d_scalars);
         TSP_HIP_CHECK(ctx, hipGetLastError());
     }
     if (!rc) rc = read_scalars(ctx, s);                                    // ---- sync 1: sizes of the task list
@@ -564,6 +540,7 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
     const int64_t *h = ctx->h_scalars;
     if (h[S_INVALID]) return cleanup(TSP_ERR_NOT_CANONICAL);
     if (h[S_UNSUPPORTED]) return cleanup(TSP_ERR_UNSUPPORTED);
+    if (h[S_INTERNAL]) return cleanup(TSP_ERR_HIP);
     if (A->ntiles < 0) A->ntiles = h[A->scalar_slot];
     if (B->ntiles < 0) B->ntiles = h[B->scalar_slot];
     P->c_tiles = h[S_C_TILES];
