@@ -34,13 +34,14 @@ enum : int32_t { ROW_FAST = 0, ROW_MERGE = 1 };
 
 template <int G> struct ConvCfg;
 template <> struct ConvCfg<64> {                  // one wave per tile-row, four tile-rows per block
-    static constexpr int kWords = 768;            // bitmap words: tile columns may span 24576
-    static constexpr int kWindow = 64;            // tiles handled per pass over the entries
+    static constexpr int kWords = 512;            // bitmap words: tile columns may span 16384
+    static constexpr int kWindow = 32;            // tiles handled per pass over the entries
 };
 template <> struct ConvCfg<256> {                 // one block per tile-row
-    static constexpr int kWords = 4096;           // span of 131072 tile columns
-    static constexpr int kWindow = 512;
+    static constexpr int kWords = 1024;           // span of 32768 tile columns
+    static constexpr int kWindow = 128;
 };
+constexpr int kConvCache = 8;                     // entries per thread kept in registers between passes
 
 __device__ __forceinline__ uint16_t to_half_bits(uint16_t v) { return v; }
 __device__ __forceinline__ uint16_t to_half_bits(float v) { return __half_as_ushort(__float2half_rn(v)); }
@@ -127,14 +128,14 @@ __device__ __forceinline__ uint32_t group_exclusive_scan(uint32_t *arr, int n, i
 template <int G, bool FILL, typename RP, typename VT>
 __global__ __launch_bounds__(kConvThreads) void k_convert_rows(const ConvArgs<RP, VT> a) {
     constexpr int kWords = ConvCfg<G>::kWords, kWindow = ConvCfg<G>::kWindow, kGroups = kConvThreads / G;
-    __shared__ int64_t s_rp_all[kGroups][17];
+    __shared__ int s_rp_all[kGroups][20];
     __shared__ uint32_t s_bm_all[kGroups][kWords], s_pre_all[kGroups][kWords];
     __shared__ uint32_t s_mask_all[kGroups][kWindow * 8];
     __shared__ uint32_t s_lm_all[kGroups][kWindow], s_rm_all[kGroups][kWindow];
     __shared__ uint32_t s_lo_all[kGroups][kWindow], s_ro_all[kGroups][kWindow];
     __shared__ int s_red_all[kGroups][8];
     const int gi = threadIdx.x / G, gt = threadIdx.x % G;
-    int64_t *s_rp = s_rp_all[gi];
+    int *s_rp = s_rp_all[gi];
     uint32_t *s_bm = s_bm_all[gi], *s_pre = s_pre_all[gi], *s_mask = s_mask_all[gi];
     uint32_t *s_lm = s_lm_all[gi], *s_rm = s_rm_all[gi], *s_lo = s_lo_all[gi], *s_ro = s_ro_all[gi];
     int *s_red = s_red_all[gi];
@@ -142,35 +143,95 @@ __global__ __launch_bounds__(kConvThreads) void k_convert_rows(const ConvArgs<RP
     if (I >= a.tile_rows) return;                 // whole group (G = 256: whole block)
     bool bad = false;
 
-    // the 17 row pointers of the tile-row, clamped so that whatever they hold the entry ranges are
-    // disjoint stretches inside the arrays
-    if (gt == 0) {
-        int64_t prev = 0;
-        for (int k = 0; k <= 16; ++k) {
-            const int64_t row = min(I * T + k, a.rows);
-            const int64_t v = (int64_t)a.row_ptr[row];
-            const int64_t lo = k == 0 ? 0 : prev;
-            bad |= v < lo || v > a.nnz || (row == 0 && v != 0) || (row == a.rows && v != a.nnz);
-            prev = min(max(v, lo), a.nnz);
-            s_rp[k] = prev;
+    // what the packing pass needs from the prefix sums: requested before anything else
+    int64_t t0 = 0;
+    uint32_t lrun = 0, rrun = 0, lend = 0, rend = 0;
+    int row_class = ROW_FAST;
+    if (FILL) {
+        t0 = a.tile_row_ptr[I];
+        lrun = a.row_lbase[I];
+        rrun = a.row_rbase[I];
+        lend = a.row_lbase[I + 1];
+        rend = a.row_rbase[I + 1];
+        row_class = a.row_class[I];
+    }
+    // The 17 row pointers of the tile-row, one per lane, clamped into [0, nnz] and made non-decreasing
+    // (a running maximum) so that whatever they hold the entry ranges are disjoint stretches inside the
+    // arrays; nnz < 2^31, so the clamped values fit 32 bits.
+    if (gt < 64) {
+        const int64_t row = min(I * T + min(gt, 16), a.rows);
+        const int64_t raw = (int64_t)a.row_ptr[row];
+        int v = (int)min(max(raw, (int64_t)0), a.nnz);
+        // inclusive running maximum over the lanes
+        v = max(v, TSP_DPP(v, v, 0x111, 0xf, false));
+        v = max(v, TSP_DPP(v, v, 0x112, 0xf, false));
+        v = max(v, TSP_DPP(v, v, 0x114, 0xf, false));
+        v = max(v, TSP_DPP(v, v, 0x118, 0xf, false));
+        v = max(v, TSP_DPP(v, v, 0x142, 0xa, false));
+        if (gt <= 16) {
+            s_rp[gt] = v;
+            bad = raw != (int64_t)v || (row == 0 && raw != 0) || (row == a.rows && raw != a.nnz);
         }
     }
     group_sync<G>();
     const int64_t e0 = s_rp[0], e1 = s_rp[16];
-    if (FILL && a.row_class[I] != ROW_FAST) return;
+    if (FILL && row_class != ROW_FAST) return;
     if (e0 == e1) {
-        if (!FILL && gt == 0) {
-            a.row_tiles[I] = 0;
-            a.row_lgroups[I] = 0;
-            a.row_rgroups[I] = 0;
-            a.row_class[I] = ROW_FAST;
-            if (bad && a.validate) a.d_scalars[S_INVALID] = 1;
+        if (!FILL) {
+            const bool any_bad = group_max<G>(bad ? 1 : 0, s_red) != 0;
+            if (gt == 0) {
+                a.row_tiles[I] = 0;
+                a.row_lgroups[I] = 0;
+                a.row_rgroups[I] = 0;
+                a.row_class[I] = ROW_FAST;
+                if (any_bad && a.validate) a.d_scalars[S_INVALID] = 1;
+            }
         }
         return;
     }
-    // span of tile columns: first and last entry of every non-empty row
+    if (FILL) {
+        // zero the tile-row's groups now; the entries drop their values into their slots at the end, by
+        // which time these stores have long been acknowledged
+        const uint4 zero = make_uint4(0, 0, 0, 0);
+        if (a.forms & TSP_FORM_LEFT)
+            for (int64_t g = (int64_t)lrun + gt, end = min((int64_t)lend, a.group_capacity); g < end; g += G)
+                a.ldata[g] = zero;
+        if (a.forms & TSP_FORM_RIGHT)
+            for (int64_t g = (int64_t)rrun + gt, end = min((int64_t)rend, a.group_capacity); g < end; g += G)
+                a.rdata[g] = zero;
+    }
+    auto row_of = [&](int64_t e) {
+        const int x = (int)e;
+        int r = x >= s_rp[8] ? 8 : 0;
+        r += x >= s_rp[r + 4] ? 4 : 0;
+        r += x >= s_rp[r + 2] ? 2 : 0;
+        r += x >= s_rp[r + 1] ? 1 : 0;
+        return r;
+    };
+
+    // Tile-rows of up to G*kConvCache entries keep their column indices (and, when packing, values) in
+    // registers: all loads are requested at once and the later passes do not touch memory again.
+    const bool cached = e1 - e0 <= (int64_t)G * kConvCache;
+    int c_reg[kConvCache], p_reg[kConvCache];
+    VT v_reg[kConvCache];
     int jmin = INT_MAX, jmax = -1;
-    if (gt < 16) {
+    if (cached) {
+#pragma unroll
+        for (int k = 0; k < kConvCache; ++k) {
+            const int64_t e = e0 + gt + (int64_t)k * G;
+            c_reg[k] = e < e1 ? a.col[e] : 0;
+            if (FILL) v_reg[k] = e < e1 ? a.val[e] : VT(0);
+            if (!FILL) p_reg[k] = e < e1 && e > e0 ? a.col[e - 1] : -1;      // left neighbour, for the order check
+        }
+#pragma unroll
+        for (int k = 0; k < kConvCache; ++k) {
+            const int64_t e = e0 + gt + (int64_t)k * G;
+            if (e < e1) {
+                jmin = min(jmin, c_reg[k] >> 4);
+                jmax = max(jmax, c_reg[k] >> 4);
+            }
+        }
+    } else if (gt < 16) {                         // first and last entry of every non-empty row
         const int64_t p = s_rp[gt], e = s_rp[gt + 1];
         if (p < e) {
             jmin = a.col[p] >> 4;
@@ -182,36 +243,44 @@ __global__ __launch_bounds__(kConvThreads) void k_convert_rows(const ConvArgs<RP
     const int64_t span = (int64_t)jmax - jmin + 1;
     const int words = (int)((span + 31) >> 5);
     if (jmin < 0 || span <= 0 || words > kWords) {
-        if (!FILL && gt == 0) {                   // the merge path takes this tile-row (and validates it)
-            // (a span that cannot occur in a matrix of this width means the indices are out of range)
-            if (a.validate && (bad || jmin < 0 || jmax >= (a.cols + T - 1) / T)) a.d_scalars[S_INVALID] = 1;
-            a.row_tiles[I] = 0;
-            a.row_lgroups[I] = 0;
-            a.row_rgroups[I] = 0;
-            a.row_class[I] = ROW_MERGE;
+        if (!FILL) {                              // the merge path takes this tile-row (and validates it)
+            const bool any_bad = group_max<G>(bad ? 1 : 0, s_red) != 0;
+            if (gt == 0) {
+                // (a span that cannot occur in a matrix of this width means the indices are out of range)
+                if (a.validate && (any_bad || jmin < 0 || jmax >= (a.cols + T - 1) / T)) a.d_scalars[S_INVALID] = 1;
+                a.row_tiles[I] = 0;
+                a.row_lgroups[I] = 0;
+                a.row_rgroups[I] = 0;
+                a.row_class[I] = ROW_MERGE;
+            }
         }
         return;
     }
-    auto row_of = [&](int64_t e) {
-        int r = e >= s_rp[8] ? 8 : 0;
-        r += e >= s_rp[r + 4] ? 4 : 0;
-        r += e >= s_rp[r + 2] ? 2 : 0;
-        r += e >= s_rp[r + 1] ? 1 : 0;
-        return r;
+    // f(e, column, value, column of the entry before e) for every entry this thread owns
+    auto for_each_entry = [&](auto f) {
+        if (cached) {
+#pragma unroll
+            for (int k = 0; k < kConvCache; ++k) {
+                const int64_t e = e0 + gt + (int64_t)k * G;
+                if (e < e1) f(e, c_reg[k], v_reg[k], p_reg[k]);
+            }
+        } else {
+            for (int64_t e = e0 + gt; e < e1; e += G)
+                f(e, a.col[e], FILL ? a.val[e] : VT(0), !FILL && e > e0 ? a.col[e - 1] : -1);
+        }
     };
 
     // 1. tile columns -> bitmap
     for (int w = gt; w < words; w += G) s_bm[w] = 0;
     group_sync<G>();
-    for (int64_t e = e0 + gt; e < e1; e += G) {
-        const int c = a.col[e];
+    for_each_entry([&](int64_t e, int c, VT, int before) {
         const uint32_t j = (uint32_t)((c >> 4) - jmin);
         if (j < (uint32_t)span) atomicOr(&s_bm[j >> 5], 1u << (j & 31));
         if (!FILL && a.validate) {
             bad |= c < 0 || c >= a.cols || j >= (uint32_t)span;
-            if (e > s_rp[row_of(e)]) bad |= c <= a.col[e - 1];
+            if (e > s_rp[row_of(e)]) bad |= c <= before;
         }
-    }
+    });
     group_sync<G>();
     for (int w = gt; w < words; w += G) s_pre[w] = __popc(s_bm[w]);
     group_sync<G>();
@@ -222,13 +291,8 @@ __global__ __launch_bounds__(kConvThreads) void k_convert_rows(const ConvArgs<RP
         return (int)s_pre[j >> 5] + __popc(s_bm[j >> 5] & ((1u << (j & 31)) - 1u));
     };
 
-    int64_t t0 = 0;
-    uint32_t lrun = 0, rrun = 0;
     uint16_t *const l16 = reinterpret_cast<uint16_t *>(a.ldata), *const r16 = reinterpret_cast<uint16_t *>(a.rdata);
     if (FILL) {
-        t0 = a.tile_row_ptr[I];
-        lrun = a.row_lbase[I];
-        rrun = a.row_rbase[I];
         // tile columns, ascending
         for (int w = gt; w < words; w += G) {
             uint32_t bits = s_bm[w];
@@ -240,15 +304,6 @@ __global__ __launch_bounds__(kConvThreads) void k_convert_rows(const ConvArgs<RP
                 ++t;
             }
         }
-        // zero the tile-row's groups; the entries then drop their values into their slots
-        const uint4 zero = make_uint4(0, 0, 0, 0);
-        if (a.forms & TSP_FORM_LEFT)
-            for (int64_t g = (int64_t)lrun + gt, end = min((int64_t)a.row_lbase[I + 1], a.group_capacity); g < end; g += G)
-                a.ldata[g] = zero;
-        if (a.forms & TSP_FORM_RIGHT)
-            for (int64_t g = (int64_t)rrun + gt, end = min((int64_t)a.row_rbase[I + 1], a.group_capacity); g < end; g += G)
-                a.rdata[g] = zero;
-        __builtin_amdgcn_s_waitcnt(0x0F70);       // vmcnt(0): the zeros are in L2 before any value is stored
     }
     uint32_t lcount = 0, rcount = 0;
     for (int win0 = 0; win0 < ntiles; win0 += kWindow) {
@@ -256,14 +311,13 @@ __global__ __launch_bounds__(kConvThreads) void k_convert_rows(const ConvArgs<RP
         // 2. row masks of the tiles of this window
         for (int k = gt; k < nw * 8; k += G) s_mask[k] = 0;
         group_sync<G>();
-        for (int64_t e = e0 + gt; e < e1; e += G) {
-            const int c = a.col[e];
+        for_each_entry([&](int64_t e, int c, VT, int) {
             const int t = tile_rank(c) - win0;
             if (t >= 0 && t < nw) {
                 const int r = row_of(e);
                 atomicOr(&s_mask[t * 8 + (r >> 1)], 1u << ((r & 1) * 16 + (c & 15)));
             }
-        }
+        });
         group_sync<G>();
         for (int t = gt; t < nw; t += G) {
             uint32_t lm = 0, rm = 0;
@@ -286,6 +340,9 @@ __global__ __launch_bounds__(kConvThreads) void k_convert_rows(const ConvArgs<RP
         }
         group_sync<G>();
         if (FILL) {
+            // the zeros stored at the start must be in L2 before any value is stored over them: every
+            // wave waits for its own stores here, ahead of the barriers inside the scans below
+            __builtin_amdgcn_s_waitcnt(0x0F70);
             const uint32_t ltot = group_exclusive_scan<G>(s_lo, nw, s_red);
             const uint32_t rtot = group_exclusive_scan<G>(s_ro, nw, s_red);
             // tile headers and bitmaps
@@ -302,12 +359,11 @@ __global__ __launch_bounds__(kConvThreads) void k_convert_rows(const ConvArgs<RP
                 }
             }
             // 3. values
-            for (int64_t e = e0 + gt; e < e1; e += G) {
-                const int c = a.col[e];
+            for_each_entry([&](int64_t e, int c, VT value, int) {
                 const int t = tile_rank(c) - win0;
                 if (t >= 0 && t < nw) {
                     const int r = row_of(e), cc = c & 15;
-                    const uint16_t v = to_half_bits(a.val[e]);
+                    const uint16_t v = to_half_bits(value);
                     if (a.forms & TSP_FORM_LEFT) {
                         const int g = (cc >> 3) * 16 + r;
                         const int64_t idx = (int64_t)lrun + s_lo[t] + __popc(s_lm[t] & ((1u << g) - 1u));
@@ -319,7 +375,7 @@ __global__ __launch_bounds__(kConvThreads) void k_convert_rows(const ConvArgs<RP
                         if (idx < a.group_capacity) r16[idx * 8 + (r & 7)] = v;
                     }
                 }
-            }
+            });
             lrun += ltot;
             rrun += rtot;
             group_sync<G>();
@@ -535,6 +591,7 @@ static int launch_convert(tsp_context *ctx, const tsp_csr *A, tsp_tiles_s *t, in
     // span more tile columns than the bitmap of the chosen kernel holds
     const bool wide_groups = ntr > 0 && A->nnz / ntr > 1024;
     const int64_t bitmap_span = 32ll * (wide_groups ? ConvCfg<256>::kWords : ConvCfg<64>::kWords);
+    // (tile-rows of a narrow matrix cannot exceed the bitmap, and then the merge kernels are not launched)
     const bool may_merge = t->tile_cols > bitmap_span;
     const unsigned grid_fast = (unsigned)(wide_groups ? ntr : (ntr + 3) / 4);
     const unsigned grid_merge = (unsigned)((ntr + kMergeGroupsPerBlock - 1) / kMergeGroupsPerBlock);

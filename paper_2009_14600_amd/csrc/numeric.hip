@@ -16,11 +16,13 @@
 //
 // The paper notes that this kernel is bound by the scattered tile reads behind the task list
 // (Section 6.2).  The chain task-list entry -> tile header -> tile elements is three dependent
-// memory accesses, so a wave takes a run of consecutive output tiles and software-pipelines them:
-// while tile c is multiplied, the tile headers of c+1 and the task-list entries of c+2 are in flight.  A
-// segment's entries are read 64 at a time, one per lane, and handed to the two half-waves with
-// cross-lane reads.  All gathers go through buffer descriptors whose range check returns zeros
-// for masked-off lanes (no branches, no zero-filled registers).  Workgroup ids are remapped so
+// memory accesses, so a wave takes a run of eight consecutive output tiles, whose task-list
+// segments are contiguous, and reads 64 entries and their tile headers at once, one per lane: the
+// first two accesses are paid once per run, not per tile.  The entries are handed to the two
+// half-waves with cross-lane reads.  The loop over the eight tiles is fully unrolled, each tile
+// requests only the operands it has entries for, and a tile is written out after the next tile's
+// loads have been requested.  All gathers go through buffer descriptors whose range check returns
+// zeros for masked-off lanes (no branches, no zero-filled registers).  Workgroup ids are remapped so
 // that consecutive runs of output tiles execute on the same XCD and share its L2.
 //
 // Emission: the counting pass left, per C tile, the 16 row masks of its structural pattern and
@@ -81,6 +83,14 @@ struct NumericSizes {
     uint64_t pairs, a_tiles, b_tiles, a_groups, b_groups;   // element counts of the arrays
 };
 
+// What a lane needs to emit its four accumulator values of one output tile.
+struct Emission {
+    uint2 cm2;            // row masks of rows 4*ig .. 4*ig+3 (16 bits each)
+    uint4 coff4;          // entries of those CSR rows to the left of the tile
+    longlong2 rb01, rb23; // starts of those CSR rows
+    int32_t col;          // column of this lane inside C
+};
+
 template <class Array>
 __global__ __launch_bounds__(kNumThreads) void k_numeric(
     const int64_t c_tiles, const NumericSizes z, const int64_t *__restrict__ pair_off,
@@ -97,7 +107,7 @@ __global__ __launch_bounds__(kNumThreads) void k_numeric(
     const int64_t wave = (int64_t)logical * (kNumThreads / 64) + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t c_begin = wave * kTilesPerWave;
     if (c_begin >= c_tiles) return;
-    const int64_t c_end = min(c_begin + kTilesPerWave, c_tiles);
+    const int n_tiles = (int)min((int64_t)kTilesPerWave, c_tiles - c_begin);
     const int lane = threadIdx.x & 63;
     const int hl = lane & 31, upper = lane >> 5;
     const uint32_t bit = 1u << hl, below = bit - 1u;
@@ -107,97 +117,107 @@ __global__ __launch_bounds__(kNumThreads) void k_numeric(
     const Array b_rmask(b_rmask_, z.b_tiles * 4), b_roff(b_roff_, z.b_tiles * 4);
     const Array a_ldata(a_ldata_, z.a_groups * 16), b_rdata(b_rdata_, z.b_groups * 16);
 
-    // one task-list entry per lane: 64 entries from position s0 of the segment [.., s1)
-    struct Entries {
-        uint32_t a, b;
-        bool valid;
+    // segment bounds of the wave's tiles, relative to the first one (one vector load, then scalars)
+    const int64_t off_lane = pair_off[c_begin + min(lane, n_tiles)];
+    const int64_t base = ((int64_t)__builtin_amdgcn_readlane((int)(off_lane >> 32), 0) << 32) |
+                         (uint32_t)__builtin_amdgcn_readlane((int)off_lane, 0);
+    const int rel_lane = (int)(off_lane - base);
+    const int rel_end = __builtin_amdgcn_readlane(rel_lane, 8);        // lanes >= n_tiles hold the end
+
+    // 64 consecutive task-list entries starting at relative position `start`, one per lane, with the
+    // headers of their tiles; lanes past the end of the wave's entries hold all-zero headers
+    auto load_headers = [&](int start) {
+        const bool valid = start + lane < rel_end;
+        const uint32_t e = (uint32_t)(base + start + lane);
+        const uint32_t a = pair_a.u32(e, valid), b = pair_b.u32(e, valid);
+        return Header{a_lmask.u32(a, valid), a_loff.u32(a, valid), b_rmask.u32(b, valid), b_roff.u32(b, valid)};
     };
-    auto load_entries = [&](int64_t s0, int64_t s1) {
-        const bool valid = s0 + lane < s1;
-        const uint32_t e = (uint32_t)(s0 + lane);
-        return Entries{pair_a.u32(e, valid), pair_b.u32(e, valid), valid};
-    };
-    auto load_headers = [&](const Entries &e) {
-        return Header{a_lmask.u32(e.a, e.valid), a_loff.u32(e.a, e.valid), b_rmask.u32(e.b, e.valid),
-                      b_roff.u32(e.b, e.valid)};
-    };
-    // operands of entry `src` (index into the 64 entries the lanes hold) for this lane, or zeros:
-    // lanes past the end of the segment hold all-zero headers
-    auto load_operands = [&](const Header &h, int src, Group &av, Group &bv) {
+    // operands of the entry held by lane `src` for this lane, or zeros when the entry is not part of
+    // the current segment (valid == false) or the group is empty
+    auto load_operands = [&](const Header &h, int src, bool valid, Group &av, Group &bv) {
         const uint32_t lm = (uint32_t)__shfl((int)h.lm, src, 64), lo = (uint32_t)__shfl((int)h.lo, src, 64);
         const uint32_t rm = (uint32_t)__shfl((int)h.rm, src, 64), ro = (uint32_t)__shfl((int)h.ro, src, 64);
-        av.u = a_ldata.group(lo + __popc(lm & below), (lm & bit) != 0);
-        bv.u = b_rdata.group(ro + __popc(rm & below), (rm & bit) != 0);
+        av.u = a_ldata.group(lo + __popc(lm & below), valid && (lm & bit) != 0);
+        bv.u = b_rdata.group(ro + __popc(rm & below), valid && (rm & bit) != 0);
     };
-
-    // pipeline registers: headers of tile c, entries of tile c+1; entries of c+2 are requested first
-    // in every step so that the three dependent accesses of consecutive tiles overlap
-    int64_t s0_cur = pair_off[c_begin], s1_cur = pair_off[c_begin + 1];
-    int64_t s1_nxt = c_begin + 1 < c_end ? pair_off[c_begin + 2] : s1_cur;
-    Header h_cur;
-    Entries e_nxt;
-    {
-        const Entries e_cur = load_entries(s0_cur, s1_cur);
-        e_nxt = load_entries(s1_cur, s1_nxt);
-        h_cur = load_headers(e_cur);
-    }
-    for (int64_t c = c_begin; c < c_end; ++c) {
-        const int64_t s1_far = c + 2 < c_end ? pair_off[c + 3] : s1_nxt;
-        const Entries e_far = load_entries(s1_nxt, s1_far);
-        const Header h_nxt = load_headers(e_nxt);
-        // what the emission needs, requested before the multiplication: row masks (4 x 16 bit), the
-        // rows' entry counts left of the tile (4 x 32 bit) and the rows' starts (4 x 64 bit; the plan
-        // pads row_ptr to whole tile-rows, so rows past the matrix edge read valid memory)
-        const int64_t I = c_tile_row[c], J = c_tile_col[c];
-        const uint2 cm2 = *reinterpret_cast<const uint2 *>(c_row_mask + c * T + 4 * ig);
-        const uint4 coff4 = *reinterpret_cast<const uint4 *>(c_row_off + c * T + 4 * ig);
-        const longlong2 rb01 = *reinterpret_cast<const longlong2 *>(c_row_ptr + I * T + 4 * ig);
-        const longlong2 rb23 = *reinterpret_cast<const longlong2 *>(c_row_ptr + I * T + 4 * ig + 2);
-        float4v acc = {0.f, 0.f, 0.f, 0.f};
-        const int count = (int)min(s1_cur - s0_cur, (int64_t)64);
-        for (int it = 0; it < count; it += 8) {
-            Group a0, b0, a1, b1, a2, b2, a3, b3;
-            // the cross-lane reads stay in range through & 63; lanes past count hold zero headers
-            load_operands(h_cur, (it + upper) & 63, a0, b0);
-            load_operands(h_cur, (it + 2 + upper) & 63, a1, b1);
-            load_operands(h_cur, (it + 4 + upper) & 63, a2, b2);
-            load_operands(h_cur, (it + 6 + upper) & 63, a3, b3);
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a0.h, b0.h, acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1.h, b1.h, acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a2.h, b2.h, acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a3.h, b3.h, acc, 0, 0, 0);
-        }
-        // segments longer than 64 entries: the rest, 64 at a time, without the cross-tile pipeline
-        for (int64_t s = s0_cur + 64; s < s1_cur; s += 64) {
-            const Header h = load_headers(load_entries(s, s1_cur));
-            const int cnt = (int)min(s1_cur - s, (int64_t)64);
-            for (int it = 0; it < cnt; it += 4) {
-                Group a0, b0, a1, b1;
-                load_operands(h, (it + upper) & 63, a0, b0);
-                load_operands(h, (it + 2 + upper) & 63, a1, b1);
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a0.h, b0.h, acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1.h, b1.h, acc, 0, 0, 0);
-            }
-        }
-        // emission
-        const uint32_t cm[4] = {cm2.x & 0xFFFFu, cm2.x >> 16, cm2.y & 0xFFFFu, cm2.y >> 16};
-        const uint32_t coff[4] = {coff4.x, coff4.y, coff4.z, coff4.w};
-        const int64_t rbase[4] = {rb01.x, rb01.y, rb23.x, rb23.y};
-        const int32_t col = (int32_t)(J * T + j);
+    auto emit = [&](const Emission &em, const float4v &acc) {
+        const uint32_t cm[4] = {em.cm2.x & 0xFFFFu, em.cm2.x >> 16, em.cm2.y & 0xFFFFu, em.cm2.y >> 16};
+        const uint32_t coff[4] = {em.coff4.x, em.coff4.y, em.coff4.z, em.coff4.w};
+        const int64_t rbase[4] = {em.rb01.x, em.rb01.y, em.rb23.x, em.rb23.y};
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
             if ((cm[v] >> j) & 1u) {
                 const int64_t pos = rbase[v] + (int64_t)(coff[v] + __popc(cm[v] & ((1u << j) - 1u)));
-                c_col[pos] = col;
+                c_col[pos] = em.col;
                 c_val[pos] = acc[v];
             }
         }
-        s0_cur = s1_cur;
-        s1_cur = s1_nxt;
-        s1_nxt = s1_far;
-        h_cur = h_nxt;
-        e_nxt = e_far;
+    };
+    // multiply the `count` entries that start at lane `o` of the headers h into acc, two entries per
+    // MFMA; the loads of up to four MFMAs are requested together, `between` runs once after the first
+    // batch of loads has been requested
+    auto multiply = [&](const Header &h, int o, int count, float4v &acc, auto between) {
+        bool first = true;
+        for (int it = 0; it < count; it += 8) {
+            Group a0, b0, a1, b1, a2, b2, a3, b3;
+            const int left = count - it;                                // > 0, uniform
+            load_operands(h, (o + it + upper) & 63, upper < left, a0, b0);
+            if (left > 2) load_operands(h, (o + it + 2 + upper) & 63, 2 + upper < left, a1, b1);
+            if (left > 4) load_operands(h, (o + it + 4 + upper) & 63, 4 + upper < left, a2, b2);
+            if (left > 6) load_operands(h, (o + it + 6 + upper) & 63, 6 + upper < left, a3, b3);
+            if (first) between();
+            first = false;
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a0.h, b0.h, acc, 0, 0, 0);
+            if (left > 2) acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1.h, b1.h, acc, 0, 0, 0);
+            if (left > 4) acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a2.h, b2.h, acc, 0, 0, 0);
+            if (left > 6) acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a3.h, b3.h, acc, 0, 0, 0);
+        }
+        if (first) between();
+    };
+
+    int h_start = 0;                              // relative position of the entry lane 0 of `heads` holds
+    Header heads = load_headers(0);
+    Emission em_prev{};
+    float4v acc_prev = {0.f, 0.f, 0.f, 0.f};
+    bool have_prev = false;
+#pragma unroll
+    for (int t = 0; t < kTilesPerWave; ++t) {
+        if (t < n_tiles) {                        // uniform
+            const int64_t c = c_begin + t;
+            const int r0 = __builtin_amdgcn_readlane(rel_lane, t), r1 = __builtin_amdgcn_readlane(rel_lane, t + 1);
+            const int n = r1 - r0, first_part = min(n, 64);
+            // what the emission needs, requested before the multiplication: row masks (4 x 16 bit), the
+            // rows' entry counts left of the tile (4 x 32 bit) and the rows' starts (4 x 64 bit; the plan
+            // pads row_ptr to whole tile-rows, so rows past the matrix edge read valid memory)
+            const int64_t I = c_tile_row[c], J = c_tile_col[c];
+            Emission em;
+            em.cm2 = *reinterpret_cast<const uint2 *>(c_row_mask + c * T + 4 * ig);
+            em.coff4 = *reinterpret_cast<const uint4 *>(c_row_off + c * T + 4 * ig);
+            em.rb01 = *reinterpret_cast<const longlong2 *>(c_row_ptr + I * T + 4 * ig);
+            em.rb23 = *reinterpret_cast<const longlong2 *>(c_row_ptr + I * T + 4 * ig + 2);
+            em.col = (int32_t)(J * T + j);
+            // the 64 entries in `heads` must cover the first 64 entries of this segment
+            if (r0 < h_start || r0 + first_part > h_start + 64) {
+                h_start = r0;
+                heads = load_headers(h_start);
+            }
+            float4v acc = {0.f, 0.f, 0.f, 0.f};
+            // the previous tile is written out after this tile's loads are on their way, so that no
+            // wait for a load ever includes the acknowledgement of a store
+            multiply(heads, r0 - h_start, first_part, acc, [&]() {
+                if (have_prev) emit(em_prev, acc_prev);
+            });
+            // segments longer than 64 entries: the rest, 64 at a time
+            for (int s = r0 + 64; s < r1; s += 64) {
+                const Header h = load_headers(s);
+                multiply(h, 0, min(r1 - s, 64), acc, []() {});
+            }
+            em_prev = em;
+            acc_prev = acc;
+            have_prev = true;
+        }
     }
+    if (have_prev) emit(em_prev, acc_prev);
 }
 
 int numeric_enqueue(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s *P, tsp_csr *C, hipStream_t s) {
