@@ -16,10 +16,10 @@
 //
 // The paper notes that this kernel is bound by the scattered tile reads behind the task list
 // (Section 6.2).  The chain task-list entry -> tile header -> tile elements is three dependent
-// memory accesses, so a wave takes a run of eight consecutive output tiles, whose task-list
+// memory accesses, so a wave takes a run of four or eight consecutive output tiles, whose task-list
 // segments are contiguous, and reads 64 entries and their tile headers at once, one per lane: the
 // first two accesses are paid once per run, not per tile.  The entries are handed to the two
-// half-waves with cross-lane reads.  The loop over the eight tiles is fully unrolled, each tile
+// half-waves with cross-lane reads.  The loop over the run's tiles is fully unrolled, each tile
 // requests only the operands it has entries for, and a tile is written out after the next tile's
 // loads have been requested.  All gathers go through buffer descriptors whose range check returns
 // zeros for masked-off lanes (no branches, no zero-filled registers).  Workgroup ids are remapped so
@@ -43,7 +43,7 @@ union Group {
 };
 
 constexpr int kNumThreads = 256;       // 4 waves per block
-constexpr int kTilesPerWave = 8;       // consecutive output tiles one wave pipelines through
+constexpr int kMaxTilesPerWave = 8;    // consecutive output tiles one wave walks: 4 or 8
 constexpr int kXcds = 8;
 
 struct Header {          // tile headers of one task-list entry, held by the lane that read the entry
@@ -91,9 +91,9 @@ struct Emission {
     int32_t col;          // column of this lane inside C
 };
 
-template <class Array>
+template <class Array, int kTilesPerWave>
 __global__ __launch_bounds__(kNumThreads) void k_numeric(
-    const int64_t c_tiles, const NumericSizes z, const int64_t *__restrict__ pair_off,
+    const int64_t c_tiles, const int tiles_per_wave, const NumericSizes z, const int64_t *__restrict__ pair_off,
     const int32_t *__restrict__ pair_a_, const int32_t *__restrict__ pair_b_, const uint32_t *__restrict__ a_lmask_,
     const uint32_t *__restrict__ a_loff_, const uint4 *__restrict__ a_ldata_, const uint32_t *__restrict__ b_rmask_,
     const uint32_t *__restrict__ b_roff_, const uint4 *__restrict__ b_rdata_, const int32_t *__restrict__ c_tile_row,
@@ -105,9 +105,9 @@ __global__ __launch_bounds__(kNumThreads) void k_numeric(
     const int logical = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
     // wave-uniform values are kept in scalar registers; their loads become scalar loads
     const int64_t wave = (int64_t)logical * (kNumThreads / 64) + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int64_t c_begin = wave * kTilesPerWave;
-    if (c_begin >= c_tiles) return;
-    const int n_tiles = (int)min((int64_t)kTilesPerWave, c_tiles - c_begin);
+    const int64_t run_begin = wave * tiles_per_wave;
+    if (run_begin >= c_tiles) return;
+    const int64_t run_end = min(run_begin + tiles_per_wave, c_tiles);
     const int lane = threadIdx.x & 63;
     const int hl = lane & 31, upper = lane >> 5;
     const uint32_t bit = 1u << hl, below = bit - 1u;
@@ -117,12 +117,31 @@ __global__ __launch_bounds__(kNumThreads) void k_numeric(
     const Array b_rmask(b_rmask_, z.b_tiles * 4), b_roff(b_roff_, z.b_tiles * 4);
     const Array a_ldata(a_ldata_, z.a_groups * 16), b_rdata(b_rdata_, z.b_groups * 16);
 
-    // segment bounds of the wave's tiles, relative to the first one (one vector load, then scalars)
+    auto emit = [&](const Emission &em, const float4v &acc) {
+        const uint32_t cm[4] = {em.cm2.x & 0xFFFFu, em.cm2.x >> 16, em.cm2.y & 0xFFFFu, em.cm2.y >> 16};
+        const uint32_t coff[4] = {em.coff4.x, em.coff4.y, em.coff4.z, em.coff4.w};
+        const int64_t rbase[4] = {em.rb01.x, em.rb01.y, em.rb23.x, em.rb23.y};
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            if ((cm[v] >> j) & 1u) {
+                const int64_t pos = rbase[v] + (int64_t)(coff[v] + __popc(cm[v] & ((1u << j) - 1u)));
+                c_col[pos] = em.col;
+                c_val[pos] = acc[v];
+            }
+        }
+    };
+    Emission em_prev{};
+    float4v acc_prev = {0.f, 0.f, 0.f, 0.f};
+    bool have_prev = false;
+  // the run is walked in groups of kTilesPerWave tiles
+  for (int64_t c_begin = run_begin; c_begin < run_end; c_begin += kTilesPerWave) {
+    const int n_tiles = (int)min((int64_t)kTilesPerWave, run_end - c_begin);
+    // segment bounds of the group's tiles, relative to the first one (one vector load, then scalars)
     const int64_t off_lane = pair_off[c_begin + min(lane, n_tiles)];
     const int64_t base = ((int64_t)__builtin_amdgcn_readlane((int)(off_lane >> 32), 0) << 32) |
                          (uint32_t)__builtin_amdgcn_readlane((int)off_lane, 0);
     const int rel_lane = (int)(off_lane - base);
-    const int rel_end = __builtin_amdgcn_readlane(rel_lane, 8);        // lanes >= n_tiles hold the end
+    const int rel_end = __builtin_amdgcn_readlane(rel_lane, kTilesPerWave);        // lanes >= n_tiles hold the end
 
     // 64 consecutive task-list entries starting at relative position `start`, one per lane, with the
     // headers of their tiles; lanes past the end of the wave's entries hold all-zero headers
@@ -139,19 +158,6 @@ __global__ __launch_bounds__(kNumThreads) void k_numeric(
         const uint32_t rm = (uint32_t)__shfl((int)h.rm, src, 64), ro = (uint32_t)__shfl((int)h.ro, src, 64);
         av.u = a_ldata.group(lo + __popc(lm & below), valid && (lm & bit) != 0);
         bv.u = b_rdata.group(ro + __popc(rm & below), valid && (rm & bit) != 0);
-    };
-    auto emit = [&](const Emission &em, const float4v &acc) {
-        const uint32_t cm[4] = {em.cm2.x & 0xFFFFu, em.cm2.x >> 16, em.cm2.y & 0xFFFFu, em.cm2.y >> 16};
-        const uint32_t coff[4] = {em.coff4.x, em.coff4.y, em.coff4.z, em.coff4.w};
-        const int64_t rbase[4] = {em.rb01.x, em.rb01.y, em.rb23.x, em.rb23.y};
-#pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            if ((cm[v] >> j) & 1u) {
-                const int64_t pos = rbase[v] + (int64_t)(coff[v] + __popc(cm[v] & ((1u << j) - 1u)));
-                c_col[pos] = em.col;
-                c_val[pos] = acc[v];
-            }
-        }
     };
     // multiply the `count` entries that start at lane `o` of the headers h into acc, two entries per
     // MFMA; the loads of up to four MFMAs are requested together, `between` runs once after the first
@@ -177,9 +183,6 @@ __global__ __launch_bounds__(kNumThreads) void k_numeric(
 
     int h_start = 0;                              // relative position of the entry lane 0 of `heads` holds
     Header heads = load_headers(0);
-    Emission em_prev{};
-    float4v acc_prev = {0.f, 0.f, 0.f, 0.f};
-    bool have_prev = false;
 #pragma unroll
     for (int t = 0; t < kTilesPerWave; ++t) {
         if (t < n_tiles) {                        // uniform
@@ -217,6 +220,7 @@ __global__ __launch_bounds__(kNumThreads) void k_numeric(
             have_prev = true;
         }
     }
+  }
     if (have_prev) emit(em_prev, acc_prev);
 }
 
@@ -238,7 +242,11 @@ int numeric_enqueue(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s
                                   hipMemcpyDeviceToDevice, s);
     if (e == hipSuccess && P->c_tiles > 0) {
         KernelTimer kt(ctx, TSP_KERNEL_NUMERIC, s);
-        const int64_t tiles_per_block = (int64_t)(kNumThreads / 64) * kTilesPerWave;
+        // Tiles one wave walks.  Short runs keep the tiles in flight on an XCD close together, so that
+        // the B tiles they share stay in that XCD's L2; long runs amortise the header gather when the
+        // segments are short (measured on the stencil and Laplacian workloads).
+        const int tiles_per_wave = P->pairs > 4 * P->c_tiles ? 4 : 8;
+        const int64_t tiles_per_block = (int64_t)(kNumThreads / 64) * tiles_per_wave;
         int64_t blocks = (P->c_tiles + tiles_per_block - 1) / tiles_per_block;
         blocks = (blocks + kXcds - 1) / kXcds * kXcds;             // the XCD remap needs a multiple of 8
         const NumericSizes z{(uint64_t)P->pairs, (uint64_t)A->tile_capacity, (uint64_t)B->tile_capacity,
@@ -246,8 +254,9 @@ int numeric_enqueue(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s
         const uint64_t limit = (1ull << 32) - 64;
         const bool narrow = z.pairs * 4 < limit && z.a_groups * 16 < limit && z.b_groups * 16 < limit &&
                             z.a_tiles * 4 < limit && z.b_tiles * 4 < limit && !ctx->force_wide;
-        auto kernel = narrow ? k_numeric<BufferArray> : k_numeric<PointerArray>;
-        hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(kNumThreads), 0, s, P->c_tiles, z, P->pair_off,
+        auto kernel = narrow ? (tiles_per_wave == 4 ? k_numeric<BufferArray, 4> : k_numeric<BufferArray, 8>)
+                             : (tiles_per_wave == 4 ? k_numeric<PointerArray, 4> : k_numeric<PointerArray, 8>);
+        hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(kNumThreads), 0, s, P->c_tiles, tiles_per_wave, z, P->pair_off,
                            P->pair_a, P->pair_b, A->lmask, A->loff, A->ldata, B->rmask, B->roff, B->rdata,
                            P->c_tile_row, P->c_tile_col, P->c_row_mask, P->c_row_off, P->c_row_ptr, col, val);
         e = hipGetLastError();

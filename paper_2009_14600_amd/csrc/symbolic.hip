@@ -371,14 +371,22 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_emit(
 // segment: c_mask[r] |= OR over the set bits k of the A tile's row mask r of the B tile's row mask k.
 // The segment's entries are read 16 at a time, one per lane, and the bitmaps of four pairs are
 // requested together so that their latencies overlap.
+typedef unsigned short ushort2v __attribute__((ext_vector_type(2)));
+// OR over the set bits k of `am` of row mask k of the B tile; x, y hold the 16 row masks, two per
+// 32-bit word (row 2i in the low half).  Each word is multiplied, half by half, with the two bits
+// (0 or 1) of `am` that select its rows: one packed 16-bit multiply does the selection of two rows.
 __device__ __forceinline__ uint32_t boolean_row_product(uint32_t am, const uint4 &x, const uint4 &y) {
-    const uint32_t w[8] = {x.x, x.y, x.z, x.w, y.x, y.y, y.z, y.w};   // masks of rows 2i (low half) and 2i+1 (high)
+    const uint32_t w[8] = {x.x, x.y, x.z, x.w, y.x, y.y, y.z, y.w};
+    const uint32_t am2 = am | ((am >> 1) << 16);              // bit 2i+1 of am sits at bit 16+2i
     uint32_t acc = 0;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-        const uint32_t lo = (uint32_t)(-(int32_t)((am >> (2 * i)) & 1u)) & 0x0000FFFFu;
-        const uint32_t hi = (uint32_t)(-(int32_t)((am >> (2 * i + 1)) & 1u)) & 0xFFFF0000u;
-        acc |= w[i] & (lo | hi);
+        const uint32_t sel = (am2 >> (2 * i)) & 0x00010001u;   // low half: bit 2i of am, high half: bit 2i+1
+        union { uint32_t u; ushort2v v; } a, b, r;
+        a.u = w[i];
+        b.u = sel;
+        r.v = a.v * b.v;
+        acc |= r.u;
     }
     return acc;
 }
