@@ -20,6 +20,7 @@
 #include "common.hpp"
 #include "chain.hpp"
 
+#include <algorithm>
 #include <climits>
 #include <new>
 
@@ -528,8 +529,13 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
     }
     if (ntr > 0) {
         KernelTimer kt(ctx, TSP_KERNEL_SYM_COUNT, s);
-        hipLaunchKernelGGL(k_sym_count, dim3((unsigned)ntr), dim3(kSymThreads), kMaxWords * sizeof(uint32_t), s, ra,
-                           rb, lanes, kMaxWords, row_jmin, row_c_tiles, row_pairs, row_words, row_cand, ctx->d_scalars);
+        // the bitmap cannot be wider than B's tile grid; short tile-rows get one wave each, so that
+        // many more of them are in flight (the kernels are bound by dependent loads, not by work)
+        const int max_words = (int)std::min<int64_t>(kMaxWords, (B->tile_cols + 31) / 32 + 1);
+        const int64_t per_row = A->nnz / ntr;
+        const int threads = per_row <= 256 ? 64 : per_row <= 4096 ? 128 : kSymThreads;
+        hipLaunchKernelGGL(k_sym_count, dim3((unsigned)ntr), dim3(threads), max_words * sizeof(uint32_t), s, ra, rb,
+                           lanes, max_words, row_jmin, row_c_tiles, row_pairs, row_words, row_cand, ctx->d_scalars);
         TSP_HIP_CHECK(ctx, hipGetLastError());
     }
     {
@@ -577,7 +583,9 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
         const size_t lds = (size_t)(2 * words_cap + 2 * window) * sizeof(uint32_t);
         lanes = lanes_per_a_tile(B);
         KernelTimer kt(ctx, TSP_KERNEL_SYM_EMIT, s);
-        hipLaunchKernelGGL(k_sym_emit, dim3((unsigned)ntr), dim3(kSymThreads), lds, s, ra, rb, lanes, words_cap,
+        const int64_t per_row = P->candidates / ntr;
+        const int threads = per_row <= 256 ? 64 : per_row <= 4096 ? 128 : kSymThreads;
+        hipLaunchKernelGGL(k_sym_emit, dim3((unsigned)ntr), dim3(threads), lds, s, ra, rb, lanes, words_cap,
                            window, row_jmin, P->c_tile_row_ptr, row_pair_ptr, P->c_tile_row, P->c_tile_col,
                            P->pair_off, P->pair_a, P->pair_b);
         TSP_HIP_CHECK(ctx, hipGetLastError());
