@@ -33,15 +33,22 @@ constexpr int kConvThreads = 256;
 enum : int32_t { ROW_FAST = 0, ROW_MERGE = 1 };
 
 template <int G> struct ConvCfg;
+template <int G> constexpr int conv_block_threads() { return G == 64 ? 256 : G; }
 template <> struct ConvCfg<64> {                  // one wave per tile-row, four tile-rows per block
     static constexpr int kWords = 512;            // bitmap words: tile columns may span 16384
     static constexpr int kWindow = 32;            // tiles handled per pass over the entries
+    static constexpr int kCache = 8;              // entries per thread kept in registers between passes
 };
-template <> struct ConvCfg<256> {                 // one block per tile-row
+template <> struct ConvCfg<128> {                 // one 128-thread block per tile-row
+    static constexpr int kWords = 1024;
+    static constexpr int kWindow = 64;
+    static constexpr int kCache = 8;
+};
+template <> struct ConvCfg<256> {                 // one 256-thread block per tile-row
     static constexpr int kWords = 1024;           // span of 32768 tile columns
     static constexpr int kWindow = 128;
+    static constexpr int kCache = 8;
 };
-constexpr int kConvCache = 8;                     // entries per thread kept in registers between passes
 
 __device__ __forceinline__ uint16_t to_half_bits(uint16_t v) { return v; }
 __device__ __forceinline__ uint16_t to_half_bits(float v) { return __half_as_ushort(__float2half_rn(v)); }
@@ -78,7 +85,9 @@ __device__ __forceinline__ int group_max(int v, int *red) {
         __syncthreads();
         if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
         __syncthreads();
-        v = max(max(red[0], red[1]), max(red[2], red[3]));
+        v = red[0];
+#pragma unroll
+        for (int w = 1; w < G / 64; ++w) v = max(v, red[w]);
     }
     return v;
 }
@@ -89,7 +98,9 @@ __device__ __forceinline__ uint32_t group_sum(uint32_t v, int *red) {
         __syncthreads();
         if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = (int)v;
         __syncthreads();
-        v = (uint32_t)red[0] + (uint32_t)red[1] + (uint32_t)red[2] + (uint32_t)red[3];
+        v = 0;
+#pragma unroll
+        for (int w = 0; w < G / 64; ++w) v += (uint32_t)red[w];
     }
     return v;
 }
@@ -126,8 +137,9 @@ __device__ __forceinline__ uint32_t group_exclusive_scan(uint32_t *arr, int n, i
 // Fast path: LDS bitmap over the tile-row's span of tile columns.
 // ------------------------------------------------------------------------------------------------
 template <int G, bool FILL, typename RP, typename VT>
-__global__ __launch_bounds__(kConvThreads) void k_convert_rows(const ConvArgs<RP, VT> a) {
-    constexpr int kWords = ConvCfg<G>::kWords, kWindow = ConvCfg<G>::kWindow, kGroups = kConvThreads / G;
+__global__ __launch_bounds__(conv_block_threads<G>()) void k_convert_rows(const ConvArgs<RP, VT> a) {
+    constexpr int kWords = ConvCfg<G>::kWords, kWindow = ConvCfg<G>::kWindow, kGroups = conv_block_threads<G>() / G;
+    constexpr int kConvCache = ConvCfg<G>::kCache;
     __shared__ int s_rp_all[kGroups][20];
     __shared__ uint32_t s_bm_all[kGroups][kWords], s_pre_all[kGroups][kWords];
     __shared__ uint32_t s_mask_all[kGroups][kWindow * 8];
@@ -587,20 +599,32 @@ static int launch_convert(tsp_context *ctx, const tsp_csr *A, tsp_tiles_s *t, in
     a.ldata = t->ldata;
     a.rdata = t->rdata;
     a.d_scalars = ctx->d_scalars;
-    // a wave per tile-row unless the tile-rows are long; the merge path only when a tile-row could
-    // span more tile columns than the bitmap of the chosen kernel holds
-    const bool wide_groups = ntr > 0 && A->nnz / ntr > 1024;
-    const int64_t bitmap_span = 32ll * (wide_groups ? ConvCfg<256>::kWords : ConvCfg<64>::kWords);
+    // threads per tile-row from the mean number of entries per tile-row (the kernels are bound by
+    // dependent steps, so small groups, many in flight, win as long as the entries fit their registers);
+    // the merge path only when a tile-row could span more tile columns than the chosen bitmap holds
+    const int64_t per_row = ntr > 0 ? A->nnz / ntr : 0;
+    const int G = per_row <= 64 * ConvCfg<64>::kCache ? 64 : per_row <= 128 * ConvCfg<128>::kCache ? 128 : 256;
+    const int64_t bitmap_span =
+        32ll * (G == 64 ? ConvCfg<64>::kWords : G == 128 ? ConvCfg<128>::kWords : ConvCfg<256>::kWords);
     // (tile-rows of a narrow matrix cannot exceed the bitmap, and then the merge kernels are not launched)
     const bool may_merge = t->tile_cols > bitmap_span;
-    const unsigned grid_fast = (unsigned)(wide_groups ? ntr : (ntr + 3) / 4);
+    const unsigned grid_fast = (unsigned)(G == 64 ? (ntr + 3) / 4 : ntr);
     const unsigned grid_merge = (unsigned)((ntr + kMergeGroupsPerBlock - 1) / kMergeGroupsPerBlock);
+    auto launch_rows = [&](bool fill) {
+        if (G == 64) {
+            if (fill) hipLaunchKernelGGL((k_convert_rows<64, true, RP, VT>), dim3(grid_fast), dim3(256), 0, s, a);
+            else hipLaunchKernelGGL((k_convert_rows<64, false, RP, VT>), dim3(grid_fast), dim3(256), 0, s, a);
+        } else if (G == 128) {
+            if (fill) hipLaunchKernelGGL((k_convert_rows<128, true, RP, VT>), dim3(grid_fast), dim3(128), 0, s, a);
+            else hipLaunchKernelGGL((k_convert_rows<128, false, RP, VT>), dim3(grid_fast), dim3(128), 0, s, a);
+        } else {
+            if (fill) hipLaunchKernelGGL((k_convert_rows<256, true, RP, VT>), dim3(grid_fast), dim3(256), 0, s, a);
+            else hipLaunchKernelGGL((k_convert_rows<256, false, RP, VT>), dim3(grid_fast), dim3(256), 0, s, a);
+        }
+    };
     if (ntr > 0) {
         KernelTimer kt(ctx, TSP_KERNEL_COUNT_TILES, s);
-        if (wide_groups)
-            hipLaunchKernelGGL((k_convert_rows<256, false, RP, VT>), dim3(grid_fast), dim3(kConvThreads), 0, s, a);
-        else
-            hipLaunchKernelGGL((k_convert_rows<64, false, RP, VT>), dim3(grid_fast), dim3(kConvThreads), 0, s, a);
+        launch_rows(false);
         if (may_merge)
             hipLaunchKernelGGL((k_convert_merge<false, RP, VT>), dim3(grid_merge), dim3(kConvThreads), 0, s, a);
     }
@@ -616,10 +640,7 @@ static int launch_convert(tsp_context *ctx, const tsp_csr *A, tsp_tiles_s *t, in
     }
     if (ntr > 0) {
         KernelTimer kt(ctx, TSP_KERNEL_FILL_TILES, s);
-        if (wide_groups)
-            hipLaunchKernelGGL((k_convert_rows<256, true, RP, VT>), dim3(grid_fast), dim3(kConvThreads), 0, s, a);
-        else
-            hipLaunchKernelGGL((k_convert_rows<64, true, RP, VT>), dim3(grid_fast), dim3(kConvThreads), 0, s, a);
+        launch_rows(true);
         if (may_merge)
             hipLaunchKernelGGL((k_convert_merge<true, RP, VT>), dim3(grid_merge), dim3(kConvThreads), 0, s, a);
     }
