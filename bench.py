@@ -31,6 +31,16 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_F16_PEAK_TFLOPS = 2500.0  # dense fp16 MFMA, published
 
 
+# HBM bytes per launch measured with rocprofv3 (--pmc FETCH_SIZE, then --pmc WRITE_SIZE, one run each, on
+# this bench at --steps 3), scaled by what the same counters read for a 1 GiB device copy: fetched bytes =
+# 2048 * FETCH_SIZE, written bytes = 1024 * WRITE_SIZE.  profiles/hbm_traffic_all_kernels.txt holds the
+# readings and commands.  Keyed by (workload, kernel); a kernel that has changed since needs a new reading.
+MEASURED_TRAFFIC_BYTES = {
+    (2, "numeric"): 2048 * 27186.6 + 1024 * 28253.7,
+    (3, "numeric"): 2048 * 337034.0 + 1024 * 1122351.8,
+}
+
+
 def popcount32(x):
     x = x.astype(np.uint32)
     x = x - ((x >> 1) & 0x55555555)
@@ -151,7 +161,9 @@ def main():
     dom_us = kavg[dominant]
     achieved = dom_bytes / (dom_us * 1e-6) / 1e9 if dom_us > 0 else 0.0
     roofline = {"kernel": dominant, "bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 5), "traffic": None,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 5),
+                "traffic": (int(MEASURED_TRAFFIC_BYTES[(args.workload, dominant)])
+                            if (args.workload, dominant) in MEASURED_TRAFFIC_BYTES else None),
                 "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_us": round(dom_us, 2)}
     # the numeric kernel is the one dense contraction: issued MFMA work against the matrix-core peak
     num_us = kavg["numeric"]
@@ -173,30 +185,32 @@ def main():
         rl = np.diff(A.row_ptr).astype(np.int64)
         csum = np.concatenate([[0], np.cumsum(rl[A.col_idx])])
         per_row = csum[A.row_ptr.astype(np.int64)]          # products of rows [0, i)
-        budget = 6e7                      # products: ~10-30 s of single-thread oracle work
+        budget = 4e8                      # products: a few seconds of single-thread oracle work per run
         rows = int(np.searchsorted(per_row, budget, side="right"))
         rows = max(1, min(A.rows, rows))
         sample_products = int(per_row[rows])
         sub = inputs.CSRMatrix(rows, A.cols, A.row_ptr[:rows + 1], A.col_idx[:A.row_ptr[rows]],
                                A.val[:A.row_ptr[rows]])
-        def timed(nthreads):
+        def timed(nthreads, seconds=10.0):
+            """Repeat the sample until about `seconds` of wall time have gone by; mean time of one run."""
             t0 = time.perf_counter()
             r = reference.spgemm(sub, A, threads=nthreads)
             dt = time.perf_counter() - t0
-            reps = int(min(50, 3.0 / max(dt, 1e-3)))          # short samples: average a few runs
+            reps = int(min(2000, seconds / max(dt, 1e-4)))
             if reps > 1:
                 t0 = time.perf_counter()
                 for _ in range(reps):
                     reference.spgemm(sub, A, threads=nthreads)
                 dt = (time.perf_counter() - t0) / reps
-            return r, dt
+            return r, dt, max(reps, 1)
 
-        r1, t1 = timed(1)
-        _, tn = timed(threads)
+        r1, t1, _ = timed(1)
+        _, tn, reps = timed(threads)
         assert r1.products == sample_products
         cpu = {"value": round(2.0 * sample_products / tn / 1e9, 4), "unit": "GFLOP/s", "cores": threads,
                "kind": "oracle",
-               "sample": f"rows [0,{rows}) of C = A*A ({sample_products} products, {r1.nnz} entries of C)",
+               "sample": f"rows [0,{rows}) of {A.rows} of C = A*A ({sample_products} products, {r1.nnz} entries of C), "
+                         f"mean of {reps} runs",
                "single_thread_value": round(2.0 * sample_products / t1 / 1e9, 4),
                "seconds": round(tn, 3), "single_thread_seconds": round(t1, 3)}
 
@@ -204,7 +218,7 @@ def main():
         "metric": "spGEMM GFLOP/s (2 x intermediate products / s), C = A*A, CSR in -> CSR out",
         "value": round(gflops, 3), "unit": "GFLOP/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "f16 inputs, f32 accumulate", "data": "synthetic",
+        "vs_baseline": None, "dtype": "f16 x f16 -> f32", "data": "synthetic",
         "config": {"workload": f"configs[{args.workload - 1}]: {inputs.CONFIG_NAMES[args.workload]}",
                    "rows": A.rows, "nnz_A": A.nnz, "products": products, "nnz_C": st["c_nnz"],
                    "a_tiles": st["a_tiles"], "pairs": st["pairs"], "c_tiles": st["c_tiles"],
