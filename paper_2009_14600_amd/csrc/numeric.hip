@@ -43,7 +43,7 @@ union Group {
 };
 
 constexpr int kNumThreads = 256;       // 4 waves per block
-constexpr int kMaxTilesPerWave = 8;    // consecutive output tiles one wave walks: 4 or 8
+constexpr int kGroupTiles = 4;         // output tiles computed together and written out row by row
 constexpr int kXcds = 8;
 
 struct Header {          // tile headers of one task-list entry, held by the lane that read the entry
@@ -83,65 +83,59 @@ struct NumericSizes {
     uint64_t pairs, a_tiles, b_tiles, a_groups, b_groups;   // element counts of the arrays
 };
 
-// What a lane needs to emit its four accumulator values of one output tile.
+// What a lane needs to write out its column of one output tile: lane l of a group of four tiles
+// holds, after the transposition, column l%16 of all 16 rows of tile l/16.
 struct Emission {
-    uint2 cm2;            // row masks of rows 4*ig .. 4*ig+3 (16 bits each)
-    uint4 coff4;          // entries of those CSR rows to the left of the tile
-    longlong2 rb01, rb23; // starts of those CSR rows
-    int32_t col;          // column of this lane inside C
+    uint4 m0, m1;             // the tile's 16 row masks, 16 bits each
+    uint4 o0, o1, o2, o3;     // per row: position of the tile's first entry, from the start of the tile-row
+    int64_t base;             // position of the tile-row's first entry in C
+    int32_t col;              // column of this lane inside C
+    bool valid;               // the lane's tile exists
 };
+
+__device__ __forceinline__ void swap_rows(float &x, float &y, bool halves) {
+    // rows = groups of 16 lanes.  halves == false: rows 1, 3 of x <-> rows 0, 2 of y;
+    // halves == true: rows 2, 3 of x <-> rows 0, 1 of y
+    const unsigned a = __float_as_uint(x), b = __float_as_uint(y);
+    const auto r = halves ? __builtin_amdgcn_permlane32_swap(a, b, false, false)
+                          : __builtin_amdgcn_permlane16_swap(a, b, false, false);
+    x = __uint_as_float(r[0]);
+    y = __uint_as_float(r[1]);
+}
 
 template <class Array, int kTilesPerWave>
 __global__ __launch_bounds__(kNumThreads) void k_numeric(
-    const int64_t c_tiles, const int tiles_per_wave, const NumericSizes z, const int64_t *__restrict__ pair_off,
+    const int64_t c_tiles, const NumericSizes z, const int64_t *__restrict__ pair_off,
     const int32_t *__restrict__ pair_a_, const int32_t *__restrict__ pair_b_, const uint32_t *__restrict__ a_lmask_,
     const uint32_t *__restrict__ a_loff_, const uint4 *__restrict__ a_ldata_, const uint32_t *__restrict__ b_rmask_,
     const uint32_t *__restrict__ b_roff_, const uint4 *__restrict__ b_rdata_, const int32_t *__restrict__ c_tile_row,
     const int32_t *__restrict__ c_tile_col, const uint16_t *__restrict__ c_row_mask,
     const uint32_t *__restrict__ c_row_off, const int64_t *__restrict__ c_row_ptr, int32_t *__restrict__ c_col,
     float *__restrict__ c_val) {
+    static_assert(kTilesPerWave % kGroupTiles == 0 && kTilesPerWave <= 32, "whole groups; offsets fit one wave load");
     // consecutive logical blocks on the same XCD (workgroups are dealt to the XCDs round-robin)
     const int per_xcd = gridDim.x / kXcds;
     const int logical = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
     // wave-uniform values are kept in scalar registers; their loads become scalar loads
     const int64_t wave = (int64_t)logical * (kNumThreads / 64) + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int64_t run_begin = wave * tiles_per_wave;
+    const int64_t run_begin = wave * kTilesPerWave;
     if (run_begin >= c_tiles) return;
-    const int64_t run_end = min(run_begin + tiles_per_wave, c_tiles);
+    const int run_tiles = (int)min((int64_t)kTilesPerWave, c_tiles - run_begin);
     const int lane = threadIdx.x & 63;
     const int hl = lane & 31, upper = lane >> 5;
     const uint32_t bit = 1u << hl, below = bit - 1u;
-    const int j = lane & 15, ig = lane >> 4;
+    const int j = lane & 15, tq = lane >> 4;
     const Array pair_a(pair_a_, z.pairs * 4), pair_b(pair_b_, z.pairs * 4);
     const Array a_lmask(a_lmask_, z.a_tiles * 4), a_loff(a_loff_, z.a_tiles * 4);
     const Array b_rmask(b_rmask_, z.b_tiles * 4), b_roff(b_roff_, z.b_tiles * 4);
     const Array a_ldata(a_ldata_, z.a_groups * 16), b_rdata(b_rdata_, z.b_groups * 16);
 
-    auto emit = [&](const Emission &em, const float4v &acc) {
-        const uint32_t cm[4] = {em.cm2.x & 0xFFFFu, em.cm2.x >> 16, em.cm2.y & 0xFFFFu, em.cm2.y >> 16};
-        const uint32_t coff[4] = {em.coff4.x, em.coff4.y, em.coff4.z, em.coff4.w};
-        const int64_t rbase[4] = {em.rb01.x, em.rb01.y, em.rb23.x, em.rb23.y};
-#pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            if ((cm[v] >> j) & 1u) {
-                const int64_t pos = rbase[v] + (int64_t)(coff[v] + __popc(cm[v] & ((1u << j) - 1u)));
-                c_col[pos] = em.col;
-                c_val[pos] = acc[v];
-            }
-        }
-    };
-    Emission em_prev{};
-    float4v acc_prev = {0.f, 0.f, 0.f, 0.f};
-    bool have_prev = false;
-  // the run is walked in groups of kTilesPerWave tiles
-  for (int64_t c_begin = run_begin; c_begin < run_end; c_begin += kTilesPerWave) {
-    const int n_tiles = (int)min((int64_t)kTilesPerWave, run_end - c_begin);
-    // segment bounds of the group's tiles, relative to the first one (one vector load, then scalars)
-    const int64_t off_lane = pair_off[c_begin + min(lane, n_tiles)];
+    // segment bounds of the run's tiles, relative to the first one (one vector load, then scalars)
+    const int64_t off_lane = pair_off[run_begin + min(lane, run_tiles)];
     const int64_t base = ((int64_t)__builtin_amdgcn_readlane((int)(off_lane >> 32), 0) << 32) |
                          (uint32_t)__builtin_amdgcn_readlane((int)off_lane, 0);
     const int rel_lane = (int)(off_lane - base);
-    const int rel_end = __builtin_amdgcn_readlane(rel_lane, kTilesPerWave);        // lanes >= n_tiles hold the end
+    const int rel_end = __builtin_amdgcn_readlane(rel_lane, kTilesPerWave);        // lanes >= run_tiles hold the end
 
     // 64 consecutive task-list entries starting at relative position `start`, one per lane, with the
     // headers of their tiles; lanes past the end of the wave's entries hold all-zero headers
@@ -160,10 +154,8 @@ __global__ __launch_bounds__(kNumThreads) void k_numeric(
         bv.u = b_rdata.group(ro + __popc(rm & below), valid && (rm & bit) != 0);
     };
     // multiply the `count` entries that start at lane `o` of the headers h into acc, two entries per
-    // MFMA; the loads of up to four MFMAs are requested together, `between` runs once after the first
-    // batch of loads has been requested
-    auto multiply = [&](const Header &h, int o, int count, float4v &acc, auto between) {
-        bool first = true;
+    // MFMA; the loads of up to four MFMAs are requested together
+    auto multiply = [&](const Header &h, int o, int count, float4v &acc) {
         for (int it = 0; it < count; it += 8) {
             Group a0, b0, a1, b1, a2, b2, a3, b3;
             const int left = count - it;                                // > 0, uniform
@@ -171,57 +163,82 @@ __global__ __launch_bounds__(kNumThreads) void k_numeric(
             if (left > 2) load_operands(h, (o + it + 2 + upper) & 63, 2 + upper < left, a1, b1);
             if (left > 4) load_operands(h, (o + it + 4 + upper) & 63, 4 + upper < left, a2, b2);
             if (left > 6) load_operands(h, (o + it + 6 + upper) & 63, 6 + upper < left, a3, b3);
-            if (first) between();
-            first = false;
             acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a0.h, b0.h, acc, 0, 0, 0);
             if (left > 2) acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1.h, b1.h, acc, 0, 0, 0);
             if (left > 4) acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a2.h, b2.h, acc, 0, 0, 0);
             if (left > 6) acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a3.h, b3.h, acc, 0, 0, 0);
         }
-        if (first) between();
     };
 
     int h_start = 0;                              // relative position of the entry lane 0 of `heads` holds
     Header heads = load_headers(0);
 #pragma unroll
-    for (int t = 0; t < kTilesPerWave; ++t) {
-        if (t < n_tiles) {                        // uniform
-            const int64_t c = c_begin + t;
-            const int r0 = __builtin_amdgcn_readlane(rel_lane, t), r1 = __builtin_amdgcn_readlane(rel_lane, t + 1);
-            const int n = r1 - r0, first_part = min(n, 64);
-            // what the emission needs, requested before the multiplication: row masks (4 x 16 bit), the
-            // rows' entry counts left of the tile (4 x 32 bit) and the rows' starts (4 x 64 bit; the plan
-            // pads row_ptr to whole tile-rows, so rows past the matrix edge read valid memory)
-            const int64_t I = c_tile_row[c], J = c_tile_col[c];
+    for (int g = 0; g < kTilesPerWave / kGroupTiles; ++g) {
+        if (g * kGroupTiles < run_tiles) {        // uniform
+            // Requested before the multiplications, used after them: what lane (tq, j) needs to write
+            // out column j of tile tq of this group (requesting them afterwards saves 26 registers and
+            // gains occupancy, but measured slower: the kernel then waits for them with nothing to do).
             Emission em;
-            em.cm2 = *reinterpret_cast<const uint2 *>(c_row_mask + c * T + 4 * ig);
-            em.coff4 = *reinterpret_cast<const uint4 *>(c_row_off + c * T + 4 * ig);
-            em.rb01 = *reinterpret_cast<const longlong2 *>(c_row_ptr + I * T + 4 * ig);
-            em.rb23 = *reinterpret_cast<const longlong2 *>(c_row_ptr + I * T + 4 * ig + 2);
-            em.col = (int32_t)(J * T + j);
-            // the 64 entries in `heads` must cover the first 64 entries of this segment
-            if (r0 < h_start || r0 + first_part > h_start + 64) {
-                h_start = r0;
-                heads = load_headers(h_start);
+            em.valid = g * kGroupTiles + tq < run_tiles;
+            {
+                const int64_t c = run_begin + (em.valid ? g * kGroupTiles + tq : 0);
+                const uint4 *mp = reinterpret_cast<const uint4 *>(c_row_mask + c * T);
+                const uint4 *op = reinterpret_cast<const uint4 *>(c_row_off + c * T);
+                em.m0 = mp[0]; em.m1 = mp[1];
+                em.o0 = op[0]; em.o1 = op[1]; em.o2 = op[2]; em.o3 = op[3];
+                em.base = c_row_ptr[(int64_t)c_tile_row[c] * T];
+                em.col = c_tile_col[c] * T + j;
             }
-            float4v acc = {0.f, 0.f, 0.f, 0.f};
-            // the previous tile is written out after this tile's loads are on their way, so that no
-            // wait for a load ever includes the acknowledgement of a store
-            multiply(heads, r0 - h_start, first_part, acc, [&]() {
-                if (have_prev) emit(em_prev, acc_prev);
-            });
-            // segments longer than 64 entries: the rest, 64 at a time
-            for (int s = r0 + 64; s < r1; s += 64) {
-                const Header h = load_headers(s);
-                multiply(h, 0, min(r1 - s, 64), acc, []() {});
+            float4v acc[kGroupTiles];
+#pragma unroll
+            for (int t = 0; t < kGroupTiles; ++t) {
+                acc[t] = float4v{0.f, 0.f, 0.f, 0.f};
+                const int tile = g * kGroupTiles + t;
+                if (tile < run_tiles) {           // uniform
+                    const int r0 = __builtin_amdgcn_readlane(rel_lane, tile);
+                    const int r1 = __builtin_amdgcn_readlane(rel_lane, tile + 1);
+                    const int n = r1 - r0, first_part = min(n, 64);
+                    // the 64 entries in `heads` must cover the first 64 entries of this segment
+                    if (r0 < h_start || r0 + first_part > h_start + 64) {
+                        h_start = r0;
+                        heads = load_headers(h_start);
+                    }
+                    multiply(heads, r0 - h_start, first_part, acc[t]);
+                    // segments longer than 64 entries: the rest, 64 at a time
+                    for (int s = r0 + 64; s < r1; s += 64) {
+                        const Header h = load_headers(s);
+                        multiply(h, 0, min(r1 - s, 64), acc[t]);
+                    }
+                }
             }
-            em_prev = em;
-            acc_prev = acc;
-            have_prev = true;
+            // Transposition between tile index and row block: register v of tile t holds rows 4q+v in
+            // lanes 16q..16q+15; afterwards rows[v][q] holds row 4q+v of tile tq in lanes 16tq..16tq+15,
+            // so that one store instruction writes one CSR row across the four tiles, which are
+            // neighbours in that row: one contiguous run per instruction instead of four.
+            float rows[4][kGroupTiles];
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+#pragma unroll
+                for (int t = 0; t < kGroupTiles; ++t) rows[v][t] = acc[t][v];
+                swap_rows(rows[v][0], rows[v][1], false);
+                swap_rows(rows[v][2], rows[v][3], false);
+                swap_rows(rows[v][0], rows[v][2], true);
+                swap_rows(rows[v][1], rows[v][3], true);
+            }
+            const uint32_t mw[8] = {em.m0.x, em.m0.y, em.m0.z, em.m0.w, em.m1.x, em.m1.y, em.m1.z, em.m1.w};
+            const uint32_t ow[16] = {em.o0.x, em.o0.y, em.o0.z, em.o0.w, em.o1.x, em.o1.y, em.o1.z, em.o1.w,
+                                     em.o2.x, em.o2.y, em.o2.z, em.o2.w, em.o3.x, em.o3.y, em.o3.z, em.o3.w};
+#pragma unroll
+            for (int r = 0; r < T; ++r) {
+                const uint32_t m = (r & 1) ? mw[r >> 1] >> 16 : mw[r >> 1] & 0xFFFFu;
+                if (em.valid && ((m >> j) & 1u)) {
+                    const int64_t pos = em.base + (int64_t)ow[r] + __popc(m & ((1u << j) - 1u));
+                    c_col[pos] = em.col;
+                    c_val[pos] = rows[r & 3][r >> 2];
+                }
+            }
         }
     }
-  }
-    if (have_prev) emit(em_prev, acc_prev);
 }
 
 int numeric_enqueue(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s *P, tsp_csr *C, hipStream_t s) {
@@ -256,7 +273,7 @@ int numeric_enqueue(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s
                             z.a_tiles * 4 < limit && z.b_tiles * 4 < limit && !ctx->force_wide;
         auto kernel = narrow ? (tiles_per_wave == 4 ? k_numeric<BufferArray, 4> : k_numeric<BufferArray, 8>)
                              : (tiles_per_wave == 4 ? k_numeric<PointerArray, 4> : k_numeric<PointerArray, 8>);
-        hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(kNumThreads), 0, s, P->c_tiles, tiles_per_wave, z, P->pair_off,
+        hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(kNumThreads), 0, s, P->c_tiles, z, P->pair_off,
                            P->pair_a, P->pair_b, A->lmask, A->loff, A->ldata, B->rmask, B->roff, B->rdata,
                            P->c_tile_row, P->c_tile_col, P->c_row_mask, P->c_row_off, P->c_row_ptr, col, val);
         e = hipGetLastError();

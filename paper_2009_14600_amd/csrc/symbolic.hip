@@ -435,25 +435,36 @@ __global__ __launch_bounds__(256) void k_count_masks(int64_t c_tiles, const int6
     if (in) c_row_mask[c * T + r] = (uint16_t)((acc | (acc >> 16)) & 0xFFFFu);
 }
 
-// Per tile-row of C (16 lanes, lane r = row r): running count of entries of CSR row 16I+r in the
-// tiles to the left, and the row's total.
+// Per tile-row of C (16 lanes, lane r = row r): the length of CSR row 16I+r, and for every tile of
+// the tile-row the position of its first entry in that row, counted from the first entry of the
+// tile-row (entries of rows 16I..16I+r-1 plus the row's entries in the tiles to the left).  The
+// multiplication pass adds the start of the tile-row and the rank inside the tile.  Offsets are
+// 32-bit: a tile-row of C with 2^32 entries or more raises the "unsupported" flag.
 __global__ __launch_bounds__(256) void k_row_offsets(int64_t c_tile_rows, int64_t c_rows,
                                                      const int32_t *__restrict__ c_tile_row_ptr,
                                                      const uint16_t *__restrict__ c_row_mask,
                                                      uint32_t *__restrict__ c_row_off,
-                                                     int32_t *__restrict__ row_nnz) {
+                                                     int32_t *__restrict__ row_nnz, int64_t *d_scalars) {
     const int64_t I = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 4;
     const int r = threadIdx.x & 15;
-    if (I >= c_tile_rows) return;
+    if (I >= c_tile_rows) return;                  // whole 16-lane groups leave together
     const int64_t c0 = c_tile_row_ptr[I], c1 = c_tile_row_ptr[I + 1];
-    uint32_t run = 0;
-    for (int64_t c = c0; c < c1; ++c) {
-        const uint32_t m = c_row_mask[c * T + r];
-        c_row_off[c * T + r] = run;
-        run += __popc(m);
-    }
+    uint32_t total = 0;                            // <= 16 * tiles of the tile-row: fits
+    for (int64_t c = c0; c < c1; ++c) total += __popc(c_row_mask[c * T + r]);
     const int64_t row = I * T + r;
-    if (row < c_rows) row_nnz[row] = (int32_t)run;
+    if (row < c_rows) row_nnz[row] = (int32_t)total;
+    uint64_t before = total;                       // inclusive prefix over the 16 rows
+#pragma unroll
+    for (int d = 1; d < T; d <<= 1) {
+        const uint64_t up = __shfl_up(before, d, T);
+        if (r >= d) before += up;
+    }
+    if (r == T - 1 && before > 0xFFFFFFFFull) d_scalars[S_UNSUPPORTED] = 1;
+    uint32_t run = (uint32_t)(before - total);
+    for (int64_t c = c0; c < c1; ++c) {
+        c_row_off[c * T + r] = run;
+        run += __popc(c_row_mask[c * T + r]);
+    }
 }
 
 void plan_release(tsp_context *ctx, tsp_plan_s *p, hipStream_t s) {
@@ -605,7 +616,7 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
         const unsigned grid = (unsigned)((ntr * 16 + 255) / 256);
         KernelTimer kt(ctx, TSP_KERNEL_ROW_OFFSETS, s);
         hipLaunchKernelGGL(k_row_offsets, dim3(grid), dim3(256), 0, s, ntr, P->c_rows, P->c_tile_row_ptr,
-                           P->c_row_mask, P->c_row_off, row_nnz);
+                           P->c_row_mask, P->c_row_off, row_nnz, ctx->d_scalars);
     }
     TSP_HIP_CHECK(ctx, hipGetLastError());
     {
@@ -616,6 +627,7 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
     phase_end(ctx, TSP_PHASE_COUNT, s);
     if (!rc) rc = read_scalars(ctx, s);                                    // ---- sync 2: nnz(C)
     if (rc) return cleanup(rc);
+    if (ctx->h_scalars[S_UNSUPPORTED]) return cleanup(TSP_ERR_UNSUPPORTED);
     P->c_nnz = ctx->h_scalars[S_C_NNZ];
     ctx->stats.a_tiles = A->ntiles;
     ctx->stats.b_tiles = B->ntiles;
