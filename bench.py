@@ -82,6 +82,7 @@ def main():
     ap.add_argument("--workload", type=int, default=2, help="index 1..5 into BASELINE.json configs")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-validate", action="store_true", help="switch the input validation kernel off")
+    ap.add_argument("--numeric-run", type=int, default=0, help="tiles per wave of the multiplication kernel (0: automatic)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU only (--gpus 1); the path has no multi-GPU part",
@@ -102,6 +103,8 @@ def main():
     dA = tsp.to_device(A)
     sA = dA._struct()
     handle = tsp.Handle(validate=not args.no_validate)
+    if args.numeric_run:
+        handle.set_option(tsp.OPT_NUMERIC_RUN, args.numeric_run)
 
     def step():
         out = handle.spgemm_raw(sA, sA)

@@ -87,8 +87,10 @@ enum {
     TSP_OPT_VALIDATE = 1,      /* 1 (default): check that CSR inputs are canonical                 */
     TSP_OPT_PHASE_TIMERS = 2,  /* 1: bracket every phase with HIP events on the call's stream and   */
                                /*    report the durations in tsp_stats; 0 (default): no events      */
-    TSP_OPT_WIDE_INDEX = 3     /* 1: always use the kernels that address arrays of 4 GiB and more   */
+    TSP_OPT_WIDE_INDEX = 3,    /* 1: always use the kernels that address arrays of 4 GiB and more   */
                                /*    through 64-bit pointers; 0 (default): chosen from the sizes    */
+    TSP_OPT_NUMERIC_RUN = 4    /* output tiles one wave of the multiplication kernel walks: 4 or 8; */
+                               /*    0 (default): chosen from the mean segment length               */
 };
 
 /* Phases reported in tsp_stats.phase_us, in pipeline order. */

@@ -14,6 +14,9 @@ LIB = os.path.join(HERE, "libtsp.so")
 SOURCES = ["context.hip", "scan.hip", "convert.hip", "symbolic.hip", "numeric.hip", "spgemm.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         # MFMA accumulators in ordinary vector registers: the kernels hold few of them, and the copies to and
+         # from the accumulation registers cost more instructions than the registers save
+         "-mllvm", "-amdgpu-mfma-vgpr-form=1",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC] + os.environ.get("TSP_EXTRA_FLAGS", "").split()
 
 

@@ -45,40 +45,35 @@ union Group {
 constexpr int kNumThreads = 256;       // 4 waves per block
 constexpr int kGroupTiles = 4;         // output tiles computed together and written out row by row
 constexpr int kXcds = 8;
+constexpr int kBlockEntries = 64;      // task-list entries staged at a time: one per lane
 
-struct Header {          // tile headers of one task-list entry, held by the lane that read the entry
-    uint32_t lm, lo, rm, ro;
+struct Header {          // tile headers of one task-list entry, as the lanes of the wave read them from LDS
+    uint32_t lm, lo, rm, ro;   // group masks and BYTE offsets of the first group: left form of A, right form of B
 };
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-// Read-only array behind a buffer descriptor: a lane that passes valid = false (or an index past the
-// end) gets zeros back from the hardware range check, so predicated loads need neither branches nor
-// zero-initialised registers.  Offsets are 32-bit: the array must be smaller than 4 GiB.
+constexpr uint32_t kSkip = 0xFFFFFFFFu;   // byte offset that the range check of a buffer descriptor rejects
+
+// Array behind a buffer descriptor: a byte offset of kSkip (or any offset past the end) reads zeros
+// and writes nothing, so predicated accesses need neither branches nor zero-initialised registers.
+// Offsets are 32-bit: the array must be smaller than 4 GiB.
 struct BufferArray {
     __amdgpu_buffer_rsrc_t rsrc;
     __device__ __forceinline__ BufferArray(const void *base, uint64_t bytes)
         : rsrc(__builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (uint32_t)bytes, 0x00020000)) {}
-    __device__ __forceinline__ uint32_t u32(uint32_t index, bool valid) const {
-        return __builtin_amdgcn_raw_buffer_load_b32(rsrc, valid ? index * 4u : 0xFFFFFFFFu, 0, 0);
+    __device__ __forceinline__ uint32_t u32(uint32_t byte_off) const {
+        return __builtin_amdgcn_raw_buffer_load_b32(rsrc, byte_off, 0, 0);
     }
-    __device__ __forceinline__ uint4 group(uint32_t index, bool valid) const {
-        const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, valid ? index * 16u : 0xFFFFFFFFu, 0, 0);
+    template <int kPlus>
+    __device__ __forceinline__ uint4 u128(uint32_t byte_off) const {
+        const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, byte_off, kPlus, 0);
         return make_uint4(v.x, v.y, v.z, v.w);
     }
-};
-// Same interface on plain pointers, for arrays of 4 GiB and more.
-struct PointerArray {
-    const void *base;
-    __device__ __forceinline__ PointerArray(const void *b, uint64_t) : base(b) {}
-    __device__ __forceinline__ uint32_t u32(uint32_t index, bool valid) const {
-        return valid ? static_cast<const uint32_t *>(base)[index] : 0u;
-    }
-    __device__ __forceinline__ uint4 group(uint32_t index, bool valid) const {
-        return valid ? static_cast<const uint4 *>(base)[index] : make_uint4(0, 0, 0, 0);
+    __device__ __forceinline__ void put(uint32_t byte_off, uint32_t value) const {
+        __builtin_amdgcn_raw_buffer_store_b32(value, rsrc, byte_off, 0, 0);
     }
 };
-
 struct NumericSizes {
     uint64_t pairs, a_tiles, b_tiles, a_groups, b_groups;   // element counts of the arrays
 };
@@ -86,11 +81,10 @@ struct NumericSizes {
 // What a lane needs to write out its column of one output tile: lane l of a group of four tiles
 // holds, after the transposition, column l%16 of all 16 rows of tile l/16.
 struct Emission {
-    uint4 m0, m1;             // the tile's 16 row masks, 16 bits each
+    uint4 m0, m1;             // the tile's 16 row masks, 16 bits each (all zero: no such tile)
     uint4 o0, o1, o2, o3;     // per row: position of the tile's first entry, from the start of the tile-row
     int64_t base;             // position of the tile-row's first entry in C
     int32_t col;              // column of this lane inside C
-    bool valid;               // the lane's tile exists
 };
 
 __device__ __forceinline__ void swap_rows(float &x, float &y, bool halves) {
@@ -103,9 +97,11 @@ __device__ __forceinline__ void swap_rows(float &x, float &y, bool halves) {
     y = __uint_as_float(r[1]);
 }
 
-template <class Array, int kTilesPerWave>
+// kNarrow: every array is smaller than 4 GiB and is addressed through a buffer descriptor with
+// 32-bit byte offsets; otherwise 64-bit pointers and branches.
+template <bool kNarrow, int kTilesPerWave>
 __global__ __launch_bounds__(kNumThreads) void k_numeric(
-    const int64_t c_tiles, const NumericSizes z, const int64_t *__restrict__ pair_off,
+    const int64_t c_tiles, const int64_t c_nnz, const NumericSizes z, const int64_t *__restrict__ pair_off,
     const int32_t *__restrict__ pair_a_, const int32_t *__restrict__ pair_b_, const uint32_t *__restrict__ a_lmask_,
     const uint32_t *__restrict__ a_loff_, const uint4 *__restrict__ a_ldata_, const uint32_t *__restrict__ b_rmask_,
     const uint32_t *__restrict__ b_roff_, const uint4 *__restrict__ b_rdata_, const int32_t *__restrict__ c_tile_row,
@@ -113,11 +109,15 @@ __global__ __launch_bounds__(kNumThreads) void k_numeric(
     const uint32_t *__restrict__ c_row_off, const int64_t *__restrict__ c_row_ptr, int32_t *__restrict__ c_col,
     float *__restrict__ c_val) {
     static_assert(kTilesPerWave % kGroupTiles == 0 && kTilesPerWave <= 32, "whole groups; offsets fit one wave load");
+    // headers of the 64 task-list entries a wave is working on, one 16-byte record per entry; one
+    // spare record per wave: the second half-wave may address the entry after the last one
+    __shared__ uint4 lds_heads[kNumThreads / 64][kBlockEntries + 16];
     // consecutive logical blocks on the same XCD (workgroups are dealt to the XCDs round-robin)
     const int per_xcd = gridDim.x / kXcds;
     const int logical = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
     // wave-uniform values are kept in scalar registers; their loads become scalar loads
-    const int64_t wave = (int64_t)logical * (kNumThreads / 64) + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wave_in_block = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t wave = (int64_t)logical * (kNumThreads / 64) + wave_in_block;
     const int64_t run_begin = wave * kTilesPerWave;
     if (run_begin >= c_tiles) return;
     const int run_tiles = (int)min((int64_t)kTilesPerWave, c_tiles - run_begin);
@@ -125,10 +125,13 @@ __global__ __launch_bounds__(kNumThreads) void k_numeric(
     const int hl = lane & 31, upper = lane >> 5;
     const uint32_t bit = 1u << hl, below = bit - 1u;
     const int j = lane & 15, tq = lane >> 4;
-    const Array pair_a(pair_a_, z.pairs * 4), pair_b(pair_b_, z.pairs * 4);
-    const Array a_lmask(a_lmask_, z.a_tiles * 4), a_loff(a_loff_, z.a_tiles * 4);
-    const Array b_rmask(b_rmask_, z.b_tiles * 4), b_roff(b_roff_, z.b_tiles * 4);
-    const Array a_ldata(a_ldata_, z.a_groups * 16), b_rdata(b_rdata_, z.b_groups * 16);
+    // descriptors (used by the narrow kernels only)
+    const BufferArray pair_a(pair_a_, z.pairs * 4), pair_b(pair_b_, z.pairs * 4);
+    const BufferArray a_lmask(a_lmask_, z.a_tiles * 4), a_loff(a_loff_, z.a_tiles * 4);
+    const BufferArray b_rmask(b_rmask_, z.b_tiles * 4), b_roff(b_roff_, z.b_tiles * 4);
+    const BufferArray a_ldata(a_ldata_, z.a_groups * 16), b_rdata(b_rdata_, z.b_groups * 16);
+    uint4 *const my_heads = lds_heads[wave_in_block];
+    const uint4 *const my_half = my_heads + upper;    // lanes 32-63 read the entry after the one lanes 0-31 read
 
     // segment bounds of the run's tiles, relative to the first one (one vector load, then scalars)
     const int64_t off_lane = pair_off[run_begin + min(lane, run_tiles)];
@@ -137,32 +140,53 @@ __global__ __launch_bounds__(kNumThreads) void k_numeric(
     const int rel_lane = (int)(off_lane - base);
     const int rel_end = __builtin_amdgcn_readlane(rel_lane, kTilesPerWave);        // lanes >= run_tiles hold the end
 
-    // 64 consecutive task-list entries starting at relative position `start`, one per lane, with the
-    // headers of their tiles; lanes past the end of the wave's entries hold all-zero headers
-    auto load_headers = [&](int start) {
+    // 64 consecutive task-list entries starting at relative position `start`, one per lane: the
+    // headers of their tiles go to LDS, where any lane can read any entry's record with one load
+    // (entries past the end of the wave's run leave all-zero records: empty tiles)
+    auto stage_headers = [&](int start) {
         const bool valid = start + lane < rel_end;
-        const uint32_t e = (uint32_t)(base + start + lane);
-        const uint32_t a = pair_a.u32(e, valid), b = pair_b.u32(e, valid);
-        return Header{a_lmask.u32(a, valid), a_loff.u32(a, valid), b_rmask.u32(b, valid), b_roff.u32(b, valid)};
+        uint4 record = make_uint4(0, 0, 0, 0);
+        if constexpr (kNarrow) {
+            const uint32_t e = valid ? (uint32_t)(base + start + lane) * 4u : kSkip;
+            const uint32_t a = pair_a.u32(e), b = pair_b.u32(e);
+            const uint32_t ao = valid ? a * 4u : kSkip, bo = valid ? b * 4u : kSkip;
+            // group offsets become byte offsets: the descriptors address bytes
+            record = make_uint4(a_lmask.u32(ao), a_loff.u32(ao) << 4, b_rmask.u32(bo), b_roff.u32(bo) << 4);
+        } else if (valid) {
+            const int64_t e = base + start + lane;
+            const int64_t a = pair_a_[e], b = pair_b_[e];
+            record = make_uint4(a_lmask_[a], a_loff_[a], b_rmask_[b], b_roff_[b]);
+        }
+        wave_sync();                               // earlier reads of the records are done
+        my_heads[lane] = record;
+        wave_sync();
     };
-    // operands of the entry held by lane `src` for this lane, or zeros when the entry is not part of
-    // the current segment (valid == false) or the group is empty
-    auto load_operands = [&](const Header &h, int src, bool valid, Group &av, Group &bv) {
-        const uint32_t lm = (uint32_t)__shfl((int)h.lm, src, 64), lo = (uint32_t)__shfl((int)h.lo, src, 64);
-        const uint32_t rm = (uint32_t)__shfl((int)h.rm, src, 64), ro = (uint32_t)__shfl((int)h.ro, src, 64);
-        av.u = a_ldata.group(lo + __popc(lm & below), valid && (lm & bit) != 0);
-        bv.u = b_rdata.group(ro + __popc(rm & below), valid && (rm & bit) != 0);
+    // operands of a step (entry `src` of the block for lanes 0-31, entry src+1 for lanes 32-63, the
+    // latter only if two == true): the lane's 16-byte group of the A tile and of the B tile, zeros
+    // when the group is empty
+    auto load_operands = [&](int src, bool two, Group &av, Group &bv) {
+        const uint4 h = my_half[src];
+        const uint32_t mine = (two || !upper) ? bit : 0u;
+        if constexpr (kNarrow) {
+            const uint32_t ao = ((uint32_t)__popc(h.x & below) << 4) + h.y;
+            const uint32_t bo = ((uint32_t)__popc(h.z & below) << 4) + h.w;
+            av.u = a_ldata.template u128<0>((h.x & mine) ? ao : kSkip);
+            bv.u = b_rdata.template u128<0>((h.z & mine) ? bo : kSkip);
+        } else {
+            av.u = (h.x & mine) ? a_ldata_[(uint64_t)h.y + __popc(h.x & below)] : make_uint4(0, 0, 0, 0);
+            bv.u = (h.z & mine) ? b_rdata_[(uint64_t)h.w + __popc(h.z & below)] : make_uint4(0, 0, 0, 0);
+        }
     };
-    // multiply the `count` entries that start at lane `o` of the headers h into acc, two entries per
-    // MFMA; the loads of up to four MFMAs are requested together
-    auto multiply = [&](const Header &h, int o, int count, float4v &acc) {
+    // multiply the `count` entries that start at entry `o` of the staged block into acc, two entries
+    // per MFMA; the loads of up to four MFMAs are requested together
+    auto multiply = [&](int o, int count, float4v &acc) {
         for (int it = 0; it < count; it += 8) {
             Group a0, b0, a1, b1, a2, b2, a3, b3;
             const int left = count - it;                                // > 0, uniform
-            load_operands(h, (o + it + upper) & 63, upper < left, a0, b0);
-            if (left > 2) load_operands(h, (o + it + 2 + upper) & 63, 2 + upper < left, a1, b1);
-            if (left > 4) load_operands(h, (o + it + 4 + upper) & 63, 4 + upper < left, a2, b2);
-            if (left > 6) load_operands(h, (o + it + 6 + upper) & 63, 6 + upper < left, a3, b3);
+            load_operands(o + it, left > 1, a0, b0);
+            if (left > 2) load_operands(o + it + 2, left > 3, a1, b1);
+            if (left > 4) load_operands(o + it + 4, left > 5, a2, b2);
+            if (left > 6) load_operands(o + it + 6, left > 7, a3, b3);
             acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a0.h, b0.h, acc, 0, 0, 0);
             if (left > 2) acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1.h, b1.h, acc, 0, 0, 0);
             if (left > 4) acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a2.h, b2.h, acc, 0, 0, 0);
@@ -170,8 +194,8 @@ __global__ __launch_bounds__(kNumThreads) void k_numeric(
         }
     };
 
-    int h_start = 0;                              // relative position of the entry lane 0 of `heads` holds
-    Header heads = load_headers(0);
+    int h_start = 0;                              // relative position of the first staged entry
+    stage_headers(0);
 #pragma unroll
     for (int g = 0; g < kTilesPerWave / kGroupTiles; ++g) {
         if (g * kGroupTiles < run_tiles) {        // uniform
@@ -179,13 +203,23 @@ __global__ __launch_bounds__(kNumThreads) void k_numeric(
             // out column j of tile tq of this group (requesting them afterwards saves 26 registers and
             // gains occupancy, but measured slower: the kernel then waits for them with nothing to do).
             Emission em;
-            em.valid = g * kGroupTiles + tq < run_tiles;
+            const bool mine_exists = g * kGroupTiles + tq < run_tiles;
             {
-                const int64_t c = run_begin + (em.valid ? g * kGroupTiles + tq : 0);
-                const uint4 *mp = reinterpret_cast<const uint4 *>(c_row_mask + c * T);
-                const uint4 *op = reinterpret_cast<const uint4 *>(c_row_off + c * T);
-                em.m0 = mp[0]; em.m1 = mp[1];
-                em.o0 = op[0]; em.o1 = op[1]; em.o2 = op[2]; em.o3 = op[3];
+                const int64_t c = run_begin + (mine_exists ? g * kGroupTiles + tq : 0);
+                if constexpr (kNarrow) {
+                    const BufferArray masks(c_row_mask, (uint64_t)c_tiles * T * 2), offs(c_row_off, (uint64_t)c_tiles * T * 4);
+                    const uint32_t mo = mine_exists ? (uint32_t)c * (T * 2) : kSkip;
+                    const uint32_t oo = mine_exists ? (uint32_t)c * (T * 4) : kSkip;
+                    em.m0 = masks.u128<0>(mo); em.m1 = masks.u128<16>(mo);
+                    em.o0 = offs.u128<0>(oo); em.o1 = offs.u128<16>(oo);
+                    em.o2 = offs.u128<32>(oo); em.o3 = offs.u128<48>(oo);
+                } else {
+                    const uint4 *mp = reinterpret_cast<const uint4 *>(c_row_mask + c * T);
+                    const uint4 *op = reinterpret_cast<const uint4 *>(c_row_off + c * T);
+                    const uint4 none = make_uint4(0, 0, 0, 0);
+                    em.m0 = mine_exists ? mp[0] : none; em.m1 = mine_exists ? mp[1] : none;
+                    em.o0 = op[0]; em.o1 = op[1]; em.o2 = op[2]; em.o3 = op[3];
+                }
                 em.base = c_row_ptr[(int64_t)c_tile_row[c] * T];
                 em.col = c_tile_col[c] * T + j;
             }
@@ -197,17 +231,18 @@ __global__ __launch_bounds__(kNumThreads) void k_numeric(
                 if (tile < run_tiles) {           // uniform
                     const int r0 = __builtin_amdgcn_readlane(rel_lane, tile);
                     const int r1 = __builtin_amdgcn_readlane(rel_lane, tile + 1);
-                    const int n = r1 - r0, first_part = min(n, 64);
-                    // the 64 entries in `heads` must cover the first 64 entries of this segment
-                    if (r0 < h_start || r0 + first_part > h_start + 64) {
+                    const int n = r1 - r0, first_part = min(n, kBlockEntries);
+                    // the staged block must cover the first 64 entries of this segment
+                    if (r0 < h_start || r0 + first_part > h_start + kBlockEntries) {
                         h_start = r0;
-                        heads = load_headers(h_start);
+                        stage_headers(h_start);
                     }
-                    multiply(heads, r0 - h_start, first_part, acc[t]);
+                    multiply(r0 - h_start, first_part, acc[t]);
                     // segments longer than 64 entries: the rest, 64 at a time
-                    for (int s = r0 + 64; s < r1; s += 64) {
-                        const Header h = load_headers(s);
-                        multiply(h, 0, min(r1 - s, 64), acc[t]);
+                    for (int s = r0 + kBlockEntries; s < r1; s += kBlockEntries) {
+                        h_start = s;
+                        stage_headers(s);
+                        multiply(0, min(r1 - s, kBlockEntries), acc[t]);
                     }
                 }
             }
@@ -228,13 +263,33 @@ __global__ __launch_bounds__(kNumThreads) void k_numeric(
             const uint32_t mw[8] = {em.m0.x, em.m0.y, em.m0.z, em.m0.w, em.m1.x, em.m1.y, em.m1.z, em.m1.w};
             const uint32_t ow[16] = {em.o0.x, em.o0.y, em.o0.z, em.o0.w, em.o1.x, em.o1.y, em.o1.z, em.o1.w,
                                      em.o2.x, em.o2.y, em.o2.z, em.o2.w, em.o3.x, em.o3.y, em.o3.z, em.o3.w};
+            // row r of the tile: mask in the low (even r) or high (odd r) half of mw[r / 2]; the entry
+            // of column j exists if its bit is set and sits after the set bits below it
+            const uint32_t my_bit[2] = {1u << j, 1u << (j + 16)};
+            const uint32_t my_below[2] = {(1u << j) - 1u, ((1u << j) - 1u) << 16};
+            if constexpr (kNarrow) {
+                const BufferArray out_col(c_col, (uint64_t)c_nnz * 4), out_val(c_val, (uint64_t)c_nnz * 4);
+                const uint32_t base4 = (uint32_t)em.base << 2;
 #pragma unroll
-            for (int r = 0; r < T; ++r) {
-                const uint32_t m = (r & 1) ? mw[r >> 1] >> 16 : mw[r >> 1] & 0xFFFFu;
-                if (em.valid && ((m >> j) & 1u)) {
-                    const int64_t pos = em.base + (int64_t)ow[r] + __popc(m & ((1u << j) - 1u));
-                    c_col[pos] = em.col;
-                    c_val[pos] = rows[r & 3][r >> 2];
+                for (int r = 0; r < T; ++r) {
+                    const uint32_t w = mw[r >> 1];
+                    // lanes without an entry are switched off rather than sent out of range: a store
+                    // costs by the lanes that take part in it
+                    if (w & my_bit[r & 1]) {
+                        const uint32_t at = (((uint32_t)__popc(w & my_below[r & 1]) + ow[r]) << 2) + base4;
+                        out_col.put(at, (uint32_t)em.col);
+                        out_val.put(at, __float_as_uint(rows[r & 3][r >> 2]));
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int r = 0; r < T; ++r) {
+                    const uint32_t w = mw[r >> 1];
+                    if (w & my_bit[r & 1]) {
+                        const int64_t pos = em.base + (int64_t)ow[r] + __popc(w & my_below[r & 1]);
+                        c_col[pos] = em.col;
+                        c_val[pos] = rows[r & 3][r >> 2];
+                    }
                 }
             }
         }
@@ -259,10 +314,10 @@ int numeric_enqueue(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s
                                   hipMemcpyDeviceToDevice, s);
     if (e == hipSuccess && P->c_tiles > 0) {
         KernelTimer kt(ctx, TSP_KERNEL_NUMERIC, s);
-        // Tiles one wave walks.  Short runs keep the tiles in flight on an XCD close together, so that
-        // the B tiles they share stay in that XCD's L2; long runs amortise the header gather when the
-        // segments are short (measured on the stencil and Laplacian workloads).
-        const int tiles_per_wave = P->pairs > 4 * P->c_tiles ? 4 : 8;
+        // Tiles one wave walks: one group of four measured fastest on all workloads (more waves in
+        // flight); two groups per wave remain available through TSP_OPT_NUMERIC_RUN.
+        int tiles_per_wave = kGroupTiles;
+        if (ctx->numeric_run_len == 4 || ctx->numeric_run_len == 8) tiles_per_wave = ctx->numeric_run_len;
         const int64_t tiles_per_block = (int64_t)(kNumThreads / 64) * tiles_per_wave;
         int64_t blocks = (P->c_tiles + tiles_per_block - 1) / tiles_per_block;
         blocks = (blocks + kXcds - 1) / kXcds * kXcds;             // the XCD remap needs a multiple of 8
@@ -270,10 +325,11 @@ int numeric_enqueue(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s
                              (uint64_t)A->group_capacity, (uint64_t)B->group_capacity};
         const uint64_t limit = (1ull << 32) - 64;
         const bool narrow = z.pairs * 4 < limit && z.a_groups * 16 < limit && z.b_groups * 16 < limit &&
-                            z.a_tiles * 4 < limit && z.b_tiles * 4 < limit && !ctx->force_wide;
-        auto kernel = narrow ? (tiles_per_wave == 4 ? k_numeric<BufferArray, 4> : k_numeric<BufferArray, 8>)
-                             : (tiles_per_wave == 4 ? k_numeric<PointerArray, 4> : k_numeric<PointerArray, 8>);
-        hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(kNumThreads), 0, s, P->c_tiles, z, P->pair_off,
+                            z.a_tiles * 4 < limit && z.b_tiles * 4 < limit && (uint64_t)P->c_tiles * T * 4 < limit &&
+                            (uint64_t)P->c_nnz * 4 < limit && !ctx->force_wide;
+        auto kernel = narrow ? (tiles_per_wave == 4 ? k_numeric<true, 4> : k_numeric<true, 8>)
+                             : (tiles_per_wave == 4 ? k_numeric<false, 4> : k_numeric<false, 8>);
+        hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(kNumThreads), 0, s, P->c_tiles, P->c_nnz, z, P->pair_off,
                            P->pair_a, P->pair_b, A->lmask, A->loff, A->ldata, B->rmask, B->roff, B->rdata,
                            P->c_tile_row, P->c_tile_col, P->c_row_mask, P->c_row_off, P->c_row_ptr, col, val);
         e = hipGetLastError();
