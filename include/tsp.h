@@ -89,8 +89,11 @@ enum {
                                /*    report the durations in tsp_stats; 0 (default): no events      */
     TSP_OPT_WIDE_INDEX = 3,    /* 1: always use the kernels that address arrays of 4 GiB and more   */
                                /*    through 64-bit pointers; 0 (default): chosen from the sizes    */
-    TSP_OPT_NUMERIC_RUN = 4    /* output tiles one wave of the multiplication kernel walks: 4 or 8; */
-                               /*    0 (default): chosen from the mean segment length               */
+    TSP_OPT_NUMERIC_RUN = 4,   /* output tiles one wave of the multiplication kernel walks: 4 or 8; */
+                               /*    0 (default): 4                                                 */
+    TSP_OPT_MATRIX_CORES = 5   /* 1 (default): block products on the MFMA units (Section 4.3);      */
+                               /*    0: on the vector ALUs, one fp32 FMA per inner index and output */
+                               /*    element (the paper's comparison build, Section 5, Algorithm 2) */
 };
 
 /* Phases reported in tsp_stats.phase_us, in pipeline order. */

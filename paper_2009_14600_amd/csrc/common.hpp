@@ -49,6 +49,7 @@ struct tsp_context {
     int timers = 0;
     int force_wide = 0;                            // use the 64-bit-pointer kernels whatever the sizes
     int numeric_run_len = 0;                       // tiles per wave of the multiplication kernel, 0: automatic
+    int matrix_cores = 1;                          // 0: block products on the vector ALUs
     int last_hip = 0;
     tsp_stats stats{};
     void *chain_slots = nullptr;                   // device, for the chained scans (chain.hpp)

@@ -99,7 +99,10 @@ __device__ __forceinline__ void swap_rows(float &x, float &y, bool halves) {
 
 // kNarrow: every array is smaller than 4 GiB and is addressed through a buffer descriptor with
 // 32-bit byte offsets; otherwise 64-bit pointers and branches.
-template <bool kNarrow, int kTilesPerWave>
+// kMatrixCores == false: the block products run on the vector ALUs, every lane looping over the
+// inner index for its four output elements (the paper's comparison build without tensor cores,
+// Section 5, Algorithm 2); everything around the product is shared.
+template <bool kNarrow, int kTilesPerWave, bool kMatrixCores>
 __global__ __launch_bounds__(kNumThreads) void k_numeric(
     const int64_t c_tiles, const int64_t c_nnz, const NumericSizes z, const int64_t *__restrict__ pair_off,
     const int32_t *__restrict__ pair_a_, const int32_t *__restrict__ pair_b_, const uint32_t *__restrict__ a_lmask_,
@@ -112,6 +115,8 @@ __global__ __launch_bounds__(kNumThreads) void k_numeric(
     // headers of the 64 task-list entries a wave is working on, one 16-byte record per entry; one
     // spare record per wave: the second half-wave may address the entry after the last one
     __shared__ uint4 lds_heads[kNumThreads / 64][kBlockEntries + 16];
+    // operand groups of one step, as the lanes loaded them (vector-ALU build only)
+    __shared__ uint4 lds_operands[kMatrixCores ? 1 : kNumThreads / 64][2][64];
     // consecutive logical blocks on the same XCD (workgroups are dealt to the XCDs round-robin)
     const int per_xcd = gridDim.x / kXcds;
     const int logical = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
@@ -180,17 +185,45 @@ __global__ __launch_bounds__(kNumThreads) void k_numeric(
     // multiply the `count` entries that start at entry `o` of the staged block into acc, two entries
     // per MFMA; the loads of up to four MFMAs are requested together
     auto multiply = [&](int o, int count, float4v &acc) {
-        for (int it = 0; it < count; it += 8) {
-            Group a0, b0, a1, b1, a2, b2, a3, b3;
-            const int left = count - it;                                // > 0, uniform
-            load_operands(o + it, left > 1, a0, b0);
-            if (left > 2) load_operands(o + it + 2, left > 3, a1, b1);
-            if (left > 4) load_operands(o + it + 4, left > 5, a2, b2);
-            if (left > 6) load_operands(o + it + 6, left > 7, a3, b3);
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a0.h, b0.h, acc, 0, 0, 0);
-            if (left > 2) acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1.h, b1.h, acc, 0, 0, 0);
-            if (left > 4) acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a2.h, b2.h, acc, 0, 0, 0);
-            if (left > 6) acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a3.h, b3.h, acc, 0, 0, 0);
+        if constexpr (kMatrixCores) {
+            for (int it = 0; it < count; it += 8) {
+                Group a0, b0, a1, b1, a2, b2, a3, b3;
+                const int left = count - it;                                // > 0, uniform
+                load_operands(o + it, left > 1, a0, b0);
+                if (left > 2) load_operands(o + it + 2, left > 3, a1, b1);
+                if (left > 4) load_operands(o + it + 4, left > 5, a2, b2);
+                if (left > 6) load_operands(o + it + 6, left > 7, a3, b3);
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a0.h, b0.h, acc, 0, 0, 0);
+                if (left > 2) acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1.h, b1.h, acc, 0, 0, 0);
+                if (left > 4) acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a2.h, b2.h, acc, 0, 0, 0);
+                if (left > 6) acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a3.h, b3.h, acc, 0, 0, 0);
+            }
+        } else {
+            // Two entries per step, loaded exactly as for the MFMA: lane 32e + 16h + x holds, of entry
+            // e, inner indices 8h..8h+7 of row x of the A tile and of column x of the B tile.  The
+            // groups go through LDS; lane (tq, j) then owns c[4tq+v][j], v = 0..3, and adds
+            // a[4tq+v][k] * b[k][j] over the 16 inner indices of both entries, in fp32.
+            uint4(*const ops)[64] = lds_operands[wave_in_block];
+            for (int it = 0; it < count; it += 2) {
+                Group a, b;
+                load_operands(o + it, count - it > 1, a, b);
+                wave_sync();                       // the previous step's reads are done
+                ops[0][lane] = a.u;
+                ops[1][lane] = b.u;
+                wave_sync();
+#pragma unroll
+                for (int eh = 0; eh < 4; ++eh) {   // entry e = eh / 2, half h = eh % 2
+                    Group col;
+                    col.u = ops[1][16 * eh + j];
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        Group row;
+                        row.u = ops[0][16 * eh + 4 * tq + v];
+#pragma unroll
+                        for (int x = 0; x < 8; ++x) acc[v] = fmaf((float)row.h[x], (float)col.h[x], acc[v]);
+                    }
+                }
+            }
         }
     };
 
@@ -318,6 +351,7 @@ int numeric_enqueue(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s
         // flight); two groups per wave remain available through TSP_OPT_NUMERIC_RUN.
         int tiles_per_wave = kGroupTiles;
         if (ctx->numeric_run_len == 4 || ctx->numeric_run_len == 8) tiles_per_wave = ctx->numeric_run_len;
+        if (!ctx->matrix_cores) tiles_per_wave = kGroupTiles;
         const int64_t tiles_per_block = (int64_t)(kNumThreads / 64) * tiles_per_wave;
         int64_t blocks = (P->c_tiles + tiles_per_block - 1) / tiles_per_block;
         blocks = (blocks + kXcds - 1) / kXcds * kXcds;             // the XCD remap needs a multiple of 8
@@ -327,8 +361,9 @@ int numeric_enqueue(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s
         const bool narrow = z.pairs * 4 < limit && z.a_groups * 16 < limit && z.b_groups * 16 < limit &&
                             z.a_tiles * 4 < limit && z.b_tiles * 4 < limit && (uint64_t)P->c_tiles * T * 4 < limit &&
                             (uint64_t)P->c_nnz * 4 < limit && !ctx->force_wide;
-        auto kernel = narrow ? (tiles_per_wave == 4 ? k_numeric<true, 4> : k_numeric<true, 8>)
-                             : (tiles_per_wave == 4 ? k_numeric<false, 4> : k_numeric<false, 8>);
+        auto kernel = narrow ? (tiles_per_wave == 4 ? k_numeric<true, 4, true> : k_numeric<true, 8, true>)
+                             : (tiles_per_wave == 4 ? k_numeric<false, 4, true> : k_numeric<false, 8, true>);
+        if (!ctx->matrix_cores) kernel = narrow ? k_numeric<true, 4, false> : k_numeric<false, 4, false>;
         hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(kNumThreads), 0, s, P->c_tiles, P->c_nnz, z, P->pair_off,
                            P->pair_a, P->pair_b, A->lmask, A->loff, A->ldata, B->rmask, B->roff, B->rdata,
                            P->c_tile_row, P->c_tile_col, P->c_row_mask, P->c_row_off, P->c_row_ptr, col, val);

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libtsp.so")
 TSP_I32, TSP_I64 = 0, 1
 TSP_F16, TSP_F32 = 0, 1
 FORM_LEFT, FORM_RIGHT = 1, 2
-OPT_VALIDATE, OPT_PHASE_TIMERS, OPT_WIDE_INDEX, OPT_NUMERIC_RUN = 1, 2, 3, 4
+OPT_VALIDATE, OPT_PHASE_TIMERS, OPT_WIDE_INDEX, OPT_NUMERIC_RUN, OPT_MATRIX_CORES = 1, 2, 3, 4, 5
 PHASES = ("convert", "symbolic", "count", "numeric")
 KERNELS = ("validate", "count_tiles", "scan_tiles", "fill_tiles", "sym_count", "scan_sym", "sym_emit",
            "count_masks", "row_offsets", "scan_rows", "numeric")

@@ -268,3 +268,45 @@ def test_phases_against_paper_objects(tsp, handle, oracle, maker):
     C.free(); C2.free(); plan.free(); tA.free()
     if not same:
         tB.free()
+
+
+# ------------------------------------------------------------------ block products without the matrix cores
+@pytest.fixture
+def vector_handle(tsp):
+    """A handle whose multiplication pass runs on the vector ALUs (paper Section 5, the comparison
+    build without tensor cores, Algorithm 2)."""
+    h = tsp.Handle(validate=True)
+    h.set_option(tsp.OPT_MATRIX_CORES, 0)
+    yield h
+    h.close()
+
+
+@pytest.mark.parametrize("index", [1, 2, 3, 4, 5])
+def test_vector_alu_numeric_small_configs(tsp, vector_handle, oracle, index):
+    A = inputs.config(index, small=True)
+    print(f"vector ALU, config {index} small: {A.name} rows={A.rows} nnz={A.nnz}", flush=True)
+    run_and_check(tsp, vector_handle, oracle, A)
+
+
+def test_vector_alu_numeric_rectangular_long_segments_and_subnormals(tsp, vector_handle, oracle):
+    A = inputs.random_sparse(200, 1500, 0.2, 31, empty_row_fraction=0.1, values="uniform")   # segments > 64 entries
+    B = inputs.random_sparse(1500, 90, 0.2, 32, empty_row_fraction=0.1, values="uniform")
+    print("vector ALU, 200x1500x90", flush=True)
+    run_and_check(tsp, vector_handle, oracle, A, B)
+    T1 = inputs.random_sparse(64, 64, 0.2, 31, values="tiny")        # fp16 subnormals must not be flushed
+    T2 = inputs.random_sparse(64, 64, 0.2, 32, values="smallint")
+    print("vector ALU, subnormal inputs", flush=True)
+    _, ref = run_and_check(tsp, vector_handle, oracle, T1, T2)
+    assert (ref.mag > 1e-6).sum() > 100
+
+
+def test_vector_alu_and_matrix_core_patterns_agree(tsp, handle, vector_handle):
+    A = inputs.config(5, small=True)
+    dA = tsp.to_device(A)
+    C1, C2 = handle.spgemm(dA, dA), vector_handle.spgemm(dA, dA)
+    r1, c1, v1 = C1.to_host()
+    r2, c2, v2 = C2.to_host()
+    C1.free()
+    C2.free()
+    assert np.array_equal(r1, r2) and np.array_equal(c1, c2)
+    assert np.allclose(v1, v2, rtol=1e-4, atol=1e-6)
