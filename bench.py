@@ -84,6 +84,8 @@ def main():
     ap.add_argument("--no-validate", action="store_true", help="switch the input validation kernel off")
     ap.add_argument("--no-matrix-cores", action="store_true",
                     help="block products on the vector ALUs instead of MFMA (the paper's nonTCU comparison)")
+    ap.add_argument("--compact-zeros", action="store_true",
+                    help="finish every step with the compaction of zero-valued entries (paper Section 4.4)")
     ap.add_argument("--numeric-run", type=int, default=0, help="tiles per wave of the multiplication kernel (0: automatic)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -107,6 +109,8 @@ def main():
     handle = tsp.Handle(validate=not args.no_validate)
     if args.no_matrix_cores:
         handle.set_option(tsp.OPT_MATRIX_CORES, 0)
+    if args.compact_zeros:
+        handle.set_option(tsp.OPT_COMPACT_ZEROS, 1)
     if args.numeric_run:
         handle.set_option(tsp.OPT_NUMERIC_RUN, args.numeric_run)
 
@@ -229,7 +233,7 @@ def main():
         "config": {"workload": f"configs[{args.workload - 1}]: {inputs.CONFIG_NAMES[args.workload]}",
                    "rows": A.rows, "nnz_A": A.nnz, "products": products, "nnz_C": st["c_nnz"],
                    "a_tiles": st["a_tiles"], "pairs": st["pairs"], "c_tiles": st["c_tiles"],
-                   "validate_inputs": not args.no_validate, "matrix_cores": not args.no_matrix_cores, "first_call_ms": round(first * 1e3, 3)},
+                   "validate_inputs": not args.no_validate, "matrix_cores": not args.no_matrix_cores, "compact_zeros": args.compact_zeros, "first_call_ms": round(first * 1e3, 3)},
         "roofline": roofline, "mfma": mfma, "end_to_end": end_to_end,
         "kernel_us": {k: round(v, 2) for k, v in kavg.items()},
         "phase_us": {k: round(v, 2) for k, v in pavg.items()},

@@ -91,9 +91,11 @@ enum {
                                /*    through 64-bit pointers; 0 (default): chosen from the sizes    */
     TSP_OPT_NUMERIC_RUN = 4,   /* output tiles one wave of the multiplication kernel walks: 4 or 8; */
                                /*    0 (default): 4                                                 */
-    TSP_OPT_MATRIX_CORES = 5   /* 1 (default): block products on the MFMA units (Section 4.3);      */
+    TSP_OPT_MATRIX_CORES = 5,  /* 1 (default): block products on the MFMA units (Section 4.3);      */
                                /*    0: on the vector ALUs, one fp32 FMA per inner index and output */
                                /*    element (the paper's comparison build, Section 5, Algorithm 2) */
+    TSP_OPT_COMPACT_ZEROS = 6  /* 1: tsp_spgemm finishes with tsp_compact_zeros (Algorithm 1 lines  */
+                               /*    19-20); 0 (default): C keeps every structural position         */
 };
 
 /* Phases reported in tsp_stats.phase_us, in pipeline order. */
@@ -163,6 +165,19 @@ int tsp_spgemm(tsp_handle handle, const tsp_csr *A, const tsp_csr *B, tsp_csr *C
 
 /* Release the arrays of a matrix returned by this library and zero the struct. */
 int tsp_csr_free(tsp_handle handle, tsp_csr *C, void *stream);
+
+/*
+ * Compaction of zeros (paper Section 4.4, Algorithm 1 lines 19-20): *out = C without the entries
+ * whose value compares equal to zero (+0.0 and -0.0; NaN stays), order kept, so that a product
+ * whose terms cancelled, or that only met stored zeros, leaves no entry behind.  C: device CSR with
+ * float values (TSP_F32) and a 32- or 64-bit row_ptr, borrowed, not modified; row ranges are
+ * clamped to [0, C.nnz], so a malformed row_ptr cannot cause an out-of-bounds access.  *out:
+ * row_ptr (TSP_I64), col_idx, val (TSP_F32) from the handle's allocator, owned by the caller
+ * (tsp_csr_free); zeroed on failure.  Synchronises the stream once (the new nnz sizes the
+ * allocation).  C and out must be different objects.
+ * Errors: INVALID_ARG, ALLOC_FAILED, INDEX_OVERFLOW, HIP.
+ */
+int tsp_compact_zeros(tsp_handle handle, const tsp_csr *C, tsp_csr *out, void *stream);
 
 /* ----- the pipeline phase by phase (tsp_spgemm is exactly these calls in order) ----------- */
 

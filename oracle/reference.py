@@ -141,6 +141,18 @@ def spgemm(A, B, threads: int = 1) -> OracleResult:
 # Intermediate objects of the paper's pipeline, for small inputs.
 # --------------------------------------------------------------------------------------
 
+def compact_zeros(res: OracleResult) -> OracleResult:
+    """Compaction of zeros (paper Section 4.4; Algorithm 1, the two compaction steps after the
+    multiplication kernel): the entries whose accumulated value is zero are removed, the others
+    keep their order; rows may become empty.  The decision is taken on the value the oracle
+    holds (fp64 sums of exact products), so it equals the GPU's fp32 decision whenever the sums
+    are exact in both (small integers, stored zeros), which is what the parity tests use."""
+    keep = res.val != 0.0
+    before = np.concatenate([[0], np.cumsum(keep)]).astype(np.int64)
+    return OracleResult(res.row_begin, before[res.row_ptr], res.col[keep], res.val[keep], res.mag[keep],
+                        res.products)
+
+
 @dataclass
 class BitmapMatrix:
     """Bitmap format (paper Section 2.1.2): non-empty T x T tiles in COO order (row-major),

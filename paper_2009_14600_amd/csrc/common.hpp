@@ -50,6 +50,7 @@ struct tsp_context {
     int force_wide = 0;                            // use the 64-bit-pointer kernels whatever the sizes
     int numeric_run_len = 0;                       // tiles per wave of the multiplication kernel, 0: automatic
     int matrix_cores = 1;                          // 0: block products on the vector ALUs
+    int compact = 0;                               // 1: tsp_spgemm removes zero-valued entries from C
     int last_hip = 0;
     tsp_stats stats{};
     void *chain_slots = nullptr;                   // device, for the chained scans (chain.hpp)
@@ -145,6 +146,7 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
 void plan_release(tsp_context *ctx, tsp_plan_s *p, hipStream_t s);
 int numeric_enqueue(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s *plan, tsp_csr *C,
                     hipStream_t s);
+int compact_zeros(tsp_context *ctx, const tsp_csr *C, tsp_csr *out, hipStream_t s);
 
 #ifdef __HIPCC__
 // ---- device helpers -------------------------------------------------------------------

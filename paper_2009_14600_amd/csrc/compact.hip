@@ -1,0 +1,181 @@
+// Compaction of zeros (paper Section 4.4, Algorithm 1 lines 19-20): the multiplication pass writes
+// every structural position of C; numerical cancellation (and stored zeros in the inputs) leaves
+// some of them with the value 0.  This pass removes them, so that the result is strictly sparse:
+// count the survivors per row, prefix-sum into the new row_ptr, copy the survivors in order.
+// The paper compacts the element array with a library primitive and drops empty tiles; here the
+// output is already CSR, so a row-wise stream compaction does both.
+#include "chain.hpp"
+#include "common.hpp"
+
+namespace tsp {
+
+constexpr int kCompactThreads = 256;
+constexpr int kCompactLanes = 16;              // lanes that share one CSR row
+
+template <typename RP>
+struct CompactArgs {
+    const RP *row_ptr;
+    const int32_t *col;
+    const float *val;
+    int64_t rows, nnz;
+};
+
+// Entry range of a row, clamped so that a row_ptr that is not monotone or runs past nnz cannot
+// take a read or a write out of bounds (count and copy see the same ranges).
+template <typename RP>
+__device__ __forceinline__ void row_range(const CompactArgs<RP> &a, int64_t row, int64_t &e0, int64_t &e1) {
+    e0 = min(max((int64_t)a.row_ptr[row], (int64_t)0), a.nnz);
+    e1 = min(max((int64_t)a.row_ptr[row + 1], e0), a.nnz);
+}
+
+// +0.0 and -0.0 are zeros, NaN is not
+__device__ __forceinline__ bool survives(float v) { return !(v == 0.0f); }
+
+template <typename RP>
+__global__ __launch_bounds__(kCompactThreads) void k_compact_count(CompactArgs<RP> a, int32_t *__restrict__ keep) {
+    const int64_t row = ((int64_t)blockIdx.x * kCompactThreads + threadIdx.x) / kCompactLanes;
+    const int l = threadIdx.x % kCompactLanes;
+    if (row >= a.rows) return;                 // whole 16-lane groups leave together
+    int64_t e0, e1;
+    row_range(a, row, e0, e1);
+    int n = 0;
+    for (int64_t e = e0 + l; e < e1; e += kCompactLanes) n += survives(a.val[e]) ? 1 : 0;
+#pragma unroll
+    for (int d = kCompactLanes / 2; d > 0; d >>= 1) n += __shfl_xor(n, d, kCompactLanes);
+    if (l == 0) keep[row] = n;
+}
+
+// new row_ptr = exclusive prefix of the survivor counts; one launch, blocks chained (chain.hpp)
+constexpr int kCompactScanItems = 4, kCompactScanBlock = kCompactThreads * kCompactScanItems;
+__global__ __launch_bounds__(kCompactThreads) void k_compact_scan(int64_t rows, const int32_t *__restrict__ keep,
+                                                                 int64_t *__restrict__ new_row_ptr, ChainSlot *slots,
+                                                                 unsigned epoch, int64_t *__restrict__ d_scalars) {
+    __shared__ uint64_t lds[kCompactThreads / 64 + kChainValues];
+    const int64_t i0 = (int64_t)blockIdx.x * kCompactScanBlock + (int64_t)threadIdx.x * kCompactScanItems;
+    int32_t x[kCompactScanItems];
+    uint64_t sum = 0, total;
+#pragma unroll
+    for (int k = 0; k < kCompactScanItems; ++k) {
+        x[k] = i0 + k < rows ? keep[i0 + k] : 0;
+        sum += (uint32_t)x[k];
+    }
+    const uint64_t local = block_exclusive_scan64<kCompactThreads>(sum, &total, lds);
+    unsigned long long agg[kChainValues] = {total, 0, 0}, prefix[kChainValues];
+    chain_exclusive_prefix(slots, epoch, agg, prefix, lds + kCompactThreads / 64, d_scalars + S_INTERNAL);
+    uint64_t run = prefix[0] + local;
+#pragma unroll
+    for (int k = 0; k < kCompactScanItems; ++k) {
+        if (i0 + k < rows) new_row_ptr[i0 + k] = (int64_t)run;
+        run += (uint32_t)x[k];
+    }
+    if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) {
+        new_row_ptr[rows] = (int64_t)(prefix[0] + total);
+        d_scalars[S_C_NNZ] = (int64_t)(prefix[0] + total);
+    }
+}
+
+template <typename RP>
+__global__ __launch_bounds__(kCompactThreads) void k_compact_fill(CompactArgs<RP> a,
+                                                                 const int64_t *__restrict__ new_row_ptr,
+                                                                 int32_t *__restrict__ out_col,
+                                                                 float *__restrict__ out_val) {
+    const int64_t row = ((int64_t)blockIdx.x * kCompactThreads + threadIdx.x) / kCompactLanes;
+    const int l = threadIdx.x % kCompactLanes;
+    if (row >= a.rows) return;
+    int64_t e0, e1;
+    row_range(a, row, e0, e1);
+    int64_t at = new_row_ptr[row];
+    const int shift = (threadIdx.x & 63) / kCompactLanes * kCompactLanes;   // this group's bits in the wave ballot
+    for (int64_t e = e0; e < e1; e += kCompactLanes) {                     // the 16 lanes run the same trip count
+        const bool in = e + l < e1;
+        const float v = in ? a.val[e + l] : 0.0f;
+        const bool on = in && survives(v);
+        const uint32_t mine = (uint32_t)(__ballot(on) >> shift) & 0xFFFFu;
+        if (on) {
+            const int64_t p = at + __popc(mine & ((1u << l) - 1u));
+            out_col[p] = a.col[e + l];
+            out_val[p] = v;
+        }
+        at += __popc(mine);
+    }
+}
+
+__global__ void k_compact_clear(int64_t *d_scalars) {
+    if (threadIdx.x == 0) {
+        d_scalars[S_INTERNAL] = 0;
+        d_scalars[S_C_NNZ] = 0;
+    }
+}
+
+template <typename RP>
+static int compact_run(tsp_context *ctx, const tsp_csr *C, tsp_csr *out, hipStream_t s) {
+    const int64_t rows = C->rows;
+    CompactArgs<RP> a{static_cast<const RP *>(C->row_ptr), C->col_idx, static_cast<const float *>(C->val), rows, C->nnz};
+    int32_t *keep = ctx_alloc_n<int32_t>(ctx, (size_t)rows + 1, s);
+    int64_t *new_row_ptr = ctx_alloc_n<int64_t>(ctx, (size_t)rows + 1, s);
+    int32_t *col = nullptr;
+    float *val = nullptr;
+    auto fail = [&](int code) {
+        ctx_free(ctx, keep, s);
+        ctx_free(ctx, new_row_ptr, s);
+        ctx_free(ctx, col, s);
+        ctx_free(ctx, val, s);
+        return code;
+    };
+    if (!keep || !new_row_ptr) return fail(TSP_ERR_ALLOC_FAILED);
+    const int64_t row_blocks = (rows * kCompactLanes + kCompactThreads - 1) / kCompactThreads;
+    const int64_t scan_blocks = rows > 0 ? (rows + kCompactScanBlock - 1) / kCompactScanBlock : 1;
+    unsigned epoch = 0;
+    ChainSlot *slots = static_cast<ChainSlot *>(chain_prepare(ctx, scan_blocks, &epoch, s));
+    if (!slots) return fail(TSP_ERR_ALLOC_FAILED);
+    hipLaunchKernelGGL(k_compact_clear, dim3(1), dim3(64), 0, s, ctx->d_scalars);
+    if (rows > 0)
+        hipLaunchKernelGGL(k_compact_count<RP>, dim3((unsigned)row_blocks), dim3(kCompactThreads), 0, s, a, keep);
+    hipLaunchKernelGGL(k_compact_scan, dim3((unsigned)scan_blocks), dim3(kCompactThreads), 0, s, rows, keep,
+                       new_row_ptr, slots, epoch, ctx->d_scalars);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(hip_fail(ctx, e));
+    int rc = read_scalars(ctx, s);                       // host synchronisation: the new nnz
+    if (rc) return fail(rc);
+    if (ctx->h_scalars[S_INTERNAL]) return fail(TSP_ERR_HIP);
+    const int64_t nnz = ctx->h_scalars[S_C_NNZ];
+    col = ctx_alloc_n<int32_t>(ctx, (size_t)nnz, s);
+    val = ctx_alloc_n<float>(ctx, (size_t)nnz, s);
+    if (!col || !val) return fail(TSP_ERR_ALLOC_FAILED);
+    if (rows > 0 && nnz > 0) {
+        hipLaunchKernelGGL(k_compact_fill<RP>, dim3((unsigned)row_blocks), dim3(kCompactThreads), 0, s, a, new_row_ptr,
+                           col, val);
+        e = hipGetLastError();
+        if (e != hipSuccess) return fail(hip_fail(ctx, e));
+    }
+    ctx_free(ctx, keep, s);
+    out->rows = C->rows;
+    out->cols = C->cols;
+    out->nnz = nnz;
+    out->row_ptr = new_row_ptr;
+    out->col_idx = col;
+    out->val = val;
+    out->row_ptr_type = TSP_I64;
+    out->val_type = TSP_F32;
+    return TSP_OK;
+}
+
+int compact_zeros(tsp_context *ctx, const tsp_csr *C, tsp_csr *out, hipStream_t s) {
+    std::memset(out, 0, sizeof(*out));
+    if (C->rows < 0 || C->cols < 0 || C->nnz < 0 || !C->row_ptr) return TSP_ERR_INVALID_ARG;
+    if (C->val_type != TSP_F32) return TSP_ERR_INVALID_ARG;
+    if (C->nnz > 0 && (!C->col_idx || !C->val)) return TSP_ERR_INVALID_ARG;
+    if (C->rows >= INT32_MAX - 16) return TSP_ERR_INDEX_OVERFLOW;
+    if (C->row_ptr_type == TSP_I64) return compact_run<int64_t>(ctx, C, out, s);
+    if (C->row_ptr_type == TSP_I32) return compact_run<int32_t>(ctx, C, out, s);
+    return TSP_ERR_INVALID_ARG;
+}
+
+}  // namespace tsp
+
+using namespace tsp;
+
+extern "C" int tsp_compact_zeros(tsp_handle ctx, const tsp_csr *C, tsp_csr *out, void *stream) {
+    if (!ctx || !C || !out || C == out) return TSP_ERR_INVALID_ARG;
+    return compact_zeros(ctx, C, out, (hipStream_t)stream);
+}

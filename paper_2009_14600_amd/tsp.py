@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libtsp.so")
 TSP_I32, TSP_I64 = 0, 1
 TSP_F16, TSP_F32 = 0, 1
 FORM_LEFT, FORM_RIGHT = 1, 2
-OPT_VALIDATE, OPT_PHASE_TIMERS, OPT_WIDE_INDEX, OPT_NUMERIC_RUN, OPT_MATRIX_CORES = 1, 2, 3, 4, 5
+OPT_VALIDATE, OPT_PHASE_TIMERS, OPT_WIDE_INDEX, OPT_NUMERIC_RUN, OPT_MATRIX_CORES, OPT_COMPACT_ZEROS = 1, 2, 3, 4, 5, 6
 PHASES = ("convert", "symbolic", "count", "numeric")
 KERNELS = ("validate", "count_tiles", "scan_tiles", "fill_tiles", "sym_count", "scan_sym", "sym_emit",
            "count_masks", "row_offsets", "scan_rows", "numeric")
@@ -25,7 +25,8 @@ KERNELS = ("validate", "count_tiles", "scan_tiles", "fill_tiles", "sym_count", "
 EXPORTS = [
     "tsp_create", "tsp_destroy", "tsp_set_option", "tsp_trim", "tsp_spgemm", "tsp_csr_free",
     "tsp_convert", "tsp_tiles_free", "tsp_tiles_get_view", "tsp_symbolic", "tsp_plan_free",
-    "tsp_plan_get_view", "tsp_numeric", "tsp_get_stats", "tsp_strerror", "tsp_last_hip_error",
+    "tsp_plan_get_view", "tsp_numeric", "tsp_compact_zeros", "tsp_get_stats", "tsp_strerror",
+    "tsp_last_hip_error",
 ]
 
 
@@ -106,6 +107,7 @@ def load_library():
     lib.tsp_plan_free.argtypes = [vp, vp, vp]
     lib.tsp_plan_get_view.argtypes = [vp, P(_PlanView)]
     lib.tsp_numeric.argtypes = [vp, vp, vp, vp, P(_Csr), vp]
+    lib.tsp_compact_zeros.argtypes = [vp, P(_Csr), P(_Csr), vp]
     lib.tsp_get_stats.argtypes = [vp, P(_Stats)]
     lib.tsp_strerror.argtypes = [ci]
     lib.tsp_strerror.restype = ctypes.c_char_p
@@ -265,6 +267,13 @@ class Handle:
         sb = sa if B is A else B._struct()
         out = _Csr()
         _check(self._lib.tsp_spgemm(self._h, ctypes.byref(sa), ctypes.byref(sb), ctypes.byref(out), self._stream()))
+        return self._wrap_output(out)
+
+    def compact_zeros(self, C: DeviceCSR) -> DeviceCSR:
+        """C without its zero-valued entries (tsp_compact_zeros)."""
+        sc = C._struct()
+        out = _Csr()
+        _check(self._lib.tsp_compact_zeros(self._h, ctypes.byref(sc), ctypes.byref(out), self._stream()))
         return self._wrap_output(out)
 
     def spgemm_raw(self, sa: _Csr, sb: _Csr):

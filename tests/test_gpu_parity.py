@@ -310,3 +310,88 @@ def test_vector_alu_and_matrix_core_patterns_agree(tsp, handle, vector_handle):
     C2.free()
     assert np.array_equal(r1, r2) and np.array_equal(c1, c2)
     assert np.allclose(v1, v2, rtol=1e-4, atol=1e-6)
+
+
+# ------------------------------------------------------------------ compaction of zeros (Section 4.4)
+def _assert_same_csr(C, want, what):
+    row_ptr, col, val = C.to_host()
+    assert np.array_equal(row_ptr, want.row_ptr), f"{what}: row_ptr differs"
+    assert np.array_equal(col, want.col), f"{what}: col_idx differs"
+    assert np.array_equal(val.astype(np.float64), want.val), f"{what}: values differ"
+
+
+@pytest.mark.parametrize("M,K,N,density,seed", [
+    (23, 31, 17, 0.3, 1), (300, 200, 500, 0.05, 2), (64, 2000, 64, 0.1, 3), (1, 1, 1, 1.0, 4)])
+def test_compact_zeros_small_integers(tsp, handle, oracle, M, K, N, density, seed):
+    """Small-integer values: all sums are exact in fp32 and fp64, so both sides drop the same entries."""
+    A = inputs.random_sparse(M, K, density, seed, empty_row_fraction=0.1, values="smallint")
+    B = inputs.random_sparse(K, N, density, seed + 9, empty_row_fraction=0.1, values="smallint")
+    print(f"compaction {M}x{K}x{N}", flush=True)
+    dA, dB = tsp.to_device(A), tsp.to_device(B)
+    C = handle.spgemm(dA, dB)
+    ref = oracle.spgemm(A, B)
+    want = oracle.compact_zeros(ref)
+    D = handle.compact_zeros(C)
+    try:
+        assert C.nnz == ref.nnz and D.nnz == want.nnz
+        _assert_same_csr(D, want, "tsp_compact_zeros")
+    finally:
+        C.free()
+        D.free()
+
+
+def test_compact_zeros_option_cancellation_stored_zeros_and_empty(tsp, oracle):
+    h = tsp.Handle(validate=True)
+    h.set_option(tsp.OPT_COMPACT_ZEROS, 1)
+    try:
+        A = inputs.from_coo(2, 2, [0, 0, 1, 1], [0, 1, 0, 1], [1.0, -1.0, 2.0, 0.0], name="cancel")
+        B = inputs.from_coo(2, 2, [0, 0, 1, 1], [0, 1, 0, 1], [1.0, 1.0, 1.0, 1.0], name="ones")
+        C = h.spgemm(tsp.to_device(A), tsp.to_device(B))
+        _assert_same_csr(C, oracle.compact_zeros(oracle.spgemm(A, B)), "option, worked example")
+        assert C.nnz == 2
+        C.free()
+        # 0/1 matrix: nothing cancels, the option changes nothing
+        G = inputs.rmat(9, 8, seed=6)
+        dG = tsp.to_device(G)
+        C = h.spgemm(dG, dG)
+        ref = oracle.spgemm(G, G)
+        assert C.nnz == ref.nnz
+        _assert_same_csr(C, oracle.compact_zeros(ref), "option, 0/1 matrix")
+        C.free()
+        # all-zero values: every row becomes empty
+        Z = inputs.random_sparse(50, 50, 0.2, 8, values="ones")
+        Z.val[:] = 0
+        dZ = tsp.to_device(Z)
+        C = h.spgemm(dZ, dZ)
+        assert C.nnz == 0 and int(C.row_ptr.abs().sum()) == 0
+        C.free()
+        # empty operands
+        E = inputs.random_sparse(40, 30, 0.0, 9)
+        F = inputs.random_sparse(30, 20, 0.3, 10)
+        C = h.spgemm(tsp.to_device(E), tsp.to_device(F))
+        assert C.nnz == 0 and (C.rows, C.cols) == (40, 20)
+        C.free()
+    finally:
+        h.close()
+
+
+def test_compact_zeros_on_a_caller_matrix_with_int32_row_ptr(tsp, handle):
+    import torch
+    rng = np.random.default_rng(12)
+    rows, cols = 1000, 777
+    lens = rng.integers(0, 40, rows)
+    row_ptr = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    nnz = int(row_ptr[-1])
+    col = np.concatenate([np.sort(rng.choice(cols, n, replace=False)) for n in lens]).astype(np.int32)
+    val = rng.integers(-1, 2, nnz).astype(np.float32)          # about a third zeros, some of them -0.0
+    val[::7] = -0.0
+    val[5] = np.nan
+    C = tsp.DeviceCSR(rows, cols, torch.from_numpy(row_ptr).cuda(), torch.from_numpy(col).cuda(),
+                      torch.from_numpy(val).cuda())
+    D = handle.compact_zeros(C)
+    keep = ~(val == 0.0)
+    want_ptr = np.concatenate([[0], np.cumsum(keep)])[row_ptr]
+    rp, c, v = D.to_host()
+    D.free()
+    assert np.array_equal(rp, want_ptr) and np.array_equal(c, col[keep])
+    assert np.array_equal(v.view(np.uint32), val[keep].view(np.uint32))

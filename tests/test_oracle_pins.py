@@ -212,3 +212,35 @@ def test_row_range_and_threads_agree(oracle):
     part = oracle.spgemm_rows(A, A, 100, 117)
     lo, hi = full.row_ptr[100], full.row_ptr[117]
     assert np.array_equal(part.col, full.col[lo:hi]) and np.array_equal(part.val, full.val[lo:hi])
+
+
+# ------------------------------------------------------------------ compaction of zeros (Section 4.4)
+def test_compaction_worked_example(oracle):
+    """A = [[1,-1],[2,0s]], B = [[1,1],[1,1]] (0s = stored zero): A*B = [[0,0],[2,2]] structurally
+    full; compaction leaves row 0 empty and row 1 = {(0,2),(1,2)} (computed by hand)."""
+    A = inputs.from_coo(2, 2, [0, 0, 1, 1], [0, 1, 0, 1], [1.0, -1.0, 2.0, 0.0], name="cancel")
+    B = inputs.from_coo(2, 2, [0, 0, 1, 1], [0, 1, 0, 1], [1.0, 1.0, 1.0, 1.0], name="ones")
+    ref = oracle.spgemm(A, B)
+    assert ref.nnz == 4 and list(ref.val) == [0.0, 0.0, 2.0, 2.0]
+    out = oracle.compact_zeros(ref)
+    assert list(out.row_ptr) == [0, 0, 2]
+    assert list(out.col) == [0, 1] and list(out.val) == [2.0, 2.0]
+
+
+@pytest.mark.parametrize("M,K,N,density,seed", [(23, 31, 17, 0.3, 1), (40, 40, 40, 0.2, 2), (8, 64, 8, 0.5, 3)])
+def test_compaction_equals_nonzeros_of_the_dense_product(oracle, M, K, N, density, seed):
+    """Small-integer values: every sum is exact, so the compacted pattern is exactly the set of
+    non-zero entries of the brute-force dense product (many entries cancel)."""
+    A = inputs.random_sparse(M, K, density, seed, values="smallint")
+    B = inputs.random_sparse(K, N, density, seed + 9, values="smallint")
+    c, _, pat = brute_force_product(A, B)
+    out = oracle.compact_zeros(oracle.spgemm(A, B))
+    want = pat & (c != 0.0)
+    assert want.sum() < pat.sum(), "the case should contain cancellations"
+    got = np.zeros_like(want)
+    for i in range(M):
+        cols = out.col[out.row_ptr[i]:out.row_ptr[i + 1]]
+        assert np.all(np.diff(cols) > 0)
+        got[i, cols] = True
+        assert np.array_equal(out.val[out.row_ptr[i]:out.row_ptr[i + 1]], c[i, cols])
+    assert np.array_equal(got, want)
