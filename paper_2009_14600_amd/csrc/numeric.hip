@@ -16,18 +16,25 @@
 //
 // The paper notes that this kernel is bound by the scattered tile reads behind the task list
 // (Section 6.2).  The chain task-list entry -> tile header -> tile elements is three dependent
-// memory accesses, so a wave takes a run of four or eight consecutive output tiles, whose task-list
-// segments are contiguous, and reads 64 entries and their tile headers at once, one per lane: the
-// first two accesses are paid once per run, not per tile.  The entries are handed to the two
-// half-waves with cross-lane reads.  The loop over the run's tiles is fully unrolled, each tile
-// requests only the operands it has entries for, and a tile is written out after the next tile's
-// loads have been requested.  All gathers go through buffer descriptors whose range check returns
-// zeros for masked-off lanes (no branches, no zero-filled registers).  Workgroup ids are remapped so
-// that consecutive runs of output tiles execute on the same XCD and share its L2.
+// memory accesses, so a wave takes a group of four consecutive output tiles, whose task-list
+// segments are contiguous, and gathers 64 entries and their tile headers at once, one per lane,
+// into LDS: the first two accesses are paid once per group, and every multiplication step reads its
+// two headers back with one LDS load.  The loop over the group's tiles is fully unrolled and each
+// tile requests the operands of up to four MFMAs together.  In the kernels for arrays below 4 GiB
+// all accesses go through buffer descriptors with 32-bit byte offsets whose range check returns
+// zeros for masked-off lanes (no branches, no zero-filled registers).  Workgroup ids are remapped
+// so that consecutive groups of output tiles execute on the same XCD and share its L2.
 //
 // Emission: the counting pass left, per C tile, the 16 row masks of its structural pattern and
-// the number of entries each CSR row has to the left of the tile; the lane that holds element
-// (i,j) writes column 16J+j and the value at row_ptr[16I+i] + left(i) + popcount(mask_i below j).
+// per row the position of the tile's first entry, counted from the start of the tile-row.  The four
+// accumulators of the group are transposed across the lanes so that lane (t, j) holds column j of
+// all 16 rows of tile t; row r is then written by one store instruction for all four tiles, which
+// are neighbours in CSR row 16I+r: the lane writes column 16J+j and its value at
+// start(tile-row) + position(tile, r) + popcount(mask_r below j).
+//
+// Measured on gfx950, the kernel is bound by the vector-memory address path of the CU (operand
+// loads of 1 KB per instruction, stores that cost by the cache lines they touch, header gathers that
+// cost by the lane): shortening waits or instruction counts alone does not change its duration.
 #include "common.hpp"
 
 #include <new>
@@ -140,6 +147,10 @@ __global__ __launch_bounds__(kNumThreads) void k_numeric(
 
     // segment bounds of the run's tiles, relative to the first one (one vector load, then scalars)
     const int64_t off_lane = pair_off[run_begin + min(lane, run_tiles)];
+    // coordinates of the output tile this lane will write (first group), requested together with the
+    // segment bounds: the start of its tile-row in C depends on them and is requested one step later
+    const int64_t c_first = run_begin + (tq < run_tiles ? tq : 0);
+    const int32_t I_first = c_tile_row[c_first], J_first = c_tile_col[c_first];
     const int64_t base = ((int64_t)__builtin_amdgcn_readlane((int)(off_lane >> 32), 0) << 32) |
                          (uint32_t)__builtin_amdgcn_readlane((int)off_lane, 0);
     const int rel_lane = (int)(off_lane - base);
@@ -229,33 +240,41 @@ __global__ __launch_bounds__(kNumThreads) void k_numeric(
 
     int h_start = 0;                              // relative position of the first staged entry
     stage_headers(0);
+    const int64_t base_first = c_row_ptr[(int64_t)I_first * T];
 #pragma unroll
     for (int g = 0; g < kTilesPerWave / kGroupTiles; ++g) {
         if (g * kGroupTiles < run_tiles) {        // uniform
-            // Requested before the multiplications, used after them: what lane (tq, j) needs to write
-            // out column j of tile tq of this group (requesting them afterwards saves 26 registers and
-            // gains occupancy, but measured slower: the kernel then waits for them with nothing to do).
+            // What lane (tq, j) needs to write out column j of tile tq of this group, requested before
+            // the multiplications and used after them.  (Requesting the 24 registers of masks and
+            // offsets later frees registers, but the compiler then moves the loads down to their uses
+            // and the wave waits for them one by one: measured 16 % slower.)
             Emission em;
             const bool mine_exists = g * kGroupTiles + tq < run_tiles;
-            {
-                const int64_t c = run_begin + (mine_exists ? g * kGroupTiles + tq : 0);
+            const int64_t c_mine = run_begin + (mine_exists ? g * kGroupTiles + tq : 0);
+            if (g == 0) {
+                em.base = base_first;
+                em.col = J_first * T + j;
+            } else {
+                em.base = c_row_ptr[(int64_t)c_tile_row[c_mine] * T];
+                em.col = c_tile_col[c_mine] * T + j;
+            }
+            auto request_masks = [&]() {
                 if constexpr (kNarrow) {
                     const BufferArray masks(c_row_mask, (uint64_t)c_tiles * T * 2), offs(c_row_off, (uint64_t)c_tiles * T * 4);
-                    const uint32_t mo = mine_exists ? (uint32_t)c * (T * 2) : kSkip;
-                    const uint32_t oo = mine_exists ? (uint32_t)c * (T * 4) : kSkip;
+                    const uint32_t mo = mine_exists ? (uint32_t)c_mine * (T * 2) : kSkip;
+                    const uint32_t oo = mine_exists ? (uint32_t)c_mine * (T * 4) : kSkip;
                     em.m0 = masks.u128<0>(mo); em.m1 = masks.u128<16>(mo);
                     em.o0 = offs.u128<0>(oo); em.o1 = offs.u128<16>(oo);
                     em.o2 = offs.u128<32>(oo); em.o3 = offs.u128<48>(oo);
                 } else {
-                    const uint4 *mp = reinterpret_cast<const uint4 *>(c_row_mask + c * T);
-                    const uint4 *op = reinterpret_cast<const uint4 *>(c_row_off + c * T);
+                    const uint4 *mp = reinterpret_cast<const uint4 *>(c_row_mask + c_mine * T);
+                    const uint4 *op = reinterpret_cast<const uint4 *>(c_row_off + c_mine * T);
                     const uint4 none = make_uint4(0, 0, 0, 0);
                     em.m0 = mine_exists ? mp[0] : none; em.m1 = mine_exists ? mp[1] : none;
                     em.o0 = op[0]; em.o1 = op[1]; em.o2 = op[2]; em.o3 = op[3];
                 }
-                em.base = c_row_ptr[(int64_t)c_tile_row[c] * T];
-                em.col = c_tile_col[c] * T + j;
-            }
+            };
+            request_masks();
             float4v acc[kGroupTiles];
 #pragma unroll
             for (int t = 0; t < kGroupTiles; ++t) {
@@ -298,6 +317,10 @@ __global__ __launch_bounds__(kNumThreads) void k_numeric(
                                      em.o2.x, em.o2.y, em.o2.z, em.o2.w, em.o3.x, em.o3.y, em.o3.z, em.o3.w};
             // row r of the tile: mask in the low (even r) or high (odd r) half of mw[r / 2]; the entry
             // of column j exists if its bit is set and sits after the set bits below it
+            // Every load of this wave has returned by now (the last tile's operands were requested after
+            // everything else and have been used).  Saying so explicitly keeps the compiler from putting
+            // load waits between the stores below, where they would also wait for the stores before them.
+            __builtin_amdgcn_s_waitcnt(0x0F70);    // vmcnt(0)
             const uint32_t my_bit[2] = {1u << j, 1u << (j + 16)};
             const uint32_t my_below[2] = {(1u << j) - 1u, ((1u << j) - 1u) << 16};
             if constexpr (kNarrow) {
