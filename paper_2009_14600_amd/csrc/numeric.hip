@@ -163,11 +163,14 @@ __global__ __launch_bounds__(kNumThreads) void k_numeric(
         const bool valid = start + lane < rel_end;
         uint4 record = make_uint4(0, 0, 0, 0);
         if constexpr (kNarrow) {
-            const uint32_t e = valid ? (uint32_t)(base + start + lane) * 4u : kSkip;
-            const uint32_t a = pair_a.u32(e), b = pair_b.u32(e);
-            const uint32_t ao = valid ? a * 4u : kSkip, bo = valid ? b * 4u : kSkip;
-            // group offsets become byte offsets: the descriptors address bytes
-            record = make_uint4(a_lmask.u32(ao), a_loff.u32(ao) << 4, b_rmask.u32(bo), b_roff.u32(bo) << 4);
+            // lanes without an entry are switched off, not sent out of range: a gather costs by the
+            // lanes that take part in it
+            if (valid) {
+                const uint32_t e = (uint32_t)(base + start + lane) * 4u;
+                const uint32_t ao = pair_a.u32(e) * 4u, bo = pair_b.u32(e) * 4u;
+                // group offsets become byte offsets: the descriptors address bytes
+                record = make_uint4(a_lmask.u32(ao), a_loff.u32(ao) << 4, b_rmask.u32(bo), b_roff.u32(bo) << 4);
+            }
         } else if (valid) {
             const int64_t e = base + start + lane;
             const int64_t a = pair_a_[e], b = pair_b_[e];
