@@ -4,7 +4,6 @@
 // count the survivors per row, prefix-sum into the new row_ptr, copy the survivors in order.
 // The paper compacts the element array with a library primitive and drops empty tiles; here the
 // output is already CSR, so a row-wise stream compaction does both.
-#include "chain.hpp"
 #include "common.hpp"
 
 namespace tsp {
@@ -43,35 +42,6 @@ __global__ __launch_bounds__(kCompactThreads) void k_compact_count(CompactArgs<R
 #pragma unroll
     for (int d = kCompactLanes / 2; d > 0; d >>= 1) n += __shfl_xor(n, d, kCompactLanes);
     if (l == 0) keep[row] = n;
-}
-
-// new row_ptr = exclusive prefix of the survivor counts; one launch, blocks chained (chain.hpp)
-constexpr int kCompactScanItems = 4, kCompactScanBlock = kCompactThreads * kCompactScanItems;
-__global__ __launch_bounds__(kCompactThreads) void k_compact_scan(int64_t rows, const int32_t *__restrict__ keep,
-                                                                 int64_t *__restrict__ new_row_ptr, ChainSlot *slots,
-                                                                 unsigned epoch, int64_t *__restrict__ d_scalars) {
-    __shared__ uint64_t lds[kCompactThreads / 64 + kChainValues];
-    const int64_t i0 = (int64_t)blockIdx.x * kCompactScanBlock + (int64_t)threadIdx.x * kCompactScanItems;
-    int32_t x[kCompactScanItems];
-    uint64_t sum = 0, total;
-#pragma unroll
-    for (int k = 0; k < kCompactScanItems; ++k) {
-        x[k] = i0 + k < rows ? keep[i0 + k] : 0;
-        sum += (uint32_t)x[k];
-    }
-    const uint64_t local = block_exclusive_scan64<kCompactThreads>(sum, &total, lds);
-    unsigned long long agg[kChainValues] = {total, 0, 0}, prefix[kChainValues];
-    chain_exclusive_prefix(slots, epoch, agg, prefix, lds + kCompactThreads / 64, d_scalars + S_INTERNAL);
-    uint64_t run = prefix[0] + local;
-#pragma unroll
-    for (int k = 0; k < kCompactScanItems; ++k) {
-        if (i0 + k < rows) new_row_ptr[i0 + k] = (int64_t)run;
-        run += (uint32_t)x[k];
-    }
-    if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) {
-        new_row_ptr[rows] = (int64_t)(prefix[0] + total);
-        d_scalars[S_C_NNZ] = (int64_t)(prefix[0] + total);
-    }
 }
 
 template <typename RP>
@@ -124,18 +94,18 @@ static int compact_run(tsp_context *ctx, const tsp_csr *C, tsp_csr *out, hipStre
     };
     if (!keep || !new_row_ptr) return fail(TSP_ERR_ALLOC_FAILED);
     const int64_t row_blocks = (rows * kCompactLanes + kCompactThreads - 1) / kCompactThreads;
-    const int64_t scan_blocks = rows > 0 ? (rows + kCompactScanBlock - 1) / kCompactScanBlock : 1;
-    unsigned epoch = 0;
-    ChainSlot *slots = static_cast<ChainSlot *>(chain_prepare(ctx, scan_blocks, &epoch, s));
-    if (!slots) return fail(TSP_ERR_ALLOC_FAILED);
+    int64_t *tmp = ctx_alloc_n<int64_t>(ctx, scan_tmp_entries(rows), s);
+    if (!tmp) return fail(TSP_ERR_ALLOC_FAILED);
     hipLaunchKernelGGL(k_compact_clear, dim3(1), dim3(64), 0, s, ctx->d_scalars);
     if (rows > 0)
         hipLaunchKernelGGL(k_compact_count<RP>, dim3((unsigned)row_blocks), dim3(kCompactThreads), 0, s, a, keep);
-    hipLaunchKernelGGL(k_compact_scan, dim3((unsigned)scan_blocks), dim3(kCompactThreads), 0, s, rows, keep,
-                       new_row_ptr, slots, epoch, ctx->d_scalars);
+    // new row_ptr = exclusive prefix of the survivor counts, the total to the scalar block
+    int rc = scan_exclusive_i32_to_i64(ctx, keep, new_row_ptr, rows, ctx->d_scalars + S_C_NNZ, nullptr, tmp, s);
+    ctx_free(ctx, tmp, s);
+    if (rc) return fail(rc);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(hip_fail(ctx, e));
-    int rc = read_scalars(ctx, s);                       // host synchronisation: the new nnz
+    rc = read_scalars(ctx, s);                           // host synchronisation: the new nnz
     if (rc) return fail(rc);
     if (ctx->h_scalars[S_INTERNAL]) return fail(TSP_ERR_HIP);
     const int64_t nnz = ctx->h_scalars[S_C_NNZ];
