@@ -22,7 +22,8 @@
  *    undefined.  A stored entry is structural whatever its value (an explicit 0.0 counts).
  *  - The output pattern is structural: position (i,j) is present when some k has a_ik and
  *    b_kj stored, also when the terms cancel (the counting pass of Section 4.2 defines the
- *    size; the numeric-zero compaction of Section 4.4 is not applied).
+ *    size).  The numeric-zero compaction of Section 4.4 is a separate call,
+ *    tsp_compact_zeros, or the option TSP_OPT_COMPACT_ZEROS.
  */
 #ifndef TSP_H
 #define TSP_H
@@ -155,11 +156,15 @@ int tsp_trim(tsp_handle handle, void *stream);
  * On success *C is filled: rows = A.rows, cols = B.cols, nnz, row_ptr (TSP_I64), col_idx,
  * val (TSP_F32), the three arrays freshly taken from the handle's allocator and owned by the
  * caller, who releases them with tsp_csr_free.  Columns ascend strictly within each row.
- * On failure *C is zeroed and nothing is leaked.  When the call returns, the stream has been
- * synchronised (the sizes of the task list and of C are read back to size the allocations,
- * the step Algorithm 1 calls AllocateMemGPU) and C is complete.
+ * On failure *C is zeroed and nothing is leaked.  The call synchronises the stream twice (the
+ * sizes of the task list and of C are read back to size the allocations, the steps Algorithm 1
+ * calls AllocateMemGPU); the multiplication pass that fills col_idx and val is enqueued after the
+ * second and is NOT waited for: C.nnz and the pointers are final when the call returns, the
+ * contents once the stream has reached that point (hipStreamSynchronize, or further work on the
+ * same stream).  With TSP_OPT_PHASE_TIMERS the call waits for the end.
  * Errors: INVALID_ARG, SHAPE_MISMATCH, NOT_CANONICAL, ALLOC_FAILED, INDEX_OVERFLOW, HIP,
- * UNSUPPORTED (B has more than 2^24 tile columns, i.e. B.cols > 268 million).
+ * UNSUPPORTED (a tile-row of C spans more than 131072 tile columns between its first and its
+ * last candidate tile, i.e. 2097152 columns; or a tile-row of C holds 2^32 entries or more).
  */
 int tsp_spgemm(tsp_handle handle, const tsp_csr *A, const tsp_csr *B, tsp_csr *C, void *stream);
 
@@ -240,7 +245,8 @@ typedef struct {
     const int64_t *pair_off;         /* int64[c_tiles + 1] segment offsets into the task list       */
     const int32_t *pair_a, *pair_b;  /* int32[pairs] tile index in A / in B                         */
     const uint16_t *c_row_mask;      /* uint16[c_tiles * 16] structural pattern of each output tile */
-    const uint32_t *c_row_off;       /* uint32[c_tiles * 16] entries of CSR row 16I+r before tile   */
+    const uint32_t *c_row_off;       /* uint32[c_tiles * 16] position of the tile's first entry in  */
+                                     /* CSR row 16I+r, counted from the first entry of tile-row I   */
     const int64_t *c_row_ptr;        /* int64[c_rows + 1]                                           */
 } tsp_plan_view;
 int tsp_plan_get_view(tsp_plan plan, tsp_plan_view *view);

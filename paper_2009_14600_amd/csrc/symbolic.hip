@@ -515,6 +515,12 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
         return code;
     };
 
+    // a failed HIP call leaves through cleanup(), which releases the scratch arrays and the plan
+#define SYM_CHECK(expr)                                              \
+    do {                                                             \
+        hipError_t e_ = (expr);                                      \
+        if (e_ != hipSuccess) return cleanup(hip_fail(ctx, e_));     \
+    } while (0)
     phase_begin(ctx, TSP_PHASE_SYMBOLIC, s);
     row_jmin = ctx_alloc_n<int32_t>(ctx, (size_t)ntr + 1, s);
     row_c_tiles = ctx_alloc_n<int32_t>(ctx, (size_t)ntr + 1, s);
@@ -547,7 +553,7 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
         const int threads = per_row <= 256 ? 64 : per_row <= 4096 ? 128 : kSymThreads;
         hipLaunchKernelGGL(k_sym_count, dim3((unsigned)ntr), dim3(threads), max_words * sizeof(uint32_t), s, ra, rb,
                            lanes, max_words, row_jmin, row_c_tiles, row_pairs, row_words, row_cand, ctx->d_scalars);
-        TSP_HIP_CHECK(ctx, hipGetLastError());
+        SYM_CHECK(hipGetLastError());
     }
     {
         KernelTimer kt(ctx, TSP_KERNEL_SCAN_SYM, s);
@@ -558,7 +564,7 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
         hipLaunchKernelGGL(k_sym_row_scan, dim3((unsigned)blocks), dim3(kRowScanThreads), 0, s, ntr, row_c_tiles,
                            row_pairs, row_words, row_cand, P->c_tile_row_ptr, row_pair_ptr, slots, epoch,
                            ctx->d_scalars);
-        TSP_HIP_CHECK(ctx, hipGetLastError());
+        SYM_CHECK(hipGetLastError());
     }
     if (!rc) rc = read_scalars(ctx, s);                                    // ---- sync 1: sizes of the task list
     if (rc) return cleanup(rc);
@@ -599,9 +605,9 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
         hipLaunchKernelGGL(k_sym_emit, dim3((unsigned)ntr), dim3(threads), lds, s, ra, rb, lanes, words_cap,
                            window, row_jmin, P->c_tile_row_ptr, row_pair_ptr, P->c_tile_row, P->c_tile_col,
                            P->pair_off, P->pair_a, P->pair_b);
-        TSP_HIP_CHECK(ctx, hipGetLastError());
+        SYM_CHECK(hipGetLastError());
     } else {
-        TSP_HIP_CHECK(ctx, hipMemsetAsync(P->pair_off, 0, sizeof(int64_t), s));
+        SYM_CHECK(hipMemsetAsync(P->pair_off, 0, sizeof(int64_t), s));
     }
     phase_end(ctx, TSP_PHASE_SYMBOLIC, s);
 
@@ -618,7 +624,7 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
         hipLaunchKernelGGL(k_row_offsets, dim3(grid), dim3(256), 0, s, ntr, P->c_rows, P->c_tile_row_ptr,
                            P->c_row_mask, P->c_row_off, row_nnz, ctx->d_scalars);
     }
-    TSP_HIP_CHECK(ctx, hipGetLastError());
+    SYM_CHECK(hipGetLastError());
     {
         KernelTimer kt(ctx, TSP_KERNEL_SCAN_ROWS, s);
         rc = scan_exclusive_i32_to_i64(ctx, row_nnz, P->c_row_ptr, P->c_rows, ctx->d_scalars + S_C_NNZ, nullptr, tmp,
@@ -638,6 +644,7 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
     *out = P;
     return cleanup(TSP_OK);
 }
+#undef SYM_CHECK
 
 }  // namespace tsp
 
