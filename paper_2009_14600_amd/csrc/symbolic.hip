@@ -398,10 +398,15 @@ __global__ __launch_bounds__(256) void k_count_masks(int64_t c_tiles, const int6
                                                      const uint16_t *__restrict__ a_row_mask,
                                                      const uint16_t *__restrict__ b_row_mask,
                                                      uint16_t *__restrict__ c_row_mask) {
+    // the 16 row masks of the B tiles of a batch of four pairs, per 16-lane group: every lane fetches
+    // one mask and reads all 16 back (two 16-byte LDS loads instead of two 16-byte global loads per
+    // lane: the kernel is bound by the vector-memory address path, not by LDS)
+    __shared__ uint4 lds_b[256 / 16][4][2];
     const int per_xcd = gridDim.x / 8;
     const int64_t logical = (int64_t)(blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
     const int64_t c = (logical * blockDim.x + threadIdx.x) >> 4;
     const int r = threadIdx.x & 15;
+    uint4(*const mine)[2] = lds_b[threadIdx.x >> 4];
     const bool in = c < c_tiles;
     const int64_t s0 = in ? pair_off[c] : 0, s1 = in ? pair_off[c + 1] : 0;
     uint32_t acc = 0;
@@ -414,22 +419,22 @@ __global__ __launch_bounds__(256) void k_count_masks(int64_t c_tiles, const int6
         }
         const int cnt = (int)max((int64_t)0, min((int64_t)16, s1 - base));
         for (int i = 0; __any(i < cnt); i += 4) {
-            uint32_t am[4];
-            uint4 x[4], y[4];
+            uint32_t am[4], bm[4];
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const int a = __shfl(a_mine, (i + u) & 15, 16), b = __shfl(b_mine, (i + u) & 15, 16);
-                am[u] = 0;
-                x[u] = y[u] = make_uint4(0, 0, 0, 0);
+                am[u] = bm[u] = 0;
                 if (i + u < cnt) {
                     am[u] = a_row_mask[(int64_t)a * T + r];
-                    const uint4 *bp = reinterpret_cast<const uint4 *>(b_row_mask + (int64_t)b * T);
-                    x[u] = bp[0];
-                    y[u] = bp[1];
+                    bm[u] = b_row_mask[(int64_t)b * T + r];
                 }
             }
+            wave_sync();                           // the previous batch has been read
 #pragma unroll
-            for (int u = 0; u < 4; ++u) acc |= boolean_row_product(am[u], x[u], y[u]);
+            for (int u = 0; u < 4; ++u) reinterpret_cast<uint16_t *>(mine[u])[r] = (uint16_t)bm[u];
+            wave_sync();
+#pragma unroll
+            for (int u = 0; u < 4; ++u) acc |= boolean_row_product(am[u], mine[u][0], mine[u][1]);
         }
     }
     if (in) c_row_mask[c * T + r] = (uint16_t)((acc | (acc >> 16)) & 0xFFFFu);
