@@ -57,12 +57,18 @@ def _ptr(a: np.ndarray):
 class _Operand:
     """Contiguous int64/int32/float64 arrays of a CSR matrix for the C calls."""
 
-    def __init__(self, m):
+    def __init__(self, m, full_precision: bool = False):
         self.rows, self.cols = int(m.rows), int(m.cols)
         self.row_ptr = np.ascontiguousarray(m.row_ptr, dtype=np.int64)
         self.col = np.ascontiguousarray(m.col_idx, dtype=np.int32)
-        # the inputs are fp16 numbers; widening them to fp64 is exact
-        self.val = np.ascontiguousarray(np.asarray(m.val, dtype=np.float16).astype(np.float64))
+        if full_precision:
+            # the values as stored (fp32 or fp64 inputs, not rounded): the "full precision" side of
+            # the paper's precision comparison (Section 6.3)
+            self.val = np.ascontiguousarray(np.asarray(m.val).astype(np.float64))
+        else:
+            # the inputs are fp16 numbers (others are rounded to nearest-even fp16 first, Section
+            # 2.6); widening them to fp64 is exact
+            self.val = np.ascontiguousarray(np.asarray(m.val).astype(np.float16).astype(np.float64))
 
 
 def row_nnz(A, B, row_begin: int = 0, row_end: int | None = None):
@@ -116,11 +122,12 @@ def spgemm_rows(A, B, row_begin: int, row_end: int, _ops=None) -> OracleResult:
     return OracleResult(row_begin, row_ptr, col, val, mag, int(products))
 
 
-def spgemm(A, B, threads: int = 1) -> OracleResult:
+def spgemm(A, B, threads: int = 1, full_precision: bool = False) -> OracleResult:
     """All of C = A*B.  threads > 1 runs independent row blocks on a thread pool (the C
     calls release the GIL); every row is still computed by the same serial code, so the
-    result does not depend on the thread count."""
-    ops = (_Operand(A), _Operand(B))
+    result does not depend on the thread count.  full_precision: use the stored values
+    without the rounding to fp16 (the reference side of the precision study, Section 6.3)."""
+    ops = (_Operand(A, full_precision), _Operand(B, full_precision))
     rows = ops[0].rows
     if threads <= 1 or rows < 4 * threads:
         return spgemm_rows(A, B, 0, rows, _ops=ops)

@@ -395,3 +395,31 @@ def test_compact_zeros_on_a_caller_matrix_with_int32_row_ptr(tsp, handle):
     D.free()
     assert np.array_equal(rp, want_ptr) and np.array_equal(c, col[keep])
     assert np.array_equal(v.view(np.uint32), val[keep].view(np.uint32))
+
+
+# ------------------------------------------------------------------ precision study (Section 6.3, Eq. 3)
+def test_smape_against_full_precision_as_in_the_paper(tsp, handle, oracle):
+    """The paper's two observations on synthetic inputs: 0/1 patterns give SMAPE 0 %; real
+    fp32 inputs, rounded to fp16 on the device, give a SMAPE of a few hundredths of a percent
+    against a full-precision product of the unrounded values."""
+    import torch
+    G = inputs.rmat(10, 8, seed=3)
+    C = handle.spgemm(tsp.to_device(G), tsp.to_device(G))
+    _, _, val = C.to_host()
+    C.free()
+    assert oracle.smape_percent(oracle.spgemm(G, G, full_precision=True).val, val) == 0.0
+
+    rng = np.random.default_rng(63)
+    A = inputs.random_sparse(700, 700, 0.02, 41)
+    A32 = inputs.CSRMatrix(A.rows, A.cols, A.row_ptr, A.col_idx, rng.uniform(-1, 1, A.nnz).astype(np.float32), "fp32")
+    dA = tsp.DeviceCSR(A.rows, A.cols, torch.from_numpy(A32.row_ptr.astype(np.int32)).cuda(),
+                       torch.from_numpy(A32.col_idx.astype(np.int32)).cuda(), torch.from_numpy(A32.val).cuda())
+    C = handle.spgemm(dA, dA)
+    full = oracle.spgemm(A32, A32, full_precision=True)
+    assert_matches_oracle(C, oracle.spgemm(A32, A32), "fp32 inputs")     # parity with the fp16-rounded oracle
+    _, col, val = C.to_host()
+    C.free()
+    assert np.array_equal(col, full.col)
+    s = oracle.smape_percent(full.val, val)
+    print(f"SMAPE against full precision: {s:.4f} %", flush=True)
+    assert 0.0 < s < 0.1

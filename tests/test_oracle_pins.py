@@ -244,3 +244,38 @@ def test_compaction_equals_nonzeros_of_the_dense_product(oracle, M, K, N, densit
         got[i, cols] = True
         assert np.array_equal(out.val[out.row_ptr[i]:out.row_ptr[i + 1]], c[i, cols])
     assert np.array_equal(got, want)
+
+
+# ------------------------------------------------------------------ precision measure (Section 6.3, Eq. 3)
+def test_smape_hand_computed(oracle):
+    """x = (1, 2), x^ = (1.1, 1.8): 100/2 * (0.1/2.1 + 0.2/3.8) = 5.01253...%; symmetric in its
+    arguments; a pair of zeros contributes nothing."""
+    want = 50.0 * (0.1 / 2.1 + 0.2 / 3.8)
+    assert abs(oracle.smape_percent([1.0, 2.0], [1.1, 1.8]) - want) < 1e-12
+    assert abs(oracle.smape_percent([1.1, 1.8], [1.0, 2.0]) - want) < 1e-12
+    assert oracle.smape_percent([0.0, 1.0], [0.0, 1.0]) == 0.0
+    assert abs(oracle.smape_percent([0.0, 1.0], [0.0, -1.0]) - 50.0) < 1e-12     # opposite signs: a full term
+
+
+def test_full_precision_reference_differs_only_by_the_fp16_rounding(oracle):
+    rng = np.random.default_rng(7)
+    A = inputs.random_sparse(60, 50, 0.2, 21)
+    A32 = inputs.CSRMatrix(A.rows, A.cols, A.row_ptr, A.col_idx, rng.uniform(-1, 1, A.nnz).astype(np.float32), "fp32")
+    full = oracle.spgemm(A32, _t(A32), full_precision=True)
+    rounded = oracle.spgemm(A32, _t(A32))
+    c, _, _ = brute_force_product(A32, _t(A32))            # dense triple loop on the unrounded values
+    got = np.zeros_like(c)
+    for i in range(A32.rows):
+        got[i, full.col[full.row_ptr[i]:full.row_ptr[i + 1]]] = full.val[full.row_ptr[i]:full.row_ptr[i + 1]]
+    assert np.allclose(got, c, rtol=1e-13, atol=1e-15)
+    assert np.array_equal(full.col, rounded.col)
+    s = oracle.smape_percent(full.val, rounded.val)
+    assert 0.0 < s < 0.1, s                               # fp16 rounding: relative 2^-11 per operand at most
+
+
+def _t(A):
+    """Transpose of a CSR matrix (host, any value type)."""
+    rows = np.repeat(np.arange(A.rows), np.diff(A.row_ptr))
+    order = np.lexsort((rows, A.col_idx))
+    row_ptr = np.concatenate([[0], np.cumsum(np.bincount(A.col_idx, minlength=A.cols))]).astype(np.int32)
+    return inputs.CSRMatrix(A.cols, A.rows, row_ptr, rows[order].astype(np.int32), np.asarray(A.val)[order], "t")
