@@ -58,9 +58,7 @@ def algorithmic_bytes(kernel, A, st, groups_left, groups_right):
     tile_meta = ta * (4 + 32 + 4 + 4 + 4 + 4)          # tile_col, row masks, 2 group masks, 2 group offsets
     csr_in = 4 * (n + 1) + 6 * nnz
     table = {
-        "validate": 4 * (n + 1) + 4 * nnz,
-        "count_tiles": 4 * (n + 1) + 4 * nnz + 4 * ntr,
-        "fill_tiles": csr_in + 4 * ntr + tile_meta + 16 * (groups_left + groups_right),
+        "convert": csr_in + 8 * ntr + tile_meta + 16 * (groups_left + groups_right),
         # symbolic kernels: tile CSR of A, and per candidate the B tile's column and occupancy word
         "sym_count": 8 * ntr + 8 * ta + 8 * st["candidate_pairs"] + 12 * ntr,
         "sym_emit": 8 * ntr + 8 * ta + 8 * st["candidate_pairs"] + 16 * ntr + 16 * ct + 8 * pairs,
@@ -69,7 +67,7 @@ def algorithmic_bytes(kernel, A, st, groups_left, groups_right):
         "numeric": (8 * ct + 8 * pairs + 8 * ct + 32 * ct + 64 * ct + 8 * (n + 1)      # task list, C tile info
                     + 16 * ta + 16 * (groups_left + groups_right)                    # tiles, each once
                     + 8 * cnnz),                                                     # C col_idx + val
-        "scan_tiles": 12 * ntr, "scan_sym": 24 * ntr, "scan_rows": 16 * n,
+        "scan_sym": 24 * ntr, "scan_rows": 16 * n,
     }
     return int(table[kernel])
 
@@ -163,8 +161,9 @@ def main():
     # group counts of the tile storage, for the algorithmic byte model
     tiles = handle.convert(dA)
     tv = tiles.view()
-    groups_left = int(popcount32(tv["left_group_mask"].cpu().numpy().view(np.uint32)).sum())
-    groups_right = int(popcount32(tv["right_group_mask"].cpu().numpy().view(np.uint32)).sum())
+    valid = tsp.tile_indices(tv)                           # the tile arrays have unused slots between tile-rows
+    groups_left = int(popcount32(tv["left_group_mask"][valid].cpu().numpy().view(np.uint32)).sum())
+    groups_right = int(popcount32(tv["right_group_mask"][valid].cpu().numpy().view(np.uint32)).sum())
     tiles.free()
 
     dominant = max(kavg, key=kavg.get)

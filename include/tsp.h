@@ -108,20 +108,17 @@ enum {
     TSP_PHASE_COUNT_ = 4
 };
 
-/* Kernels reported in tsp_stats.kernel_us (a prefix sum is three small launches, timed together). */
+/* Kernels reported in tsp_stats.kernel_us (a prefix sum of three small launches is timed as one). */
 enum {
-    TSP_KERNEL_VALIDATE = 0,
-    TSP_KERNEL_COUNT_TILES = 1,
-    TSP_KERNEL_SCAN_TILES = 2,
-    TSP_KERNEL_FILL_TILES = 3,
-    TSP_KERNEL_SYM_COUNT = 4,
-    TSP_KERNEL_SCAN_SYM = 5,
-    TSP_KERNEL_SYM_EMIT = 6,
-    TSP_KERNEL_COUNT_MASKS = 7,
-    TSP_KERNEL_ROW_OFFSETS = 8,
-    TSP_KERNEL_SCAN_ROWS = 9,
-    TSP_KERNEL_NUMERIC = 10,
-    TSP_KERNEL_COUNT_ = 11
+    TSP_KERNEL_CONVERT = 0,      /* CSR -> tiles, one pass (when B is not A: B's conversion)        */
+    TSP_KERNEL_SYM_COUNT = 1,    /* C tiles and task-list entries per tile-row                      */
+    TSP_KERNEL_SCAN_SYM = 2,     /* their prefix sums                                               */
+    TSP_KERNEL_SYM_EMIT = 3,     /* C tile coordinates and task list                                */
+    TSP_KERNEL_COUNT_MASKS = 4,  /* counting pass: boolean products of the bitmaps                  */
+    TSP_KERNEL_ROW_OFFSETS = 5,  /* entries per CSR row, write offsets per (C tile, row)            */
+    TSP_KERNEL_SCAN_ROWS = 6,    /* row_ptr of C                                                    */
+    TSP_KERNEL_NUMERIC = 7,      /* multiplication pass + CSR emission                              */
+    TSP_KERNEL_COUNT_ = 8
 };
 
 /* Counters and timings of the most recent tsp_spgemm / phase calls on a handle. */
@@ -192,17 +189,23 @@ enum {
 };
 
 /*
- * CSR -> tile format (Section 2.1.2 with 16x16 tiles): tile occupancy scan, then per-tile
- * packing.  `forms` is a bit set of TSP_FORM_*.  Synchronises the stream once (tile count).
- * The result is owned by the caller (tsp_tiles_free).
+ * CSR -> tile format (Section 2.1.2 with 16x16 tiles), one pass over the matrix.  `forms` is a
+ * bit set of TSP_FORM_*.  Synchronises the stream once (tile count, validation result).
+ * The result is owned by the caller (tsp_tiles_free).  The tile arrays have one slot per stored
+ * entry of A (52 bytes each) although only the slots of actual tiles are written: that is
+ * what lets the conversion run without a counting pass (see tsp_tiles_view).
  */
 int tsp_convert(tsp_handle handle, const tsp_csr *A, int forms, tsp_tiles *out, void *stream);
 int tsp_tiles_free(tsp_handle handle, tsp_tiles tiles, void *stream);
 
 /*
  * Read-only view of a tile matrix, for inspection and tests.  Device pointers unless noted.
- * Tiles are stored tile-row by tile-row, ascending tile column inside a tile-row (CSR of
- * tiles).  row_mask[t*16 + r] has bit c set when slot (r,c) of tile t is occupied.
+ * The tiles of tile-row I are the tile indices tile_row_ptr[I] .. tile_row_end[I]-1, ascending
+ * tile column among them.  tile_row_ptr[I] is the position of the tile-row's first entry in the
+ * CSR arrays, so tile indices ("slots") run up to tile_slots = nnz and the indices between two
+ * tile-rows are unused: their array elements are never written and must not be read.  A tile
+ * index is what the task list of a plan holds.
+ * row_mask[t*16 + r] has bit c set when slot (r,c) of tile t is occupied.
  * Element storage is in 16-byte groups of 8 fp16 values, zero filled where a slot is empty,
  * and only non-empty groups are stored.  Left form: group id g = h*16 + r holds slots
  * (r, 8h..8h+7); right form: group id g = h*16 + c holds slots (8h..8h+7, c).  Bit g of the
@@ -212,13 +215,15 @@ int tsp_tiles_free(tsp_handle handle, tsp_tiles tiles, void *stream);
 typedef struct {
     int64_t rows, cols;              /* of the matrix (host values)                                 */
     int64_t tile_rows, tile_cols;    /* ceil(rows/16), ceil(cols/16)                                */
-    int64_t ntiles;
+    int64_t ntiles;                  /* number of tiles                                             */
+    int64_t tile_slots;              /* length of the per-tile arrays (= nnz of the matrix)          */
     int32_t forms;
-    const int32_t *tile_row_ptr;     /* int32[tile_rows + 1]                                        */
-    const int32_t *tile_col;         /* int32[ntiles]                                               */
-    const uint16_t *row_mask;        /* uint16[ntiles * 16]                                         */
-    const uint32_t *left_group_mask, *right_group_mask;   /* uint32[ntiles] (always present)        */
-    const uint32_t *left_group_off, *right_group_off;     /* uint32[ntiles] (NULL if form absent)   */
+    const int32_t *tile_row_ptr;     /* int32[tile_rows] first tile index of every tile-row          */
+    const int32_t *tile_row_end;     /* int32[tile_rows] one past its last tile index                */
+    const int32_t *tile_col;         /* int32[tile_slots]                                            */
+    const uint16_t *row_mask;        /* uint16[tile_slots * 16]                                      */
+    const uint32_t *left_group_mask, *right_group_mask;   /* uint32[tile_slots] (always present)     */
+    const uint32_t *left_group_off, *right_group_off;     /* uint32[tile_slots] (NULL if form absent) */
     const uint16_t *left_elements, *right_elements;       /* fp16 bits, 8 per group (NULL if absent) */
     int64_t left_groups_capacity, right_groups_capacity;  /* groups the element arrays can hold     */
 } tsp_tiles_view;

@@ -72,7 +72,8 @@ struct tsp_tiles_s {
     int64_t tile_capacity = 0;
     int forms = 0;
     int scalar_slot = 0;                 // S_TILES_A or S_TILES_B: where the device leaves ntiles
-    int32_t *tile_row_ptr = nullptr;
+    int32_t *tile_row_ptr = nullptr;               // first tile slot of every tile-row
+    int32_t *tile_row_end = nullptr;               // one past its last tile
     int32_t *tile_col = nullptr;
     uint16_t *row_mask = nullptr;
     uint32_t *lmask = nullptr, *rmask = nullptr;

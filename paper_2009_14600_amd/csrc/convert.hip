@@ -1,29 +1,31 @@
-// CSR -> tile ("bitmap") format, paper Section 2.1.2 with 16x16 tiles: a tile occupancy scan
-// (how many non-empty tiles, and how many element groups, each tile-row has), a prefix sum, and a
-// packing pass that writes, per non-empty tile, its tile column, its bitmap (16 row masks) and its
-// elements.
+// CSR -> tile ("bitmap") format, paper Section 2.1.2 with 16x16 tiles, in one pass over the matrix:
+// per non-empty tile its tile column, its bitmap (16 row masks) and its elements.
 //
-// A group of G threads (one wave, or one 256-thread block for long tile-rows) owns one tile-row,
-// i.e. 16 CSR rows whose entries are one contiguous stretch of the CSR arrays, and visits the
+// Where things go needs no counting pass and no prefix sum: tile-row I (16 CSR rows, whose entries
+// are the stretch [e0, e1) of the CSR arrays) keeps its tiles in the tile slots e0, e0+1, ... and its
+// element groups in the group slots e0, e0+1, ... of each form.  A tile-row has at most e1-e0 tiles
+// and at most e1-e0 groups per form, so the stretches of different tile-rows cannot meet; the slots
+// in between stay unused (the arrays are sized by nnz and never touched there).
+//
+// A group of G threads (one wave, or one block for long tile-rows) owns one tile-row and visits its
 // entries in parallel:
 //   1. every entry marks its tile column in an LDS bitmap that spans the tile-row's first to last
 //      tile column; the popcount is the number of tiles and the rank of a bit is the tile's
 //      position inside the tile-row, so the tiles come out sorted by column without a sort;
 //   2. every entry ORs its bit into its tile's row masks (LDS); from the 16 row masks of a tile
-//      follow the two group masks (which 8-element row pieces / column pieces are non-empty);
-//   3. (packing pass) every entry stores its value into its slot of the left-form and of the
-//      right-form group of its tile; the groups were zeroed first.
+//      follow the two group masks (which 8-element row pieces / column pieces are non-empty) and,
+//      by a prefix sum inside the tile-row, the group offsets;
+//   3. the groups are zeroed and every entry stores its value into its slot of the left-form and
+//      of the right-form group of its tile.
 // The element storage is laid out for the matrix-core operand registers (see tsp_tiles_view in
-// tsp.h).  Group offsets come from the prefix sum of the per-tile-row group counts, so the stored
-// groups are contiguous from the start of the element arrays.
-// Tile-rows whose tile columns span more than the LDS bitmap take a second path: 16 lanes merge
-// the 16 sorted rows, one tile per step (any span, one tile at a time).
-// The occupancy pass also checks that the input is canonical (it reads every index anyway).
+// tsp.h).  Tile-rows whose tile columns span more than the LDS bitmap take a second path: 16 lanes
+// merge the 16 sorted rows, one tile per step (any span, one tile at a time).
+// The same pass checks that the input is canonical (it reads every index anyway).
 #include "common.hpp"
-#include "chain.hpp"
 
 #include <hip/hip_fp16.h>
 
+#include <algorithm>
 #include <climits>
 #include <new>
 
@@ -60,10 +62,8 @@ struct ConvArgs {
     const VT *val;
     int64_t rows, cols, nnz, tile_rows, tile_capacity, group_capacity;
     int forms, validate;
-    // occupancy pass outputs / packing pass inputs, one entry per tile-row
-    int32_t *row_tiles, *row_lgroups, *row_rgroups, *row_class;
-    const int32_t *tile_row_ptr;
-    const uint32_t *row_lbase, *row_rbase;
+    int32_t *row_class;                 // per tile-row: which path takes it
+    int32_t *tile_row_ptr, *tile_row_end;  // per tile-row: first tile slot, one past the last
     // tile arrays
     int32_t *tile_col;
     uint16_t *row_mask;
@@ -136,7 +136,7 @@ __device__ __forceinline__ uint32_t group_exclusive_scan(uint32_t *arr, int n, i
 // ------------------------------------------------------------------------------------------------
 // Fast path: LDS bitmap over the tile-row's span of tile columns.
 // ------------------------------------------------------------------------------------------------
-template <int G, bool FILL, typename RP, typename VT>
+template <int G, typename RP, typename VT>
 __global__ __launch_bounds__(conv_block_threads<G>()) void k_convert_rows(const ConvArgs<RP, VT> a) {
     constexpr int kWords = ConvCfg<G>::kWords, kWindow = ConvCfg<G>::kWindow, kGroups = conv_block_threads<G>() / G;
     constexpr int kConvCache = ConvCfg<G>::kCache;
@@ -152,21 +152,9 @@ __global__ __launch_bounds__(conv_block_threads<G>()) void k_convert_rows(const 
     uint32_t *s_lm = s_lm_all[gi], *s_rm = s_rm_all[gi], *s_lo = s_lo_all[gi], *s_ro = s_ro_all[gi];
     int *s_red = s_red_all[gi];
     const int64_t I = (int64_t)blockIdx.x * kGroups + gi;
-    if (I >= a.tile_rows) return;                 // whole group (G = 256: whole block)
+    if (I >= a.tile_rows) return;                 // whole group (G > 64: whole block)
     bool bad = false;
 
-    // what the packing pass needs from the prefix sums: requested before anything else
-    int64_t t0 = 0;
-    uint32_t lrun = 0, rrun = 0, lend = 0, rend = 0;
-    int row_class = ROW_FAST;
-    if (FILL) {
-        t0 = a.tile_row_ptr[I];
-        lrun = a.row_lbase[I];
-        rrun = a.row_rbase[I];
-        lend = a.row_lbase[I + 1];
-        rend = a.row_rbase[I + 1];
-        row_class = a.row_class[I];
-    }
     // The 17 row pointers of the tile-row, one per lane, clamped into [0, nnz] and made non-decreasing
     // (a running maximum) so that whatever they hold the entry ranges are disjoint stretches inside the
     // arrays; nnz < 2^31, so the clamped values fit 32 bits.
@@ -187,30 +175,21 @@ __global__ __launch_bounds__(conv_block_threads<G>()) void k_convert_rows(const 
     }
     group_sync<G>();
     const int64_t e0 = s_rp[0], e1 = s_rp[16];
-    if (FILL && row_class != ROW_FAST) return;
-    if (e0 == e1) {
-        if (!FILL) {
-            const bool any_bad = group_max<G>(bad ? 1 : 0, s_red) != 0;
-            if (gt == 0) {
-                a.row_tiles[I] = 0;
-                a.row_lgroups[I] = 0;
-                a.row_rgroups[I] = 0;
-                a.row_class[I] = ROW_FAST;
-                if (any_bad && a.validate) a.d_scalars[S_INVALID] = 1;
-            }
+    // the tile-row's slots: tiles and groups both start at slot e0 (see the top of the file)
+    const int64_t t0 = e0;
+    uint32_t lrun = (uint32_t)e0, rrun = (uint32_t)e0;
+    auto finish = [&](int ntiles, int row_class) {
+        const bool any_bad = group_max<G>(bad ? 1 : 0, s_red) != 0;
+        if (gt == 0) {
+            a.tile_row_ptr[I] = (int32_t)t0;
+            a.tile_row_end[I] = (int32_t)(t0 + ntiles);
+            a.row_class[I] = row_class;
+            if (any_bad && a.validate) a.d_scalars[S_INVALID] = 1;
         }
+    };
+    if (e0 == e1) {
+        finish(0, ROW_FAST);
         return;
-    }
-    if (FILL) {
-        // zero the tile-row's groups now; the entries drop their values into their slots at the end, by
-        // which time these stores have long been acknowledged
-        const uint4 zero = make_uint4(0, 0, 0, 0);
-        if (a.forms & TSP_FORM_LEFT)
-            for (int64_t g = (int64_t)lrun + gt, end = min((int64_t)lend, a.group_capacity); g < end; g += G)
-                a.ldata[g] = zero;
-        if (a.forms & TSP_FORM_RIGHT)
-            for (int64_t g = (int64_t)rrun + gt, end = min((int64_t)rend, a.group_capacity); g < end; g += G)
-                a.rdata[g] = zero;
     }
     auto row_of = [&](int64_t e) {
         const int x = (int)e;
@@ -221,8 +200,8 @@ __global__ __launch_bounds__(conv_block_threads<G>()) void k_convert_rows(const 
         return r;
     };
 
-    // Tile-rows of up to G*kConvCache entries keep their column indices (and, when packing, values) in
-    // registers: all loads are requested at once and the later passes do not touch memory again.
+    // Tile-rows of up to G*kConvCache entries keep their column indices and values in registers: all
+    // loads are requested at once and the later passes do not touch the CSR arrays again.
     const bool cached = e1 - e0 <= (int64_t)G * kConvCache;
     int c_reg[kConvCache], p_reg[kConvCache];
     VT v_reg[kConvCache];
@@ -232,8 +211,8 @@ __global__ __launch_bounds__(conv_block_threads<G>()) void k_convert_rows(const 
         for (int k = 0; k < kConvCache; ++k) {
             const int64_t e = e0 + gt + (int64_t)k * G;
             c_reg[k] = e < e1 ? a.col[e] : 0;
-            if (FILL) v_reg[k] = e < e1 ? a.val[e] : VT(0);
-            if (!FILL) p_reg[k] = e < e1 && e > e0 ? a.col[e - 1] : -1;      // left neighbour, for the order check
+            v_reg[k] = e < e1 ? a.val[e] : VT(0);
+            p_reg[k] = a.validate && e < e1 && e > e0 ? a.col[e - 1] : -1;   // left neighbour, for the order check
         }
 #pragma unroll
         for (int k = 0; k < kConvCache; ++k) {
@@ -255,16 +234,13 @@ __global__ __launch_bounds__(conv_block_threads<G>()) void k_convert_rows(const 
     const int64_t span = (int64_t)jmax - jmin + 1;
     const int words = (int)((span + 31) >> 5);
     if (jmin < 0 || span <= 0 || words > kWords) {
-        if (!FILL) {                              // the merge path takes this tile-row (and validates it)
-            const bool any_bad = group_max<G>(bad ? 1 : 0, s_red) != 0;
-            if (gt == 0) {
-                // (a span that cannot occur in a matrix of this width means the indices are out of range)
-                if (a.validate && (any_bad || jmin < 0 || jmax >= (a.cols + T - 1) / T)) a.d_scalars[S_INVALID] = 1;
-                a.row_tiles[I] = 0;
-                a.row_lgroups[I] = 0;
-                a.row_rgroups[I] = 0;
-                a.row_class[I] = ROW_MERGE;
-            }
+        // the merge path takes this tile-row (and validates it); a span that cannot occur in a matrix
+        // of this width means the indices are out of range
+        bad |= jmin < 0 || jmax >= (a.cols + T - 1) / T;
+        const bool any_bad = group_max<G>(bad ? 1 : 0, s_red) != 0;
+        if (gt == 0) {
+            a.row_class[I] = ROW_MERGE;
+            if (any_bad && a.validate) a.d_scalars[S_INVALID] = 1;
         }
         return;
     }
@@ -278,7 +254,7 @@ __global__ __launch_bounds__(conv_block_threads<G>()) void k_convert_rows(const 
             }
         } else {
             for (int64_t e = e0 + gt; e < e1; e += G)
-                f(e, a.col[e], FILL ? a.val[e] : VT(0), !FILL && e > e0 ? a.col[e - 1] : -1);
+                f(e, a.col[e], a.val[e], a.validate && e > e0 ? a.col[e - 1] : -1);
         }
     };
 
@@ -288,7 +264,7 @@ __global__ __launch_bounds__(conv_block_threads<G>()) void k_convert_rows(const 
     for_each_entry([&](int64_t e, int c, VT, int before) {
         const uint32_t j = (uint32_t)((c >> 4) - jmin);
         if (j < (uint32_t)span) atomicOr(&s_bm[j >> 5], 1u << (j & 31));
-        if (!FILL && a.validate) {
+        if (a.validate) {
             bad |= c < 0 || c >= a.cols || j >= (uint32_t)span;
             if (e > s_rp[row_of(e)]) bad |= c <= before;
         }
@@ -304,20 +280,17 @@ __global__ __launch_bounds__(conv_block_threads<G>()) void k_convert_rows(const 
     };
 
     uint16_t *const l16 = reinterpret_cast<uint16_t *>(a.ldata), *const r16 = reinterpret_cast<uint16_t *>(a.rdata);
-    if (FILL) {
-        // tile columns, ascending
-        for (int w = gt; w < words; w += G) {
-            uint32_t bits = s_bm[w];
-            int64_t t = t0 + s_pre[w];
-            while (bits) {
-                const int b = __ffs(bits) - 1;
-                bits &= bits - 1;
-                if (t < a.tile_capacity) a.tile_col[t] = jmin + w * 32 + b;
-                ++t;
-            }
+    // tile columns, ascending
+    for (int w = gt; w < words; w += G) {
+        uint32_t bits = s_bm[w];
+        int64_t t = t0 + s_pre[w];
+        while (bits) {
+            const int b = __ffs(bits) - 1;
+            bits &= bits - 1;
+            if (t < a.tile_capacity) a.tile_col[t] = jmin + w * 32 + b;
+            ++t;
         }
     }
-    uint32_t lcount = 0, rcount = 0;
     for (int win0 = 0; win0 < ntiles; win0 += kWindow) {
         const int nw = min(kWindow, ntiles - win0);
         // 2. row masks of the tiles of this window
@@ -343,68 +316,60 @@ __global__ __launch_bounds__(conv_block_threads<G>()) void k_convert_rows(const 
             }
             s_lm[t] = lm;
             s_rm[t] = rm;
-            lcount += __popc(lm);
-            rcount += __popc(rm);
-            if (FILL) {
-                s_lo[t] = __popc(lm);
-                s_ro[t] = __popc(rm);
-            }
+            s_lo[t] = __popc(lm);
+            s_ro[t] = __popc(rm);
         }
         group_sync<G>();
-        if (FILL) {
-            // the zeros stored at the start must be in L2 before any value is stored over them: every
-            // wave waits for its own stores here, ahead of the barriers inside the scans below
-            __builtin_amdgcn_s_waitcnt(0x0F70);
-            const uint32_t ltot = group_exclusive_scan<G>(s_lo, nw, s_red);
-            const uint32_t rtot = group_exclusive_scan<G>(s_ro, nw, s_red);
-            // tile headers and bitmaps
-            for (int t = gt; t < nw; t += G) {
-                const int64_t tg = t0 + win0 + t;
-                if (tg < a.tile_capacity) {
-                    uint4 *dst = reinterpret_cast<uint4 *>(a.row_mask + tg * T);
-                    dst[0] = make_uint4(s_mask[t * 8 + 0], s_mask[t * 8 + 1], s_mask[t * 8 + 2], s_mask[t * 8 + 3]);
-                    dst[1] = make_uint4(s_mask[t * 8 + 4], s_mask[t * 8 + 5], s_mask[t * 8 + 6], s_mask[t * 8 + 7]);
-                    a.lmask[tg] = s_lm[t];
-                    a.rmask[tg] = s_rm[t];
-                    if (a.forms & TSP_FORM_LEFT) a.loff[tg] = lrun + s_lo[t];
-                    if (a.forms & TSP_FORM_RIGHT) a.roff[tg] = rrun + s_ro[t];
+        const uint32_t ltot = group_exclusive_scan<G>(s_lo, nw, s_red);
+        const uint32_t rtot = group_exclusive_scan<G>(s_ro, nw, s_red);
+        // the window's groups are zeroed; the entries drop their values into their slots below
+        const uint4 zero = make_uint4(0, 0, 0, 0);
+        if (a.forms & TSP_FORM_LEFT)
+            for (int64_t g = (int64_t)lrun + gt, end = min((int64_t)lrun + ltot, a.group_capacity); g < end; g += G)
+                a.ldata[g] = zero;
+        if (a.forms & TSP_FORM_RIGHT)
+            for (int64_t g = (int64_t)rrun + gt, end = min((int64_t)rrun + rtot, a.group_capacity); g < end; g += G)
+                a.rdata[g] = zero;
+        // tile headers and bitmaps
+        for (int t = gt; t < nw; t += G) {
+            const int64_t tg = t0 + win0 + t;
+            if (tg < a.tile_capacity) {
+                uint4 *dst = reinterpret_cast<uint4 *>(a.row_mask + tg * T);
+                dst[0] = make_uint4(s_mask[t * 8 + 0], s_mask[t * 8 + 1], s_mask[t * 8 + 2], s_mask[t * 8 + 3]);
+                dst[1] = make_uint4(s_mask[t * 8 + 4], s_mask[t * 8 + 5], s_mask[t * 8 + 6], s_mask[t * 8 + 7]);
+                a.lmask[tg] = s_lm[t];
+                a.rmask[tg] = s_rm[t];
+                if (a.forms & TSP_FORM_LEFT) a.loff[tg] = lrun + s_lo[t];
+                if (a.forms & TSP_FORM_RIGHT) a.roff[tg] = rrun + s_ro[t];
+            }
+        }
+        // the zeros must be in L2 before any value is stored over them: every wave waits for its own
+        // stores, then the group meets
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        group_sync<G>();
+        // 3. values
+        for_each_entry([&](int64_t e, int c, VT value, int) {
+            const int t = tile_rank(c) - win0;
+            if (t >= 0 && t < nw) {
+                const int r = row_of(e), cc = c & 15;
+                const uint16_t v = to_half_bits(value);
+                if (a.forms & TSP_FORM_LEFT) {
+                    const int g = (cc >> 3) * 16 + r;
+                    const int64_t idx = (int64_t)lrun + s_lo[t] + __popc(s_lm[t] & ((1u << g) - 1u));
+                    if (idx < a.group_capacity) l16[idx * 8 + (cc & 7)] = v;
+                }
+                if (a.forms & TSP_FORM_RIGHT) {
+                    const int g = (r >> 3) * 16 + cc;
+                    const int64_t idx = (int64_t)rrun + s_ro[t] + __popc(s_rm[t] & ((1u << g) - 1u));
+                    if (idx < a.group_capacity) r16[idx * 8 + (r & 7)] = v;
                 }
             }
-            // 3. values
-            for_each_entry([&](int64_t e, int c, VT value, int) {
-                const int t = tile_rank(c) - win0;
-                if (t >= 0 && t < nw) {
-                    const int r = row_of(e), cc = c & 15;
-                    const uint16_t v = to_half_bits(value);
-                    if (a.forms & TSP_FORM_LEFT) {
-                        const int g = (cc >> 3) * 16 + r;
-                        const int64_t idx = (int64_t)lrun + s_lo[t] + __popc(s_lm[t] & ((1u << g) - 1u));
-                        if (idx < a.group_capacity) l16[idx * 8 + (cc & 7)] = v;
-                    }
-                    if (a.forms & TSP_FORM_RIGHT) {
-                        const int g = (r >> 3) * 16 + cc;
-                        const int64_t idx = (int64_t)rrun + s_ro[t] + __popc(s_rm[t] & ((1u << g) - 1u));
-                        if (idx < a.group_capacity) r16[idx * 8 + (r & 7)] = v;
-                    }
-                }
-            });
-            lrun += ltot;
-            rrun += rtot;
-            group_sync<G>();
-        }
+        });
+        lrun += ltot;
+        rrun += rtot;
+        group_sync<G>();
     }
-    if (!FILL) {
-        lcount = group_sum<G>(lcount, s_red);
-        rcount = group_sum<G>(rcount, s_red);
-        const bool any_bad = group_max<G>(bad ? 1 : 0, s_red) != 0;
-        if (gt == 0) {
-            a.row_tiles[I] = ntiles;
-            a.row_lgroups[I] = (int32_t)lcount;
-            a.row_rgroups[I] = (int32_t)rcount;
-            a.row_class[I] = ROW_FAST;
-            if (any_bad && a.validate) a.d_scalars[S_INVALID] = 1;
-        }
-    }
+    finish(ntiles, ROW_FAST);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -415,7 +380,7 @@ __global__ __launch_bounds__(conv_block_threads<G>()) void k_convert_rows(const 
 // ------------------------------------------------------------------------------------------------
 constexpr int kMergeGroupsPerBlock = kConvThreads / 16;
 
-template <bool FILL, typename RP, typename VT>
+template <typename RP, typename VT>
 __global__ __launch_bounds__(kConvThreads) void k_convert_merge(const ConvArgs<RP, VT> a) {
     __shared__ __align__(16) uint16_t dense_all[kMergeGroupsPerBlock][T * T];
     const int g = threadIdx.x >> 4, r = threadIdx.x & 15;
@@ -432,15 +397,11 @@ __global__ __launch_bounds__(kConvThreads) void k_convert_merge(const ConvArgs<R
         p = min(max(p, (int64_t)0), a.nnz);      // never read outside the arrays, whatever row_ptr holds
         e = min(max(e, p), a.nnz);
     }
-    int64_t t = 0;
-    uint32_t lrun = 0, rrun = 0;
-    if (FILL && mine) {
-        t = a.tile_row_ptr[I];
-        lrun = a.row_lbase[I];
-        rrun = a.row_rbase[I];
-    }
+    // the tile-row's slots start at the first entry of its first row (lane 0 of the group)
+    const int64_t first = __shfl(p, 0, 16);
+    int64_t t = first;
+    uint32_t lrun = (uint32_t)first, rrun = (uint32_t)first;
     int ntiles = 0;
-    uint32_t lcount = 0, rcount = 0;
     int cur = p < e ? (a.col[p] >> 4) : INT_MAX;
     int prev_col = -1;
     const uint32_t below_lo = (1u << r) - 1u, below_hi = (1u << (16 + r)) - 1u;
@@ -449,10 +410,8 @@ __global__ __launch_bounds__(kConvThreads) void k_convert_merge(const ConvArgs<R
         if (__all(m == INT_MAX)) break;
         const bool active = m != INT_MAX;
         uint4 *myrow = reinterpret_cast<uint4 *>(dense + r * T);
-        if (FILL) {                               // dense image of the tile in LDS; every lane fills its own row
-            myrow[0] = make_uint4(0, 0, 0, 0);
-            myrow[1] = make_uint4(0, 0, 0, 0);
-        }
+        myrow[0] = make_uint4(0, 0, 0, 0);        // dense image of the tile in LDS; every lane fills its own row
+        myrow[1] = make_uint4(0, 0, 0, 0);
         uint32_t mask = 0;
         if (active && cur == m) {
             do {
@@ -460,7 +419,7 @@ __global__ __launch_bounds__(kConvThreads) void k_convert_merge(const ConvArgs<R
                 bad |= c <= prev_col || c >= a.cols;
                 prev_col = c;
                 mask |= 1u << (c & 15);
-                if (FILL) dense[r * T + (c & 15)] = to_half_bits(a.val[p]);
+                dense[r * T + (c & 15)] = to_half_bits(a.val[p]);
                 ++p;
             } while (p < e && (a.col[p] >> 4) == m);
             cur = p < e ? (a.col[p] >> 4) : INT_MAX;
@@ -471,9 +430,7 @@ __global__ __launch_bounds__(kConvThreads) void k_convert_merge(const ConvArgs<R
         const uint32_t rm = group16_or(r < 8 ? mask : (mask << 16));
         if (active) {
             ++ntiles;
-            lcount += __popc(lm);
-            rcount += __popc(rm);
-            if (FILL && t < a.tile_capacity) {
+            if (t < a.tile_capacity) {
                 if (a.forms & TSP_FORM_LEFT) {
                     const int64_t g0 = (int64_t)lrun + __popc(lm & below_lo), g1 = (int64_t)lrun + __popc(lm & below_hi);
                     if ((mask & 0xFFu) && g0 < a.group_capacity) a.ldata[g0] = myrow[0];
@@ -503,71 +460,16 @@ __global__ __launch_bounds__(kConvThreads) void k_convert_merge(const ConvArgs<R
         }
         wave_sync();   // column reads above finish before the rows are cleared again
     }
-    if (!FILL) {
-        const bool any_bad = group16_or(bad ? 1u : 0u) != 0;
-        if (mine && r == 0) {
-            a.row_tiles[I] = ntiles;
-            a.row_lgroups[I] = (int32_t)lcount;
-            a.row_rgroups[I] = (int32_t)rcount;
-            if (any_bad && a.validate) a.d_scalars[S_INVALID] = 1;
-        }
-    }
-}
-
-// Prefix sums over the tile-rows (tiles, left groups, right groups) in one launch: a block scans
-// 1024 tile-rows (4 per thread, one 16-byte load per array) and the blocks are chained (chain.hpp).
-constexpr int kRowScanThreads = 256, kRowScanItems = 4, kRowScanBlock = kRowScanThreads * kRowScanItems;
-__global__ __launch_bounds__(kRowScanThreads) void k_convert_scan(int64_t ntr, const int32_t *__restrict__ row_tiles,
-                                                                const int32_t *__restrict__ row_lg,
-                                                                const int32_t *__restrict__ row_rg,
-                                                                int32_t *__restrict__ tile_row_ptr,
-                                                                uint32_t *__restrict__ row_lbase,
-                                                                uint32_t *__restrict__ row_rbase, ChainSlot *slots,
-                                                                unsigned epoch, int64_t *__restrict__ d_scalars,
-                                                                int total_slot) {
-    __shared__ uint64_t lds[kRowScanThreads / 64 + kChainValues];
-    const int32_t *in[3] = {row_tiles, row_lg, row_rg};
-    const int64_t i0 = (int64_t)blockIdx.x * kRowScanBlock + (int64_t)threadIdx.x * kRowScanItems;
-    int32_t x[3][kRowScanItems];
-    uint64_t sum[3] = {0, 0, 0}, local[3];
-    unsigned long long agg[kChainValues], prefix[kChainValues];
-#pragma unroll
-    for (int q = 0; q < 3; ++q) {
-        if (i0 + kRowScanItems <= ntr) {                     // one aligned 16-byte load
-            const int4 v = *reinterpret_cast<const int4 *>(in[q] + i0);
-            x[q][0] = v.x, x[q][1] = v.y, x[q][2] = v.z, x[q][3] = v.w;
-        } else {
-#pragma unroll
-            for (int k = 0; k < kRowScanItems; ++k) x[q][k] = i0 + k < ntr ? in[q][i0 + k] : 0;
-        }
-#pragma unroll
-        for (int k = 0; k < kRowScanItems; ++k) sum[q] += (uint32_t)x[q][k];
-        uint64_t total;
-        local[q] = block_exclusive_scan64<kRowScanThreads>(sum[q], &total, lds);
-        agg[q] = total;
-    }
-    chain_exclusive_prefix(slots, epoch, agg, prefix, lds + kRowScanThreads / 64, d_scalars + S_INTERNAL);
-    uint64_t run[3] = {prefix[0] + local[0], prefix[1] + local[1], prefix[2] + local[2]};
-#pragma unroll
-    for (int k = 0; k < kRowScanItems; ++k) {
-        if (i0 + k < ntr) {
-            tile_row_ptr[i0 + k] = (int32_t)run[0];
-            row_lbase[i0 + k] = (uint32_t)run[1];
-            row_rbase[i0 + k] = (uint32_t)run[2];
-        }
-#pragma unroll
-        for (int q = 0; q < 3; ++q) run[q] += (uint32_t)x[q][k];
-    }
-    if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) {
-        tile_row_ptr[ntr] = (int32_t)(prefix[0] + agg[0]);
-        row_lbase[ntr] = (uint32_t)(prefix[1] + agg[1]);
-        row_rbase[ntr] = (uint32_t)(prefix[2] + agg[2]);
-        d_scalars[total_slot] = (int64_t)(prefix[0] + agg[0]);
+    const bool any_bad = group16_or(bad ? 1u : 0u) != 0;
+    if (mine && r == 0) {
+        a.tile_row_ptr[I] = (int32_t)first;
+        a.tile_row_end[I] = (int32_t)(first + ntiles);
+        if (any_bad && a.validate) a.d_scalars[S_INVALID] = 1;
     }
 }
 
 template <typename RP, typename VT>
-static int launch_convert(tsp_context *ctx, const tsp_csr *A, tsp_tiles_s *t, int32_t *scratch, hipStream_t s) {
+static int launch_convert(tsp_context *ctx, const tsp_csr *A, tsp_tiles_s *t, int32_t *row_class, hipStream_t s) {
     const int64_t ntr = t->tile_rows;
     ConvArgs<RP, VT> a{};
     a.row_ptr = static_cast<const RP *>(A->row_ptr);
@@ -581,15 +483,9 @@ static int launch_convert(tsp_context *ctx, const tsp_csr *A, tsp_tiles_s *t, in
     a.group_capacity = t->group_capacity;
     a.forms = t->forms;
     a.validate = ctx->validate;
-    a.row_tiles = scratch;
-    a.row_lgroups = scratch + (ntr + 1);
-    a.row_rgroups = scratch + 2 * (ntr + 1);
-    a.row_class = scratch + 3 * (ntr + 1);
-    uint32_t *lbase = reinterpret_cast<uint32_t *>(scratch + 4 * (ntr + 1));
-    uint32_t *rbase = reinterpret_cast<uint32_t *>(scratch + 5 * (ntr + 1));
+    a.row_class = row_class;
     a.tile_row_ptr = t->tile_row_ptr;
-    a.row_lbase = lbase;
-    a.row_rbase = rbase;
+    a.tile_row_end = t->tile_row_end;
     a.tile_col = t->tile_col;
     a.row_mask = t->row_mask;
     a.lmask = t->lmask;
@@ -599,50 +495,24 @@ static int launch_convert(tsp_context *ctx, const tsp_csr *A, tsp_tiles_s *t, in
     a.ldata = t->ldata;
     a.rdata = t->rdata;
     a.d_scalars = ctx->d_scalars;
-    // threads per tile-row from the mean number of entries per tile-row (the kernels are bound by
+    // threads per tile-row from the mean number of entries per tile-row (the kernel is bound by
     // dependent steps, so small groups, many in flight, win as long as the entries fit their registers);
     // the merge path only when a tile-row could span more tile columns than the chosen bitmap holds
     const int64_t per_row = ntr > 0 ? A->nnz / ntr : 0;
     const int G = per_row <= 64 * ConvCfg<64>::kCache ? 64 : per_row <= 128 * ConvCfg<128>::kCache ? 128 : 256;
     const int64_t bitmap_span =
         32ll * (G == 64 ? ConvCfg<64>::kWords : G == 128 ? ConvCfg<128>::kWords : ConvCfg<256>::kWords);
-    // (tile-rows of a narrow matrix cannot exceed the bitmap, and then the merge kernels are not launched)
+    // (tile-rows of a narrow matrix cannot exceed the bitmap, and then the merge kernel is not launched)
     const bool may_merge = t->tile_cols > bitmap_span;
     const unsigned grid_fast = (unsigned)(G == 64 ? (ntr + 3) / 4 : ntr);
     const unsigned grid_merge = (unsigned)((ntr + kMergeGroupsPerBlock - 1) / kMergeGroupsPerBlock);
-    auto launch_rows = [&](bool fill) {
-        if (G == 64) {
-            if (fill) hipLaunchKernelGGL((k_convert_rows<64, true, RP, VT>), dim3(grid_fast), dim3(256), 0, s, a);
-            else hipLaunchKernelGGL((k_convert_rows<64, false, RP, VT>), dim3(grid_fast), dim3(256), 0, s, a);
-        } else if (G == 128) {
-            if (fill) hipLaunchKernelGGL((k_convert_rows<128, true, RP, VT>), dim3(grid_fast), dim3(128), 0, s, a);
-            else hipLaunchKernelGGL((k_convert_rows<128, false, RP, VT>), dim3(grid_fast), dim3(128), 0, s, a);
-        } else {
-            if (fill) hipLaunchKernelGGL((k_convert_rows<256, true, RP, VT>), dim3(grid_fast), dim3(256), 0, s, a);
-            else hipLaunchKernelGGL((k_convert_rows<256, false, RP, VT>), dim3(grid_fast), dim3(256), 0, s, a);
-        }
-    };
     if (ntr > 0) {
-        KernelTimer kt(ctx, TSP_KERNEL_COUNT_TILES, s);
-        launch_rows(false);
+        KernelTimer kt(ctx, TSP_KERNEL_CONVERT, s);
+        if (G == 64) hipLaunchKernelGGL((k_convert_rows<64, RP, VT>), dim3(grid_fast), dim3(256), 0, s, a);
+        else if (G == 128) hipLaunchKernelGGL((k_convert_rows<128, RP, VT>), dim3(grid_fast), dim3(128), 0, s, a);
+        else hipLaunchKernelGGL((k_convert_rows<256, RP, VT>), dim3(grid_fast), dim3(256), 0, s, a);
         if (may_merge)
-            hipLaunchKernelGGL((k_convert_merge<false, RP, VT>), dim3(grid_merge), dim3(kConvThreads), 0, s, a);
-    }
-    {
-        KernelTimer kt(ctx, TSP_KERNEL_SCAN_TILES, s);
-        const int64_t blocks = ntr > 0 ? (ntr + kRowScanBlock - 1) / kRowScanBlock : 1;
-        unsigned epoch = 0;
-        ChainSlot *slots = static_cast<ChainSlot *>(chain_prepare(ctx, blocks, &epoch, s));
-        if (!slots) return TSP_ERR_ALLOC_FAILED;
-        hipLaunchKernelGGL(k_convert_scan, dim3((unsigned)blocks), dim3(kRowScanThreads), 0, s, ntr, a.row_tiles,
-                           a.row_lgroups, a.row_rgroups, t->tile_row_ptr, lbase, rbase, slots, epoch, ctx->d_scalars,
-                           t->scalar_slot);
-    }
-    if (ntr > 0) {
-        KernelTimer kt(ctx, TSP_KERNEL_FILL_TILES, s);
-        launch_rows(true);
-        if (may_merge)
-            hipLaunchKernelGGL((k_convert_merge<true, RP, VT>), dim3(grid_merge), dim3(kConvThreads), 0, s, a);
+            hipLaunchKernelGGL((k_convert_merge<RP, VT>), dim3(grid_merge), dim3(kConvThreads), 0, s, a);
     }
     TSP_HIP_CHECK(ctx, hipGetLastError());
     return TSP_OK;
@@ -663,6 +533,7 @@ static int check_csr_host(const tsp_csr *A) {
 void tiles_release(tsp_context *ctx, tsp_tiles_s *t, hipStream_t s) {
     if (!t) return;
     ctx_free(ctx, t->tile_row_ptr, s);
+    ctx_free(ctx, t->tile_row_end, s);
     ctx_free(ctx, t->tile_col, s);
     ctx_free(ctx, t->row_mask, s);
     ctx_free(ctx, t->lmask, s);
@@ -674,8 +545,9 @@ void tiles_release(tsp_context *ctx, tsp_tiles_s *t, hipStream_t s) {
     delete t;
 }
 
-// Enqueues the whole conversion without synchronising: the tile arrays are sized by the bound
-// ntiles <= min(nnz, tile_rows*tile_cols); the exact count is left in d_scalars[scalar_slot].
+// Enqueues the whole conversion without synchronising: the tile arrays have one slot per stored entry
+// (see the top of the file); the number of tiles is the sum of tile_row_end - tile_row_ptr, which the
+// symbolic phase (or tsp_convert) adds up.
 int convert_enqueue(tsp_context *ctx, const tsp_csr *A, int forms, int scalar_slot, tsp_tiles_s **out,
                     hipStream_t s) {
     *out = nullptr;
@@ -692,16 +564,16 @@ int convert_enqueue(tsp_context *ctx, const tsp_csr *A, int forms, int scalar_sl
     t->tile_cols = (A->cols + T - 1) / T;
     t->forms = forms;
     t->scalar_slot = scalar_slot;
-    const double grid_tiles = (double)t->tile_rows * (double)t->tile_cols;
-    t->tile_capacity = grid_tiles < (double)A->nnz ? (int64_t)grid_tiles : A->nnz;
+    t->tile_capacity = A->nnz;
     t->group_capacity = A->nnz;
     const size_t cap = (size_t)t->tile_capacity;
     t->tile_row_ptr = ctx_alloc_n<int32_t>(ctx, (size_t)t->tile_rows + 1, s);
+    t->tile_row_end = ctx_alloc_n<int32_t>(ctx, (size_t)t->tile_rows + 1, s);
     t->tile_col = ctx_alloc_n<int32_t>(ctx, cap, s);
     t->row_mask = ctx_alloc_n<uint16_t>(ctx, cap * T, s);
     t->lmask = ctx_alloc_n<uint32_t>(ctx, cap, s);
     t->rmask = ctx_alloc_n<uint32_t>(ctx, cap, s);
-    bool ok = t->tile_row_ptr && t->tile_col && t->row_mask && t->lmask && t->rmask;
+    bool ok = t->tile_row_ptr && t->tile_row_end && t->tile_col && t->row_mask && t->lmask && t->rmask;
     if (forms & TSP_FORM_LEFT) {
         t->loff = ctx_alloc_n<uint32_t>(ctx, cap, s);
         t->ldata = ctx_alloc_n<uint4>(ctx, (size_t)t->group_capacity, s);
@@ -712,7 +584,7 @@ int convert_enqueue(tsp_context *ctx, const tsp_csr *A, int forms, int scalar_sl
         t->rdata = ctx_alloc_n<uint4>(ctx, (size_t)t->group_capacity, s);
         ok = ok && t->roff && t->rdata;
     }
-    int32_t *scratch = ctx_alloc_n<int32_t>(ctx, 6 * ((size_t)t->tile_rows + 1), s);
+    int32_t *scratch = ctx_alloc_n<int32_t>(ctx, (size_t)t->tile_rows + 1, s);   // path of every tile-row
     ok = ok && scratch;
     rc = ok ? TSP_OK : TSP_ERR_ALLOC_FAILED;
     if (!rc) {
@@ -729,6 +601,22 @@ int convert_enqueue(tsp_context *ctx, const tsp_csr *A, int forms, int scalar_sl
     }
     *out = t;
     return TSP_OK;
+}
+
+// Number of tiles of a tile matrix (tsp_convert only; tsp_spgemm lets the symbolic phase add them up).
+__global__ __launch_bounds__(256) void k_tiles_total(int64_t tile_rows, const int32_t *__restrict__ trp,
+                                                    const int32_t *__restrict__ tend, int64_t *d_scalars, int slot) {
+    __shared__ uint32_t part[4];
+    uint32_t n = 0;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < tile_rows; i += (int64_t)gridDim.x * 256)
+        n += (uint32_t)(tend[i] - trp[i]);
+    n = wave_sum(n);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = n;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const unsigned long long all = (unsigned long long)part[0] + part[1] + part[2] + part[3];
+        if (all) atomicAdd(reinterpret_cast<unsigned long long *>(d_scalars + slot), all);
+    }
 }
 
 __global__ void k_clear_scalars(int64_t *d_scalars) {
@@ -749,6 +637,11 @@ extern "C" int tsp_convert(tsp_handle ctx, const tsp_csr *A, int forms, tsp_tile
     int rc = convert_enqueue(ctx, A, forms, S_TILES_A, &t, s);
     phase_end(ctx, TSP_PHASE_CONVERT, s);
     if (rc) return rc;
+    if (t->tile_rows > 0) {
+        const unsigned blocks = (unsigned)std::min<int64_t>(64, (t->tile_rows + 255) / 256);
+        hipLaunchKernelGGL(k_tiles_total, dim3(blocks), dim3(256), 0, s, t->tile_rows, t->tile_row_ptr, t->tile_row_end,
+                           ctx->d_scalars, (int)S_TILES_A);
+    }
     rc = read_scalars(ctx, s);
     if (!rc && ctx->h_scalars[S_INVALID]) rc = TSP_ERR_NOT_CANONICAL;
     if (rc) {
@@ -775,7 +668,9 @@ extern "C" int tsp_tiles_get_view(tsp_tiles t, tsp_tiles_view *v) {
     v->tile_cols = t->tile_cols;
     v->ntiles = t->ntiles;
     v->forms = t->forms;
+    v->tile_slots = t->tile_capacity;
     v->tile_row_ptr = t->tile_row_ptr;
+    v->tile_row_end = t->tile_row_end;
     v->tile_col = t->tile_col;
     v->row_mask = t->row_mask;
     v->left_group_mask = t->lmask;

@@ -31,7 +31,8 @@ constexpr int kMaxWords = 4096;        // LDS bitmap words per tile-row: span of
 constexpr int kWindow = 2048;          // C tiles of one tile-row handled per LDS window
 
 struct TileRefs {
-    const int32_t *trp;      // tile_row_ptr
+    const int32_t *trp;      // first tile of every tile-row
+    const int32_t *tend;     // one past the last
     const int32_t *tcol;     // tile_col
     const uint32_t *lmask;   // left group mask  -> row occupancy
     const uint32_t *rmask;   // right group mask -> column occupancy
@@ -84,7 +85,7 @@ __device__ __forceinline__ void for_each_survivor(const TileRefs &A, const TileR
         const uint32_t K = (uint32_t)A.tcol[a];
         if (K >= (uint32_t)B.tile_rows) continue;            // only possible for a non-canonical input
         const uint32_t col_occ = fold16(A.rmask[a]);
-        const int b0 = B.trp[K], b1 = B.trp[K + 1];
+        const int b0 = B.trp[K], b1 = B.tend[K];
         for (int b = b0 + l; b < b1; b += lanes_per_a) {
             ++*candidates;
             if (col_occ & fold16(B.lmask[b])) f(a, b, B.tcol[b]);
@@ -106,7 +107,7 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_count(TileRefs A, TileRefs 
     __shared__ int s_jmin, s_jmax;
     uint32_t *bm = lds_dyn;
     const int I = blockIdx.x;
-    const int a0 = A.trp[I], a1 = A.trp[I + 1];
+    const int a0 = A.trp[I], a1 = A.tend[I];
     if (threadIdx.x == 0) {
         s_jmin = INT_MAX;
         s_jmax = -1;
@@ -116,7 +117,7 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_count(TileRefs A, TileRefs 
     for (int a = a0 + threadIdx.x; a < a1; a += blockDim.x) {
         const uint32_t K = (uint32_t)A.tcol[a];
         if (K >= (uint32_t)B.tile_rows) continue;
-        const int b0 = B.trp[K], b1 = B.trp[K + 1];
+        const int b0 = B.trp[K], b1 = B.tend[K];
         if (b0 < b1) {
             jmin = min(jmin, B.tcol[b0]);
             jmax = max(jmax, B.tcol[b1 - 1]);
@@ -181,13 +182,19 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_count(TileRefs A, TileRefs 
 // launch: C tiles per row -> c_tile_row_ptr, pairs per row -> row_pair_ptr, plus the totals and maxima
 // the host needs to size the task list.  A block scans 1024 tile-rows; the blocks are chained.
 constexpr int kRowScanThreads = 256, kRowScanItems = 4, kRowScanBlock = kRowScanThreads * kRowScanItems;
+struct TileCount {           // an operand whose number of tiles is still to be summed (slot < 0: nothing to do)
+    const int32_t *trp, *tend;
+    int64_t tile_rows;
+    int slot;
+};
 __global__ __launch_bounds__(kRowScanThreads) void k_sym_row_scan(
     int64_t ntr, const int32_t *__restrict__ row_c_tiles, const int32_t *__restrict__ row_pairs,
     const int32_t *__restrict__ row_words, const int32_t *__restrict__ row_cand,
     int32_t *__restrict__ c_tile_row_ptr, int64_t *__restrict__ row_pair_ptr, ChainSlot *slots, unsigned epoch,
-    int64_t *__restrict__ d_scalars) {
+    int64_t *__restrict__ d_scalars, TileCount count_a, TileCount count_b) {
     __shared__ uint64_t lds[kRowScanThreads / 64 + kChainValues];
     __shared__ int lds_m[2][kRowScanThreads / 64];
+    __shared__ uint32_t lds_t[2][kRowScanThreads / 64];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t i0 = (int64_t)blockIdx.x * kRowScanBlock + (int64_t)threadIdx.x * kRowScanItems;
     int32_t xc[kRowScanItems], xp[kRowScanItems];
@@ -203,6 +210,19 @@ __global__ __launch_bounds__(kRowScanThreads) void k_sym_row_scan(
         max_c = max(max_c, xc[k]);
         max_w = max(max_w, in ? row_words[i0 + k] : 0);
         cand += in ? (uint32_t)row_cand[i0 + k] : 0u;
+    }
+    // tiles of the operands whose converter has not been waited for: summed here, one atomic per block
+    uint32_t tiles_a = 0, tiles_b = 0;
+#pragma unroll
+    for (int k = 0; k < kRowScanItems; ++k) {
+        if (count_a.slot >= 0 && i0 + k < count_a.tile_rows) tiles_a += (uint32_t)(count_a.tend[i0 + k] - count_a.trp[i0 + k]);
+        if (count_b.slot >= 0 && i0 + k < count_b.tile_rows) tiles_b += (uint32_t)(count_b.tend[i0 + k] - count_b.trp[i0 + k]);
+    }
+    tiles_a = wave_sum(tiles_a);
+    tiles_b = wave_sum(tiles_b);
+    if (lane == 0) {
+        lds_t[0][wave] = tiles_a;
+        lds_t[1][wave] = tiles_b;
     }
     unsigned long long agg[kChainValues], prefix[kChainValues];
     uint64_t total, unused;
@@ -241,6 +261,13 @@ __global__ __launch_bounds__(kRowScanThreads) void k_sym_row_scan(
         }
         atomicMax((unsigned long long *)&d_scalars[S_MAX_ROW_C_TILES], (unsigned long long)mc);
         atomicMax((unsigned long long *)&d_scalars[S_MAX_ROW_WORDS], (unsigned long long)mw);
+        unsigned long long ta = 0, tb = 0;
+        for (int w = 0; w < kRowScanThreads / 64; ++w) {
+            ta += lds_t[0][w];
+            tb += lds_t[1][w];
+        }
+        if (ta) atomicAdd((unsigned long long *)&d_scalars[count_a.slot], ta);
+        if (tb) atomicAdd((unsigned long long *)&d_scalars[count_b.slot], tb);
         if (blockIdx.x == gridDim.x - 1) {
             c_tile_row_ptr[ntr] = (int32_t)(prefix[0] + agg[0]);
             row_pair_ptr[ntr] = (int64_t)(prefix[1] + agg[1]);
@@ -268,14 +295,14 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_emit(
     const int c0 = c_tile_row_ptr[I], nC = c_tile_row_ptr[I + 1] - c0;
     if (I == (int)gridDim.x - 1 && threadIdx.x == 0) pair_off[c_tile_row_ptr[gridDim.x]] = row_pair_ptr[gridDim.x];
     if (nC <= 0) return;
-    const int a0 = A.trp[I], a1 = A.trp[I + 1];
+    const int a0 = A.trp[I], a1 = A.tend[I];
     const int jmin = row_jmin[I];
     // the span is recomputed from the bitmap extent the first pass used: highest J over the row
     int jmax = -1;
     for (int a = a0 + threadIdx.x; a < a1; a += blockDim.x) {
         const uint32_t K = (uint32_t)A.tcol[a];
         if (K >= (uint32_t)B.tile_rows) continue;
-        const int b0 = B.trp[K], b1 = B.trp[K + 1];
+        const int b0 = B.trp[K], b1 = B.tend[K];
         if (b0 < b1) jmax = max(jmax, B.tcol[b1 - 1]);
     }
     __shared__ int s_jmax;
@@ -539,8 +566,8 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
     if (!row_jmin || !row_c_tiles || !row_pairs || !row_words || !row_cand || !row_pair_ptr || !P->c_tile_row_ptr || !tmp)
         return cleanup(TSP_ERR_ALLOC_FAILED);
 
-    TileRefs ra{A->tile_row_ptr, A->tile_col, A->lmask, A->rmask, (int32_t)A->tile_rows};
-    TileRefs rb{B->tile_row_ptr, B->tile_col, B->lmask, B->rmask, (int32_t)B->tile_rows};
+    TileRefs ra{A->tile_row_ptr, A->tile_row_end, A->tile_col, A->lmask, A->rmask, (int32_t)A->tile_rows};
+    TileRefs rb{B->tile_row_ptr, B->tile_row_end, B->tile_col, B->lmask, B->rmask, (int32_t)B->tile_rows};
     // tiles-per-tile-row of B is not known on the host before the first read-back: estimate the
     // sharing width from the bound nnz/tile_rows (an upper bound on the mean), capped
     int lanes = 4;
@@ -562,13 +589,19 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
     }
     {
         KernelTimer kt(ctx, TSP_KERNEL_SCAN_SYM, s);
-        const int64_t blocks = ntr > 0 ? (ntr + kRowScanBlock - 1) / kRowScanBlock : 1;
+        // the same launch sums the tiles of operands that come straight from the converter
+        const TileCount ca{A->tile_row_ptr, A->tile_row_end, A->tile_rows, A->ntiles < 0 ? A->scalar_slot : -1};
+        const TileCount cb{B->tile_row_ptr, B->tile_row_end, B->tile_rows, B->ntiles < 0 && B != A ? B->scalar_slot : -1};
+        int64_t rows_covered = ntr;
+        if (ca.slot >= 0) rows_covered = std::max(rows_covered, ca.tile_rows);
+        if (cb.slot >= 0) rows_covered = std::max(rows_covered, cb.tile_rows);
+        const int64_t blocks = rows_covered > 0 ? (rows_covered + kRowScanBlock - 1) / kRowScanBlock : 1;
         unsigned epoch = 0;
         ChainSlot *slots = static_cast<ChainSlot *>(chain_prepare(ctx, blocks, &epoch, s));
         if (!slots) return cleanup(TSP_ERR_ALLOC_FAILED);
         hipLaunchKernelGGL(k_sym_row_scan, dim3((unsigned)blocks), dim3(kRowScanThreads), 0, s, ntr, row_c_tiles,
                            row_pairs, row_words, row_cand, P->c_tile_row_ptr, row_pair_ptr, slots, epoch,
-                           ctx->d_scalars);
+                           ctx->d_scalars, ca, cb);
         SYM_CHECK(hipGetLastError());
     }
     if (!rc) rc = read_scalars(ctx, s);                                    // ---- sync 1: sizes of the task list

@@ -19,8 +19,7 @@ TSP_F16, TSP_F32 = 0, 1
 FORM_LEFT, FORM_RIGHT = 1, 2
 OPT_VALIDATE, OPT_PHASE_TIMERS, OPT_WIDE_INDEX, OPT_NUMERIC_RUN, OPT_MATRIX_CORES, OPT_COMPACT_ZEROS = 1, 2, 3, 4, 5, 6
 PHASES = ("convert", "symbolic", "count", "numeric")
-KERNELS = ("validate", "count_tiles", "scan_tiles", "fill_tiles", "sym_count", "scan_sym", "sym_emit",
-           "count_masks", "row_offsets", "scan_rows", "numeric")
+KERNELS = ("convert", "sym_count", "scan_sym", "sym_emit", "count_masks", "row_offsets", "scan_rows", "numeric")
 
 EXPORTS = [
     "tsp_create", "tsp_destroy", "tsp_set_option", "tsp_trim", "tsp_spgemm", "tsp_csr_free",
@@ -55,13 +54,15 @@ class _Stats(ctypes.Structure):
                 ("pairs", ctypes.c_int64), ("c_tiles", ctypes.c_int64), ("c_nnz", ctypes.c_int64),
                 ("workspace_bytes", ctypes.c_int64), ("workspace_peak_bytes", ctypes.c_int64),
                 ("phase_us", ctypes.c_float * 4), ("total_us", ctypes.c_float),
-                ("kernel_us", ctypes.c_float * 11)]
+                ("kernel_us", ctypes.c_float * len(KERNELS))]
 
 
 class _TilesView(ctypes.Structure):
     _fields_ = [("rows", ctypes.c_int64), ("cols", ctypes.c_int64), ("tile_rows", ctypes.c_int64),
-                ("tile_cols", ctypes.c_int64), ("ntiles", ctypes.c_int64), ("forms", ctypes.c_int32),
-                ("tile_row_ptr", ctypes.c_void_p), ("tile_col", ctypes.c_void_p), ("row_mask", ctypes.c_void_p),
+                ("tile_cols", ctypes.c_int64), ("ntiles", ctypes.c_int64), ("tile_slots", ctypes.c_int64),
+                ("forms", ctypes.c_int32),
+                ("tile_row_ptr", ctypes.c_void_p), ("tile_row_end", ctypes.c_void_p),
+                ("tile_col", ctypes.c_void_p), ("row_mask", ctypes.c_void_p),
                 ("left_group_mask", ctypes.c_void_p), ("right_group_mask", ctypes.c_void_p),
                 ("left_group_off", ctypes.c_void_p), ("right_group_off", ctypes.c_void_p),
                 ("left_elements", ctypes.c_void_p), ("right_elements", ctypes.c_void_p),
@@ -311,13 +312,16 @@ class Tiles:
             self._t = ctypes.c_void_p()
 
     def view(self) -> dict:
-        """Tensor views of the tile arrays (tsp_tiles_view)."""
+        """Tensor views of the tile arrays (tsp_tiles_view).  The per-tile arrays have tile_slots
+        elements; only the indices tile_row_ptr[I] .. tile_row_end[I]-1 of every tile-row hold tiles."""
         h, torch = self._handle, self._handle._torch
         v = _TilesView()
         _check(h._lib.tsp_tiles_get_view(self._t, ctypes.byref(v)))
-        n = v.ntiles
-        out = dict(rows=v.rows, cols=v.cols, tile_rows=v.tile_rows, tile_cols=v.tile_cols, ntiles=n, forms=v.forms,
-                   tile_row_ptr=h._view(v.tile_row_ptr, v.tile_rows + 1, torch.int32),
+        n = v.tile_slots
+        out = dict(rows=v.rows, cols=v.cols, tile_rows=v.tile_rows, tile_cols=v.tile_cols, ntiles=v.ntiles,
+                   tile_slots=n, forms=v.forms,
+                   tile_row_ptr=h._view(v.tile_row_ptr, v.tile_rows, torch.int32),
+                   tile_row_end=h._view(v.tile_row_end, v.tile_rows, torch.int32),
                    tile_col=h._view(v.tile_col, n, torch.int32),
                    row_mask=h._view(v.row_mask, n * 16, torch.int16),
                    left_group_mask=h._view(v.left_group_mask, n, torch.int32),
@@ -329,6 +333,17 @@ class Tiles:
             out["right_group_off"] = h._view(v.right_group_off, n, torch.int32)
             out["right_elements"] = h._view(v.right_elements, v.right_groups_capacity * 8, torch.float16)
         return out
+
+
+def tile_indices(view: dict):
+    """The tile indices of a tile matrix in storage order (tile-row by tile-row), as a tensor."""
+    torch = _torch()
+    begin, end = view["tile_row_ptr"].to(torch.int64), view["tile_row_end"].to(torch.int64)
+    counts = end - begin
+    starts = torch.repeat_interleave(begin, counts)
+    first = torch.cumsum(counts, 0) - counts
+    within = torch.arange(int(counts.sum()), device=begin.device) - torch.repeat_interleave(first, counts)
+    return starts + within
 
 
 class Plan:

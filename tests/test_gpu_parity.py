@@ -231,22 +231,30 @@ def test_phases_against_paper_objects(tsp, handle, oracle, maker):
     dB = dA if same else tsp.to_device(B)
     tA = handle.convert(dA)
     tB = tA if same else handle.convert(dB)
-    refs = []
+    refs, slots = [], []
     for M, tiles in ((A, tA), (B, tB)):
         bm = oracle.bitmap_format(M, 16)
         refs.append(bm)
-        v = {k: (x.cpu().numpy() if hasattr(x, "cpu") else x) for k, x in tiles.view().items()}
+        view = tiles.view()
+        slot = tsp.tile_indices(view).cpu().numpy()      # tile index of the k-th tile in storage order
+        slots.append(slot)
+        v = {k: (x.cpu().numpy() if hasattr(x, "cpu") else x) for k, x in view.items()}
         n = bm.tile_row.shape[0]
-        assert v["ntiles"] == n and v["tile_rows"] == bm.tile_rows and v["tile_cols"] == bm.tile_cols
-        assert np.array_equal(np.repeat(np.arange(bm.tile_rows), np.diff(v["tile_row_ptr"])), bm.tile_row)
-        assert np.array_equal(v["tile_col"], bm.tile_col)
-        assert np.array_equal(v["row_mask"].view(np.uint16).reshape(n, 16), bm.row_mask.astype(np.uint16))
+        assert v["ntiles"] == n == slot.shape[0]
+        assert v["tile_rows"] == bm.tile_rows and v["tile_cols"] == bm.tile_cols and v["tile_slots"] == M.nnz
+        # a tile-row's tiles start at the position of its first entry in the CSR arrays
+        first_entry = M.row_ptr[np.minimum(np.arange(bm.tile_rows) * 16, M.rows)]
+        assert np.array_equal(v["tile_row_ptr"], first_entry)
+        counts = v["tile_row_end"] - v["tile_row_ptr"]
+        assert np.array_equal(np.repeat(np.arange(bm.tile_rows), counts), bm.tile_row)
+        assert np.array_equal(v["tile_col"][slot], bm.tile_col)
+        assert np.array_equal(v["row_mask"].view(np.uint16).reshape(-1, 16)[slot], bm.row_mask.astype(np.uint16))
         for t in range(n):
             occ = np.array([[(int(bm.row_mask[t, r]) >> c) & 1 for c in range(16)] for r in range(16)], dtype=bool)
             want = np.zeros((16, 16), dtype=np.float16)
             want[occ] = bm.elements[bm.index[t]:bm.index[t + 1]]      # ascending slot order = row-major
             for form in ("left", "right"):
-                got = _decode_groups(v, form, t)
+                got = _decode_groups(v, form, int(slot[t]))
                 assert np.array_equal(got.view(np.uint16), want.view(np.uint16)), (t, form)
     plan = handle.symbolic(tA, tB)
     pv = {k: (x.cpu().numpy() if hasattr(x, "cpu") else x) for k, x in plan.view().items()}
@@ -255,7 +263,8 @@ def test_phases_against_paper_objects(tsp, handle, oracle, maker):
     assert pv["pairs"] == tl.a_tile.shape[0] and pv["c_tiles"] == tl.c_tile_row.shape[0]
     assert pv["candidate_pairs"] == tl.candidates
     assert np.array_equal(pv["pair_off"], tl.offsets)
-    assert np.array_equal(pv["pair_a"], tl.a_tile) and np.array_equal(pv["pair_b"], tl.b_tile)
+    # the task list names tiles by their index in the tile arrays
+    assert np.array_equal(pv["pair_a"], slots[0][tl.a_tile]) and np.array_equal(pv["pair_b"], slots[1][tl.b_tile])
     assert np.array_equal(pv["c_tile_row"], tl.c_tile_row) and np.array_equal(pv["c_tile_col"], tl.c_tile_col)
     assert np.array_equal(pv["c_row_mask"].view(np.uint16).reshape(-1, 16), masks.astype(np.uint16))
     assert pv["c_nnz"] == counts.sum()
