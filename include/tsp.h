@@ -210,7 +210,7 @@ int tsp_tiles_free(tsp_handle handle, tsp_tiles tiles, void *stream);
  * and only non-empty groups are stored.  Left form: group id g = h*16 + r holds slots
  * (r, 8h..8h+7); right form: group id g = h*16 + c holds slots (8h..8h+7, c).  Bit g of the
  * group mask says whether group g is stored; the stored groups of a tile are consecutive, in
- * ascending g, starting at group index *_group_off[t] of the form's element array.
+ * ascending g, starting at the group index *_head[2t + 1] of the form's element array.
  */
 typedef struct {
     int64_t rows, cols;              /* of the matrix (host values)                                 */
@@ -223,7 +223,8 @@ typedef struct {
     const int32_t *tile_col;         /* int32[tile_slots]                                            */
     const uint16_t *row_mask;        /* uint16[tile_slots * 16]                                      */
     const uint32_t *left_group_mask, *right_group_mask;   /* uint32[tile_slots] (always present)     */
-    const uint32_t *left_group_off, *right_group_off;     /* uint32[tile_slots] (NULL if form absent) */
+    const uint32_t *left_head, *right_head;   /* uint32[tile_slots * 2] per tile {group mask, index of   */
+                                              /* its first group} of the form (NULL if form absent)     */
     const uint16_t *left_elements, *right_elements;       /* fp16 bits, 8 per group (NULL if absent) */
     int64_t left_groups_capacity, right_groups_capacity;  /* groups the element arrays can hold     */
 } tsp_tiles_view;

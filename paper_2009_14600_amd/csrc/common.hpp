@@ -77,7 +77,7 @@ struct tsp_tiles_s {
     int32_t *tile_col = nullptr;
     uint16_t *row_mask = nullptr;
     uint32_t *lmask = nullptr, *rmask = nullptr;
-    uint32_t *loff = nullptr, *roff = nullptr;
+    uint2 *lhead = nullptr, *rhead = nullptr;      // per form: {group mask, index of the tile's first group}
     uint4 *ldata = nullptr, *rdata = nullptr;
     int64_t group_capacity = 0;
 };

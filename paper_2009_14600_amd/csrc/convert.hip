@@ -67,7 +67,8 @@ struct ConvArgs {
     // tile arrays
     int32_t *tile_col;
     uint16_t *row_mask;
-    uint32_t *lmask, *rmask, *loff, *roff;
+    uint32_t *lmask, *rmask;
+    uint2 *lhead, *rhead;
     uint4 *ldata, *rdata;
     int64_t *d_scalars;
 };
@@ -339,8 +340,8 @@ __global__ __launch_bounds__(conv_block_threads<G>()) void k_convert_rows(const 
                 dst[1] = make_uint4(s_mask[t * 8 + 4], s_mask[t * 8 + 5], s_mask[t * 8 + 6], s_mask[t * 8 + 7]);
                 a.lmask[tg] = s_lm[t];
                 a.rmask[tg] = s_rm[t];
-                if (a.forms & TSP_FORM_LEFT) a.loff[tg] = lrun + s_lo[t];
-                if (a.forms & TSP_FORM_RIGHT) a.roff[tg] = rrun + s_ro[t];
+                if (a.forms & TSP_FORM_LEFT) a.lhead[tg] = make_uint2(s_lm[t], lrun + s_lo[t]);
+                if (a.forms & TSP_FORM_RIGHT) a.rhead[tg] = make_uint2(s_rm[t], rrun + s_ro[t]);
             }
         }
         // the zeros must be in L2 before any value is stored over them: every wave waits for its own
@@ -450,8 +451,8 @@ __global__ __launch_bounds__(kConvThreads) void k_convert_merge(const ConvArgs<R
                     a.tile_col[t] = m;
                     a.lmask[t] = lm;
                     a.rmask[t] = rm;
-                    if (a.forms & TSP_FORM_LEFT) a.loff[t] = lrun;
-                    if (a.forms & TSP_FORM_RIGHT) a.roff[t] = rrun;
+                    if (a.forms & TSP_FORM_LEFT) a.lhead[t] = make_uint2(lm, lrun);
+                    if (a.forms & TSP_FORM_RIGHT) a.rhead[t] = make_uint2(rm, rrun);
                 }
             }
             lrun += __popc(lm);
@@ -490,8 +491,8 @@ static int launch_convert(tsp_context *ctx, const tsp_csr *A, tsp_tiles_s *t, in
     a.row_mask = t->row_mask;
     a.lmask = t->lmask;
     a.rmask = t->rmask;
-    a.loff = t->loff;
-    a.roff = t->roff;
+    a.lhead = t->lhead;
+    a.rhead = t->rhead;
     a.ldata = t->ldata;
     a.rdata = t->rdata;
     a.d_scalars = ctx->d_scalars;
@@ -538,8 +539,8 @@ void tiles_release(tsp_context *ctx, tsp_tiles_s *t, hipStream_t s) {
     ctx_free(ctx, t->row_mask, s);
     ctx_free(ctx, t->lmask, s);
     ctx_free(ctx, t->rmask, s);
-    ctx_free(ctx, t->loff, s);
-    ctx_free(ctx, t->roff, s);
+    ctx_free(ctx, t->lhead, s);
+    ctx_free(ctx, t->rhead, s);
     ctx_free(ctx, t->ldata, s);
     ctx_free(ctx, t->rdata, s);
     delete t;
@@ -575,14 +576,14 @@ int convert_enqueue(tsp_context *ctx, const tsp_csr *A, int forms, int scalar_sl
     t->rmask = ctx_alloc_n<uint32_t>(ctx, cap, s);
     bool ok = t->tile_row_ptr && t->tile_row_end && t->tile_col && t->row_mask && t->lmask && t->rmask;
     if (forms & TSP_FORM_LEFT) {
-        t->loff = ctx_alloc_n<uint32_t>(ctx, cap, s);
+        t->lhead = ctx_alloc_n<uint2>(ctx, cap, s);
         t->ldata = ctx_alloc_n<uint4>(ctx, (size_t)t->group_capacity, s);
-        ok = ok && t->loff && t->ldata;
+        ok = ok && t->lhead && t->ldata;
     }
     if (forms & TSP_FORM_RIGHT) {
-        t->roff = ctx_alloc_n<uint32_t>(ctx, cap, s);
+        t->rhead = ctx_alloc_n<uint2>(ctx, cap, s);
         t->rdata = ctx_alloc_n<uint4>(ctx, (size_t)t->group_capacity, s);
-        ok = ok && t->roff && t->rdata;
+        ok = ok && t->rhead && t->rdata;
     }
     int32_t *scratch = ctx_alloc_n<int32_t>(ctx, (size_t)t->tile_rows + 1, s);   // path of every tile-row
     ok = ok && scratch;
@@ -675,8 +676,8 @@ extern "C" int tsp_tiles_get_view(tsp_tiles t, tsp_tiles_view *v) {
     v->row_mask = t->row_mask;
     v->left_group_mask = t->lmask;
     v->right_group_mask = t->rmask;
-    v->left_group_off = t->loff;
-    v->right_group_off = t->roff;
+    v->left_head = reinterpret_cast<const uint32_t *>(t->lhead);
+    v->right_head = reinterpret_cast<const uint32_t *>(t->rhead);
     v->left_elements = reinterpret_cast<const uint16_t *>(t->ldata);
     v->right_elements = reinterpret_cast<const uint16_t *>(t->rdata);
     v->left_groups_capacity = t->ldata ? t->group_capacity : 0;

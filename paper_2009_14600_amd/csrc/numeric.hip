@@ -72,6 +72,11 @@ struct BufferArray {
     __device__ __forceinline__ uint32_t u32(uint32_t byte_off) const {
         return __builtin_amdgcn_raw_buffer_load_b32(rsrc, byte_off, 0, 0);
     }
+    __device__ __forceinline__ uint2 u64(uint32_t byte_off) const {
+        typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+        const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rsrc, byte_off, 0, 0);
+        return make_uint2(v.x, v.y);
+    }
     template <int kPlus>
     __device__ __forceinline__ uint4 u128(uint32_t byte_off) const {
         const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, byte_off, kPlus, 0);
@@ -112,9 +117,8 @@ __device__ __forceinline__ void swap_rows(float &x, float &y, bool halves) {
 template <bool kNarrow, int kTilesPerWave, bool kMatrixCores>
 __global__ __launch_bounds__(kNumThreads) void k_numeric(
     const int64_t c_tiles, const int64_t c_nnz, const NumericSizes z, const int64_t *__restrict__ pair_off,
-    const int32_t *__restrict__ pair_a_, const int32_t *__restrict__ pair_b_, const uint32_t *__restrict__ a_lmask_,
-    const uint32_t *__restrict__ a_loff_, const uint4 *__restrict__ a_ldata_, const uint32_t *__restrict__ b_rmask_,
-    const uint32_t *__restrict__ b_roff_, const uint4 *__restrict__ b_rdata_, const int32_t *__restrict__ c_tile_row,
+    const int32_t *__restrict__ pair_a_, const int32_t *__restrict__ pair_b_, const uint2 *__restrict__ a_lhead_,
+    const uint4 *__restrict__ a_ldata_, const uint2 *__restrict__ b_rhead_, const uint4 *__restrict__ b_rdata_, const int32_t *__restrict__ c_tile_row,
     const int32_t *__restrict__ c_tile_col, const uint16_t *__restrict__ c_row_mask,
     const uint32_t *__restrict__ c_row_off, const int64_t *__restrict__ c_row_ptr, int32_t *__restrict__ c_col,
     float *__restrict__ c_val) {
@@ -139,8 +143,7 @@ __global__ __launch_bounds__(kNumThreads) void k_numeric(
     const int j = lane & 15, tq = lane >> 4;
     // descriptors (used by the narrow kernels only)
     const BufferArray pair_a(pair_a_, z.pairs * 4), pair_b(pair_b_, z.pairs * 4);
-    const BufferArray a_lmask(a_lmask_, z.a_tiles * 4), a_loff(a_loff_, z.a_tiles * 4);
-    const BufferArray b_rmask(b_rmask_, z.b_tiles * 4), b_roff(b_roff_, z.b_tiles * 4);
+    const BufferArray a_lhead(a_lhead_, z.a_tiles * 8), b_rhead(b_rhead_, z.b_tiles * 8);
     const BufferArray a_ldata(a_ldata_, z.a_groups * 16), b_rdata(b_rdata_, z.b_groups * 16);
     uint4 *const my_heads = lds_heads[wave_in_block];
     const uint4 *const my_half = my_heads + upper;    // lanes 32-63 read the entry after the one lanes 0-31 read
@@ -167,14 +170,15 @@ __global__ __launch_bounds__(kNumThreads) void k_numeric(
             // lanes that take part in it
             if (valid) {
                 const uint32_t e = (uint32_t)(base + start + lane) * 4u;
-                const uint32_t ao = pair_a.u32(e) * 4u, bo = pair_b.u32(e) * 4u;
+                const uint2 la = a_lhead.u64(pair_a.u32(e) * 8u), rb = b_rhead.u64(pair_b.u32(e) * 8u);
                 // group offsets become byte offsets: the descriptors address bytes
-                record = make_uint4(a_lmask.u32(ao), a_loff.u32(ao) << 4, b_rmask.u32(bo), b_roff.u32(bo) << 4);
+                record = make_uint4(la.x, la.y << 4, rb.x, rb.y << 4);
             }
         } else if (valid) {
             const int64_t e = base + start + lane;
             const int64_t a = pair_a_[e], b = pair_b_[e];
-            record = make_uint4(a_lmask_[a], a_loff_[a], b_rmask_[b], b_roff_[b]);
+            const uint2 la = a_lhead_[a], rb = b_rhead_[b];
+            record = make_uint4(la.x, la.y, rb.x, rb.y);
         }
         wave_sync();                               // earlier reads of the records are done
         my_heads[lane] = record;
@@ -385,13 +389,13 @@ int numeric_enqueue(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s
                              (uint64_t)A->group_capacity, (uint64_t)B->group_capacity};
         const uint64_t limit = (1ull << 32) - 64;
         const bool narrow = z.pairs * 4 < limit && z.a_groups * 16 < limit && z.b_groups * 16 < limit &&
-                            z.a_tiles * 4 < limit && z.b_tiles * 4 < limit && (uint64_t)P->c_tiles * T * 4 < limit &&
+                            z.a_tiles * 8 < limit && z.b_tiles * 8 < limit && (uint64_t)P->c_tiles * T * 4 < limit &&
                             (uint64_t)P->c_nnz * 4 < limit && !ctx->force_wide;
         auto kernel = narrow ? (tiles_per_wave == 4 ? k_numeric<true, 4, true> : k_numeric<true, 8, true>)
                              : (tiles_per_wave == 4 ? k_numeric<false, 4, true> : k_numeric<false, 8, true>);
         if (!ctx->matrix_cores) kernel = narrow ? k_numeric<true, 4, false> : k_numeric<false, 4, false>;
         hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(kNumThreads), 0, s, P->c_tiles, P->c_nnz, z, P->pair_off,
-                           P->pair_a, P->pair_b, A->lmask, A->loff, A->ldata, B->rmask, B->roff, B->rdata,
+                           P->pair_a, P->pair_b, A->lhead, A->ldata, B->rhead, B->rdata,
                            P->c_tile_row, P->c_tile_col, P->c_row_mask, P->c_row_off, P->c_row_ptr, col, val);
         e = hipGetLastError();
     }

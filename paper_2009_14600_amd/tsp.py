@@ -64,7 +64,7 @@ class _TilesView(ctypes.Structure):
                 ("tile_row_ptr", ctypes.c_void_p), ("tile_row_end", ctypes.c_void_p),
                 ("tile_col", ctypes.c_void_p), ("row_mask", ctypes.c_void_p),
                 ("left_group_mask", ctypes.c_void_p), ("right_group_mask", ctypes.c_void_p),
-                ("left_group_off", ctypes.c_void_p), ("right_group_off", ctypes.c_void_p),
+                ("left_head", ctypes.c_void_p), ("right_head", ctypes.c_void_p),
                 ("left_elements", ctypes.c_void_p), ("right_elements", ctypes.c_void_p),
                 ("left_groups_capacity", ctypes.c_int64), ("right_groups_capacity", ctypes.c_int64)]
 
@@ -327,10 +327,10 @@ class Tiles:
                    left_group_mask=h._view(v.left_group_mask, n, torch.int32),
                    right_group_mask=h._view(v.right_group_mask, n, torch.int32))
         if v.forms & FORM_LEFT:
-            out["left_group_off"] = h._view(v.left_group_off, n, torch.int32)
+            out["left_group_off"] = h._view(v.left_head, n * 2, torch.int32).view(n, 2)[:, 1]
             out["left_elements"] = h._view(v.left_elements, v.left_groups_capacity * 8, torch.float16)
         if v.forms & FORM_RIGHT:
-            out["right_group_off"] = h._view(v.right_group_off, n, torch.int32)
+            out["right_group_off"] = h._view(v.right_head, n * 2, torch.int32).view(n, 2)[:, 1]
             out["right_elements"] = h._view(v.right_elements, v.right_groups_capacity * 8, torch.float16)
         return out
 
