@@ -39,17 +39,14 @@ template <int G> constexpr int conv_block_threads() { return G == 64 ? 256 : G; 
 template <> struct ConvCfg<64> {                  // one wave per tile-row, four tile-rows per block
     static constexpr int kWords = 512;            // bitmap words: tile columns may span 16384
     static constexpr int kWindow = 32;            // tiles handled per pass over the entries
-    static constexpr int kCache = 8;              // entries per thread kept in registers between passes
 };
 template <> struct ConvCfg<128> {                 // one 128-thread block per tile-row
     static constexpr int kWords = 1024;
     static constexpr int kWindow = 64;
-    static constexpr int kCache = 8;
 };
 template <> struct ConvCfg<256> {                 // one 256-thread block per tile-row
     static constexpr int kWords = 1024;           // span of 32768 tile columns
     static constexpr int kWindow = 128;
-    static constexpr int kCache = 8;
 };
 
 __device__ __forceinline__ uint16_t to_half_bits(uint16_t v) { return v; }
@@ -137,10 +134,11 @@ __device__ __forceinline__ uint32_t group_exclusive_scan(uint32_t *arr, int n, i
 // ------------------------------------------------------------------------------------------------
 // Fast path: LDS bitmap over the tile-row's span of tile columns.
 // ------------------------------------------------------------------------------------------------
-template <int G, typename RP, typename VT>
+// kConvCache: entries per thread kept in registers between the passes (tile-rows with more entries
+// than G*kConvCache read the CSR arrays again in every pass)
+template <int G, int kConvCache, typename RP, typename VT>
 __global__ __launch_bounds__(conv_block_threads<G>()) void k_convert_rows(const ConvArgs<RP, VT> a) {
     constexpr int kWords = ConvCfg<G>::kWords, kWindow = ConvCfg<G>::kWindow, kGroups = conv_block_threads<G>() / G;
-    constexpr int kConvCache = ConvCfg<G>::kCache;
     __shared__ int s_rp_all[kGroups][20];
     __shared__ uint32_t s_bm_all[kGroups][kWords], s_pre_all[kGroups][kWords];
     __shared__ uint32_t s_mask_all[kGroups][kWindow * 8];
@@ -499,8 +497,12 @@ static int launch_convert(tsp_context *ctx, const tsp_csr *A, tsp_tiles_s *t, in
     // threads per tile-row from the mean number of entries per tile-row (the kernel is bound by
     // dependent steps, so small groups, many in flight, win as long as the entries fit their registers);
     // the merge path only when a tile-row could span more tile columns than the chosen bitmap holds
-    const int64_t per_row = ntr > 0 ? A->nnz / ntr : 0;
-    const int G = per_row <= 64 * ConvCfg<64>::kCache ? 64 : per_row <= 128 * ConvCfg<128>::kCache ? 128 : 256;
+    // Registers per thread for the entries: the mean tile-row plus 15 %, so that most tile-rows stay in
+    // registers without the kernel paying (in occupancy) for registers it does not use.
+    const int64_t per_row = ntr > 0 ? A->nnz / ntr : 0, need = per_row + (3 * per_row + 19) / 20;
+    const int G = need <= 64 * 8 ? 64 : need <= 128 * 8 ? 128 : 256;
+    const int64_t want = (need + G - 1) / G;
+    const int cache = G == 64 ? (want <= 2 ? 2 : want <= 4 ? 4 : 8) : (want <= 6 ? 6 : 8);
     const int64_t bitmap_span =
         32ll * (G == 64 ? ConvCfg<64>::kWords : G == 128 ? ConvCfg<128>::kWords : ConvCfg<256>::kWords);
     // (tile-rows of a narrow matrix cannot exceed the bitmap, and then the merge kernel is not launched)
@@ -509,9 +511,16 @@ static int launch_convert(tsp_context *ctx, const tsp_csr *A, tsp_tiles_s *t, in
     const unsigned grid_merge = (unsigned)((ntr + kMergeGroupsPerBlock - 1) / kMergeGroupsPerBlock);
     if (ntr > 0) {
         KernelTimer kt(ctx, TSP_KERNEL_CONVERT, s);
-        if (G == 64) hipLaunchKernelGGL((k_convert_rows<64, RP, VT>), dim3(grid_fast), dim3(256), 0, s, a);
-        else if (G == 128) hipLaunchKernelGGL((k_convert_rows<128, RP, VT>), dim3(grid_fast), dim3(128), 0, s, a);
-        else hipLaunchKernelGGL((k_convert_rows<256, RP, VT>), dim3(grid_fast), dim3(256), 0, s, a);
+#define TSP_LAUNCH_ROWS(g, c, threads) \
+    hipLaunchKernelGGL((k_convert_rows<g, c, RP, VT>), dim3(grid_fast), dim3(threads), 0, s, a)
+        if (G == 64 && cache == 2) TSP_LAUNCH_ROWS(64, 2, 256);
+        else if (G == 64 && cache == 4) TSP_LAUNCH_ROWS(64, 4, 256);
+        else if (G == 64) TSP_LAUNCH_ROWS(64, 8, 256);
+        else if (G == 128 && cache == 6) TSP_LAUNCH_ROWS(128, 6, 128);
+        else if (G == 128) TSP_LAUNCH_ROWS(128, 8, 128);
+        else if (cache == 6) TSP_LAUNCH_ROWS(256, 6, 256);
+        else TSP_LAUNCH_ROWS(256, 8, 256);
+#undef TSP_LAUNCH_ROWS
         if (may_merge)
             hipLaunchKernelGGL((k_convert_merge<RP, VT>), dim3(grid_merge), dim3(kConvThreads), 0, s, a);
     }
