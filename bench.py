@@ -36,8 +36,8 @@ MFMA_F16_PEAK_TFLOPS = 2500.0  # dense fp16 MFMA, published
 # 2048 * FETCH_SIZE, written bytes = 1024 * WRITE_SIZE.  profiles/hbm_traffic_all_kernels.txt holds the
 # readings and commands.  Keyed by (workload, kernel); a kernel that has changed since needs a new reading.
 MEASURED_TRAFFIC_BYTES = {
-    (2, "numeric"): 2048 * 27186.6 + 1024 * 28253.7,
-    (3, "numeric"): 2048 * 337034.0 + 1024 * 1122351.8,
+    (2, "numeric"): 2048 * 30344.7 + 1024 * 26551.6,
+    (3, "numeric"): 2048 * 335840.0 + 1024 * 1060909.3,
 }
 
 
@@ -55,7 +55,7 @@ def algorithmic_bytes(kernel, A, st, groups_left, groups_right):
     n, nnz = A.rows, A.nnz
     ta, ct, pairs, cnnz = st["a_tiles"], st["c_tiles"], st["pairs"], st["c_nnz"]
     ntr = (n + 15) // 16
-    tile_meta = ta * (4 + 32 + 4 + 4 + 4 + 4)          # tile_col, row masks, 2 group masks, 2 group offsets
+    tile_meta = ta * (4 + 32 + 4 + 4 + 8 + 8)          # tile_col, row masks, 2 group masks, 2 headers {mask, first group}
     csr_in = 4 * (n + 1) + 6 * nnz
     table = {
         "convert": csr_in + 8 * ntr + tile_meta + 16 * (groups_left + groups_right),
@@ -65,7 +65,7 @@ def algorithmic_bytes(kernel, A, st, groups_left, groups_right):
         "count_masks": 8 * ct + 8 * pairs + 32 * ta + 32 * ta + 32 * ct,
         "row_offsets": 4 * ntr + 32 * ct + 64 * ct + 4 * n,
         "numeric": (8 * ct + 8 * pairs + 8 * ct + 32 * ct + 64 * ct + 8 * (n + 1)      # task list, C tile info
-                    + 16 * ta + 16 * (groups_left + groups_right)                    # tiles, each once
+                    + 16 * ta + 16 * (groups_left + groups_right)                    # tile headers and groups, each once
                     + 8 * cnnz),                                                     # C col_idx + val
         "scan_sym": 24 * ntr, "scan_rows": 16 * n,
     }
