@@ -29,6 +29,7 @@ namespace tsp {
 constexpr int kSymThreads = 256;
 constexpr int kMaxWords = 4096;        // LDS bitmap words per tile-row: span of 131072 tile columns
 constexpr int kWindow = 2048;          // C tiles of one tile-row handled per LDS window
+constexpr int kSurvivorUnroll = 4;     // B tiles one lane requests per trip of the candidate loop
 
 struct TileRefs {
     const int32_t *trp;      // first tile of every tile-row
@@ -76,7 +77,8 @@ __device__ __forceinline__ uint32_t block_exclusive_scan_lds(uint32_t *arr, int 
 // Visits every surviving candidate pair of tile-row I whose A tile index lies in [a_begin,a_end).
 // `lanes_per_a` lanes share one A tile and stride over the tiles of B's tile-row K.
 // f(a, b, J) is called once per survivor; *candidates counts all candidates visited by this thread.
-template <class F>
+// kLongRows: built for operands whose B tile-rows are long (more tiles than lanes share an A tile).
+template <bool kLongRows, class F>
 __device__ __forceinline__ void for_each_survivor(const TileRefs &A, const TileRefs &B, int a_begin, int a_end,
                                                   int lanes_per_a, uint32_t *candidates, F f) {
     const int sub = threadIdx.x / lanes_per_a, l = threadIdx.x % lanes_per_a;
@@ -86,7 +88,24 @@ __device__ __forceinline__ void for_each_survivor(const TileRefs &A, const TileR
         if (K >= (uint32_t)B.tile_rows) continue;            // only possible for a non-canonical input
         const uint32_t col_occ = fold16(A.rmask[a]);
         const int b0 = B.trp[K], b1 = B.tend[K];
-        for (int b = b0 + l; b < b1; b += lanes_per_a) {
+        // several tiles of B's tile-row per trip, their loads requested together (long tile-rows are
+        // bound by the round trips of this loop)
+        int b = b0 + l;
+        if constexpr (kLongRows)
+        for (; b + (kSurvivorUnroll - 1) * lanes_per_a < b1; b += kSurvivorUnroll * lanes_per_a) {
+            uint32_t occ[kSurvivorUnroll];
+            int col[kSurvivorUnroll];
+#pragma unroll
+            for (int u = 0; u < kSurvivorUnroll; ++u) {
+                occ[u] = B.lmask[b + u * lanes_per_a];
+                col[u] = B.tcol[b + u * lanes_per_a];
+            }
+            *candidates += kSurvivorUnroll;
+#pragma unroll
+            for (int u = 0; u < kSurvivorUnroll; ++u)
+                if (col_occ & fold16(occ[u])) f(a, b + u * lanes_per_a, col[u]);
+        }
+        for (; b < b1; b += lanes_per_a) {
             ++*candidates;
             if (col_occ & fold16(B.lmask[b])) f(a, b, B.tcol[b]);
         }
@@ -95,6 +114,7 @@ __device__ __forceinline__ void for_each_survivor(const TileRefs &A, const TileR
 
 // Pass 1 per tile-row: span of candidate tile columns, number of C tiles, of surviving pairs, of
 // candidates.  Dynamic LDS: max_words words.
+template <bool kLongRows>
 __global__ __launch_bounds__(kSymThreads) void k_sym_count(TileRefs A, TileRefs B, int lanes_per_a, int max_words,
                                                            int32_t *__restrict__ row_jmin,
                                                            int32_t *__restrict__ row_c_tiles,
@@ -156,7 +176,7 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_count(TileRefs A, TileRefs 
     for (int w = threadIdx.x; w < words; w += blockDim.x) bm[w] = 0;
     __syncthreads();
     uint32_t cand = 0, surv = 0;
-    for_each_survivor(A, B, a0, a1, lanes_per_a, &cand, [&](int, int, int J) {
+    for_each_survivor<kLongRows>(A, B, a0, a1, lanes_per_a, &cand, [&](int, int, int J) {
         const uint32_t j = (uint32_t)(J - jmin);
         if (j < (uint32_t)span) {
             atomicOr(&bm[j >> 5], 1u << (j & 31));
@@ -280,6 +300,7 @@ __global__ __launch_bounds__(kRowScanThreads) void k_sym_row_scan(
 
 // Pass 2 per tile-row: C tile coordinates, task-list offsets, task list.
 // Dynamic LDS: 2*words_cap + 2*window words.
+template <bool kLongRows>
 __global__ __launch_bounds__(kSymThreads) void k_sym_emit(
     TileRefs A, TileRefs B, int lanes_per_a, int words_cap, int window, const int32_t *__restrict__ row_jmin,
     const int32_t *__restrict__ c_tile_row_ptr, const int64_t *__restrict__ row_pair_ptr,
@@ -316,7 +337,7 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_emit(
     for (int w = threadIdx.x; w < words; w += blockDim.x) bm[w] = 0;
     __syncthreads();
     uint32_t dummy = 0;
-    for_each_survivor(A, B, a0, a1, lanes_per_a, &dummy, [&](int, int, int J) {
+    for_each_survivor<kLongRows>(A, B, a0, a1, lanes_per_a, &dummy, [&](int, int, int J) {
         const uint32_t j = (uint32_t)(J - jmin);
         if (j < (uint32_t)span) atomicOr(&bm[j >> 5], 1u << (j & 31));
     });
@@ -353,7 +374,7 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_emit(
         for (int ch = a0; ch < a1; ch += 32) {
             for (int c = threadIdx.x; c < nw; c += blockDim.x) contrib[c] = 0;
             __syncthreads();
-            for_each_survivor(A, B, ch, min(ch + 32, a1), lanes_per_a, &dummy, [&](int a, int, int J) {
+            for_each_survivor<kLongRows>(A, B, ch, min(ch + 32, a1), lanes_per_a, &dummy, [&](int a, int, int J) {
                 const int c = rank_in_window(J);
                 if (c >= 0) atomicOr(&contrib[c], 1u << (a - ch));
             });
@@ -369,13 +390,13 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_emit(
             if (!one_chunk) {
                 for (int c = threadIdx.x; c < nw; c += blockDim.x) contrib[c] = 0;
                 __syncthreads();
-                for_each_survivor(A, B, ch, min(ch + 32, a1), lanes_per_a, &dummy, [&](int a, int, int J) {
+                for_each_survivor<kLongRows>(A, B, ch, min(ch + 32, a1), lanes_per_a, &dummy, [&](int a, int, int J) {
                     const int c = rank_in_window(J);
                     if (c >= 0) atomicOr(&contrib[c], 1u << (a - ch));
                 });
                 __syncthreads();
             }
-            for_each_survivor(A, B, ch, min(ch + 32, a1), lanes_per_a, &dummy, [&](int a, int b, int J) {
+            for_each_survivor<kLongRows>(A, B, ch, min(ch + 32, a1), lanes_per_a, &dummy, [&](int a, int b, int J) {
                 const int c = rank_in_window(J);
                 if (c >= 0) {
                     const int64_t pos = row_base + (int64_t)win_base + (int64_t)cnt[c] +
@@ -571,10 +592,15 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
     // tiles-per-tile-row of B is not known on the host before the first read-back: estimate the
     // sharing width from the bound nnz/tile_rows (an upper bound on the mean), capped
     int lanes = 4;
+    bool long_rows = false;                // B tile-rows long enough for the unrolled candidate loop
     {
         const double mean_bound = B->tile_rows > 0 ? (double)B->nnz / (double)B->tile_rows : 1.0;
         while (lanes < 32 && lanes * 4 < mean_bound) lanes <<= 1;
-        if (B->ntiles >= 0) lanes = lanes_per_a_tile(B);
+        long_rows = mean_bound > 128.0;
+        if (B->ntiles >= 0) {
+            lanes = lanes_per_a_tile(B);
+            long_rows = (double)B->ntiles > 48.0 * (double)B->tile_rows;
+        }
     }
     if (ntr > 0) {
         KernelTimer kt(ctx, TSP_KERNEL_SYM_COUNT, s);
@@ -583,7 +609,8 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
         const int max_words = (int)std::min<int64_t>(kMaxWords, (B->tile_cols + 31) / 32 + 1);
         const int64_t per_row = A->nnz / ntr;
         const int threads = per_row <= 256 ? 64 : per_row <= 4096 ? 128 : kSymThreads;
-        hipLaunchKernelGGL(k_sym_count, dim3((unsigned)ntr), dim3(threads), max_words * sizeof(uint32_t), s, ra, rb,
+        hipLaunchKernelGGL(long_rows ? k_sym_count<true> : k_sym_count<false>, dim3((unsigned)ntr), dim3(threads),
+                           max_words * sizeof(uint32_t), s, ra, rb,
                            lanes, max_words, row_jmin, row_c_tiles, row_pairs, row_words, row_cand, ctx->d_scalars);
         SYM_CHECK(hipGetLastError());
     }
@@ -637,10 +664,12 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
         if (window < 1) window = 1;
         const size_t lds = (size_t)(2 * words_cap + 2 * window) * sizeof(uint32_t);
         lanes = lanes_per_a_tile(B);
+        long_rows = (double)B->ntiles > 48.0 * (double)B->tile_rows;
         KernelTimer kt(ctx, TSP_KERNEL_SYM_EMIT, s);
         const int64_t per_row = P->candidates / ntr;
         const int threads = per_row <= 256 ? 64 : per_row <= 4096 ? 128 : kSymThreads;
-        hipLaunchKernelGGL(k_sym_emit, dim3((unsigned)ntr), dim3(threads), lds, s, ra, rb, lanes, words_cap,
+        hipLaunchKernelGGL(long_rows ? k_sym_emit<true> : k_sym_emit<false>, dim3((unsigned)ntr), dim3(threads), lds, s,
+                           ra, rb, lanes, words_cap,
                            window, row_jmin, P->c_tile_row_ptr, row_pair_ptr, P->c_tile_row, P->c_tile_col,
                            P->pair_off, P->pair_a, P->pair_b);
         SYM_CHECK(hipGetLastError());
