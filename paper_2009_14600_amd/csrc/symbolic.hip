@@ -74,6 +74,32 @@ __device__ __forceinline__ uint32_t block_exclusive_scan_lds(uint32_t *arr, int 
     return carry;
 }
 
+// The same scan on words that may live in global memory (written by this block only; the reads go
+// past the L1 cache, the barriers order them after the writes).
+__device__ __forceinline__ uint32_t block_exclusive_scan_words(uint32_t *arr, int n, uint32_t *lds /*[>=17]*/) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+    uint32_t carry = 0;
+    __syncthreads();
+    for (int base = 0; base < n; base += blockDim.x) {
+        const int i = base + threadIdx.x;
+        const uint32_t x = i < n ? __hip_atomic_load(&arr[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0;
+        const uint32_t v = wave_inclusive_scan(x);
+        __syncthreads();
+        if (lane == 63) lds[wave] = v;
+        __syncthreads();
+        uint32_t before = 0, all = 0;
+        for (int w = 0; w < nw; ++w) {
+            uint32_t y = lds[w];
+            if (w < wave) before += y;
+            all += y;
+        }
+        if (i < n) arr[i] = carry + before + v - x;
+        carry += all;
+    }
+    __syncthreads();
+    return carry;
+}
+
 // Visits every surviving candidate pair of tile-row I whose A tile index lies in [a_begin,a_end).
 // `lanes_per_a` lanes share one A tile and stride over the tiles of B's tile-row K.
 // f(a, b, J) is called once per survivor; *candidates counts all candidates visited by this thread.
@@ -299,10 +325,12 @@ __global__ __launch_bounds__(kRowScanThreads) void k_sym_row_scan(
 }
 
 // Pass 2 per tile-row: C tile coordinates, task-list offsets, task list.
-// Dynamic LDS: 2*words_cap + 2*window words.
+// Dynamic LDS: 2*words_cap + 2*window words.  Tile-rows with more than wide_threshold C tiles are left
+// to k_sym_emit_wide.
 template <bool kLongRows>
 __global__ __launch_bounds__(kSymThreads) void k_sym_emit(
-    TileRefs A, TileRefs B, int lanes_per_a, int words_cap, int window, const int32_t *__restrict__ row_jmin,
+    TileRefs A, TileRefs B, int lanes_per_a, int words_cap, int window, int wide_threshold,
+    const int32_t *__restrict__ row_jmin,
     const int32_t *__restrict__ c_tile_row_ptr, const int64_t *__restrict__ row_pair_ptr,
     int32_t *__restrict__ c_tile_row, int32_t *__restrict__ c_tile_col, int64_t *__restrict__ pair_off,
     int32_t *__restrict__ pair_a, int32_t *__restrict__ pair_b) {
@@ -315,7 +343,7 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_emit(
     const int I = blockIdx.x;
     const int c0 = c_tile_row_ptr[I], nC = c_tile_row_ptr[I + 1] - c0;
     if (I == (int)gridDim.x - 1 && threadIdx.x == 0) pair_off[c_tile_row_ptr[gridDim.x]] = row_pair_ptr[gridDim.x];
-    if (nC <= 0) return;
+    if (nC <= 0 || nC > wide_threshold) return;      // (wider tile-rows: k_sym_emit_wide)
     const int a0 = A.trp[I], a1 = A.tend[I];
     const int jmin = row_jmin[I];
     // the span is recomputed from the bitmap extent the first pass used: highest J over the row
@@ -414,6 +442,137 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_emit(
         win_base += win_total;
         __syncthreads();
     }
+}
+
+// The same pass for the tile-rows with more than wide_threshold C tiles.  Dynamic LDS: 2*words_cap words.
+template <bool kLongRows>
+__global__ __launch_bounds__(kSymThreads) void k_sym_emit_wide(
+    TileRefs A, TileRefs B, int lanes_per_a, int words_cap, int wide_threshold,
+    const int32_t *__restrict__ row_jmin,
+    const int32_t *__restrict__ c_tile_row_ptr, const int64_t *__restrict__ row_pair_ptr,
+    int32_t *__restrict__ c_tile_row, int32_t *__restrict__ c_tile_col, int64_t *__restrict__ pair_off,
+    int32_t *__restrict__ pair_a, int32_t *__restrict__ pair_b, uint32_t *wide_contrib, uint32_t *wide_cnt) {
+    extern __shared__ uint32_t lds_dyn[];
+    __shared__ uint32_t red[32];
+    uint32_t *bm = lds_dyn;
+    uint32_t *wpre = bm + words_cap;
+    const int I = blockIdx.x;
+    const int nthreads = (int)blockDim.x;       // read once: the compiler reloads it at every use otherwise
+    const int c0 = c_tile_row_ptr[I], nC = c_tile_row_ptr[I + 1] - c0;
+    if (nC <= 0) return;
+    if (nC <= wide_threshold) return;               // k_sym_emit's tile-row
+    const int a0 = A.trp[I], a1 = A.tend[I];
+    const int jmin = row_jmin[I];
+    // the span is recomputed from the bitmap extent the first pass used: highest J over the row
+    int jmax = -1;
+    for (int a = a0 + threadIdx.x; a < a1; a += nthreads) {
+        const uint32_t K = (uint32_t)A.tcol[a];
+        if (K >= (uint32_t)B.tile_rows) continue;
+        const int b0 = B.trp[K], b1 = B.tend[K];
+        if (b0 < b1) jmax = max(jmax, B.tcol[b1 - 1]);
+    }
+    __shared__ int s_jmax;
+    if (threadIdx.x == 0) s_jmax = -1;
+    __syncthreads();
+    if (jmax >= 0) atomicMax(&s_jmax, jmax);
+    __syncthreads();
+    jmax = s_jmax;
+    const int64_t span = (int64_t)jmax - jmin + 1;
+    const int words = (int)((span + 31) >> 5);       // <= words_cap: rows over the limit have nC = 0
+    for (int w = threadIdx.x; w < words; w += nthreads) bm[w] = 0;
+    __syncthreads();
+    uint32_t dummy = 0;
+    for_each_survivor<kLongRows>(A, B, a0, a1, lanes_per_a, &dummy, [&](int, int, int J) {
+        const uint32_t j = (uint32_t)(J - jmin);
+        if (j < (uint32_t)span) atomicOr(&bm[j >> 5], 1u << (j & 31));
+    });
+    __syncthreads();
+    for (int w = threadIdx.x; w < words; w += nthreads) wpre[w] = __popc(bm[w]);
+    __syncthreads();
+    block_exclusive_scan_lds(wpre, words, red);
+    // C tile coordinates, ascending J
+    for (int w = threadIdx.x; w < words; w += nthreads) {
+        uint32_t bits = bm[w];
+        int c = c0 + (int)wpre[w];
+        while (bits) {
+            const int bit = __ffs(bits) - 1;
+            bits &= bits - 1;
+            c_tile_row[c] = I;
+            c_tile_col[c] = jmin + w * 32 + bit;
+            ++c;
+        }
+    }
+    const int64_t row_base = row_pair_ptr[I];
+    const bool one_chunk = (a1 - a0) <= 32;
+    // The pairs of the tile-row are placed window by window of C tiles: per C tile of the window a
+    // word that collects which of 32 A tiles contribute (`contrib`) and a running count (`cnt`).
+    // Every window costs three passes over all candidates of the tile-row, so a tile-row with more
+    // C tiles than the LDS window holds takes its two arrays from global memory instead and does
+    // everything in one window.  Reads of the arrays go past the L1 cache (the words are written
+    // with atomics, which are performed in L2).
+    auto place = [&](uint32_t *contrib, uint32_t *cnt, const int window) {
+        auto peek = [](const uint32_t *p) {
+            return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        };
+        uint32_t win_base = 0;
+        for (int win0 = 0; win0 < nC; win0 += window) {
+            const int nw = min(window, nC - win0);
+            auto rank_in_window = [&](int J) -> int {
+                const uint32_t j = (uint32_t)(J - jmin);
+                if (j >= (uint32_t)span) return -1;
+                const uint32_t word = bm[j >> 5];
+                const int c = (int)wpre[j >> 5] + __popc(word & ((1u << (j & 31)) - 1u)) - win0;
+                return (c >= 0 && c < nw) ? c : -1;
+            };
+            for (int c = threadIdx.x; c < nw; c += nthreads) cnt[c] = 0;
+            // count pass: 32 A tiles at a time
+            for (int ch = a0; ch < a1; ch += 32) {
+                for (int c = threadIdx.x; c < nw; c += nthreads) contrib[c] = 0;
+                __syncthreads();
+                for_each_survivor<kLongRows>(A, B, ch, min(ch + 32, a1), lanes_per_a, &dummy, [&](int a, int, int J) {
+                    const int c = rank_in_window(J);
+                    if (c >= 0) atomicOr(&contrib[c], 1u << (a - ch));
+                });
+                __syncthreads();
+                for (int c = threadIdx.x; c < nw; c += nthreads) cnt[c] = peek(&cnt[c]) + __popc(peek(&contrib[c]));
+                __syncthreads();
+            }
+            const uint32_t win_total = block_exclusive_scan_words(cnt, nw, red);
+            for (int c = threadIdx.x; c < nw; c += nthreads)
+                pair_off[c0 + win0 + c] = row_base + (int64_t)win_base + (int64_t)peek(&cnt[c]);
+            // emit pass
+            for (int ch = a0; ch < a1; ch += 32) {
+                if (!one_chunk) {
+                    for (int c = threadIdx.x; c < nw; c += nthreads) contrib[c] = 0;
+                    __syncthreads();
+                    for_each_survivor<kLongRows>(A, B, ch, min(ch + 32, a1), lanes_per_a, &dummy,
+                                                 [&](int a, int, int J) {
+                                                     const int c = rank_in_window(J);
+                                                     if (c >= 0) atomicOr(&contrib[c], 1u << (a - ch));
+                                                 });
+                    __syncthreads();
+                }
+                for_each_survivor<kLongRows>(A, B, ch, min(ch + 32, a1), lanes_per_a, &dummy, [&](int a, int b, int J) {
+                    const int c = rank_in_window(J);
+                    if (c >= 0) {
+                        const int64_t pos = row_base + (int64_t)win_base + (int64_t)peek(&cnt[c]) +
+                                            __popc(peek(&contrib[c]) & ((1u << (a - ch)) - 1u));
+                        pair_a[pos] = a;
+                        pair_b[pos] = b;
+                    }
+                });
+                __syncthreads();
+                if (!one_chunk) {
+                    for (int c = threadIdx.x; c < nw; c += nthreads)
+                        cnt[c] = peek(&cnt[c]) + __popc(peek(&contrib[c]));
+                    __syncthreads();
+                }
+            }
+            win_base += win_total;
+            __syncthreads();
+        }
+    };
+    place(wide_contrib + c0, wide_cnt + c0, nC);
 }
 
 // Counting pass: 16 lanes per C tile, lane r owns row r of the tile.  For each pair of the tile's
@@ -554,6 +713,7 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
     int rc = TSP_OK;
     int32_t *row_jmin = nullptr, *row_c_tiles = nullptr, *row_pairs = nullptr, *row_nnz = nullptr;
     int32_t *row_words = nullptr, *row_cand = nullptr;
+    uint32_t *wide_words = nullptr;
     int64_t *row_pair_ptr = nullptr, *tmp = nullptr;
     auto cleanup = [&](int code) {
         ctx_free(ctx, row_jmin, s);
@@ -561,6 +721,7 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
         ctx_free(ctx, row_pairs, s);
         ctx_free(ctx, row_words, s);
         ctx_free(ctx, row_cand, s);
+        ctx_free(ctx, wide_words, s);
         ctx_free(ctx, row_nnz, s);
         ctx_free(ctx, row_pair_ptr, s);
         ctx_free(ctx, tmp, s);
@@ -665,13 +826,24 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
         const size_t lds = (size_t)(2 * words_cap + 2 * window) * sizeof(uint32_t);
         lanes = lanes_per_a_tile(B);
         long_rows = (double)B->ntiles > 48.0 * (double)B->tile_rows;
+        // tile-rows with more C tiles than the LDS window take their two per-tile arrays from here
+        if (h[S_MAX_ROW_C_TILES] > window) {
+            wide_words = ctx_alloc_n<uint32_t>(ctx, 2 * (size_t)P->c_tiles, s);
+            if (!wide_words) return cleanup(TSP_ERR_ALLOC_FAILED);
+        }
         KernelTimer kt(ctx, TSP_KERNEL_SYM_EMIT, s);
         const int64_t per_row = P->candidates / ntr;
         const int threads = per_row <= 256 ? 64 : per_row <= 4096 ? 128 : kSymThreads;
+        uint32_t *wide_cnt = wide_words ? wide_words + P->c_tiles : nullptr;
+        const int wide_threshold = wide_words ? window : INT_MAX;   // C tiles per tile-row above which the wide launch takes it
         hipLaunchKernelGGL(long_rows ? k_sym_emit<true> : k_sym_emit<false>, dim3((unsigned)ntr), dim3(threads), lds, s,
-                           ra, rb, lanes, words_cap,
-                           window, row_jmin, P->c_tile_row_ptr, row_pair_ptr, P->c_tile_row, P->c_tile_col,
-                           P->pair_off, P->pair_a, P->pair_b);
+                           ra, rb, lanes, words_cap, window, wide_threshold, row_jmin, P->c_tile_row_ptr, row_pair_ptr,
+                           P->c_tile_row, P->c_tile_col, P->pair_off, P->pair_a, P->pair_b);
+        if (wide_words)
+            hipLaunchKernelGGL(long_rows ? k_sym_emit_wide<true> : k_sym_emit_wide<false>, dim3((unsigned)ntr),
+                               dim3(kSymThreads), (size_t)(2 * words_cap) * sizeof(uint32_t), s, ra, rb, lanes, words_cap,
+                               wide_threshold, row_jmin, P->c_tile_row_ptr, row_pair_ptr, P->c_tile_row, P->c_tile_col,
+                               P->pair_off, P->pair_a, P->pair_b, wide_words, wide_cnt);
         SYM_CHECK(hipGetLastError());
     } else {
         SYM_CHECK(hipMemsetAsync(P->pair_off, 0, sizeof(int64_t), s));

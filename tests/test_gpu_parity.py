@@ -432,3 +432,20 @@ def test_smape_against_full_precision_as_in_the_paper(tsp, handle, oracle):
     s = oracle.smape_percent(full.val, val)
     print(f"SMAPE against full precision: {s:.4f} %", flush=True)
     assert 0.0 < s < 0.1
+
+
+# ------------------------------------------------------------------ tile-rows of C wider than the LDS window
+@pytest.mark.parametrize("M,K,N,da,db", [(40, 64, 40000, 0.5, 0.05), (40, 1024, 40000, 0.1, 0.004)])
+def test_tile_rows_with_more_output_tiles_than_the_symbolic_window(tsp, handle, oracle, M, K, N, da, db):
+    """2500 output tiles per tile-row: the task list of such a tile-row is built with its per-tile
+    words in global memory (one chunk of A tiles in the first case, several in the second)."""
+    A = inputs.random_sparse(M, K, da, 71, values="smallint")
+    B = inputs.random_sparse(K, N, db, 72, values="smallint")
+    print(f"wide output tile-rows {M}x{K}x{N}", flush=True)
+    dA, dB = tsp.to_device(A), tsp.to_device(B)
+    C = handle.spgemm(dA, dB)
+    st = handle.stats()
+    assert st["c_tiles"] > 3 * 2048
+    ref = oracle.spgemm(A, B, threads=4)
+    assert_matches_oracle(C, ref, "wide output tile-rows")
+    C.free()
