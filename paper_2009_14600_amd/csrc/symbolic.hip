@@ -696,8 +696,10 @@ void plan_release(tsp_context *ctx, tsp_plan_s *p, hipStream_t s) {
 static int lanes_per_a_tile(const tsp_tiles_s *B) {
     // lanes that share one A tile stride over the tiles of one tile-row of B: match its mean length
     const double mean = B->tile_rows > 0 && B->ntiles > 0 ? (double)B->ntiles / (double)B->tile_rows : 1.0;
+    // (with the unrolled candidate loop a lane takes kSurvivorUnroll tiles per trip, so a quarter of
+    // the lanes do: more A tiles are then in flight per block)
     int l = 4;
-    while (l < 64 && l < mean) l <<= 1;
+    while (l < 64 && l * (mean > 8.0 ? kSurvivorUnroll : 1) < mean) l <<= 1;
     return l;
 }
 
@@ -756,11 +758,11 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
     bool long_rows = false;                // B tile-rows long enough for the unrolled candidate loop
     {
         const double mean_bound = B->tile_rows > 0 ? (double)B->nnz / (double)B->tile_rows : 1.0;
-        while (lanes < 32 && lanes * 4 < mean_bound) lanes <<= 1;
+        while (lanes < 8 && lanes * 4 < mean_bound) lanes <<= 1;
         long_rows = mean_bound > 128.0;
         if (B->ntiles >= 0) {
             lanes = lanes_per_a_tile(B);
-            long_rows = (double)B->ntiles > 48.0 * (double)B->tile_rows;
+            long_rows = (double)B->ntiles > 8.0 * (double)B->tile_rows;
         }
     }
     if (ntr > 0) {
