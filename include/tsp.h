@@ -101,7 +101,7 @@ enum {
 
 /* Phases reported in tsp_stats.phase_us, in pipeline order. */
 enum {
-    TSP_PHASE_CONVERT = 0,     /* CSR -> tiles: occupancy scan + packing (Section 2.1.2)            */
+    TSP_PHASE_CONVERT = 0,     /* CSR -> tiles, one pass (Section 2.1.2)                            */
     TSP_PHASE_SYMBOLIC = 1,    /* tile correspondence, zero-product cull, sizing, task list (4.1)   */
     TSP_PHASE_COUNT = 2,       /* counting pass on bitmaps, row_ptr of C (Section 4.2)              */
     TSP_PHASE_NUMERIC = 3,     /* multiplication pass + CSR emission (Sections 4.3, 4.4)            */
@@ -169,7 +169,7 @@ int tsp_spgemm(tsp_handle handle, const tsp_csr *A, const tsp_csr *B, tsp_csr *C
 int tsp_csr_free(tsp_handle handle, tsp_csr *C, void *stream);
 
 /*
- * Compaction of zeros (paper Section 4.4, Algorithm 1 lines 19-20): *out = C without the entries
+ * Compaction of zeros (paper Section 4.4; the two compaction steps that end Algorithm 1): *out = C without the entries
  * whose value compares equal to zero (+0.0 and -0.0; NaN stays), order kept, so that a product
  * whose terms cancelled, or that only met stored zeros, leaves no entry behind.  C: device CSR with
  * float values (TSP_F32) and a 32- or 64-bit row_ptr, borrowed, not modified; row ranges are
@@ -231,8 +231,8 @@ typedef struct {
 int tsp_tiles_get_view(tsp_tiles tiles, tsp_tiles_view *view);
 
 /*
- * Symbolic phase + counting pass for C = A*B on tile matrices (Sections 4.1 and 4.2, Algorithm 1
- * lines 1-17): tile correspondence, zero-product cull on the occupancy words, sizing scans, task
+ * Symbolic phase + counting pass for C = A*B on tile matrices (Sections 4.1 and 4.2; Algorithm 1
+ * up to the counting kernel): tile correspondence, zero-product cull on the occupancy words, sizing scans, task
  * list grouped by output tile (output tiles row-major, pairs of a tile in ascending inner
  * index), boolean product of the bitmaps per output tile, row_ptr of C.  A needs no particular
  * form, nor does B.  Synchronises the stream twice (task-list size; nnz of C).

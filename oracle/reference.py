@@ -10,7 +10,7 @@ Two layers:
   Gustavson in fp64 (``spgemm_oracle.c``; definition in paper Section 2.2, precision in
   Section 2.6, structural pattern as in Section 4.2).
 * ``bitmap_format`` / ``task_list`` / ``counting``: the intermediate objects the paper's
-  pipeline names (Section 2.1.2 bitmap format; Section 4.1 and Algorithm 1 lines 1-15 task
+  pipeline names (Section 2.1.2 bitmap format; Section 4.1 and Algorithm 1 (task-list part) task
   list; Section 4.2 counting kernel), written out step by step in numpy for small inputs,
   with the tile edge T as a parameter (the paper uses 8; the GPU path uses 16).
 """
@@ -219,7 +219,7 @@ class TaskList:
 
 
 def task_list(TA: BitmapMatrix, TB: BitmapMatrix) -> TaskList:
-    """Algorithm 1 lines 1-15 / Section 4.1: pair every non-empty tile A[I,K] with every
+    """Section 4.1 / Algorithm 1, task-list part: pair every non-empty tile A[I,K] with every
     non-empty tile B[K,J]; drop pairs whose boolean tile product is all zero; sort (stably)
     by B tile column, then by A tile row, so entries of one C tile are consecutive and keep
     ascending K; count entries per distinct (I,J); prefix-sum the counts into offsets."""

@@ -1,8 +1,8 @@
 // Single-pass prefix sums across the blocks of one launch ("chained scan with decoupled look-back"):
 // every block publishes the aggregate of its slice, then adds up the aggregates of the blocks before
 // it (one wave reads 64 predecessors at a time) until it meets a block whose inclusive prefix is
-// already known.  Used for the per-tile-row counts -> offsets steps (paper Section 4.1, Algorithm 1
-// lines 9-15), which are too small to be worth three launches and too slow on a single CU.
+// already known.  Used for the per-tile-row counts -> offsets steps (paper Section 4.1: Algorithm 1's
+// counts-to-offsets steps), which are too small to be worth three launches and too slow on a single CU.
 //
 // Forward progress: blocks are dispatched in index order, so the predecessors a block waits for are
 // running or finished.  The wait is bounded all the same: after kChainSpinLimit polls a block gives

@@ -1,4 +1,4 @@
-// Compaction of zeros (paper Section 4.4, Algorithm 1 lines 19-20): the multiplication pass writes
+// Compaction of zeros (paper Section 4.4; the two compaction steps that end Algorithm 1): the multiplication pass writes
 // every structural position of C; numerical cancellation (and stored zeros in the inputs) leaves
 // some of them with the value 0.  This pass removes them, so that the result is strictly sparse:
 // count the survivors per row, prefix-sum into the new row_ptr, copy the survivors in order.

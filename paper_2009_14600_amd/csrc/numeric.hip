@@ -1,4 +1,4 @@
-// Multiplication pass and CSR emission (paper Sections 4.3 and 4.4, Algorithm 1 line 18).
+// Multiplication pass and CSR emission (paper Sections 4.3 and 4.4; the multiplication kernel of Algorithm 1).
 //
 // One wave owns one output tile at a time and walks the tile's task-list segment: the pairs of a C
 // tile form one 16 x 16p by 16p x 16 product, so the inner (K) dimension of
@@ -11,7 +11,7 @@
 // Operand registers of the instruction: lane l holds, for the left matrix, row l%16 and inner
 // indices 8*(l/16)..+7; for the right matrix, column l%16 and the same inner indices.  The tile
 // format stores exactly those 8-value groups (see tsp.h), so an operand is one 16-byte load, or
-// zero when the group mask says the group is empty: nothing is "placed by bitmap" at run time.
+// zero when the group mask says the group is empty: nothing is expanded through the bitmap at run time.
 // The accumulator of lane l holds column l%16, rows 4*(l/16)..+3 of the output tile.
 //
 // The paper notes that this kernel is bound by the scattered tile reads behind the task list

@@ -1,4 +1,4 @@
-// Device-wide exclusive prefix sums (the "prefix sum" of Section 4.1 / Algorithm 1 lines 9-15
+// Device-wide exclusive prefix sums (the "prefix sum" of Section 4.1 / Algorithm 1, the counts-to-offsets steps
 // that turns per-tile-row and per-row counts into offsets and total sizes).
 #include "common.hpp"
 

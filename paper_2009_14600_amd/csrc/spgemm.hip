@@ -32,7 +32,7 @@ extern "C" int tsp_spgemm(tsp_handle ctx, const tsp_csr *A, const tsp_csr *B, ts
     phase_end(ctx, TSP_PHASE_CONVERT, s);
     if (!rc) rc = symbolic_run(ctx, ta, alias ? ta : tb, &plan, s);
     if (!rc) rc = numeric_enqueue(ctx, ta, alias ? ta : tb, plan, C, s);
-    if (!rc && ctx->compact) {                    // Algorithm 1 lines 19-20: strictly sparse result
+    if (!rc && ctx->compact) {                    // Algorithm 1, the compaction steps: strictly sparse result
         tsp_csr structural = *C;
         rc = compact_zeros(ctx, &structural, C, s);
         tsp_csr_free(ctx, &structural, stream);

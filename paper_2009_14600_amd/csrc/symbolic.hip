@@ -1,4 +1,4 @@
-// Tile-level symbolic phase and counting pass (paper Sections 4.1 and 4.2, Algorithm 1 lines 1-17).
+// Tile-level symbolic phase and counting pass (paper Sections 4.1 and 4.2; Algorithm 1 up to the counting kernel).
 //
 // The paper expands every (A tile, B tile) correspondence into a global list, culls it, sorts it
 // twice and reduces it by key.  Here one workgroup owns one tile-row I of C and never leaves LDS:
@@ -15,7 +15,7 @@
 //      deterministic although the candidates are visited in parallel.
 // Prefix sums over the tile-rows give the C tile offsets and the task-list offsets.
 // The counting pass then forms, per C tile, the boolean product of the bitmaps of its pairs
-// (Section 4.2: "simulates" the multiplication on 0/1 tiles; here with integer bit operations on
+// (Section 4.2 runs the multiplication on 0/1 tiles for this; here integer bit operations on
 // the 16-bit row masks, which gives the same pattern), and the per-row counts give row_ptr of C.
 #include "common.hpp"
 #include "chain.hpp"
@@ -224,7 +224,7 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_count(TileRefs A, TileRefs 
     }
 }
 
-// Prefix sums over the tile-rows (Algorithm 1 lines 9-15: counts -> offsets and total sizes) in one
+// Prefix sums over the tile-rows (Algorithm 1: counts -> offsets and total sizes) in one
 // launch: C tiles per row -> c_tile_row_ptr, pairs per row -> row_pair_ptr, plus the totals and maxima
 // the host needs to size the task list.  A block scans 1024 tile-rows; the blocks are chained.
 constexpr int kRowScanThreads = 256, kRowScanItems = 4, kRowScanBlock = kRowScanThreads * kRowScanItems;
