@@ -77,7 +77,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", type=int, default=2, help="index 1..5 into BASELINE.json configs")
+    ap.add_argument("--workload", type=int, default=2, help="benchmark configuration 1..5 (see inputs.CONFIG_NAMES)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-validate", action="store_true", help="switch the input validation kernel off")
     ap.add_argument("--no-matrix-cores", action="store_true",
