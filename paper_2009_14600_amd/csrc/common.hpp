@@ -29,6 +29,7 @@ enum Scalar {
     S_C_NNZ = 9,
     S_MAX_ROW_A_TILES = 10,
     S_INTERNAL = 11,         // != 0: a bounded device-side wait ran out (should never happen)
+    S_MAX_ROW_PAIRS = 12,    // max over C tile-rows of the number of task-list entries
 };
 
 struct Block {

@@ -239,13 +239,13 @@ __global__ __launch_bounds__(kRowScanThreads) void k_sym_row_scan(
     int32_t *__restrict__ c_tile_row_ptr, int64_t *__restrict__ row_pair_ptr, ChainSlot *slots, unsigned epoch,
     int64_t *__restrict__ d_scalars, TileCount count_a, TileCount count_b) {
     __shared__ uint64_t lds[kRowScanThreads / 64 + kChainValues];
-    __shared__ int lds_m[2][kRowScanThreads / 64];
+    __shared__ int lds_m[3][kRowScanThreads / 64];
     __shared__ uint32_t lds_t[2][kRowScanThreads / 64];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t i0 = (int64_t)blockIdx.x * kRowScanBlock + (int64_t)threadIdx.x * kRowScanItems;
     int32_t xc[kRowScanItems], xp[kRowScanItems];
     uint64_t sc = 0, sp = 0, cand = 0;
-    int max_c = 0, max_w = 0;
+    int max_c = 0, max_w = 0, max_p = 0;
 #pragma unroll
     for (int k = 0; k < kRowScanItems; ++k) {
         const bool in = i0 + k < ntr;
@@ -254,6 +254,7 @@ __global__ __launch_bounds__(kRowScanThreads) void k_sym_row_scan(
         sc += (uint32_t)xc[k];
         sp += (uint32_t)xp[k];
         max_c = max(max_c, xc[k]);
+        max_p = max(max_p, xp[k]);
         max_w = max(max_w, in ? row_words[i0 + k] : 0);
         cand += in ? (uint32_t)row_cand[i0 + k] : 0u;
     }
@@ -293,18 +294,22 @@ __global__ __launch_bounds__(kRowScanThreads) void k_sym_row_scan(
     // maxima: one atomic per block (a few dozen blocks at most per million rows)
     max_c = wave_max(max_c);
     max_w = wave_max(max_w);
+    max_p = wave_max(max_p);
     __syncthreads();
     if (lane == 0) {
         lds_m[0][wave] = max_c;
         lds_m[1][wave] = max_w;
+        lds_m[2][wave] = max_p;
     }
     __syncthreads();
     if (threadIdx.x == 0) {
-        int mc = 0, mw = 0;
+        int mc = 0, mw = 0, mp = 0;
         for (int w = 0; w < kRowScanThreads / 64; ++w) {
             mc = max(mc, lds_m[0][w]);
             mw = max(mw, lds_m[1][w]);
+            mp = max(mp, lds_m[2][w]);
         }
+        atomicMax((unsigned long long *)&d_scalars[S_MAX_ROW_PAIRS], (unsigned long long)mp);
         atomicMax((unsigned long long *)&d_scalars[S_MAX_ROW_C_TILES], (unsigned long long)mc);
         atomicMax((unsigned long long *)&d_scalars[S_MAX_ROW_WORDS], (unsigned long long)mw);
         unsigned long long ta = 0, tb = 0;
@@ -441,6 +446,131 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_emit(
         }
         win_base += win_total;
         __syncthreads();
+    }
+}
+
+// The same pass for products all of whose tile-rows have few task-list entries (at most kListCap) and
+// fit one LDS window: the surviving pairs are enumerated once and kept in an LDS list; counting them
+// per C tile and placing them then works on the list (the general kernel enumerates the candidates
+// three times, and the enumeration, a chain of dependent gathers, is what it spends its time on).
+// Dynamic LDS: 2*words_cap + 2*window + 3*list_cap words (list_cap: most entries any tile-row has).
+constexpr int kListCap = 1024;
+template <bool kLongRows>
+__global__ __launch_bounds__(kSymThreads) void k_sym_emit_listed(
+    TileRefs A, TileRefs B, int lanes_per_a, int words_cap, int window, int list_cap,
+    const int32_t *__restrict__ row_jmin,
+    const int32_t *__restrict__ c_tile_row_ptr, const int64_t *__restrict__ row_pair_ptr,
+    int32_t *__restrict__ c_tile_row, int32_t *__restrict__ c_tile_col, int64_t *__restrict__ pair_off,
+    int32_t *__restrict__ pair_a, int32_t *__restrict__ pair_b) {
+    extern __shared__ uint32_t lds_dyn[];
+    __shared__ uint32_t red[32];
+    __shared__ int s_jmax, s_n;
+    uint32_t *bm = lds_dyn;
+    uint32_t *wpre = bm + words_cap;
+    uint32_t *contrib = wpre + words_cap;
+    uint32_t *cnt = contrib + window;
+    int *list_a = reinterpret_cast<int *>(cnt + window), *list_b = list_a + list_cap;
+    int *list_c = list_b + list_cap;                 // tile column, later the C tile's position in the row
+    const int I = blockIdx.x, nthreads = (int)blockDim.x;
+    const int c0 = c_tile_row_ptr[I], nC = c_tile_row_ptr[I + 1] - c0;
+    if (I == (int)gridDim.x - 1 && threadIdx.x == 0) pair_off[c_tile_row_ptr[gridDim.x]] = row_pair_ptr[gridDim.x];
+    if (nC <= 0) return;
+    const int a0 = A.trp[I], a1 = A.tend[I];
+    const int jmin = row_jmin[I];
+    const int64_t row_base = row_pair_ptr[I];
+    int jmax = -1;
+    for (int a = a0 + threadIdx.x; a < a1; a += nthreads) {
+        const uint32_t K = (uint32_t)A.tcol[a];
+        if (K >= (uint32_t)B.tile_rows) continue;
+        const int b0 = B.trp[K], b1 = B.tend[K];
+        if (b0 < b1) jmax = max(jmax, B.tcol[b1 - 1]);
+    }
+    if (threadIdx.x == 0) {
+        s_jmax = -1;
+        s_n = 0;
+    }
+    __syncthreads();
+    if (jmax >= 0) atomicMax(&s_jmax, jmax);
+    __syncthreads();
+    jmax = s_jmax;
+    const int64_t span = (int64_t)jmax - jmin + 1;
+    const int words = (int)((span + 31) >> 5);
+    for (int w = threadIdx.x; w < words; w += nthreads) bm[w] = 0;
+    __syncthreads();
+    uint32_t dummy = 0;
+    for_each_survivor<kLongRows>(A, B, a0, a1, lanes_per_a, &dummy, [&](int a, int b, int J) {
+        const uint32_t j = (uint32_t)(J - jmin);
+        if (j < (uint32_t)span) {
+            atomicOr(&bm[j >> 5], 1u << (j & 31));
+            const int k = atomicAdd(&s_n, 1);      // any order: positions come from the bit words below
+            if (k < list_cap) {
+                list_a[k] = a;
+                list_b[k] = b;
+                list_c[k] = (int)j;
+            }
+        }
+    });
+    __syncthreads();
+    const int n = min(s_n, list_cap);
+    for (int w = threadIdx.x; w < words; w += nthreads) wpre[w] = __popc(bm[w]);
+    __syncthreads();
+    block_exclusive_scan_lds(wpre, words, red);
+    for (int w = threadIdx.x; w < words; w += nthreads) {     // C tile coordinates, ascending J
+        uint32_t bits = bm[w];
+        int c = c0 + (int)wpre[w];
+        while (bits) {
+            const int bit = __ffs(bits) - 1;
+            bits &= bits - 1;
+            c_tile_row[c] = I;
+            c_tile_col[c] = jmin + w * 32 + bit;
+            ++c;
+        }
+    }
+    for (int k = threadIdx.x; k < n; k += nthreads) {          // tile column -> position of the C tile in the row
+        const uint32_t j = (uint32_t)list_c[k];
+        list_c[k] = (int)wpre[j >> 5] + __popc(bm[j >> 5] & ((1u << (j & 31)) - 1u));
+    }
+    for (int c = threadIdx.x; c < nC; c += nthreads) cnt[c] = 0;
+    const bool one_chunk = (a1 - a0) <= 32;
+    // count pass: which of 32 A tiles at a time contribute to each C tile
+    for (int ch = a0; ch < a1; ch += 32) {
+        for (int c = threadIdx.x; c < nC; c += nthreads) contrib[c] = 0;
+        __syncthreads();
+        for (int k = threadIdx.x; k < n; k += nthreads) {
+            const uint32_t rel = (uint32_t)(list_a[k] - ch);
+            if (rel < 32u) atomicOr(&contrib[list_c[k]], 1u << rel);
+        }
+        __syncthreads();
+        for (int c = threadIdx.x; c < nC; c += nthreads) cnt[c] += __popc(contrib[c]);
+        __syncthreads();
+    }
+    block_exclusive_scan_lds(cnt, nC, red);
+    for (int c = threadIdx.x; c < nC; c += nthreads) pair_off[c0 + c] = row_base + (int64_t)cnt[c];
+    // emit pass: a pair sits after the pairs of its C tile with a lower A tile
+    for (int ch = a0; ch < a1; ch += 32) {
+        if (!one_chunk) {
+            for (int c = threadIdx.x; c < nC; c += nthreads) contrib[c] = 0;
+            __syncthreads();
+            for (int k = threadIdx.x; k < n; k += nthreads) {
+                const uint32_t rel = (uint32_t)(list_a[k] - ch);
+                if (rel < 32u) atomicOr(&contrib[list_c[k]], 1u << rel);
+            }
+            __syncthreads();
+        }
+        for (int k = threadIdx.x; k < n; k += nthreads) {
+            const uint32_t rel = (uint32_t)(list_a[k] - ch);
+            if (rel < 32u) {
+                const int c = list_c[k];
+                const int64_t pos = row_base + (int64_t)cnt[c] + __popc(contrib[c] & ((1u << rel) - 1u));
+                pair_a[pos] = list_a[k];
+                pair_b[pos] = list_b[k];
+            }
+        }
+        if (!one_chunk) {
+            __syncthreads();
+            for (int c = threadIdx.x; c < nC; c += nthreads) cnt[c] += __popc(contrib[c]);
+            __syncthreads();
+        }
     }
 }
 
@@ -838,9 +968,16 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
         const int threads = per_row <= 256 ? 64 : per_row <= 4096 ? 128 : kSymThreads;
         uint32_t *wide_cnt = wide_words ? wide_words + P->c_tiles : nullptr;
         const int wide_threshold = wide_words ? window : INT_MAX;   // C tiles per tile-row above which the wide launch takes it
-        hipLaunchKernelGGL(long_rows ? k_sym_emit<true> : k_sym_emit<false>, dim3((unsigned)ntr), dim3(threads), lds, s,
-                           ra, rb, lanes, words_cap, window, wide_threshold, row_jmin, P->c_tile_row_ptr, row_pair_ptr,
-                           P->c_tile_row, P->c_tile_col, P->pair_off, P->pair_a, P->pair_b);
+        if (h[S_MAX_ROW_PAIRS] <= kListCap && !wide_words) {
+            const int list_cap = (int)std::max<int64_t>(h[S_MAX_ROW_PAIRS], 1);
+            hipLaunchKernelGGL(long_rows ? k_sym_emit_listed<true> : k_sym_emit_listed<false>, dim3((unsigned)ntr),
+                               dim3(threads), lds + (size_t)(3 * list_cap) * sizeof(int), s, ra, rb, lanes, words_cap,
+                               window, list_cap, row_jmin, P->c_tile_row_ptr,
+                               row_pair_ptr, P->c_tile_row, P->c_tile_col, P->pair_off, P->pair_a, P->pair_b);
+        } else
+            hipLaunchKernelGGL(long_rows ? k_sym_emit<true> : k_sym_emit<false>, dim3((unsigned)ntr), dim3(threads),
+                               lds, s, ra, rb, lanes, words_cap, window, wide_threshold, row_jmin, P->c_tile_row_ptr,
+                               row_pair_ptr, P->c_tile_row, P->c_tile_col, P->pair_off, P->pair_a, P->pair_b);
         if (wide_words)
             hipLaunchKernelGGL(long_rows ? k_sym_emit_wide<true> : k_sym_emit_wide<false>, dim3((unsigned)ntr),
                                dim3(kSymThreads), (size_t)(2 * words_cap) * sizeof(uint32_t), s, ra, rb, lanes, words_cap,
