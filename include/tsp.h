@@ -108,7 +108,9 @@ enum {
     TSP_PHASE_COUNT_ = 4
 };
 
-/* Kernels reported in tsp_stats.kernel_us (a prefix sum of three small launches is timed as one). */
+/* Kernels reported in tsp_stats.kernel_us (a prefix sum of three small launches is timed as one).
+ * When every tile-row of C is short, the task-list kernel also runs the counting pass and the row
+ * offsets; their two entries then read 0. */
 enum {
     TSP_KERNEL_CONVERT = 0,      /* CSR -> tiles, one pass (when B is not A: B's conversion)        */
     TSP_KERNEL_SYM_COUNT = 1,    /* C tiles and task-list entries per tile-row                      */

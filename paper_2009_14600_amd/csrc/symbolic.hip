@@ -449,19 +449,45 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_emit(
     }
 }
 
+typedef unsigned short ushort2v __attribute__((ext_vector_type(2)));
+// OR over the set bits k of `am` of row mask k of the B tile; x, y hold the 16 row masks, two per
+// 32-bit word (row 2i in the low half).  Each word is multiplied, half by half, with the two bits
+// (0 or 1) of `am` that select its rows: one packed 16-bit multiply does the selection of two rows.
+__device__ __forceinline__ uint32_t boolean_row_product(uint32_t am, const uint4 &x, const uint4 &y) {
+    const uint32_t w[8] = {x.x, x.y, x.z, x.w, y.x, y.y, y.z, y.w};
+    const uint32_t am2 = am | ((am >> 1) << 16);              // bit 2i+1 of am sits at bit 16+2i
+    uint32_t acc = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const uint32_t sel = (am2 >> (2 * i)) & 0x00010001u;   // low half: bit 2i of am, high half: bit 2i+1
+        union { uint32_t u; ushort2v v; } a, b, r;
+        a.u = w[i];
+        b.u = sel;
+        r.v = a.v * b.v;
+        acc |= r.u;
+    }
+    return acc;
+}
+
 // The same pass for products all of whose tile-rows have few task-list entries (at most kListCap) and
 // fit one LDS window: the surviving pairs are enumerated once and kept in an LDS list; counting them
 // per C tile and placing them then works on the list (the general kernel enumerates the candidates
 // three times, and the enumeration, a chain of dependent gathers, is what it spends its time on).
-// Dynamic LDS: 2*words_cap + 2*window + 3*list_cap words (list_cap: most entries any tile-row has).
+// It also runs the counting pass for its C tiles.
+// Dynamic LDS: 2*words_cap + 10*window + 3*list_cap words (list_cap: most entries any tile-row has).
 constexpr int kListCap = 1024;
-template <bool kLongRows>
+constexpr int kListTiles = 512;        // and at most this many C tiles per tile-row (their bitmaps sit in LDS)
+// kFuseMasks: also run the counting pass (worth it when there are enough tile-rows to fill the chip;
+// with few, long tile-rows the separate kernel, one lane group per C tile, has more parallelism).
+template <bool kLongRows, bool kFuseMasks>
 __global__ __launch_bounds__(kSymThreads) void k_sym_emit_listed(
     TileRefs A, TileRefs B, int lanes_per_a, int words_cap, int window, int list_cap,
     const int32_t *__restrict__ row_jmin,
     const int32_t *__restrict__ c_tile_row_ptr, const int64_t *__restrict__ row_pair_ptr,
     int32_t *__restrict__ c_tile_row, int32_t *__restrict__ c_tile_col, int64_t *__restrict__ pair_off,
-    int32_t *__restrict__ pair_a, int32_t *__restrict__ pair_b) {
+    int32_t *__restrict__ pair_a, int32_t *__restrict__ pair_b, const uint16_t *__restrict__ a_row_mask,
+    const uint16_t *__restrict__ b_row_mask, uint16_t *__restrict__ c_row_mask, uint32_t *__restrict__ c_row_off,
+    int32_t *__restrict__ row_nnz, int64_t c_rows, int64_t *d_scalars) {
     extern __shared__ uint32_t lds_dyn[];
     __shared__ uint32_t red[32];
     __shared__ int s_jmax, s_n;
@@ -471,10 +497,14 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_emit_listed(
     uint32_t *cnt = contrib + window;
     int *list_a = reinterpret_cast<int *>(cnt + window), *list_b = list_a + list_cap;
     int *list_c = list_b + list_cap;                 // tile column, later the C tile's position in the row
+    uint32_t *cmask = reinterpret_cast<uint32_t *>(list_c + list_cap);   // 8 words (16 row masks) per C tile
     const int I = blockIdx.x, nthreads = (int)blockDim.x;
     const int c0 = c_tile_row_ptr[I], nC = c_tile_row_ptr[I + 1] - c0;
     if (I == (int)gridDim.x - 1 && threadIdx.x == 0) pair_off[c_tile_row_ptr[gridDim.x]] = row_pair_ptr[gridDim.x];
-    if (nC <= 0) return;
+    if (nC <= 0) {                                   // an empty tile-row of C: its 16 rows are empty
+        if (kFuseMasks && threadIdx.x < T && (int64_t)I * T + threadIdx.x < c_rows) row_nnz[(int64_t)I * T + threadIdx.x] = 0;
+        return;
+    }
     const int a0 = A.trp[I], a1 = A.tend[I];
     const int jmin = row_jmin[I];
     const int64_t row_base = row_pair_ptr[I];
@@ -570,6 +600,61 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_emit_listed(
             __syncthreads();
             for (int c = threadIdx.x; c < nC; c += nthreads) cnt[c] += __popc(contrib[c]);
             __syncthreads();
+        }
+    }
+    if constexpr (!kFuseMasks) return;
+    // Counting pass (Section 4.2) for the tile-row's C tiles, from the same list: 16 lanes per pair, lane
+    // r forms row r of the boolean product of the two bitmaps and ORs it into the C tile's bitmap in LDS.
+    // Four pairs per trip, their bitmaps requested together.
+    for (int w = threadIdx.x; w < nC * 8; w += nthreads) cmask[w] = 0;
+    __syncthreads();
+    {
+        const int g = threadIdx.x >> 4, r = threadIdx.x & 15, groups = nthreads >> 4;
+        for (int k0 = g * 4; k0 < n; k0 += groups * 4) {
+            uint32_t am[4];
+            uint4 x[4], y[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                am[u] = 0;
+                x[u] = y[u] = make_uint4(0, 0, 0, 0);
+                if (k0 + u < n) {
+                    am[u] = a_row_mask[(int64_t)list_a[k0 + u] * T + r];
+                    const uint4 *bp = reinterpret_cast<const uint4 *>(b_row_mask + (int64_t)list_b[k0 + u] * T);
+                    x[u] = bp[0];
+                    y[u] = bp[1];
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                if (k0 + u < n) {
+                    const uint32_t m = boolean_row_product(am[u], x[u], y[u]);
+                    const uint32_t m16 = (m | (m >> 16)) & 0xFFFFu;
+                    if (m16) atomicOr(&cmask[list_c[k0 + u] * 8 + (r >> 1)], m16 << ((r & 1) * 16));
+                }
+            }
+        }
+    }
+    __syncthreads();
+    uint32_t *out_words = reinterpret_cast<uint32_t *>(c_row_mask) + (int64_t)c0 * 8;
+    for (int w = threadIdx.x; w < nC * 8; w += nthreads) out_words[w] = cmask[w];
+    // ... and what k_row_offsets does for this tile-row: lane r takes CSR row 16I+r
+    if (threadIdx.x < T) {
+        const int r = threadIdx.x, word = r >> 1, shift = (r & 1) * 16;
+        uint32_t total = 0;
+        for (int c = 0; c < nC; ++c) total += __popc((cmask[c * 8 + word] >> shift) & 0xFFFFu);
+        const int64_t row = (int64_t)I * T + r;
+        if (row < c_rows) row_nnz[row] = (int32_t)total;
+        uint64_t before = total;                   // inclusive prefix over the 16 rows
+#pragma unroll
+        for (int d = 1; d < T; d <<= 1) {
+            const uint64_t up = __shfl_up(before, d, T);
+            if (r >= d) before += up;
+        }
+        if (r == T - 1 && before > 0xFFFFFFFFull) d_scalars[S_UNSUPPORTED] = 1;
+        uint32_t run = (uint32_t)(before - total);
+        for (int c = 0; c < nC; ++c) {
+            c_row_off[(int64_t)(c0 + c) * T + r] = run;
+            run += __popc((cmask[c * 8 + word] >> shift) & 0xFFFFu);
         }
     }
 }
@@ -709,26 +794,6 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_emit_wide(
 // segment: c_mask[r] |= OR over the set bits k of the A tile's row mask r of the B tile's row mask k.
 // The segment's entries are read 16 at a time, one per lane, and the bitmaps of four pairs are
 // requested together so that their latencies overlap.
-typedef unsigned short ushort2v __attribute__((ext_vector_type(2)));
-// OR over the set bits k of `am` of row mask k of the B tile; x, y hold the 16 row masks, two per
-// 32-bit word (row 2i in the low half).  Each word is multiplied, half by half, with the two bits
-// (0 or 1) of `am` that select its rows: one packed 16-bit multiply does the selection of two rows.
-__device__ __forceinline__ uint32_t boolean_row_product(uint32_t am, const uint4 &x, const uint4 &y) {
-    const uint32_t w[8] = {x.x, x.y, x.z, x.w, y.x, y.y, y.z, y.w};
-    const uint32_t am2 = am | ((am >> 1) << 16);              // bit 2i+1 of am sits at bit 16+2i
-    uint32_t acc = 0;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const uint32_t sel = (am2 >> (2 * i)) & 0x00010001u;   // low half: bit 2i of am, high half: bit 2i+1
-        union { uint32_t u; ushort2v v; } a, b, r;
-        a.u = w[i];
-        b.u = sel;
-        r.v = a.v * b.v;
-        acc |= r.u;
-    }
-    return acc;
-}
-
 __global__ __launch_bounds__(256) void k_count_masks(int64_t c_tiles, const int64_t *__restrict__ pair_off,
                                                      const int32_t *__restrict__ pair_a,
                                                      const int32_t *__restrict__ pair_b,
@@ -886,6 +951,8 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
     // sharing width from the bound nnz/tile_rows (an upper bound on the mean), capped
     int lanes = 4;
     bool long_rows = false;                // B tile-rows long enough for the unrolled candidate loop
+    bool listed = false;                   // task list built by k_sym_emit_listed
+    bool fused_masks = false;              // ... which has also run the counting pass
     {
         const double mean_bound = B->tile_rows > 0 ? (double)B->nnz / (double)B->tile_rows : 1.0;
         while (lanes < 8 && lanes * 4 < mean_bound) lanes <<= 1;
@@ -968,12 +1035,18 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
         const int threads = per_row <= 256 ? 64 : per_row <= 4096 ? 128 : kSymThreads;
         uint32_t *wide_cnt = wide_words ? wide_words + P->c_tiles : nullptr;
         const int wide_threshold = wide_words ? window : INT_MAX;   // C tiles per tile-row above which the wide launch takes it
-        if (h[S_MAX_ROW_PAIRS] <= kListCap && !wide_words) {
+        listed = h[S_MAX_ROW_PAIRS] <= kListCap && h[S_MAX_ROW_C_TILES] <= kListTiles;
+        if (listed) {
             const int list_cap = (int)std::max<int64_t>(h[S_MAX_ROW_PAIRS], 1);
-            hipLaunchKernelGGL(long_rows ? k_sym_emit_listed<true> : k_sym_emit_listed<false>, dim3((unsigned)ntr),
-                               dim3(threads), lds + (size_t)(3 * list_cap) * sizeof(int), s, ra, rb, lanes, words_cap,
-                               window, list_cap, row_jmin, P->c_tile_row_ptr,
-                               row_pair_ptr, P->c_tile_row, P->c_tile_col, P->pair_off, P->pair_a, P->pair_b);
+            fused_masks = ntr >= 1024;
+            auto kernel = fused_masks ? (long_rows ? k_sym_emit_listed<true, true> : k_sym_emit_listed<false, true>)
+                                      : (long_rows ? k_sym_emit_listed<true, false> : k_sym_emit_listed<false, false>);
+            hipLaunchKernelGGL(kernel, dim3((unsigned)ntr), dim3(threads),
+                               lds + (size_t)(3 * list_cap + (fused_masks ? 8 * window : 0)) * sizeof(int), s, ra, rb,
+                               lanes, words_cap, window, list_cap, row_jmin, P->c_tile_row_ptr,
+                               row_pair_ptr, P->c_tile_row, P->c_tile_col, P->pair_off, P->pair_a, P->pair_b,
+                               A->row_mask, B->row_mask, P->c_row_mask, P->c_row_off, row_nnz, P->c_rows,
+                               ctx->d_scalars);
         } else
             hipLaunchKernelGGL(long_rows ? k_sym_emit<true> : k_sym_emit<false>, dim3((unsigned)ntr), dim3(threads),
                                lds, s, ra, rb, lanes, words_cap, window, wide_threshold, row_jmin, P->c_tile_row_ptr,
@@ -990,13 +1063,13 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
     phase_end(ctx, TSP_PHASE_SYMBOLIC, s);
 
     phase_begin(ctx, TSP_PHASE_COUNT, s);
-    if (P->c_tiles > 0) {
+    if (P->c_tiles > 0 && !fused_masks) {       // (otherwise the list kernel has done the counting pass already)
         const unsigned grid = (unsigned)(((P->c_tiles * 16 + 255) / 256 + 7) / 8 * 8);   // multiple of 8: XCD remap
         KernelTimer kt(ctx, TSP_KERNEL_COUNT_MASKS, s);
         hipLaunchKernelGGL(k_count_masks, dim3(grid), dim3(256), 0, s, P->c_tiles, P->pair_off, P->pair_a, P->pair_b,
                            A->row_mask, B->row_mask, P->c_row_mask);
     }
-    if (ntr > 0) {
+    if (ntr > 0 && !fused_masks) {             // (otherwise done by the list kernel as well)
         const unsigned grid = (unsigned)((ntr * 16 + 255) / 256);
         KernelTimer kt(ctx, TSP_KERNEL_ROW_OFFSETS, s);
         hipLaunchKernelGGL(k_row_offsets, dim3(grid), dim3(256), 0, s, ntr, P->c_rows, P->c_tile_row_ptr,
