@@ -137,7 +137,7 @@ __device__ __forceinline__ uint32_t group_exclusive_scan(uint32_t *arr, int n, i
 // kConvCache: entries per thread kept in registers between the passes (tile-rows with more entries
 // than G*kConvCache read the CSR arrays again in every pass)
 template <int G, int kConvCache, typename RP, typename VT>
-__global__ __launch_bounds__(conv_block_threads<G>()) void k_convert_rows(const ConvArgs<RP, VT> a) {
+__device__ __forceinline__ void convert_rows(const ConvArgs<RP, VT> &a) {
     constexpr int kWords = ConvCfg<G>::kWords, kWindow = ConvCfg<G>::kWindow, kGroups = conv_block_threads<G>() / G;
     __shared__ int s_rp_all[kGroups][20];
     __shared__ uint32_t s_bm_all[kGroups][kWords], s_pre_all[kGroups][kWords];
@@ -371,6 +371,18 @@ __global__ __launch_bounds__(conv_block_threads<G>()) void k_convert_rows(const 
     finish(ntiles, ROW_FAST);
 }
 
+template <int G, int kConvCache, typename RP, typename VT>
+__global__ __launch_bounds__(conv_block_threads<G>()) void k_convert_rows(const ConvArgs<RP, VT> a) {
+    convert_rows<G, kConvCache, RP, VT>(a);
+}
+// The same for short tile-rows (few entries per thread in registers): asking for six waves per SIMD
+// makes the compiler fit 80 registers without spilling, and this kernel lives on waves in flight.
+template <int G, int kConvCache, typename RP, typename VT>
+__global__ __launch_bounds__(conv_block_threads<G>()) __attribute__((amdgpu_waves_per_eu(6, 8))) void k_convert_rows_light(
+    const ConvArgs<RP, VT> a) {
+    convert_rows<G, kConvCache, RP, VT>(a);
+}
+
 // ------------------------------------------------------------------------------------------------
 // Merge path for tile-rows whose span does not fit the bitmap: 16 lanes own one tile-row, one lane
 // per CSR row.  The columns of a CSR row ascend, so do its tile columns, and the distinct tile
@@ -513,8 +525,10 @@ static int launch_convert(tsp_context *ctx, const tsp_csr *A, tsp_tiles_s *t, in
         KernelTimer kt(ctx, TSP_KERNEL_CONVERT, s);
 #define TSP_LAUNCH_ROWS(g, c, threads) \
     hipLaunchKernelGGL((k_convert_rows<g, c, RP, VT>), dim3(grid_fast), dim3(threads), 0, s, a)
-        if (G == 64 && cache == 2) TSP_LAUNCH_ROWS(64, 2, 256);
-        else if (G == 64 && cache == 4) TSP_LAUNCH_ROWS(64, 4, 256);
+        if (G == 64 && cache == 2)
+            hipLaunchKernelGGL((k_convert_rows_light<64, 2, RP, VT>), dim3(grid_fast), dim3(256), 0, s, a);
+        else if (G == 64 && cache == 4)
+            hipLaunchKernelGGL((k_convert_rows_light<64, 4, RP, VT>), dim3(grid_fast), dim3(256), 0, s, a);
         else if (G == 64) TSP_LAUNCH_ROWS(64, 8, 256);
         else if (G == 128 && cache == 6) TSP_LAUNCH_ROWS(128, 6, 128);
         else if (G == 128) TSP_LAUNCH_ROWS(128, 8, 128);
