@@ -383,6 +383,13 @@ __global__ __launch_bounds__(conv_block_threads<G>()) __attribute__((amdgpu_wave
     convert_rows<G, kConvCache, RP, VT>(a);
 }
 
+// ... and for six entries per thread: four waves per SIMD cost the compiler seven registers.
+template <int G, int kConvCache, typename RP, typename VT>
+__global__ __launch_bounds__(conv_block_threads<G>()) __attribute__((amdgpu_waves_per_eu(4, 8))) void k_convert_rows_mid(
+    const ConvArgs<RP, VT> a) {
+    convert_rows<G, kConvCache, RP, VT>(a);
+}
+
 // ------------------------------------------------------------------------------------------------
 // Merge path for tile-rows whose span does not fit the bitmap: 16 lanes own one tile-row, one lane
 // per CSR row.  The columns of a CSR row ascend, so do its tile columns, and the distinct tile
@@ -530,9 +537,11 @@ static int launch_convert(tsp_context *ctx, const tsp_csr *A, tsp_tiles_s *t, in
         else if (G == 64 && cache == 4)
             hipLaunchKernelGGL((k_convert_rows_light<64, 4, RP, VT>), dim3(grid_fast), dim3(256), 0, s, a);
         else if (G == 64) TSP_LAUNCH_ROWS(64, 8, 256);
-        else if (G == 128 && cache == 6) TSP_LAUNCH_ROWS(128, 6, 128);
+        else if (G == 128 && cache == 6)
+            hipLaunchKernelGGL((k_convert_rows_mid<128, 6, RP, VT>), dim3(grid_fast), dim3(128), 0, s, a);
         else if (G == 128) TSP_LAUNCH_ROWS(128, 8, 128);
-        else if (cache == 6) TSP_LAUNCH_ROWS(256, 6, 256);
+        else if (cache == 6)
+            hipLaunchKernelGGL((k_convert_rows_mid<256, 6, RP, VT>), dim3(grid_fast), dim3(256), 0, s, a);
         else TSP_LAUNCH_ROWS(256, 8, 256);
 #undef TSP_LAUNCH_ROWS
         if (may_merge)
