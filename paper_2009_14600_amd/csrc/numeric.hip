@@ -38,6 +38,7 @@
 #include "common.hpp"
 
 #include <new>
+#include <utility>
 
 namespace tsp {
 
@@ -93,11 +94,23 @@ struct NumericSizes {
 // What a lane needs to write out its column of one output tile: lane l of a group of four tiles
 // holds, after the transposition, column l%16 of all 16 rows of tile l/16.
 struct Emission {
-    uint4 m0, m1;             // the tile's 16 row masks, 16 bits each (all zero: no such tile)
-    uint4 o0, o1, o2, o3;     // per row: position of the tile's first entry, from the start of the tile-row
+    uint32_t masks;           // row masks 2(j%8) (low half) and 2(j%8)+1 (high half) of the tile (zero: no such tile)
+    uint32_t first;           // row j: position of the tile's first entry, from the start of the tile-row
     int64_t base;             // position of the tile-row's first entry in C
     int32_t col;              // column of this lane inside C
 };
+
+// Value that lane kFrom of every row of 16 lanes holds, in all lanes of that row.  All lanes of the
+// row must be active.
+template <int kFrom>
+__device__ __forceinline__ uint32_t row_broadcast(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x150 + kFrom, 0xF, 0xF, false);   // row_newbcast
+}
+
+template <typename F, int... kR>
+__device__ __forceinline__ void for_each_row(F &&f, std::integer_sequence<int, kR...>) {
+    (f(std::integral_constant<int, kR>{}), ...);
+}
 
 __device__ __forceinline__ void swap_rows(float &x, float &y, bool halves) {
     // rows = groups of 16 lanes.  halves == false: rows 1, 3 of x <-> rows 0, 2 of y;
@@ -268,17 +281,11 @@ __global__ __launch_bounds__(kNumThreads) void k_numeric(
             auto request_masks = [&]() {
                 if constexpr (kNarrow) {
                     const BufferArray masks(c_row_mask, (uint64_t)c_tiles * T * 2), offs(c_row_off, (uint64_t)c_tiles * T * 4);
-                    const uint32_t mo = mine_exists ? (uint32_t)c_mine * (T * 2) : kSkip;
-                    const uint32_t oo = mine_exists ? (uint32_t)c_mine * (T * 4) : kSkip;
-                    em.m0 = masks.u128<0>(mo); em.m1 = masks.u128<16>(mo);
-                    em.o0 = offs.u128<0>(oo); em.o1 = offs.u128<16>(oo);
-                    em.o2 = offs.u128<32>(oo); em.o3 = offs.u128<48>(oo);
+                    em.masks = masks.u32(mine_exists ? (uint32_t)c_mine * (T * 2) + (uint32_t)(j & 7) * 4u : kSkip);
+                    em.first = offs.u32(mine_exists ? (uint32_t)c_mine * (T * 4) + (uint32_t)j * 4u : kSkip);
                 } else {
-                    const uint4 *mp = reinterpret_cast<const uint4 *>(c_row_mask + c_mine * T);
-                    const uint4 *op = reinterpret_cast<const uint4 *>(c_row_off + c_mine * T);
-                    const uint4 none = make_uint4(0, 0, 0, 0);
-                    em.m0 = mine_exists ? mp[0] : none; em.m1 = mine_exists ? mp[1] : none;
-                    em.o0 = op[0]; em.o1 = op[1]; em.o2 = op[2]; em.o3 = op[3];
+                    em.masks = mine_exists ? reinterpret_cast<const uint32_t *>(c_row_mask + c_mine * T)[j & 7] : 0u;
+                    em.first = c_row_off[c_mine * T + j];
                 }
             };
             request_masks();
@@ -319,42 +326,37 @@ __global__ __launch_bounds__(kNumThreads) void k_numeric(
                 swap_rows(rows[v][0], rows[v][2], true);
                 swap_rows(rows[v][1], rows[v][3], true);
             }
-            const uint32_t mw[8] = {em.m0.x, em.m0.y, em.m0.z, em.m0.w, em.m1.x, em.m1.y, em.m1.z, em.m1.w};
-            const uint32_t ow[16] = {em.o0.x, em.o0.y, em.o0.z, em.o0.w, em.o1.x, em.o1.y, em.o1.z, em.o1.w,
-                                     em.o2.x, em.o2.y, em.o2.z, em.o2.w, em.o3.x, em.o3.y, em.o3.z, em.o3.w};
-            // row r of the tile: mask in the low (even r) or high (odd r) half of mw[r / 2]; the entry
-            // of column j exists if its bit is set and sits after the set bits below it
+            // Row r of the tile: its mask is the low (even r) or high (odd r) half of the word that lane
+            // r/2 of the tile's 16 lanes loaded, its first position is what lane r loaded; the entry of
+            // column j exists if its bit is set and sits after the set bits below it.
             // Every load of this wave has returned by now (the last tile's operands were requested after
             // everything else and have been used).  Saying so explicitly keeps the compiler from putting
             // load waits between the stores below, where they would also wait for the stores before them.
             __builtin_amdgcn_s_waitcnt(0x0F70);    // vmcnt(0)
             const uint32_t my_bit[2] = {1u << j, 1u << (j + 16)};
             const uint32_t my_below[2] = {(1u << j) - 1u, ((1u << j) - 1u) << 16};
-            if constexpr (kNarrow) {
-                const BufferArray out_col(c_col, (uint64_t)c_nnz * 4), out_val(c_val, (uint64_t)c_nnz * 4);
-                const uint32_t base4 = (uint32_t)em.base << 2;
-#pragma unroll
-                for (int r = 0; r < T; ++r) {
-                    const uint32_t w = mw[r >> 1];
+            const BufferArray out_col(c_col, (uint64_t)c_nnz * 4), out_val(c_val, (uint64_t)c_nnz * 4);
+            const uint32_t base4 = (uint32_t)em.base << 2;
+            for_each_row(
+                [&](auto row) {
+                    constexpr int r = decltype(row)::value;
+                    const uint32_t w = row_broadcast<r / 2>(em.masks), first = row_broadcast<r>(em.first);
                     // lanes without an entry are switched off rather than sent out of range: a store
                     // costs by the lanes that take part in it
                     if (w & my_bit[r & 1]) {
-                        const uint32_t at = (((uint32_t)__popc(w & my_below[r & 1]) + ow[r]) << 2) + base4;
-                        out_col.put(at, (uint32_t)em.col);
-                        out_val.put(at, __float_as_uint(rows[r & 3][r >> 2]));
+                        const uint32_t rank = (uint32_t)__popc(w & my_below[r & 1]) + first;
+                        if constexpr (kNarrow) {
+                            const uint32_t at = (rank << 2) + base4;
+                            out_col.put(at, (uint32_t)em.col);
+                            out_val.put(at, __float_as_uint(rows[r & 3][r >> 2]));
+                        } else {
+                            const int64_t pos = em.base + (int64_t)rank;
+                            c_col[pos] = em.col;
+                            c_val[pos] = rows[r & 3][r >> 2];
+                        }
                     }
-                }
-            } else {
-#pragma unroll
-                for (int r = 0; r < T; ++r) {
-                    const uint32_t w = mw[r >> 1];
-                    if (w & my_bit[r & 1]) {
-                        const int64_t pos = em.base + (int64_t)ow[r] + __popc(w & my_below[r & 1]);
-                        c_col[pos] = em.col;
-                        c_val[pos] = rows[r & 3][r >> 2];
-                    }
-                }
-            }
+                },
+                std::make_integer_sequence<int, T>{});
         }
     }
 }
