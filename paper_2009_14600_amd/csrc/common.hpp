@@ -30,6 +30,7 @@ enum Scalar {
     S_MAX_ROW_A_TILES = 10,
     S_INTERNAL = 11,         // != 0: a bounded device-side wait ran out (should never happen)
     S_MAX_ROW_PAIRS = 12,    // max over C tile-rows of the number of task-list entries
+    S_MAX_ROW_ENTRIES = 13,  // max over C tile-rows of the number of structural entries
 };
 
 struct Block {
@@ -86,6 +87,7 @@ struct tsp_tiles_s {
 struct tsp_plan_s {
     int64_t c_rows = 0, c_cols = 0, c_tile_rows = 0;
     int64_t c_tiles = 0, pairs = 0, c_nnz = 0, candidates = 0;
+    int64_t max_row_c_tiles = 0, max_row_pairs = 0, max_row_entries = 0;   // largest tile-row of C
     int32_t *c_tile_row_ptr = nullptr;
     int32_t *c_tile_row = nullptr, *c_tile_col = nullptr;
     int64_t *pair_off = nullptr;
@@ -132,7 +134,8 @@ inline Tp *ctx_alloc_n(tsp_context *ctx, size_t n, hipStream_t s) {
 
 // ---- scans (scan.hip) -----------------------------------------------------------------
 // out[i] = sum of in[0..i), i = 0..n (n+1 entries).  If d_total != nullptr, *d_total = out[n]
-// as int64; if d_max != nullptr, *d_max = max(in) as int64 (0 for n = 0).
+// as int64; if d_max != nullptr, *d_max = the largest sum of 16 consecutive inputs in[16k..16k+16)
+// (the entries of a tile-row, when the inputs are row lengths), 0 for n = 0.
 // tmp: workspace of scan_tmp_entries(n) int64.
 size_t scan_tmp_entries(int64_t n);
 int scan_exclusive_i32_to_i32(tsp_context *ctx, const int32_t *in, int32_t *out, int64_t n,

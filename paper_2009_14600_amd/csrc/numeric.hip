@@ -54,6 +54,8 @@ constexpr int kNumThreads = 256;       // 4 waves per block
 constexpr int kGroupTiles = 4;         // output tiles computed together and written out row by row
 constexpr int kXcds = 8;
 constexpr int kBlockEntries = 64;      // task-list entries staged at a time: one per lane
+constexpr int kRowTiles = 16;          // whole-tile-row kernel: most output tiles a tile-row may have
+constexpr int kRowEntries = 512;       // ... and most structural entries (its output is assembled in LDS)
 
 struct Header {          // tile headers of one task-list entry, as the lanes of the wave read them from LDS
     uint32_t lm, lo, rm, ro;   // group masks and BYTE offsets of the first group: left form of A, right form of B
@@ -104,7 +106,7 @@ struct Emission {
 // row must be active.
 template <int kFrom>
 __device__ __forceinline__ uint32_t row_broadcast(uint32_t v) {
-    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x150 + kFrom, 0xF, 0xF, false);   // row_newbcast
+    return (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0x150 + kFrom, 0xF, 0xF, false);   // row_newbcast
 }
 
 template <typename F, int... kR>
@@ -127,9 +129,17 @@ __device__ __forceinline__ void swap_rows(float &x, float &y, bool halves) {
 // kMatrixCores == false: the block products run on the vector ALUs, every lane looping over the
 // inner index for its four output elements (the paper's comparison build without tensor cores,
 // Section 5, Algorithm 2); everything around the product is shared.
-template <bool kNarrow, int kTilesPerWave, bool kMatrixCores>
+//
+// kWholeRows: a wave takes one whole tile-row of C (at most kRowTiles tiles and kRowEntries entries,
+// which the host has checked) instead of kTilesPerWave consecutive tiles.  The entries of a tile-row
+// are one contiguous stretch of col_idx and val, so the wave puts them together in LDS, at the
+// positions the counting pass assigned, and writes the stretch with full-width stores.  Written
+// tile by tile, a row of a sparse tile is a run of a few entries, and a store costs by the
+// 64-byte lines it touches, not by the bytes it carries.
+template <bool kNarrow, int kTilesPerWave, bool kMatrixCores, bool kWholeRows = false>
 __global__ __launch_bounds__(kNumThreads) void k_numeric(
-    const int64_t c_tiles, const int64_t c_nnz, const NumericSizes z, const int64_t *__restrict__ pair_off,
+    const int64_t c_tiles, const int64_t c_nnz, const NumericSizes z, const int64_t c_rows, const int32_t c_tile_rows,
+    const int32_t *__restrict__ c_tile_row_ptr, const int64_t *__restrict__ pair_off,
     const int32_t *__restrict__ pair_a_, const int32_t *__restrict__ pair_b_, const uint2 *__restrict__ a_lhead_,
     const uint4 *__restrict__ a_ldata_, const uint2 *__restrict__ b_rhead_, const uint4 *__restrict__ b_rdata_, const int32_t *__restrict__ c_tile_row,
     const int32_t *__restrict__ c_tile_col, const uint16_t *__restrict__ c_row_mask,
@@ -141,15 +151,27 @@ __global__ __launch_bounds__(kNumThreads) void k_numeric(
     __shared__ uint4 lds_heads[kNumThreads / 64][kBlockEntries + 16];
     // operand groups of one step, as the lanes loaded them (vector-ALU build only)
     __shared__ uint4 lds_operands[kMatrixCores ? 1 : kNumThreads / 64][2][64];
+    // column and value of every entry of the wave's tile-row, in CSR order (whole-tile-row kernel only)
+    __shared__ uint32_t lds_entries[kWholeRows ? kNumThreads / 64 : 1][2][kWholeRows ? kRowEntries : 1];
     // consecutive logical blocks on the same XCD (workgroups are dealt to the XCDs round-robin)
     const int per_xcd = gridDim.x / kXcds;
     const int logical = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
     // wave-uniform values are kept in scalar registers; their loads become scalar loads
     const int wave_in_block = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t wave = (int64_t)logical * (kNumThreads / 64) + wave_in_block;
-    const int64_t run_begin = wave * kTilesPerWave;
-    if (run_begin >= c_tiles) return;
-    const int run_tiles = (int)min((int64_t)kTilesPerWave, c_tiles - run_begin);
+    int64_t run_begin;
+    int run_tiles;
+    if constexpr (kWholeRows) {
+        static_assert(kTilesPerWave == kRowTiles, "the unrolled groups cover a whole tile-row");
+        if (wave >= c_tile_rows) return;
+        run_begin = c_tile_row_ptr[wave];                                       // wave = tile-row of C
+        run_tiles = min(c_tile_row_ptr[wave + 1] - (int)run_begin, kTilesPerWave);
+        if (run_tiles <= 0 || run_begin + run_tiles > c_tiles) return;
+    } else {
+        run_begin = wave * kTilesPerWave;
+        if (run_begin >= c_tiles) return;
+        run_tiles = (int)min((int64_t)kTilesPerWave, c_tiles - run_begin);
+    }
     const int lane = threadIdx.x & 63;
     const int hl = lane & 31, upper = lane >> 5;
     const uint32_t bit = 1u << hl, below = bit - 1u;
@@ -166,7 +188,7 @@ __global__ __launch_bounds__(kNumThreads) void k_numeric(
     // coordinates of the output tile this lane will write (first group), requested together with the
     // segment bounds: the start of its tile-row in C depends on them and is requested one step later
     const int64_t c_first = run_begin + (tq < run_tiles ? tq : 0);
-    const int32_t I_first = c_tile_row[c_first], J_first = c_tile_col[c_first];
+    const int32_t I_first = kWholeRows ? (int32_t)wave : c_tile_row[c_first], J_first = c_tile_col[c_first];
     const int64_t base = ((int64_t)__builtin_amdgcn_readlane((int)(off_lane >> 32), 0) << 32) |
                          (uint32_t)__builtin_amdgcn_readlane((int)off_lane, 0);
     const int rel_lane = (int)(off_lane - base);
@@ -261,34 +283,51 @@ __global__ __launch_bounds__(kNumThreads) void k_numeric(
     int h_start = 0;                              // relative position of the first staged entry
     stage_headers(0);
     const int64_t base_first = c_row_ptr[(int64_t)I_first * T];
+    uint32_t(*const my_entries)[kWholeRows ? kRowEntries : 1] = lds_entries[kWholeRows ? wave_in_block : 0];
+    int row_entries = 0;                          // whole-tile-row kernel: entries of the tile-row
+    if constexpr (kWholeRows)
+        row_entries = (int)min(c_row_ptr[min((int64_t)(I_first + 1) * T, c_rows)] - base_first, (int64_t)kRowEntries);
 #pragma unroll
     for (int g = 0; g < kTilesPerWave / kGroupTiles; ++g) {
         if (g * kGroupTiles < run_tiles) {        // uniform
-            // What lane (tq, j) needs to write out column j of tile tq of this group, requested before
-            // the multiplications and used after them.  (Requesting the 24 registers of masks and
-            // offsets later frees registers, but the compiler then moves the loads down to their uses
-            // and the wave waits for them one by one: measured 16 % slower.)
+            // The row masks and row positions of the group's four tiles, requested before the
+            // multiplications and used after them: one word of each per lane, handed round inside a
+            // row of 16 lanes when the entries are written.
+            //   Tile by tile (lane (tq, j) writes column j of tile tq after the transposition): lane j of
+            //   the tile's 16 lanes takes the position of row j and the masks of rows 2(j%8), 2(j%8)+1.
+            //   Whole tile-rows (lane (q, j) writes column j of rows 4q..4q+3 of every tile, as the
+            //   accumulators hold them): lane 4t+v of the 16 takes the position of row 4q+v of tile t
+            //   and the masks of rows 4q+(v&2), +1.
             Emission em;
-            const bool mine_exists = g * kGroupTiles + tq < run_tiles;
-            const int64_t c_mine = run_begin + (mine_exists ? g * kGroupTiles + tq : 0);
-            if (g == 0) {
+            const int tile_l = kWholeRows ? j >> 2 : tq;                 // tile whose words this lane fetches
+            const int row_l = kWholeRows ? 4 * tq + (j & 3) : j;        // row whose position
+            const int pair_l = kWholeRows ? 2 * tq + ((j & 3) >> 1) : (j & 7);   // pair of rows whose masks
+            const bool mine_exists = g * kGroupTiles + tile_l < run_tiles;
+            const int64_t c_mine = run_begin + (mine_exists ? g * kGroupTiles + tile_l : 0);
+            int32_t col_of[kGroupTiles];                                // whole tile-rows: this lane's column in tile t
+            if constexpr (kWholeRows) {
+                em.base = base_first;
+                em.col = 0;
+#pragma unroll
+                for (int t = 0; t < kGroupTiles; ++t)
+                    col_of[t] = c_tile_col[run_begin + min(g * kGroupTiles + t, run_tiles - 1)] * T + j;
+            } else if (g == 0) {
                 em.base = base_first;
                 em.col = J_first * T + j;
             } else {
                 em.base = c_row_ptr[(int64_t)c_tile_row[c_mine] * T];
                 em.col = c_tile_col[c_mine] * T + j;
             }
-            auto request_masks = [&]() {
-                if constexpr (kNarrow) {
-                    const BufferArray masks(c_row_mask, (uint64_t)c_tiles * T * 2), offs(c_row_off, (uint64_t)c_tiles * T * 4);
-                    em.masks = masks.u32(mine_exists ? (uint32_t)c_mine * (T * 2) + (uint32_t)(j & 7) * 4u : kSkip);
-                    em.first = offs.u32(mine_exists ? (uint32_t)c_mine * (T * 4) + (uint32_t)j * 4u : kSkip);
-                } else {
-                    em.masks = mine_exists ? reinterpret_cast<const uint32_t *>(c_row_mask + c_mine * T)[j & 7] : 0u;
-                    em.first = c_row_off[c_mine * T + j];
-                }
-            };
-            request_masks();
+            if constexpr (kNarrow) {
+                const BufferArray masks(c_row_mask, (uint64_t)c_tiles * T * 2), offs(c_row_off, (uint64_t)c_tiles * T * 4);
+                em.masks = masks.u32(mine_exists ? (uint32_t)c_mine * (T * 2) + (uint32_t)pair_l * 4u : kSkip);
+                em.first = offs.u32(mine_exists ? (uint32_t)c_mine * (T * 4) + (uint32_t)row_l * 4u : kSkip);
+                // narrow arrays: positions in C fit 32 bits, the start of the tile-row is added once here
+                if constexpr (!kWholeRows) em.first += (uint32_t)em.base;
+            } else {
+                em.masks = mine_exists ? reinterpret_cast<const uint32_t *>(c_row_mask + c_mine * T)[pair_l] : 0u;
+                em.first = c_row_off[c_mine * T + row_l];
+            }
             float4v acc[kGroupTiles];
 #pragma unroll
             for (int t = 0; t < kGroupTiles; ++t) {
@@ -312,51 +351,89 @@ __global__ __launch_bounds__(kNumThreads) void k_numeric(
                     }
                 }
             }
-            // Transposition between tile index and row block: register v of tile t holds rows 4q+v in
-            // lanes 16q..16q+15; afterwards rows[v][q] holds row 4q+v of tile tq in lanes 16tq..16tq+15,
-            // so that one store instruction writes one CSR row across the four tiles, which are
-            // neighbours in that row: one contiguous run per instruction instead of four.
-            float rows[4][kGroupTiles];
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-#pragma unroll
-                for (int t = 0; t < kGroupTiles; ++t) rows[v][t] = acc[t][v];
-                swap_rows(rows[v][0], rows[v][1], false);
-                swap_rows(rows[v][2], rows[v][3], false);
-                swap_rows(rows[v][0], rows[v][2], true);
-                swap_rows(rows[v][1], rows[v][3], true);
-            }
-            // Row r of the tile: its mask is the low (even r) or high (odd r) half of the word that lane
-            // r/2 of the tile's 16 lanes loaded, its first position is what lane r loaded; the entry of
-            // column j exists if its bit is set and sits after the set bits below it.
-            // Every load of this wave has returned by now (the last tile's operands were requested after
-            // everything else and have been used).  Saying so explicitly keeps the compiler from putting
-            // load waits between the stores below, where they would also wait for the stores before them.
-            __builtin_amdgcn_s_waitcnt(0x0F70);    // vmcnt(0)
             const uint32_t my_bit[2] = {1u << j, 1u << (j + 16)};
             const uint32_t my_below[2] = {(1u << j) - 1u, ((1u << j) - 1u) << 16};
-            const BufferArray out_col(c_col, (uint64_t)c_nnz * 4), out_val(c_val, (uint64_t)c_nnz * 4);
-            const uint32_t base4 = (uint32_t)em.base << 2;
-            for_each_row(
-                [&](auto row) {
-                    constexpr int r = decltype(row)::value;
-                    const uint32_t w = row_broadcast<r / 2>(em.masks), first = row_broadcast<r>(em.first);
-                    // lanes without an entry are switched off rather than sent out of range: a store
-                    // costs by the lanes that take part in it
-                    if (w & my_bit[r & 1]) {
-                        const uint32_t rank = (uint32_t)__popc(w & my_below[r & 1]) + first;
-                        if constexpr (kNarrow) {
-                            const uint32_t at = (rank << 2) + base4;
-                            out_col.put(at, (uint32_t)em.col);
-                            out_val.put(at, __float_as_uint(rows[r & 3][r >> 2]));
-                        } else {
-                            const int64_t pos = em.base + (int64_t)rank;
-                            c_col[pos] = em.col;
-                            c_val[pos] = rows[r & 3][r >> 2];
+            if constexpr (kWholeRows) {
+                // Straight from the accumulators into the tile-row's stretch in LDS: register v of tile t
+                // is row 4q+v; its mask is the low (even v) or high (odd v) half of the word that lane
+                // 4t+(v&2) of this row of lanes fetched, its position is what lane 4t+v fetched.  The
+                // entry of column j exists if its bit is set and sits after the set bits below it.
+                uint32_t pair = 0;
+                for_each_row(
+                    [&](auto index) {
+                        constexpr int t = decltype(index)::value / 4, v = decltype(index)::value % 4;
+                        if (g * kGroupTiles + t >= run_tiles) return;          // uniform
+                        if constexpr (v % 2 == 0) pair = row_broadcast<4 * t + v>(em.masks);
+                        const uint32_t first = row_broadcast<4 * t + v>(em.first);
+                        if (pair & my_bit[v & 1]) {
+                            const uint32_t rank = (uint32_t)__popc(pair & my_below[v & 1]) + first;
+                            my_entries[0][rank] = (uint32_t)col_of[t];
+                            my_entries[1][rank] = __float_as_uint(acc[t][v]);
                         }
-                    }
-                },
-                std::make_integer_sequence<int, T>{});
+                    },
+                    std::make_integer_sequence<int, T>{});
+            } else {
+                // Transposition between tile index and row block: register v of tile t holds rows 4q+v in
+                // lanes 16q..16q+15; afterwards rows[v][q] holds row 4q+v of tile tq in lanes 16tq..16tq+15,
+                // so that one store instruction writes one CSR row across the four tiles, which are
+                // neighbours in that row: one contiguous run per instruction instead of four.
+                float rows[4][kGroupTiles];
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+#pragma unroll
+                    for (int t = 0; t < kGroupTiles; ++t) rows[v][t] = acc[t][v];
+                    swap_rows(rows[v][0], rows[v][1], false);
+                    swap_rows(rows[v][2], rows[v][3], false);
+                    swap_rows(rows[v][0], rows[v][2], true);
+                    swap_rows(rows[v][1], rows[v][3], true);
+                }
+                // Row r of the tile: its mask is the low (even r) or high (odd r) half of the word that
+                // lane r/2 of the tile's 16 lanes fetched, its position is what lane r fetched; the entry
+                // of column j exists if its bit is set and sits after the set bits below it.
+                // Every load of this wave has returned by now (the last tile's operands were requested
+                // after everything else and have been used).  Saying so explicitly keeps the compiler from
+                // putting load waits between the stores below, where they would also wait for the stores
+                // before them.
+                __builtin_amdgcn_s_waitcnt(0x0F70);    // vmcnt(0)
+                const BufferArray out_col(c_col, (uint64_t)c_nnz * 4), out_val(c_val, (uint64_t)c_nnz * 4);
+                uint32_t pair = 0;
+                for_each_row(
+                    [&](auto row) {
+                        constexpr int r = decltype(row)::value;
+                        if constexpr (r % 2 == 0) pair = row_broadcast<r / 2>(em.masks);
+                        const uint32_t first = row_broadcast<r>(em.first);
+                        // lanes without an entry are switched off rather than sent out of range: a store
+                        // costs by the lanes that take part in it
+                        if (pair & my_bit[r & 1]) {
+                            const uint32_t rank = (uint32_t)__popc(pair & my_below[r & 1]) + first;
+                            if constexpr (kNarrow) {
+                                out_col.put(rank << 2, (uint32_t)em.col);
+                                out_val.put(rank << 2, __float_as_uint(rows[r & 3][r >> 2]));
+                            } else {
+                                const int64_t pos = em.base + (int64_t)rank;
+                                c_col[pos] = em.col;
+                                c_val[pos] = rows[r & 3][r >> 2];
+                            }
+                        }
+                    },
+                    std::make_integer_sequence<int, T>{});
+            }
+        }
+    }
+    if constexpr (kWholeRows) {
+        // the tile-row's entries, 64 consecutive ones per store instruction
+        wave_sync();
+        for (int at = lane; at < row_entries; at += 64) {
+            const uint32_t col = my_entries[0][at], val = my_entries[1][at];
+            if constexpr (kNarrow) {
+                const BufferArray out_col(c_col, (uint64_t)c_nnz * 4), out_val(c_val, (uint64_t)c_nnz * 4);
+                const uint32_t byte = (uint32_t)(base_first + at) << 2;
+                out_col.put(byte, col);
+                out_val.put(byte, val);
+            } else {
+                c_col[base_first + at] = (int32_t)col;
+                c_val[base_first + at] = __uint_as_float(val);
+            }
         }
     }
 }
@@ -384,8 +461,12 @@ int numeric_enqueue(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s
         int tiles_per_wave = kGroupTiles;
         if (ctx->numeric_run_len == 4 || ctx->numeric_run_len == 8) tiles_per_wave = ctx->numeric_run_len;
         if (!ctx->matrix_cores) tiles_per_wave = kGroupTiles;
+        // Short, sparse tile-rows (meshes in two dimensions, for one): a wave per tile-row, output through LDS
+        const bool whole_rows = ctx->matrix_cores && ctx->numeric_run_len == 0 && P->max_row_c_tiles <= kRowTiles &&
+                                P->max_row_pairs <= kBlockEntries && P->max_row_entries <= kRowEntries;
         const int64_t tiles_per_block = (int64_t)(kNumThreads / 64) * tiles_per_wave;
-        int64_t blocks = (P->c_tiles + tiles_per_block - 1) / tiles_per_block;
+        int64_t blocks = whole_rows ? (P->c_tile_rows + kNumThreads / 64 - 1) / (kNumThreads / 64)
+                                    : (P->c_tiles + tiles_per_block - 1) / tiles_per_block;
         blocks = (blocks + kXcds - 1) / kXcds * kXcds;             // the XCD remap needs a multiple of 8
         const NumericSizes z{(uint64_t)P->pairs, (uint64_t)A->tile_capacity, (uint64_t)B->tile_capacity,
                              (uint64_t)A->group_capacity, (uint64_t)B->group_capacity};
@@ -396,7 +477,9 @@ int numeric_enqueue(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s
         auto kernel = narrow ? (tiles_per_wave == 4 ? k_numeric<true, 4, true> : k_numeric<true, 8, true>)
                              : (tiles_per_wave == 4 ? k_numeric<false, 4, true> : k_numeric<false, 8, true>);
         if (!ctx->matrix_cores) kernel = narrow ? k_numeric<true, 4, false> : k_numeric<false, 4, false>;
-        hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(kNumThreads), 0, s, P->c_tiles, P->c_nnz, z, P->pair_off,
+        if (whole_rows) kernel = narrow ? k_numeric<true, kRowTiles, true, true> : k_numeric<false, kRowTiles, true, true>;
+        hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(kNumThreads), 0, s, P->c_tiles, P->c_nnz, z, P->c_rows,
+                           (int32_t)P->c_tile_rows, P->c_tile_row_ptr, P->pair_off,
                            P->pair_a, P->pair_b, A->lhead, A->ldata, B->rhead, B->rdata,
                            P->c_tile_row, P->c_tile_col, P->c_row_mask, P->c_row_off, P->c_row_ptr, col, val);
         e = hipGetLastError();

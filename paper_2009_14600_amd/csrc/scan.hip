@@ -45,22 +45,20 @@ __device__ __forceinline__ int64_t block_max(int64_t v, int64_t *lds /*[4]*/) {
     return m;
 }
 
-// Pass 1: per-block sum and max.
+// Pass 1: per-block sum, and the largest sum of an aligned group of 16 inputs.
 __global__ __launch_bounds__(kScanThreads) void k_scan_reduce(const int32_t *__restrict__ in, int64_t n,
                                                               int64_t *__restrict__ sums,
                                                               int64_t *__restrict__ maxs) {
     __shared__ int64_t lds[8];
     const int64_t base = (int64_t)blockIdx.x * kScanBlock + (int64_t)threadIdx.x * kScanItems;
-    int64_t s = 0, m = 0;
+    static_assert(kScanItems == 8, "two neighbouring threads hold an aligned group of 16 inputs");
+    int64_t s = 0;
 #pragma unroll
     for (int i = 0; i < kScanItems; ++i)
-        if (base + i < n) {
-            int64_t x = in[base + i];
-            s += x;
-            m = max(m, x);
-        }
+        if (base + i < n) s += in[base + i];
     int64_t total;
     block_inclusive_scan(s, &total, lds);
+    int64_t m = s + (int64_t)__shfl_xor(s, 1, 64);     // inputs 16k..16k+15
     m = block_max(m, lds);
     if (threadIdx.x == 0) {
         sums[blockIdx.x] = total;

@@ -1002,6 +1002,8 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
     P->c_tiles = h[S_C_TILES];
     P->pairs = h[S_PAIRS];
     P->candidates = h[S_CANDIDATES];
+    P->max_row_c_tiles = h[S_MAX_ROW_C_TILES];
+    P->max_row_pairs = h[S_MAX_ROW_PAIRS];
     if (P->c_tiles >= INT32_MAX) return cleanup(TSP_ERR_INDEX_OVERFLOW);
 
     P->c_tile_row = ctx_alloc_n<int32_t>(ctx, (size_t)P->c_tiles, s);
@@ -1078,14 +1080,15 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
     SYM_CHECK(hipGetLastError());
     {
         KernelTimer kt(ctx, TSP_KERNEL_SCAN_ROWS, s);
-        rc = scan_exclusive_i32_to_i64(ctx, row_nnz, P->c_row_ptr, P->c_rows, ctx->d_scalars + S_C_NNZ, nullptr, tmp,
-                                       s);
+        rc = scan_exclusive_i32_to_i64(ctx, row_nnz, P->c_row_ptr, P->c_rows, ctx->d_scalars + S_C_NNZ,
+                                       ctx->d_scalars + S_MAX_ROW_ENTRIES, tmp, s);
     }
     phase_end(ctx, TSP_PHASE_COUNT, s);
     if (!rc) rc = read_scalars(ctx, s);                                    // ---- sync 2: nnz(C)
     if (rc) return cleanup(rc);
     if (ctx->h_scalars[S_UNSUPPORTED]) return cleanup(TSP_ERR_UNSUPPORTED);
     P->c_nnz = ctx->h_scalars[S_C_NNZ];
+    P->max_row_entries = ctx->h_scalars[S_MAX_ROW_ENTRIES];
     ctx->stats.a_tiles = A->ntiles;
     ctx->stats.b_tiles = B->ntiles;
     ctx->stats.candidate_pairs = P->candidates;

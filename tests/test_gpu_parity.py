@@ -449,3 +449,50 @@ def test_tile_rows_with_more_output_tiles_than_the_symbolic_window(tsp, handle, 
     ref = oracle.spgemm(A, B, threads=4)
     assert_matches_oracle(C, ref, "wide output tile-rows")
     C.free()
+
+
+# ------------------------------------------------------------------ variants of the multiplication kernel
+def _variant_handle(tsp, **options):
+    h = tsp.Handle(validate=True)
+    for name, value in options.items():
+        h.set_option(getattr(tsp, name), value)
+    return h
+
+
+def _mesh_cases():
+    """Products whose tile-rows of C are short and sparse (at most 16 output tiles, 64 task-list entries
+    and 512 entries per tile-row): the multiplication kernel takes a whole tile-row per wave and
+    assembles its output in LDS.  Grid edges that are no multiple of 16 give ragged last tile-rows."""
+    yield "laplacian 37x37", inputs.laplacian_2d(37), None
+    yield "laplacian 64x64", inputs.laplacian_2d(64), None
+    # one inner tile column, 16 and 17 output tiles per tile-row: either side of the limit
+    for n_cols in (256, 272):
+        A = inputs.random_sparse(70, 16, 0.07, 91, empty_row_fraction=0.2)
+        B = inputs.random_sparse(16, n_cols, 0.1, 92)
+        yield f"single inner tile, {n_cols} columns", A, B
+    # entries per tile-row either side of 512
+    for density in (0.10, 0.16):
+        A = inputs.random_sparse(64, 16, 0.0625, 93)
+        B = inputs.random_sparse(16, 256, density, 94, values="smallint")
+        yield f"single inner tile, density {density}", A, B
+
+
+@pytest.mark.parametrize("options", [
+    {},                                             # automatic choice
+    {"OPT_WIDE_INDEX": 1},                          # 64-bit addressing, as for arrays of 4 GiB and more
+    {"OPT_NUMERIC_RUN": 4},                         # four tiles per wave whatever the shape of the tile-rows
+    {"OPT_NUMERIC_RUN": 8},
+    {"OPT_NUMERIC_RUN": 8, "OPT_WIDE_INDEX": 1},
+], ids=lambda o: "+".join(f"{k}={v}" for k, v in o.items()) or "automatic")
+def test_multiplication_kernel_variants(tsp, oracle, options):
+    h = _variant_handle(tsp, **options)
+    try:
+        for what, A, B in _mesh_cases():
+            print(f"{options}: {what}", flush=True)
+            run_and_check(tsp, h, oracle, A, B)
+        for index in (1, 3, 5):
+            A = inputs.config(index, small=True)
+            print(f"{options}: config {index} small", flush=True)
+            run_and_check(tsp, h, oracle, A)
+    finally:
+        h.close()
