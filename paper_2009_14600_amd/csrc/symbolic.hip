@@ -1087,6 +1087,7 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
     if (!rc) rc = read_scalars(ctx, s);                                    // ---- sync 2: nnz(C)
     if (rc) return cleanup(rc);
     if (ctx->h_scalars[S_UNSUPPORTED]) return cleanup(TSP_ERR_UNSUPPORTED);
+    if (ctx->h_scalars[S_INTERNAL]) return cleanup(TSP_ERR_HIP);
     P->c_nnz = ctx->h_scalars[S_C_NNZ];
     P->max_row_entries = ctx->h_scalars[S_MAX_ROW_ENTRIES];
     ctx->stats.a_tiles = A->ntiles;
