@@ -227,6 +227,13 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_count(TileRefs A, TileRefs 
 // Prefix sums over the tile-rows (Algorithm 1: counts -> offsets and total sizes) in one
 // launch: C tiles per row -> c_tile_row_ptr, pairs per row -> row_pair_ptr, plus the totals and maxima
 // the host needs to size the task list.  A block scans 1024 tile-rows; the blocks are chained.
+// k_row_ptr turns row lengths into row_ptr in one launch, 2048 rows (128 tile-rows) per block, from the
+// number of entries of every tile-row, which the counting pass leaves in an array (one plain store per
+// tile-row: thousands of atomics on a few addresses cost tens of microseconds).  Every block adds up the
+// tile-rows before it, so the launch is for up to kMaxChunks blocks; beyond, the three-kernel scan.
+constexpr int kChunkTileRows = 128, kChunkRows = kChunkTileRows * T;
+constexpr int64_t kMaxChunks = 256;
+
 constexpr int kRowScanThreads = 256, kRowScanItems = 4, kRowScanBlock = kRowScanThreads * kRowScanItems;
 struct TileCount {           // an operand whose number of tiles is still to be summed (slot < 0: nothing to do)
     const int32_t *trp, *tend;
@@ -487,7 +494,7 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_emit_listed(
     int32_t *__restrict__ c_tile_row, int32_t *__restrict__ c_tile_col, int64_t *__restrict__ pair_off,
     int32_t *__restrict__ pair_a, int32_t *__restrict__ pair_b, const uint16_t *__restrict__ a_row_mask,
     const uint16_t *__restrict__ b_row_mask, uint16_t *__restrict__ c_row_mask, uint32_t *__restrict__ c_row_off,
-    int32_t *__restrict__ row_nnz, int64_t c_rows, int64_t *d_scalars) {
+    int32_t *__restrict__ row_nnz, int64_t c_rows, int64_t *d_scalars, uint32_t *__restrict__ tile_row_entries) {
     extern __shared__ uint32_t lds_dyn[];
     __shared__ uint32_t red[32];
     __shared__ int s_jmax, s_n;
@@ -503,6 +510,7 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_emit_listed(
     if (I == (int)gridDim.x - 1 && threadIdx.x == 0) pair_off[c_tile_row_ptr[gridDim.x]] = row_pair_ptr[gridDim.x];
     if (nC <= 0) {                                   // an empty tile-row of C: its 16 rows are empty
         if (kFuseMasks && threadIdx.x < T && (int64_t)I * T + threadIdx.x < c_rows) row_nnz[(int64_t)I * T + threadIdx.x] = 0;
+        if (kFuseMasks && threadIdx.x == 0) tile_row_entries[I] = 0;
         return;
     }
     const int a0 = A.trp[I], a1 = A.tend[I];
@@ -650,7 +658,10 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_emit_listed(
             const uint64_t up = __shfl_up(before, d, T);
             if (r >= d) before += up;
         }
-        if (r == T - 1 && before > 0xFFFFFFFFull) d_scalars[S_UNSUPPORTED] = 1;
+        if (r == T - 1) {
+            if (before > 0xFFFFFFFFull) d_scalars[S_UNSUPPORTED] = 1;
+            tile_row_entries[I] = (uint32_t)before;
+        }
         uint32_t run = (uint32_t)(before - total);
         for (int c = 0; c < nC; ++c) {
             c_row_off[(int64_t)(c0 + c) * T + r] = run;
@@ -842,6 +853,68 @@ __global__ __launch_bounds__(256) void k_count_masks(int64_t c_tiles, const int6
     if (in) c_row_mask[c * T + r] = (uint16_t)((acc | (acc >> 16)) & 0xFFFFu);
 }
 
+// row_ptr of C from the row lengths: block b takes rows [2048 b, 2048 b + 2048), starts from the
+// entries of the tile-rows before them and scans its own rows.  The last block has read every
+// tile-row and also leaves nnz(C) and the largest tile-row.
+__global__ __launch_bounds__(256) void k_row_ptr(const int32_t *__restrict__ row_nnz, int64_t c_rows,
+                                                 const uint32_t *__restrict__ tile_row_entries, int64_t c_tile_rows,
+                                                 int64_t *__restrict__ c_row_ptr, int64_t *d_scalars) {
+    __shared__ uint64_t lds[256 / 64];
+    constexpr int kItems = kChunkRows / 256;
+    const bool last = blockIdx.x == gridDim.x - 1;
+    const int64_t tile_rows_before = (int64_t)blockIdx.x * kChunkTileRows;
+    uint64_t before = 0;
+    uint32_t largest = 0;
+    // four tile-rows per load, four loads in flight (the array is padded to a multiple of four)
+    const uint4 *entries4 = reinterpret_cast<const uint4 *>(tile_row_entries);
+    const int64_t quads = ((last ? c_tile_rows : tile_rows_before) + 3) / 4;
+    for (int64_t q0 = threadIdx.x; q0 < quads; q0 += 4 * 256) {
+        uint4 e[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) e[u] = q0 + u * 256 < quads ? entries4[q0 + u * 256] : make_uint4(0, 0, 0, 0);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int64_t I = (q0 + u * 256) * 4;
+            const uint32_t v[4] = {e[u].x, e[u].y, e[u].z, e[u].w};
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                if (I + k < c_tile_rows) {
+                    if (I + k < tile_rows_before) before += v[k];
+                    largest = max(largest, v[k]);
+                }
+        }
+    }
+    uint64_t entries_before;
+    (void)block_exclusive_scan64<256>(before, &entries_before, lds);
+    const int64_t base = (int64_t)blockIdx.x * kChunkRows + (int64_t)threadIdx.x * kItems;
+    int32_t x[kItems];
+    uint64_t mine = 0;
+#pragma unroll
+    for (int i = 0; i < kItems; ++i) {
+        x[i] = base + i < c_rows ? row_nnz[base + i] : 0;
+        mine += (uint32_t)x[i];
+    }
+    uint64_t total;
+    uint64_t run = entries_before + block_exclusive_scan64<256>(mine, &total, lds);
+#pragma unroll
+    for (int i = 0; i < kItems; ++i) {
+        if (base + i < c_rows) c_row_ptr[base + i] = (int64_t)run;
+        run += (uint32_t)x[i];
+    }
+    if (last) {
+        largest = (uint32_t)wave_max((int)min(largest, 0x7FFFFFFFu));
+        __syncthreads();
+        if ((threadIdx.x & 63) == 0) lds[threadIdx.x >> 6] = largest;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            for (int w = 1; w < 256 / 64; ++w) largest = max(largest, (uint32_t)lds[w]);
+            c_row_ptr[c_rows] = (int64_t)(entries_before + total);
+            d_scalars[S_C_NNZ] = (int64_t)(entries_before + total);
+            d_scalars[S_MAX_ROW_ENTRIES] = (int64_t)largest;
+        }
+    }
+}
+
 // Per tile-row of C (16 lanes, lane r = row r): the length of CSR row 16I+r, and for every tile of
 // the tile-row the position of its first entry in that row, counted from the first entry of the
 // tile-row (entries of rows 16I..16I+r-1 plus the row's entries in the tiles to the left).  The
@@ -851,7 +924,8 @@ __global__ __launch_bounds__(256) void k_row_offsets(int64_t c_tile_rows, int64_
                                                      const int32_t *__restrict__ c_tile_row_ptr,
                                                      const uint16_t *__restrict__ c_row_mask,
                                                      uint32_t *__restrict__ c_row_off,
-                                                     int32_t *__restrict__ row_nnz, int64_t *d_scalars) {
+                                                     int32_t *__restrict__ row_nnz, int64_t *d_scalars,
+                                                     uint32_t *__restrict__ tile_row_entries) {
     const int64_t I = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 4;
     const int r = threadIdx.x & 15;
     if (I >= c_tile_rows) return;                  // whole 16-lane groups leave together
@@ -866,7 +940,10 @@ __global__ __launch_bounds__(256) void k_row_offsets(int64_t c_tile_rows, int64_
         const uint64_t up = __shfl_up(before, d, T);
         if (r >= d) before += up;
     }
-    if (r == T - 1 && before > 0xFFFFFFFFull) d_scalars[S_UNSUPPORTED] = 1;
+    if (r == T - 1) {
+        if (before > 0xFFFFFFFFull) d_scalars[S_UNSUPPORTED] = 1;
+        tile_row_entries[I] = (uint32_t)before;
+    }
     uint32_t run = (uint32_t)(before - total);
     for (int64_t c = c0; c < c1; ++c) {
         c_row_off[c * T + r] = run;
@@ -909,6 +986,7 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
     const int64_t ntr = A->tile_rows;
     int rc = TSP_OK;
     int32_t *row_jmin = nullptr, *row_c_tiles = nullptr, *row_pairs = nullptr, *row_nnz = nullptr;
+    uint32_t *tile_row_entries = nullptr;
     int32_t *row_words = nullptr, *row_cand = nullptr;
     uint32_t *wide_words = nullptr;
     int64_t *row_pair_ptr = nullptr, *tmp = nullptr;
@@ -920,6 +998,7 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
         ctx_free(ctx, row_cand, s);
         ctx_free(ctx, wide_words, s);
         ctx_free(ctx, row_nnz, s);
+        ctx_free(ctx, tile_row_entries, s);
         ctx_free(ctx, row_pair_ptr, s);
         ctx_free(ctx, tmp, s);
         if (code) plan_release(ctx, P, s);
@@ -945,6 +1024,7 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
     if (!row_jmin || !row_c_tiles || !row_pairs || !row_words || !row_cand || !row_pair_ptr || !P->c_tile_row_ptr || !tmp)
         return cleanup(TSP_ERR_ALLOC_FAILED);
 
+    const int64_t n_chunks = (ntr + kChunkTileRows - 1) / kChunkTileRows;     // blocks of k_row_ptr
     TileRefs ra{A->tile_row_ptr, A->tile_row_end, A->tile_col, A->lmask, A->rmask, (int32_t)A->tile_rows};
     TileRefs rb{B->tile_row_ptr, B->tile_row_end, B->tile_col, B->lmask, B->rmask, (int32_t)B->tile_rows};
     // tiles-per-tile-row of B is not known on the host before the first read-back: estimate the
@@ -1016,8 +1096,9 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
     // padded to whole tile-rows: the numeric pass reads the 16 row starts of a tile-row unconditionally
     P->c_row_ptr = ctx_alloc_n<int64_t>(ctx, (size_t)P->c_tile_rows * T + T + 1, s);
     row_nnz = ctx_alloc_n<int32_t>(ctx, (size_t)P->c_rows + 1, s);
+    tile_row_entries = ctx_alloc_n<uint32_t>(ctx, (size_t)ntr + 4, s);     // read four at a time
     if (!P->c_tile_row || !P->c_tile_col || !P->pair_off || !P->pair_a || !P->pair_b || !P->c_row_mask ||
-        !P->c_row_off || !P->c_row_ptr || !row_nnz)
+        !P->c_row_off || !P->c_row_ptr || !row_nnz || !tile_row_entries)
         return cleanup(TSP_ERR_ALLOC_FAILED);
 
     if (ntr > 0) {
@@ -1048,7 +1129,7 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
                                lanes, words_cap, window, list_cap, row_jmin, P->c_tile_row_ptr,
                                row_pair_ptr, P->c_tile_row, P->c_tile_col, P->pair_off, P->pair_a, P->pair_b,
                                A->row_mask, B->row_mask, P->c_row_mask, P->c_row_off, row_nnz, P->c_rows,
-                               ctx->d_scalars);
+                               ctx->d_scalars, tile_row_entries);
         } else
             hipLaunchKernelGGL(long_rows ? k_sym_emit<true> : k_sym_emit<false>, dim3((unsigned)ntr), dim3(threads),
                                lds, s, ra, rb, lanes, words_cap, window, wide_threshold, row_jmin, P->c_tile_row_ptr,
@@ -1075,13 +1156,19 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
         const unsigned grid = (unsigned)((ntr * 16 + 255) / 256);
         KernelTimer kt(ctx, TSP_KERNEL_ROW_OFFSETS, s);
         hipLaunchKernelGGL(k_row_offsets, dim3(grid), dim3(256), 0, s, ntr, P->c_rows, P->c_tile_row_ptr,
-                           P->c_row_mask, P->c_row_off, row_nnz, ctx->d_scalars);
+                           P->c_row_mask, P->c_row_off, row_nnz, ctx->d_scalars, tile_row_entries);
     }
     SYM_CHECK(hipGetLastError());
     {
         KernelTimer kt(ctx, TSP_KERNEL_SCAN_ROWS, s);
-        rc = scan_exclusive_i32_to_i64(ctx, row_nnz, P->c_row_ptr, P->c_rows, ctx->d_scalars + S_C_NNZ,
-                                       ctx->d_scalars + S_MAX_ROW_ENTRIES, tmp, s);
+        if (n_chunks > 0 && n_chunks <= kMaxChunks) {
+            hipLaunchKernelGGL(k_row_ptr, dim3((unsigned)n_chunks), dim3(256), 0, s, row_nnz, P->c_rows, tile_row_entries,
+                               ntr, P->c_row_ptr, ctx->d_scalars);
+            SYM_CHECK(hipGetLastError());
+        } else {
+            rc = scan_exclusive_i32_to_i64(ctx, row_nnz, P->c_row_ptr, P->c_rows, ctx->d_scalars + S_C_NNZ,
+                                           ctx->d_scalars + S_MAX_ROW_ENTRIES, tmp, s);
+        }
     }
     phase_end(ctx, TSP_PHASE_COUNT, s);
     if (!rc) rc = read_scalars(ctx, s);                                    // ---- sync 2: nnz(C)
