@@ -149,8 +149,9 @@ int convert_enqueue(tsp_context *ctx, const tsp_csr *A, int forms, int scalar_sl
 void tiles_release(tsp_context *ctx, tsp_tiles_s *t, hipStream_t s);
 int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **out, hipStream_t s);
 void plan_release(tsp_context *ctx, tsp_plan_s *p, hipStream_t s);
+// take_row_ptr: C gets the plan's row_ptr array itself instead of a copy; the plan cannot be used again.
 int numeric_enqueue(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s *plan, tsp_csr *C,
-                    hipStream_t s);
+                    hipStream_t s, bool take_row_ptr = false);
 int compact_zeros(tsp_context *ctx, const tsp_csr *C, tsp_csr *out, hipStream_t s);
 
 #ifdef __HIPCC__

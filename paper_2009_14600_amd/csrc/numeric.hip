@@ -438,22 +438,25 @@ __global__ __launch_bounds__(kNumThreads) void k_numeric(
     }
 }
 
-int numeric_enqueue(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s *P, tsp_csr *C, hipStream_t s) {
+int numeric_enqueue(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s *P, tsp_csr *C, hipStream_t s,
+                    bool take_row_ptr) {
     std::memset(C, 0, sizeof(*C));
     if (!(A->forms & TSP_FORM_LEFT) || !(B->forms & TSP_FORM_RIGHT)) return TSP_ERR_INVALID_ARG;
     if (A->cols != B->rows || P->c_rows != A->rows || P->c_cols != B->cols) return TSP_ERR_SHAPE_MISMATCH;
-    int64_t *row_ptr = ctx_alloc_n<int64_t>(ctx, (size_t)P->c_rows + 1, s);
+    if (!P->c_row_ptr) return TSP_ERR_INVALID_ARG;                       // a plan whose row_ptr has been handed over
+    int64_t *row_ptr = take_row_ptr ? P->c_row_ptr : ctx_alloc_n<int64_t>(ctx, (size_t)P->c_rows + 1, s);
     int32_t *col = ctx_alloc_n<int32_t>(ctx, (size_t)P->c_nnz, s);
     float *val = ctx_alloc_n<float>(ctx, (size_t)P->c_nnz, s);
     if (!row_ptr || !col || !val) {
-        ctx_free(ctx, row_ptr, s);
+        if (!take_row_ptr) ctx_free(ctx, row_ptr, s);
         ctx_free(ctx, col, s);
         ctx_free(ctx, val, s);
         return TSP_ERR_ALLOC_FAILED;
     }
     phase_begin(ctx, TSP_PHASE_NUMERIC, s);
-    hipError_t e = hipMemcpyAsync(row_ptr, P->c_row_ptr, sizeof(int64_t) * (size_t)(P->c_rows + 1),
-                                  hipMemcpyDeviceToDevice, s);
+    hipError_t e = hipSuccess;
+    if (!take_row_ptr)
+        e = hipMemcpyAsync(row_ptr, P->c_row_ptr, sizeof(int64_t) * (size_t)(P->c_rows + 1), hipMemcpyDeviceToDevice, s);
     if (e == hipSuccess && P->c_tiles > 0) {
         KernelTimer kt(ctx, TSP_KERNEL_NUMERIC, s);
         // Tiles one wave walks: one group of four measured fastest on all workloads (more waves in
@@ -486,11 +489,12 @@ int numeric_enqueue(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s
     }
     phase_end(ctx, TSP_PHASE_NUMERIC, s);
     if (e != hipSuccess) {
-        ctx_free(ctx, row_ptr, s);
+        if (!take_row_ptr) ctx_free(ctx, row_ptr, s);
         ctx_free(ctx, col, s);
         ctx_free(ctx, val, s);
         return hip_fail(ctx, e);
     }
+    if (take_row_ptr) P->c_row_ptr = nullptr;
     C->rows = P->c_rows;
     C->cols = P->c_cols;
     C->nnz = P->c_nnz;

@@ -31,7 +31,7 @@ extern "C" int tsp_spgemm(tsp_handle ctx, const tsp_csr *A, const tsp_csr *B, ts
     if (!rc && !alias) rc = convert_enqueue(ctx, B, TSP_FORM_RIGHT, S_TILES_B, &tb, s);
     phase_end(ctx, TSP_PHASE_CONVERT, s);
     if (!rc) rc = symbolic_run(ctx, ta, alias ? ta : tb, &plan, s);
-    if (!rc) rc = numeric_enqueue(ctx, ta, alias ? ta : tb, plan, C, s);
+    if (!rc) rc = numeric_enqueue(ctx, ta, alias ? ta : tb, plan, C, s, /*take_row_ptr=*/true);   // the plan ends here
     if (!rc && ctx->compact) {                    // Algorithm 1, the compaction steps: strictly sparse result
         tsp_csr structural = *C;
         rc = compact_zeros(ctx, &structural, C, s);
