@@ -59,6 +59,7 @@ struct tsp_context {
     int64_t chain_capacity = 0;                    // slots allocated
     unsigned chain_epoch = 0;                      // tag of the last chained scan
     int64_t *d_scalars = nullptr;                  // device, kScalars entries
+    bool scalars_clean = false;                    // all zero: the previous tsp_spgemm left them so
     int64_t *h_scalars = nullptr;                  // pinned host mirror
     hipEvent_t ev[2 * TSP_PHASE_COUNT_ + 2]{};     // begin/end per phase, + total begin/end
     bool ev_created = false;
@@ -149,9 +150,11 @@ int convert_enqueue(tsp_context *ctx, const tsp_csr *A, int forms, int scalar_sl
 void tiles_release(tsp_context *ctx, tsp_tiles_s *t, hipStream_t s);
 int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **out, hipStream_t s);
 void plan_release(tsp_context *ctx, tsp_plan_s *p, hipStream_t s);
-// take_row_ptr: C gets the plan's row_ptr array itself instead of a copy; the plan cannot be used again.
+// last_of_call (tsp_spgemm): C gets the plan's row_ptr array itself instead of a copy, so the plan cannot
+// be used again, and the kernel zeroes the handle's scalar block, which nothing reads any more, for the
+// next call (one launch less per call).
 int numeric_enqueue(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s *plan, tsp_csr *C,
-                    hipStream_t s, bool take_row_ptr = false);
+                    hipStream_t s, bool last_of_call = false);
 int compact_zeros(tsp_context *ctx, const tsp_csr *C, tsp_csr *out, hipStream_t s);
 
 #ifdef __HIPCC__

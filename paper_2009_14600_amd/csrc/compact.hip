@@ -97,6 +97,7 @@ static int compact_run(tsp_context *ctx, const tsp_csr *C, tsp_csr *out, hipStre
     int64_t *tmp = ctx_alloc_n<int64_t>(ctx, scan_tmp_entries(rows), s);
     if (!tmp) return fail(TSP_ERR_ALLOC_FAILED);
     hipLaunchKernelGGL(k_compact_clear, dim3(1), dim3(64), 0, s, ctx->d_scalars);
+    ctx->scalars_clean = false;
     if (rows > 0)
         hipLaunchKernelGGL(k_compact_count<RP>, dim3((unsigned)row_blocks), dim3(kCompactThreads), 0, s, a, keep);
     // new row_ptr = exclusive prefix of the survivor counts, the total to the scalar block

@@ -665,6 +665,7 @@ extern "C" int tsp_convert(tsp_handle ctx, const tsp_csr *A, int forms, tsp_tile
     *out = nullptr;
     hipStream_t s = (hipStream_t)stream;
     hipLaunchKernelGGL(k_clear_scalars, dim3(1), dim3(64), 0, s, ctx->d_scalars);
+    ctx->scalars_clean = false;
     phase_begin(ctx, TSP_PHASE_CONVERT, s);
     tsp_tiles_s *t = nullptr;
     int rc = convert_enqueue(ctx, A, forms, S_TILES_A, &t, s);

@@ -144,7 +144,8 @@ __global__ __launch_bounds__(kNumThreads) void k_numeric(
     const uint4 *__restrict__ a_ldata_, const uint2 *__restrict__ b_rhead_, const uint4 *__restrict__ b_rdata_, const int32_t *__restrict__ c_tile_row,
     const int32_t *__restrict__ c_tile_col, const uint16_t *__restrict__ c_row_mask,
     const uint32_t *__restrict__ c_row_off, const int64_t *__restrict__ c_row_ptr, int32_t *__restrict__ c_col,
-    float *__restrict__ c_val) {
+    float *__restrict__ c_val, int64_t *__restrict__ scalars_to_clear) {
+    if (scalars_to_clear && blockIdx.x == 0 && threadIdx.x < kScalars) scalars_to_clear[threadIdx.x] = 0;
     static_assert(kTilesPerWave % kGroupTiles == 0 && kTilesPerWave <= 32, "whole groups; offsets fit one wave load");
     // headers of the 64 task-list entries a wave is working on, one 16-byte record per entry; one
     // spare record per wave: the second half-wave may address the entry after the last one
@@ -439,23 +440,23 @@ __global__ __launch_bounds__(kNumThreads) void k_numeric(
 }
 
 int numeric_enqueue(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s *P, tsp_csr *C, hipStream_t s,
-                    bool take_row_ptr) {
+                    bool last_of_call) {
     std::memset(C, 0, sizeof(*C));
     if (!(A->forms & TSP_FORM_LEFT) || !(B->forms & TSP_FORM_RIGHT)) return TSP_ERR_INVALID_ARG;
     if (A->cols != B->rows || P->c_rows != A->rows || P->c_cols != B->cols) return TSP_ERR_SHAPE_MISMATCH;
     if (!P->c_row_ptr) return TSP_ERR_INVALID_ARG;                       // a plan whose row_ptr has been handed over
-    int64_t *row_ptr = take_row_ptr ? P->c_row_ptr : ctx_alloc_n<int64_t>(ctx, (size_t)P->c_rows + 1, s);
+    int64_t *row_ptr = last_of_call ? P->c_row_ptr : ctx_alloc_n<int64_t>(ctx, (size_t)P->c_rows + 1, s);
     int32_t *col = ctx_alloc_n<int32_t>(ctx, (size_t)P->c_nnz, s);
     float *val = ctx_alloc_n<float>(ctx, (size_t)P->c_nnz, s);
     if (!row_ptr || !col || !val) {
-        if (!take_row_ptr) ctx_free(ctx, row_ptr, s);
+        if (!last_of_call) ctx_free(ctx, row_ptr, s);
         ctx_free(ctx, col, s);
         ctx_free(ctx, val, s);
         return TSP_ERR_ALLOC_FAILED;
     }
     phase_begin(ctx, TSP_PHASE_NUMERIC, s);
     hipError_t e = hipSuccess;
-    if (!take_row_ptr)
+    if (!last_of_call)
         e = hipMemcpyAsync(row_ptr, P->c_row_ptr, sizeof(int64_t) * (size_t)(P->c_rows + 1), hipMemcpyDeviceToDevice, s);
     if (e == hipSuccess && P->c_tiles > 0) {
         KernelTimer kt(ctx, TSP_KERNEL_NUMERIC, s);
@@ -484,17 +485,19 @@ int numeric_enqueue(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s
         hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(kNumThreads), 0, s, P->c_tiles, P->c_nnz, z, P->c_rows,
                            (int32_t)P->c_tile_rows, P->c_tile_row_ptr, P->pair_off,
                            P->pair_a, P->pair_b, A->lhead, A->ldata, B->rhead, B->rdata,
-                           P->c_tile_row, P->c_tile_col, P->c_row_mask, P->c_row_off, P->c_row_ptr, col, val);
+                           P->c_tile_row, P->c_tile_col, P->c_row_mask, P->c_row_off, P->c_row_ptr, col, val,
+                           last_of_call && !ctx->compact ? ctx->d_scalars : nullptr);
+        if (last_of_call && !ctx->compact && hipPeekAtLastError() == hipSuccess) ctx->scalars_clean = true;
         e = hipGetLastError();
     }
     phase_end(ctx, TSP_PHASE_NUMERIC, s);
     if (e != hipSuccess) {
-        if (!take_row_ptr) ctx_free(ctx, row_ptr, s);
+        if (!last_of_call) ctx_free(ctx, row_ptr, s);
         ctx_free(ctx, col, s);
         ctx_free(ctx, val, s);
         return hip_fail(ctx, e);
     }
-    if (take_row_ptr) P->c_row_ptr = nullptr;
+    if (last_of_call) P->c_row_ptr = nullptr;
     C->rows = P->c_rows;
     C->cols = P->c_cols;
     C->nnz = P->c_nnz;

@@ -25,13 +25,15 @@ extern "C" int tsp_spgemm(tsp_handle ctx, const tsp_csr *A, const tsp_csr *B, ts
     tsp_plan_s *plan = nullptr;
 
     total_begin(ctx, s);
-    hipLaunchKernelGGL(k_clear_scalars_all, dim3(1), dim3(64), 0, s, ctx->d_scalars);
+    // (the multiplication kernel of the previous call has usually left the scalar block zeroed)
+    if (!ctx->scalars_clean) hipLaunchKernelGGL(k_clear_scalars_all, dim3(1), dim3(64), 0, s, ctx->d_scalars);
+    ctx->scalars_clean = false;
     phase_begin(ctx, TSP_PHASE_CONVERT, s);
     int rc = convert_enqueue(ctx, A, alias ? (TSP_FORM_LEFT | TSP_FORM_RIGHT) : TSP_FORM_LEFT, S_TILES_A, &ta, s);
     if (!rc && !alias) rc = convert_enqueue(ctx, B, TSP_FORM_RIGHT, S_TILES_B, &tb, s);
     phase_end(ctx, TSP_PHASE_CONVERT, s);
     if (!rc) rc = symbolic_run(ctx, ta, alias ? ta : tb, &plan, s);
-    if (!rc) rc = numeric_enqueue(ctx, ta, alias ? ta : tb, plan, C, s, /*take_row_ptr=*/true);   // the plan ends here
+    if (!rc) rc = numeric_enqueue(ctx, ta, alias ? ta : tb, plan, C, s, /*last_of_call=*/true);   // the plan ends here
     if (!rc && ctx->compact) {                    // Algorithm 1, the compaction steps: strictly sparse result
         tsp_csr structural = *C;
         rc = compact_zeros(ctx, &structural, C, s);

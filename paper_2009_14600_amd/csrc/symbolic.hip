@@ -1202,6 +1202,7 @@ extern "C" int tsp_symbolic(tsp_handle ctx, tsp_tiles A, tsp_tiles B, tsp_plan *
     if (!ctx || !A || !B || !out) return TSP_ERR_INVALID_ARG;
     if (A->ntiles < 0 || B->ntiles < 0) return TSP_ERR_INVALID_ARG;   // tiles must come from tsp_convert
     hipLaunchKernelGGL(k_clear_scalars_sym, dim3(1), dim3(64), 0, (hipStream_t)stream, ctx->d_scalars);
+    ctx->scalars_clean = false;
     return symbolic_run(ctx, A, B, out, (hipStream_t)stream);
 }
 
