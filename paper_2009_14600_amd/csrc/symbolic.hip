@@ -342,7 +342,7 @@ __global__ __launch_bounds__(kRowScanThreads) void k_sym_row_scan(
 template <bool kLongRows>
 __global__ __launch_bounds__(kSymThreads) void k_sym_emit(
     TileRefs A, TileRefs B, int lanes_per_a, int words_cap, int window, int wide_threshold,
-    const int32_t *__restrict__ row_jmin,
+    const int32_t *__restrict__ row_jmin, const int32_t *__restrict__ row_words,
     const int32_t *__restrict__ c_tile_row_ptr, const int64_t *__restrict__ row_pair_ptr,
     int32_t *__restrict__ c_tile_row, int32_t *__restrict__ c_tile_col, int64_t *__restrict__ pair_off,
     int32_t *__restrict__ pair_a, int32_t *__restrict__ pair_b) {
@@ -358,22 +358,9 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_emit(
     if (nC <= 0 || nC > wide_threshold) return;      // (wider tile-rows: k_sym_emit_wide)
     const int a0 = A.trp[I], a1 = A.tend[I];
     const int jmin = row_jmin[I];
-    // the span is recomputed from the bitmap extent the first pass used: highest J over the row
-    int jmax = -1;
-    for (int a = a0 + threadIdx.x; a < a1; a += blockDim.x) {
-        const uint32_t K = (uint32_t)A.tcol[a];
-        if (K >= (uint32_t)B.tile_rows) continue;
-        const int b0 = B.trp[K], b1 = B.tend[K];
-        if (b0 < b1) jmax = max(jmax, B.tcol[b1 - 1]);
-    }
-    __shared__ int s_jmax;
-    if (threadIdx.x == 0) s_jmax = -1;
-    __syncthreads();
-    if (jmax >= 0) atomicMax(&s_jmax, jmax);
-    __syncthreads();
-    jmax = s_jmax;
-    const int64_t span = (int64_t)jmax - jmin + 1;
-    const int words = (int)((span + 31) >> 5);       // <= words_cap: rows over the limit have nC = 0
+    // the bitmap extent the first pass found for this tile-row (rows over the limit have nC = 0)
+    const int words = min(row_words[I], words_cap);
+    const int64_t span = (int64_t)words * 32;
     for (int w = threadIdx.x; w < words; w += blockDim.x) bm[w] = 0;
     __syncthreads();
     uint32_t dummy = 0;
@@ -489,7 +476,7 @@ constexpr int kListTiles = 512;        // and at most this many C tiles per tile
 template <bool kLongRows, bool kFuseMasks>
 __global__ __launch_bounds__(kSymThreads) void k_sym_emit_listed(
     TileRefs A, TileRefs B, int lanes_per_a, int words_cap, int window, int list_cap,
-    const int32_t *__restrict__ row_jmin,
+    const int32_t *__restrict__ row_jmin, const int32_t *__restrict__ row_words,
     const int32_t *__restrict__ c_tile_row_ptr, const int64_t *__restrict__ row_pair_ptr,
     int32_t *__restrict__ c_tile_row, int32_t *__restrict__ c_tile_col, int64_t *__restrict__ pair_off,
     int32_t *__restrict__ pair_a, int32_t *__restrict__ pair_b, const uint16_t *__restrict__ a_row_mask,
@@ -497,7 +484,7 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_emit_listed(
     int32_t *__restrict__ row_nnz, int64_t c_rows, int64_t *d_scalars, uint32_t *__restrict__ tile_row_entries) {
     extern __shared__ uint32_t lds_dyn[];
     __shared__ uint32_t red[32];
-    __shared__ int s_jmax, s_n;
+    __shared__ int s_n;
     uint32_t *bm = lds_dyn;
     uint32_t *wpre = bm + words_cap;
     uint32_t *contrib = wpre + words_cap;
@@ -516,23 +503,10 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_emit_listed(
     const int a0 = A.trp[I], a1 = A.tend[I];
     const int jmin = row_jmin[I];
     const int64_t row_base = row_pair_ptr[I];
-    int jmax = -1;
-    for (int a = a0 + threadIdx.x; a < a1; a += nthreads) {
-        const uint32_t K = (uint32_t)A.tcol[a];
-        if (K >= (uint32_t)B.tile_rows) continue;
-        const int b0 = B.trp[K], b1 = B.tend[K];
-        if (b0 < b1) jmax = max(jmax, B.tcol[b1 - 1]);
-    }
-    if (threadIdx.x == 0) {
-        s_jmax = -1;
-        s_n = 0;
-    }
-    __syncthreads();
-    if (jmax >= 0) atomicMax(&s_jmax, jmax);
-    __syncthreads();
-    jmax = s_jmax;
-    const int64_t span = (int64_t)jmax - jmin + 1;
-    const int words = (int)((span + 31) >> 5);
+    if (threadIdx.x == 0) s_n = 0;
+    // the bitmap extent the first pass found for this tile-row
+    const int words = min(row_words[I], words_cap);
+    const int64_t span = (int64_t)words * 32;
     for (int w = threadIdx.x; w < words; w += nthreads) bm[w] = 0;
     __syncthreads();
     uint32_t dummy = 0;
@@ -674,7 +648,7 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_emit_listed(
 template <bool kLongRows>
 __global__ __launch_bounds__(kSymThreads) void k_sym_emit_wide(
     TileRefs A, TileRefs B, int lanes_per_a, int words_cap, int wide_threshold,
-    const int32_t *__restrict__ row_jmin,
+    const int32_t *__restrict__ row_jmin, const int32_t *__restrict__ row_words,
     const int32_t *__restrict__ c_tile_row_ptr, const int64_t *__restrict__ row_pair_ptr,
     int32_t *__restrict__ c_tile_row, int32_t *__restrict__ c_tile_col, int64_t *__restrict__ pair_off,
     int32_t *__restrict__ pair_a, int32_t *__restrict__ pair_b, uint32_t *wide_contrib, uint32_t *wide_cnt) {
@@ -689,22 +663,9 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_emit_wide(
     if (nC <= wide_threshold) return;               // k_sym_emit's tile-row
     const int a0 = A.trp[I], a1 = A.tend[I];
     const int jmin = row_jmin[I];
-    // the span is recomputed from the bitmap extent the first pass used: highest J over the row
-    int jmax = -1;
-    for (int a = a0 + threadIdx.x; a < a1; a += nthreads) {
-        const uint32_t K = (uint32_t)A.tcol[a];
-        if (K >= (uint32_t)B.tile_rows) continue;
-        const int b0 = B.trp[K], b1 = B.tend[K];
-        if (b0 < b1) jmax = max(jmax, B.tcol[b1 - 1]);
-    }
-    __shared__ int s_jmax;
-    if (threadIdx.x == 0) s_jmax = -1;
-    __syncthreads();
-    if (jmax >= 0) atomicMax(&s_jmax, jmax);
-    __syncthreads();
-    jmax = s_jmax;
-    const int64_t span = (int64_t)jmax - jmin + 1;
-    const int words = (int)((span + 31) >> 5);       // <= words_cap: rows over the limit have nC = 0
+    // the bitmap extent the first pass found for this tile-row (rows over the limit have nC = 0)
+    const int words = min(row_words[I], words_cap);
+    const int64_t span = (int64_t)words * 32;
     for (int w = threadIdx.x; w < words; w += nthreads) bm[w] = 0;
     __syncthreads();
     uint32_t dummy = 0;
@@ -1126,18 +1087,19 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
                                       : (long_rows ? k_sym_emit_listed<true, false> : k_sym_emit_listed<false, false>);
             hipLaunchKernelGGL(kernel, dim3((unsigned)ntr), dim3(threads),
                                lds + (size_t)(3 * list_cap + (fused_masks ? 8 * window : 0)) * sizeof(int), s, ra, rb,
-                               lanes, words_cap, window, list_cap, row_jmin, P->c_tile_row_ptr,
+                               lanes, words_cap, window, list_cap, row_jmin, row_words, P->c_tile_row_ptr,
                                row_pair_ptr, P->c_tile_row, P->c_tile_col, P->pair_off, P->pair_a, P->pair_b,
                                A->row_mask, B->row_mask, P->c_row_mask, P->c_row_off, row_nnz, P->c_rows,
                                ctx->d_scalars, tile_row_entries);
         } else
             hipLaunchKernelGGL(long_rows ? k_sym_emit<true> : k_sym_emit<false>, dim3((unsigned)ntr), dim3(threads),
-                               lds, s, ra, rb, lanes, words_cap, window, wide_threshold, row_jmin, P->c_tile_row_ptr,
+                               lds, s, ra, rb, lanes, words_cap, window, wide_threshold, row_jmin, row_words,
+                               P->c_tile_row_ptr,
                                row_pair_ptr, P->c_tile_row, P->c_tile_col, P->pair_off, P->pair_a, P->pair_b);
         if (wide_words)
             hipLaunchKernelGGL(long_rows ? k_sym_emit_wide<true> : k_sym_emit_wide<false>, dim3((unsigned)ntr),
                                dim3(kSymThreads), (size_t)(2 * words_cap) * sizeof(uint32_t), s, ra, rb, lanes, words_cap,
-                               wide_threshold, row_jmin, P->c_tile_row_ptr, row_pair_ptr, P->c_tile_row, P->c_tile_col,
+                               wide_threshold, row_jmin, row_words, P->c_tile_row_ptr, row_pair_ptr, P->c_tile_row, P->c_tile_col,
                                P->pair_off, P->pair_a, P->pair_b, wide_words, wide_cnt);
         SYM_CHECK(hipGetLastError());
     } else {
