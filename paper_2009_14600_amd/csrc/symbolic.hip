@@ -469,6 +469,7 @@ __device__ __forceinline__ uint32_t boolean_row_product(uint32_t am, const uint4
 // three times, and the enumeration, a chain of dependent gathers, is what it spends its time on).
 // It also runs the counting pass for its C tiles.
 // Dynamic LDS: 2*words_cap + 10*window + 3*list_cap words (list_cap: most entries any tile-row has).
+constexpr int kPairsPerTrip = 2;       // pairs a lane group of the fused counting pass takes per trip
 constexpr int kListCap = 1024;
 constexpr int kListTiles = 512;        // and at most this many C tiles per tile-row (their bitmaps sit in LDS)
 // kFuseMasks: also run the counting pass (worth it when there are enough tile-rows to fill the chip;
@@ -587,16 +588,17 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_emit_listed(
     if constexpr (!kFuseMasks) return;
     // Counting pass (Section 4.2) for the tile-row's C tiles, from the same list: 16 lanes per pair, lane
     // r forms row r of the boolean product of the two bitmaps and ORs it into the C tile's bitmap in LDS.
-    // Four pairs per trip, their bitmaps requested together.
+    // kPairsPerTrip pairs per trip, their bitmaps requested together (the pass is bound by its vector ALU
+    // work, not by the gathers: four or two per trip take the same time, eight cost registers).
     for (int w = threadIdx.x; w < nC * 8; w += nthreads) cmask[w] = 0;
     __syncthreads();
     {
         const int g = threadIdx.x >> 4, r = threadIdx.x & 15, groups = nthreads >> 4;
-        for (int k0 = g * 4; k0 < n; k0 += groups * 4) {
-            uint32_t am[4];
-            uint4 x[4], y[4];
+        for (int k0 = g * kPairsPerTrip; k0 < n; k0 += groups * kPairsPerTrip) {
+            uint32_t am[kPairsPerTrip];
+            uint4 x[kPairsPerTrip], y[kPairsPerTrip];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < kPairsPerTrip; ++u) {
                 am[u] = 0;
                 x[u] = y[u] = make_uint4(0, 0, 0, 0);
                 if (k0 + u < n) {
@@ -607,7 +609,7 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_emit_listed(
                 }
             }
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < kPairsPerTrip; ++u) {
                 if (k0 + u < n) {
                     const uint32_t m = boolean_row_product(am[u], x[u], y[u]);
                     const uint32_t m16 = (m | (m >> 16)) & 0xFFFFu;
@@ -1076,7 +1078,8 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
         }
         KernelTimer kt(ctx, TSP_KERNEL_SYM_EMIT, s);
         const int64_t per_row = P->candidates / ntr;
-        const int threads = per_row <= 256 ? 64 : per_row <= 4096 ? 128 : kSymThreads;
+        // (the fused counting pass of the list kernel wants more lanes than the enumeration does)
+        const int threads = per_row <= 256 ? 64 : per_row <= 512 ? 128 : kSymThreads;
         uint32_t *wide_cnt = wide_words ? wide_words + P->c_tiles : nullptr;
         const int wide_threshold = wide_words ? window : INT_MAX;   // C tiles per tile-row above which the wide launch takes it
         listed = h[S_MAX_ROW_PAIRS] <= kListCap && h[S_MAX_ROW_C_TILES] <= kListTiles;
