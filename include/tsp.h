@@ -91,12 +91,14 @@ enum {
     TSP_OPT_WIDE_INDEX = 3,    /* 1: always use the kernels that address arrays of 4 GiB and more   */
                                /*    through 64-bit pointers; 0 (default): chosen from the sizes    */
     TSP_OPT_NUMERIC_RUN = 4,   /* output tiles one wave of the multiplication kernel walks: 4 or 8; */
-                               /*    0 (default): 4                                                 */
+                               /*    0 (default): 4, or a whole tile-row of C where every tile-row  */
+                               /*    has at most 16 tiles, 64 task-list entries and 512 entries     */
     TSP_OPT_MATRIX_CORES = 5,  /* 1 (default): block products on the MFMA units (Section 4.3);      */
                                /*    0: on the vector ALUs, one fp32 FMA per inner index and output */
                                /*    element (the paper's comparison build, Section 5, Algorithm 2) */
-    TSP_OPT_COMPACT_ZEROS = 6  /* 1: tsp_spgemm finishes with tsp_compact_zeros (Algorithm 1 lines  */
-                               /*    19-20); 0 (default): C keeps every structural position         */
+    TSP_OPT_COMPACT_ZEROS = 6  /* 1: tsp_spgemm finishes with tsp_compact_zeros (the compaction     */
+                               /*    steps that end Algorithm 1); 0 (default): C keeps every        */
+                               /*    structural position                                            */
 };
 
 /* Phases reported in tsp_stats.phase_us, in pipeline order. */

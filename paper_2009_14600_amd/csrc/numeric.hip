@@ -30,11 +30,15 @@
 // accumulators of the group are transposed across the lanes so that lane (t, j) holds column j of
 // all 16 rows of tile t; row r is then written by one store instruction for all four tiles, which
 // are neighbours in CSR row 16I+r: the lane writes column 16J+j and its value at
-// start(tile-row) + position(tile, r) + popcount(mask_r below j).
+// start(tile-row) + position(tile, r) + popcount(mask_r below j).  Masks and positions are fetched
+// one word per lane and handed round the 16 lanes of a tile when a row is written.
+// Where every tile-row of C is short and sparse a wave takes a whole tile-row instead and assembles
+// its output in LDS (see kWholeRows below).
 //
-// Measured on gfx950, the kernel is bound by the vector-memory address path of the CU (operand
-// loads of 1 KB per instruction, stores that cost by the cache lines they touch, header gathers that
-// cost by the lane): shortening waits or instruction counts alone does not change its duration.
+// Measured on gfx950: on products with tens of entries per output tile and more the kernel is bound
+// by the vector-memory path of the CU (operand loads of 1 KB per instruction, stores that cost by the
+// cache lines they touch, header gathers that cost by the lane), and shortening waits or instruction
+// counts alone does not change its duration; on very sparse tiles it is bound by instruction issue.
 #include "common.hpp"
 
 #include <new>
