@@ -59,7 +59,7 @@ constexpr int kGroupTiles = 4;         // output tiles computed together and wri
 constexpr int kXcds = 8;
 constexpr int kBlockEntries = 64;      // task-list entries staged at a time: one per lane
 constexpr int kRowTiles = 16;          // whole-tile-row kernel: most output tiles a tile-row may have
-constexpr int kRowEntries = 512;       // ... and most structural entries (its output is assembled in LDS)
+constexpr int kRowEntries = 384;       // ... and most structural entries (its output is assembled in LDS)
 
 struct Header {          // tile headers of one task-list entry, as the lanes of the wave read them from LDS
     uint32_t lm, lo, rm, ro;   // group masks and BYTE offsets of the first group: left form of A, right form of B
@@ -244,17 +244,24 @@ __global__ __launch_bounds__(kNumThreads) void k_numeric(
     // per MFMA; the loads of up to four MFMAs are requested together
     auto multiply = [&](int o, int count, float4v &acc) {
         if constexpr (kMatrixCores) {
-            for (int it = 0; it < count; it += 8) {
+            // entries in flight: short sparse tile-rows have segments of one to four entries, and the
+            // registers of the deeper batch would cost their kernel a wave per SIMD
+            constexpr int kDepth = kWholeRows ? 4 : 8;
+            for (int it = 0; it < count; it += kDepth) {
                 Group a0, b0, a1, b1, a2, b2, a3, b3;
                 const int left = count - it;                                // > 0, uniform
                 load_operands(o + it, left > 1, a0, b0);
                 if (left > 2) load_operands(o + it + 2, left > 3, a1, b1);
-                if (left > 4) load_operands(o + it + 4, left > 5, a2, b2);
-                if (left > 6) load_operands(o + it + 6, left > 7, a3, b3);
+                if constexpr (kDepth > 4) {
+                    if (left > 4) load_operands(o + it + 4, left > 5, a2, b2);
+                    if (left > 6) load_operands(o + it + 6, left > 7, a3, b3);
+                }
                 acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a0.h, b0.h, acc, 0, 0, 0);
                 if (left > 2) acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1.h, b1.h, acc, 0, 0, 0);
-                if (left > 4) acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a2.h, b2.h, acc, 0, 0, 0);
-                if (left > 6) acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a3.h, b3.h, acc, 0, 0, 0);
+                if constexpr (kDepth > 4) {
+                    if (left > 4) acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a2.h, b2.h, acc, 0, 0, 0);
+                    if (left > 6) acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a3.h, b3.h, acc, 0, 0, 0);
+                }
             }
         } else {
             // Two entries per step, loaded exactly as for the MFMA: lane 32e + 16h + x holds, of entry
@@ -315,7 +322,7 @@ __global__ __launch_bounds__(kNumThreads) void k_numeric(
                 em.col = 0;
 #pragma unroll
                 for (int t = 0; t < kGroupTiles; ++t)
-                    col_of[t] = c_tile_col[run_begin + min(g * kGroupTiles + t, run_tiles - 1)] * T + j;
+                    col_of[t] = __builtin_amdgcn_readfirstlane(c_tile_col[run_begin + min(g * kGroupTiles + t, run_tiles - 1)]) * T;
             } else if (g == 0) {
                 em.base = base_first;
                 em.col = J_first * T + j;
@@ -372,7 +379,7 @@ __global__ __launch_bounds__(kNumThreads) void k_numeric(
                         const uint32_t first = row_broadcast<4 * t + v>(em.first);
                         if (pair & my_bit[v & 1]) {
                             const uint32_t rank = (uint32_t)__popc(pair & my_below[v & 1]) + first;
-                            my_entries[0][rank] = (uint32_t)col_of[t];
+                            my_entries[0][rank] = (uint32_t)(col_of[t] + j);
                             my_entries[1][rank] = __float_as_uint(acc[t][v]);
                         }
                     },

@@ -461,7 +461,7 @@ def _variant_handle(tsp, **options):
 
 def _mesh_cases():
     """Products whose tile-rows of C are short and sparse (at most 16 output tiles, 64 task-list entries
-    and 512 entries per tile-row): the multiplication kernel takes a whole tile-row per wave and
+    and 384 entries per tile-row): the multiplication kernel takes a whole tile-row per wave and
     assembles its output in LDS.  Grid edges that are no multiple of 16 give ragged last tile-rows."""
     yield "laplacian 37x37", inputs.laplacian_2d(37), None
     yield "laplacian 64x64", inputs.laplacian_2d(64), None
@@ -470,8 +470,8 @@ def _mesh_cases():
         A = inputs.random_sparse(70, 16, 0.07, 91, empty_row_fraction=0.2)
         B = inputs.random_sparse(16, n_cols, 0.1, 92)
         yield f"single inner tile, {n_cols} columns", A, B
-    # entries per tile-row either side of 512
-    for density in (0.10, 0.16):
+    # entries per tile-row either side of 384
+    for density in (0.07, 0.12):
         A = inputs.random_sparse(64, 16, 0.0625, 93)
         B = inputs.random_sparse(16, 256, density, 94, values="smallint")
         yield f"single inner tile, density {density}", A, B
