@@ -43,3 +43,14 @@ def test_binding_refuses_to_run_without_gpu():
         pytest.skip("a GPU is present")
     with pytest.raises(RuntimeError):
         tsp.Handle()
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The path has no multi-GPU part: bench.py says so instead of running."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    res = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"],
+                         capture_output=True, text=True, timeout=120)
+    assert res.returncode == 2
+    assert "one GPU" in res.stderr
