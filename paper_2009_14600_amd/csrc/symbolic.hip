@@ -28,6 +28,7 @@ namespace tsp {
 
 constexpr int kSymThreads = 256;
 constexpr int kMaxWords = 4096;        // LDS bitmap words per tile-row: span of 131072 tile columns
+constexpr int kDirectWords = 1024;     // counting kernel: widest tile grid of B whose bitmap is indexed by the column itself
 constexpr int kWindow = 2048;          // C tiles of one tile-row handled per LDS window
 constexpr int kSurvivorUnroll = 4;     // B tiles one lane requests per trip of the candidate loop
 
@@ -142,6 +143,7 @@ __device__ __forceinline__ void for_each_survivor(const TileRefs &A, const TileR
 // candidates.  Dynamic LDS: max_words words.
 template <bool kLongRows>
 __global__ __launch_bounds__(kSymThreads) void k_sym_count(TileRefs A, TileRefs B, int lanes_per_a, int max_words,
+                                                           int direct_words,
                                                            int32_t *__restrict__ row_jmin,
                                                            int32_t *__restrict__ row_c_tiles,
                                                            int32_t *__restrict__ row_pairs,
@@ -160,6 +162,46 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_count(TileRefs A, TileRefs 
     }
     __syncthreads();
     int jmin = INT_MAX, jmax = -1;
+    uint32_t cand = 0, surv = 0;
+    if (direct_words > 0) {
+        // B's whole tile grid fits the bitmap: mark tile columns as they are, and read the extent of the
+        // tile-row off the bitmap afterwards (no pass over the tile-rows of B for it: three dependent
+        // gathers less)
+        for (int w = threadIdx.x; w < direct_words; w += blockDim.x) bm[w] = 0;
+        __syncthreads();
+        for_each_survivor<kLongRows>(A, B, a0, a1, lanes_per_a, &cand, [&](int, int, int J) {
+            if ((uint32_t)J < (uint32_t)direct_words * 32u) {
+                atomicOr(&bm[J >> 5], 1u << (J & 31));
+                ++surv;
+            }
+        });
+        __syncthreads();
+        uint32_t tiles = 0;
+        for (int w = threadIdx.x; w < direct_words; w += blockDim.x) {
+            const uint32_t bits = bm[w];
+            if (bits) {
+                tiles += __popc(bits);
+                jmin = min(jmin, w * 32);              // word-aligned: the later passes only need J - jmin >= 0
+                jmax = max(jmax, w * 32 + 31);
+            }
+        }
+        if (jmax >= 0) {
+            atomicMin(&s_jmin, jmin);
+            atomicMax(&s_jmax, jmax);
+        }
+        tiles = block_sum_u32(tiles, red);             // (its barriers also order the two atomics above)
+        surv = block_sum_u32(surv, red);
+        cand = block_sum_u32(cand, red);
+        if (threadIdx.x == 0) {
+            const bool any = s_jmax >= 0;
+            row_jmin[I] = any ? s_jmin : 0;
+            row_c_tiles[I] = (int32_t)tiles;
+            row_pairs[I] = (int32_t)surv;
+            row_words[I] = any ? (s_jmax - s_jmin + 1) >> 5 : 0;
+            row_cand[I] = (int32_t)cand;
+        }
+        return;
+    }
     for (int a = a0 + threadIdx.x; a < a1; a += blockDim.x) {
         const uint32_t K = (uint32_t)A.tcol[a];
         if (K >= (uint32_t)B.tile_rows) continue;
@@ -201,7 +243,6 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_count(TileRefs A, TileRefs 
     }
     for (int w = threadIdx.x; w < words; w += blockDim.x) bm[w] = 0;
     __syncthreads();
-    uint32_t cand = 0, surv = 0;
     for_each_survivor<kLongRows>(A, B, a0, a1, lanes_per_a, &cand, [&](int, int, int J) {
         const uint32_t j = (uint32_t)(J - jmin);
         if (j < (uint32_t)span) {
@@ -1012,9 +1053,14 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
         const int max_words = (int)std::min<int64_t>(kMaxWords, (B->tile_cols + 31) / 32 + 1);
         const int64_t per_row = A->nnz / ntr;
         const int threads = per_row <= 256 ? 64 : per_row <= 4096 ? 128 : kSymThreads;
+        // where B's tile grid is narrow the bitmap simply covers all of it (worth it while the two sweeps
+        // over the whole bitmap cost a block less than the three dependent gathers they replace:
+        // measured, up to about six words per thread)
+        const int64_t grid_words = (B->tile_cols + 31) / 32;
+        const int direct_words = grid_words <= std::min<int64_t>(kDirectWords, 6 * threads) ? (int)grid_words : 0;
         hipLaunchKernelGGL(long_rows ? k_sym_count<true> : k_sym_count<false>, dim3((unsigned)ntr), dim3(threads),
                            max_words * sizeof(uint32_t), s, ra, rb,
-                           lanes, max_words, row_jmin, row_c_tiles, row_pairs, row_words, row_cand, ctx->d_scalars);
+                           lanes, max_words, direct_words, row_jmin, row_c_tiles, row_pairs, row_words, row_cand, ctx->d_scalars);
         SYM_CHECK(hipGetLastError());
     }
     {
