@@ -375,10 +375,11 @@ template <int G, int kConvCache, typename RP, typename VT>
 __global__ __launch_bounds__(conv_block_threads<G>()) void k_convert_rows(const ConvArgs<RP, VT> a) {
     convert_rows<G, kConvCache, RP, VT>(a);
 }
-// The same for short tile-rows (few entries per thread in registers): asking for six waves per SIMD
-// makes the compiler fit 80 registers without spilling, and this kernel lives on waves in flight.
+// The same for short tile-rows (few entries per thread in registers): asking for seven waves per SIMD
+// (as many as the LDS of seven blocks per CU allows) makes the compiler fit 72 registers with three
+// spilled words, and this kernel lives on waves in flight.
 template <int G, int kConvCache, typename RP, typename VT>
-__global__ __launch_bounds__(conv_block_threads<G>()) __attribute__((amdgpu_waves_per_eu(6, 8))) void k_convert_rows_light(
+__global__ __launch_bounds__(conv_block_threads<G>()) __attribute__((amdgpu_waves_per_eu(7, 8))) void k_convert_rows_light(
     const ConvArgs<RP, VT> a) {
     convert_rows<G, kConvCache, RP, VT>(a);
 }
