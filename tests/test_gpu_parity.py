@@ -496,3 +496,27 @@ def test_multiplication_kernel_variants(tsp, oracle, options):
             run_and_check(tsp, h, oracle, A)
     finally:
         h.close()
+
+
+# ------------------------------------------------------------------ a seeded sweep of shapes and densities
+def _sweep_cases():
+    """Forty products drawn from one seeded generator: sizes from one tile to a few hundred rows, ragged
+    edges, densities from almost empty to almost full, empty rows, square and rectangular, the value
+    kinds of inputs.random_sparse, and the input types the boundary accepts."""
+    rng = np.random.default_rng(20260914)
+    for case in range(40):
+        M, K, N = (int(x) for x in rng.integers(1, 330, size=3))
+        density = float(10.0 ** rng.uniform(-2.5, -0.05))
+        kind = ("uniform", "smallint", "ones", "tiny")[int(rng.integers(0, 4))]
+        empty = float(rng.choice([0.0, 0.1, 0.5]))
+        upload = {"value_dtype": ("f16", "f32")[int(rng.integers(0, 2))],
+                  "row_ptr_dtype": ("i32", "i64")[int(rng.integers(0, 2))]}
+        yield case, M, K, N, density, kind, empty, upload
+
+
+def test_seeded_sweep_of_small_products(tsp, handle, oracle):
+    for case, M, K, N, density, kind, empty, upload in _sweep_cases():
+        A = inputs.random_sparse(M, K, density, 7000 + case, empty_row_fraction=empty, values=kind)
+        B = inputs.random_sparse(K, N, density, 8000 + case, empty_row_fraction=empty, values=kind)
+        print(f"sweep {case}: {M}x{K}x{N} d={density:.4f} {kind} empty={empty} {upload}", flush=True)
+        run_and_check(tsp, handle, oracle, A, B, **upload)
