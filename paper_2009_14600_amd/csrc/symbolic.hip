@@ -75,32 +75,6 @@ __device__ __forceinline__ uint32_t block_exclusive_scan_lds(uint32_t *arr, int 
     return carry;
 }
 
-// The same scan on words that may live in global memory (written by this block only; the reads go
-// past the L1 cache, the barriers order them after the writes).
-__device__ __forceinline__ uint32_t block_exclusive_scan_words(uint32_t *arr, int n, uint32_t *lds /*[>=17]*/) {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
-    uint32_t carry = 0;
-    __syncthreads();
-    for (int base = 0; base < n; base += blockDim.x) {
-        const int i = base + threadIdx.x;
-        const uint32_t x = i < n ? __hip_atomic_load(&arr[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0;
-        const uint32_t v = wave_inclusive_scan(x);
-        __syncthreads();
-        if (lane == 63) lds[wave] = v;
-        __syncthreads();
-        uint32_t before = 0, all = 0;
-        for (int w = 0; w < nw; ++w) {
-            uint32_t y = lds[w];
-            if (w < wave) before += y;
-            all += y;
-        }
-        if (i < n) arr[i] = carry + before + v - x;
-        carry += all;
-    }
-    __syncthreads();
-    return carry;
-}
-
 // Visits every surviving candidate pair of tile-row I whose A tile index lies in [a_begin,a_end).
 // `lanes_per_a` lanes share one A tile and stride over the tiles of B's tile-row K.
 // f(a, b, J) is called once per survivor; *candidates counts all candidates visited by this thread.
@@ -135,6 +109,69 @@ __device__ __forceinline__ void for_each_survivor(const TileRefs &A, const TileR
         for (; b < b1; b += lanes_per_a) {
             ++*candidates;
             if (col_occ & fold16(B.lmask[b])) f(a, b, B.tcol[b]);
+        }
+    }
+}
+
+// The same walk, restricted to the B tiles whose tile column is below j_end, for tile-rows of C that are
+// worked off in several windows of tile columns: the tiles of a tile-row of B are sorted by column, so a
+// window's candidates are a stretch of it.  Where a window ended in B's tile-row K for A tile `a` is kept
+// in cursor[a] (read when from_cursor, written when keep_cursor; one word per tile of A).
+template <bool kLongRows, class F>
+__device__ __forceinline__ void for_each_survivor_below(const TileRefs &A, const TileRefs &B, int a_begin, int a_end,
+                                                        int lanes_per_a, int j_end, int32_t *cursor, bool from_cursor,
+                                                        bool keep_cursor, F f) {
+    const int sub = threadIdx.x / lanes_per_a, l = threadIdx.x % lanes_per_a;
+    const int nsub = blockDim.x / lanes_per_a;
+    // all lanes of a group of lanes_per_a lanes run the same trip count of the outer loop (the reduction
+    // at its end needs them all)
+    for (int a0 = a_begin; a0 < a_end; a0 += nsub) {
+        const int a = a0 + sub;
+        int stop = INT_MAX;                                   // first tile of this lane's stride at or past j_end
+        if (a < a_end) {
+            const uint32_t K = (uint32_t)A.tcol[a];
+            if (K < (uint32_t)B.tile_rows) {
+                const uint32_t col_occ = fold16(A.rmask[a]);
+                const int b1 = B.tend[K];
+                const int b0 = from_cursor ? __hip_atomic_load(&cursor[a], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                                           : B.trp[K];
+                int b = b0 + l;
+                stop = b1;
+                bool open = true;
+                if constexpr (kLongRows)
+                    for (; open && b + (kSurvivorUnroll - 1) * lanes_per_a < b1; b += kSurvivorUnroll * lanes_per_a) {
+                        uint32_t occ[kSurvivorUnroll];
+                        int col[kSurvivorUnroll];
+#pragma unroll
+                        for (int u = 0; u < kSurvivorUnroll; ++u) {
+                            occ[u] = B.lmask[b + u * lanes_per_a];
+                            col[u] = B.tcol[b + u * lanes_per_a];
+                        }
+#pragma unroll
+                        for (int u = 0; u < kSurvivorUnroll; ++u) {
+                            if (open && col[u] >= j_end) {
+                                open = false;
+                                stop = b + u * lanes_per_a;
+                            }
+                            if (open && (col_occ & fold16(occ[u]))) f(a, b + u * lanes_per_a, col[u]);
+                        }
+                    }
+                for (; open && b < b1; b += lanes_per_a) {
+                    const int col = B.tcol[b];
+                    if (col >= j_end) {
+                        open = false;
+                        stop = b;
+                    } else if (col_occ & fold16(B.lmask[b])) {
+                        f(a, b, col);
+                    }
+                }
+                stop = min(stop, b1);
+            }
+        }
+        if (keep_cursor) {                                    // uniform
+            for (int d = lanes_per_a >> 1; d >= 1; d >>= 1) stop = min(stop, __shfl_xor(stop, d, 64));
+            if (l == 0 && a < a_end && stop != INT_MAX)
+                __hip_atomic_store(&cursor[a], stop, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
 }
@@ -378,15 +415,16 @@ __global__ __launch_bounds__(kRowScanThreads) void k_sym_row_scan(
 }
 
 // Pass 2 per tile-row: C tile coordinates, task-list offsets, task list.
-// Dynamic LDS: 2*words_cap + 2*window words.  Tile-rows with more than wide_threshold C tiles are left
-// to k_sym_emit_wide.
+// Dynamic LDS: 2*words_cap + 2*window words.  Tile-rows with more C tiles than the window holds take
+// several windows; `cursor` (one word per tile of A, nullptr when no tile-row needs it) carries their
+// places in B's tile-rows from window to window.
 template <bool kLongRows>
 __global__ __launch_bounds__(kSymThreads) void k_sym_emit(
-    TileRefs A, TileRefs B, int lanes_per_a, int words_cap, int window, int wide_threshold,
+    TileRefs A, TileRefs B, int lanes_per_a, int words_cap, int window,
     const int32_t *__restrict__ row_jmin, const int32_t *__restrict__ row_words,
     const int32_t *__restrict__ c_tile_row_ptr, const int64_t *__restrict__ row_pair_ptr,
     int32_t *__restrict__ c_tile_row, int32_t *__restrict__ c_tile_col, int64_t *__restrict__ pair_off,
-    int32_t *__restrict__ pair_a, int32_t *__restrict__ pair_b) {
+    int32_t *__restrict__ pair_a, int32_t *__restrict__ pair_b, int32_t *cursor) {
     extern __shared__ uint32_t lds_dyn[];
     __shared__ uint32_t red[32];
     uint32_t *bm = lds_dyn;
@@ -396,7 +434,7 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_emit(
     const int I = blockIdx.x;
     const int c0 = c_tile_row_ptr[I], nC = c_tile_row_ptr[I + 1] - c0;
     if (I == (int)gridDim.x - 1 && threadIdx.x == 0) pair_off[c_tile_row_ptr[gridDim.x]] = row_pair_ptr[gridDim.x];
-    if (nC <= 0 || nC > wide_threshold) return;      // (wider tile-rows: k_sym_emit_wide)
+    if (nC <= 0 || (nC > window && !cursor)) return;      // (the host provides the cursors whenever a tile-row needs them)
     const int a0 = A.trp[I], a1 = A.tend[I];
     const int jmin = row_jmin[I];
     // the bitmap extent the first pass found for this tile-row (rows over the limit have nC = 0)
@@ -427,9 +465,45 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_emit(
     }
     const int64_t row_base = row_pair_ptr[I];
     const bool one_chunk = (a1 - a0) <= 32;
+    // A tile-row with more C tiles than the LDS window holds is worked off window by window, and every
+    // window only walks its own stretch of B's tile-rows (for_each_survivor_below): the stretches are
+    // shorter than the tile-rows, so fewer lanes share an A tile and more A tiles are in flight.
+    const bool multi = nC > window;
+    int lanes_w = lanes_per_a;
+    if (multi) {
+        int windows = (nC + window - 1) / window, f = 1;
+        while (f < windows) f <<= 1;
+        lanes_w = max(4, lanes_per_a / f);
+    }
+    __shared__ int s_j_end;
     uint32_t win_base = 0;
     for (int win0 = 0; win0 < nC; win0 += window) {
         const int nw = min(window, nC - win0);
+        int j_end = INT_MAX;                       // tile column of the first C tile after the window
+        const bool more = win0 + nw < nC;
+        if (multi) {
+            if (more) {
+                const int k = win0 + nw;
+                for (int w = threadIdx.x; w < words; w += blockDim.x) {
+                    const uint32_t bits = bm[w];
+                    const int before = (int)wpre[w];
+                    if (before <= k && k < before + __popc(bits)) {       // the k-th C tile is bit (k - before) of this word
+                        uint32_t x = bits;
+                        for (int i = before; i < k; ++i) x &= x - 1;
+                        s_j_end = jmin + w * 32 + (__ffs(x) - 1);
+                    }
+                }
+            }
+            __syncthreads();
+            if (more) j_end = s_j_end;
+        }
+        // every surviving pair of A tiles [ch, ch_end) whose C tile lies in this window
+        auto walk = [&](int ch, int ch_end, bool keep, auto f) {
+            if (multi)
+                for_each_survivor_below<kLongRows>(A, B, ch, ch_end, lanes_w, j_end, cursor, win0 > 0, keep && more, f);
+            else
+                for_each_survivor<kLongRows>(A, B, ch, ch_end, lanes_per_a, &dummy, f);
+        };
         auto rank_in_window = [&](int J) -> int {
             const uint32_t j = (uint32_t)(J - jmin);
             if (j >= (uint32_t)span) return -1;
@@ -442,7 +516,7 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_emit(
         for (int ch = a0; ch < a1; ch += 32) {
             for (int c = threadIdx.x; c < nw; c += blockDim.x) contrib[c] = 0;
             __syncthreads();
-            for_each_survivor<kLongRows>(A, B, ch, min(ch + 32, a1), lanes_per_a, &dummy, [&](int a, int, int J) {
+            walk(ch, min(ch + 32, a1), false, [&](int a, int, int J) {
                 const int c = rank_in_window(J);
                 if (c >= 0) atomicOr(&contrib[c], 1u << (a - ch));
             });
@@ -458,13 +532,13 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_emit(
             if (!one_chunk) {
                 for (int c = threadIdx.x; c < nw; c += blockDim.x) contrib[c] = 0;
                 __syncthreads();
-                for_each_survivor<kLongRows>(A, B, ch, min(ch + 32, a1), lanes_per_a, &dummy, [&](int a, int, int J) {
+                walk(ch, min(ch + 32, a1), false, [&](int a, int, int J) {
                     const int c = rank_in_window(J);
                     if (c >= 0) atomicOr(&contrib[c], 1u << (a - ch));
                 });
                 __syncthreads();
             }
-            for_each_survivor<kLongRows>(A, B, ch, min(ch + 32, a1), lanes_per_a, &dummy, [&](int a, int b, int J) {
+            walk(ch, min(ch + 32, a1), true, [&](int a, int b, int J) {
                 const int c = rank_in_window(J);
                 if (c >= 0) {
                     const int64_t pos = row_base + (int64_t)win_base + (int64_t)cnt[c] +
@@ -687,124 +761,6 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_emit_listed(
     }
 }
 
-// The same pass for the tile-rows with more than wide_threshold C tiles.  Dynamic LDS: 2*words_cap words.
-template <bool kLongRows>
-__global__ __launch_bounds__(kSymThreads) void k_sym_emit_wide(
-    TileRefs A, TileRefs B, int lanes_per_a, int words_cap, int wide_threshold,
-    const int32_t *__restrict__ row_jmin, const int32_t *__restrict__ row_words,
-    const int32_t *__restrict__ c_tile_row_ptr, const int64_t *__restrict__ row_pair_ptr,
-    int32_t *__restrict__ c_tile_row, int32_t *__restrict__ c_tile_col, int64_t *__restrict__ pair_off,
-    int32_t *__restrict__ pair_a, int32_t *__restrict__ pair_b, uint32_t *wide_contrib, uint32_t *wide_cnt) {
-    extern __shared__ uint32_t lds_dyn[];
-    __shared__ uint32_t red[32];
-    uint32_t *bm = lds_dyn;
-    uint32_t *wpre = bm + words_cap;
-    const int I = blockIdx.x;
-    const int nthreads = (int)blockDim.x;       // read once: the compiler reloads it at every use otherwise
-    const int c0 = c_tile_row_ptr[I], nC = c_tile_row_ptr[I + 1] - c0;
-    if (nC <= 0) return;
-    if (nC <= wide_threshold) return;               // k_sym_emit's tile-row
-    const int a0 = A.trp[I], a1 = A.tend[I];
-    const int jmin = row_jmin[I];
-    // the bitmap extent the first pass found for this tile-row (rows over the limit have nC = 0)
-    const int words = min(row_words[I], words_cap);
-    const int64_t span = (int64_t)words * 32;
-    for (int w = threadIdx.x; w < words; w += nthreads) bm[w] = 0;
-    __syncthreads();
-    uint32_t dummy = 0;
-    for_each_survivor<kLongRows>(A, B, a0, a1, lanes_per_a, &dummy, [&](int, int, int J) {
-        const uint32_t j = (uint32_t)(J - jmin);
-        if (j < (uint32_t)span) atomicOr(&bm[j >> 5], 1u << (j & 31));
-    });
-    __syncthreads();
-    for (int w = threadIdx.x; w < words; w += nthreads) wpre[w] = __popc(bm[w]);
-    __syncthreads();
-    block_exclusive_scan_lds(wpre, words, red);
-    // C tile coordinates, ascending J
-    for (int w = threadIdx.x; w < words; w += nthreads) {
-        uint32_t bits = bm[w];
-        int c = c0 + (int)wpre[w];
-        while (bits) {
-            const int bit = __ffs(bits) - 1;
-            bits &= bits - 1;
-            c_tile_row[c] = I;
-            c_tile_col[c] = jmin + w * 32 + bit;
-            ++c;
-        }
-    }
-    const int64_t row_base = row_pair_ptr[I];
-    const bool one_chunk = (a1 - a0) <= 32;
-    // The pairs of the tile-row are placed window by window of C tiles: per C tile of the window a
-    // word that collects which of 32 A tiles contribute (`contrib`) and a running count (`cnt`).
-    // Every window costs three passes over all candidates of the tile-row, so a tile-row with more
-    // C tiles than the LDS window holds takes its two arrays from global memory instead and does
-    // everything in one window.  Reads of the arrays go past the L1 cache (the words are written
-    // with atomics, which are performed in L2).
-    auto place = [&](uint32_t *contrib, uint32_t *cnt, const int window) {
-        auto peek = [](const uint32_t *p) {
-            return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        };
-        uint32_t win_base = 0;
-        for (int win0 = 0; win0 < nC; win0 += window) {
-            const int nw = min(window, nC - win0);
-            auto rank_in_window = [&](int J) -> int {
-                const uint32_t j = (uint32_t)(J - jmin);
-                if (j >= (uint32_t)span) return -1;
-                const uint32_t word = bm[j >> 5];
-                const int c = (int)wpre[j >> 5] + __popc(word & ((1u << (j & 31)) - 1u)) - win0;
-                return (c >= 0 && c < nw) ? c : -1;
-            };
-            for (int c = threadIdx.x; c < nw; c += nthreads) cnt[c] = 0;
-            // count pass: 32 A tiles at a time
-            for (int ch = a0; ch < a1; ch += 32) {
-                for (int c = threadIdx.x; c < nw; c += nthreads) contrib[c] = 0;
-                __syncthreads();
-                for_each_survivor<kLongRows>(A, B, ch, min(ch + 32, a1), lanes_per_a, &dummy, [&](int a, int, int J) {
-                    const int c = rank_in_window(J);
-                    if (c >= 0) atomicOr(&contrib[c], 1u << (a - ch));
-                });
-                __syncthreads();
-                for (int c = threadIdx.x; c < nw; c += nthreads) cnt[c] = peek(&cnt[c]) + __popc(peek(&contrib[c]));
-                __syncthreads();
-            }
-            const uint32_t win_total = block_exclusive_scan_words(cnt, nw, red);
-            for (int c = threadIdx.x; c < nw; c += nthreads)
-                pair_off[c0 + win0 + c] = row_base + (int64_t)win_base + (int64_t)peek(&cnt[c]);
-            // emit pass
-            for (int ch = a0; ch < a1; ch += 32) {
-                if (!one_chunk) {
-                    for (int c = threadIdx.x; c < nw; c += nthreads) contrib[c] = 0;
-                    __syncthreads();
-                    for_each_survivor<kLongRows>(A, B, ch, min(ch + 32, a1), lanes_per_a, &dummy,
-                                                 [&](int a, int, int J) {
-                                                     const int c = rank_in_window(J);
-                                                     if (c >= 0) atomicOr(&contrib[c], 1u << (a - ch));
-                                                 });
-                    __syncthreads();
-                }
-                for_each_survivor<kLongRows>(A, B, ch, min(ch + 32, a1), lanes_per_a, &dummy, [&](int a, int b, int J) {
-                    const int c = rank_in_window(J);
-                    if (c >= 0) {
-                        const int64_t pos = row_base + (int64_t)win_base + (int64_t)peek(&cnt[c]) +
-                                            __popc(peek(&contrib[c]) & ((1u << (a - ch)) - 1u));
-                        pair_a[pos] = a;
-                        pair_b[pos] = b;
-                    }
-                });
-                __syncthreads();
-                if (!one_chunk) {
-                    for (int c = threadIdx.x; c < nw; c += nthreads)
-                        cnt[c] = peek(&cnt[c]) + __popc(peek(&contrib[c]));
-                    __syncthreads();
-                }
-            }
-            win_base += win_total;
-            __syncthreads();
-        }
-    };
-    place(wide_contrib + c0, wide_cnt + c0, nC);
-}
-
 // Counting pass: 16 lanes per C tile, lane r owns row r of the tile.  For each pair of the tile's
 // segment: c_mask[r] |= OR over the set bits k of the A tile's row mask r of the B tile's row mask k.
 // The segment's entries are read 16 at a time, one per lane, and the bitmaps of four pairs are
@@ -992,7 +948,7 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
     int32_t *row_jmin = nullptr, *row_c_tiles = nullptr, *row_pairs = nullptr, *row_nnz = nullptr;
     uint32_t *tile_row_entries = nullptr;
     int32_t *row_words = nullptr, *row_cand = nullptr;
-    uint32_t *wide_words = nullptr;
+    int32_t *cursor = nullptr;
     int64_t *row_pair_ptr = nullptr, *tmp = nullptr;
     auto cleanup = [&](int code) {
         ctx_free(ctx, row_jmin, s);
@@ -1000,7 +956,7 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
         ctx_free(ctx, row_pairs, s);
         ctx_free(ctx, row_words, s);
         ctx_free(ctx, row_cand, s);
-        ctx_free(ctx, wide_words, s);
+        ctx_free(ctx, cursor, s);
         ctx_free(ctx, row_nnz, s);
         ctx_free(ctx, tile_row_entries, s);
         ctx_free(ctx, row_pair_ptr, s);
@@ -1117,17 +1073,16 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
         const size_t lds = (size_t)(2 * words_cap + 2 * window) * sizeof(uint32_t);
         lanes = lanes_per_a_tile(B);
         long_rows = (double)B->ntiles > 48.0 * (double)B->tile_rows;
-        // tile-rows with more C tiles than the LDS window take their two per-tile arrays from here
+        // tile-rows with more C tiles than the LDS window holds are worked off in several windows and keep,
+        // in one word per tile of A, where the previous window ended in B's tile-row
         if (h[S_MAX_ROW_C_TILES] > window) {
-            wide_words = ctx_alloc_n<uint32_t>(ctx, 2 * (size_t)P->c_tiles, s);
-            if (!wide_words) return cleanup(TSP_ERR_ALLOC_FAILED);
+            cursor = ctx_alloc_n<int32_t>(ctx, (size_t)A->tile_capacity, s);
+            if (!cursor) return cleanup(TSP_ERR_ALLOC_FAILED);
         }
         KernelTimer kt(ctx, TSP_KERNEL_SYM_EMIT, s);
         const int64_t per_row = P->candidates / ntr;
         // (the fused counting pass of the list kernel wants more lanes than the enumeration does)
         const int threads = per_row <= 256 ? 64 : per_row <= 512 ? 128 : kSymThreads;
-        uint32_t *wide_cnt = wide_words ? wide_words + P->c_tiles : nullptr;
-        const int wide_threshold = wide_words ? window : INT_MAX;   // C tiles per tile-row above which the wide launch takes it
         listed = h[S_MAX_ROW_PAIRS] <= kListCap && h[S_MAX_ROW_C_TILES] <= kListTiles;
         if (listed) {
             const int list_cap = (int)std::max<int64_t>(h[S_MAX_ROW_PAIRS], 1);
@@ -1142,14 +1097,9 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
                                ctx->d_scalars, tile_row_entries);
         } else
             hipLaunchKernelGGL(long_rows ? k_sym_emit<true> : k_sym_emit<false>, dim3((unsigned)ntr), dim3(threads),
-                               lds, s, ra, rb, lanes, words_cap, window, wide_threshold, row_jmin, row_words,
+                               lds, s, ra, rb, lanes, words_cap, window, row_jmin, row_words,
                                P->c_tile_row_ptr,
-                               row_pair_ptr, P->c_tile_row, P->c_tile_col, P->pair_off, P->pair_a, P->pair_b);
-        if (wide_words)
-            hipLaunchKernelGGL(long_rows ? k_sym_emit_wide<true> : k_sym_emit_wide<false>, dim3((unsigned)ntr),
-                               dim3(kSymThreads), (size_t)(2 * words_cap) * sizeof(uint32_t), s, ra, rb, lanes, words_cap,
-                               wide_threshold, row_jmin, row_words, P->c_tile_row_ptr, row_pair_ptr, P->c_tile_row, P->c_tile_col,
-                               P->pair_off, P->pair_a, P->pair_b, wide_words, wide_cnt);
+                               row_pair_ptr, P->c_tile_row, P->c_tile_col, P->pair_off, P->pair_a, P->pair_b, cursor);
         SYM_CHECK(hipGetLastError());
     } else {
         SYM_CHECK(hipMemsetAsync(P->pair_off, 0, sizeof(int64_t), s));
