@@ -473,7 +473,7 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_emit(
     if (multi) {
         int windows = (nC + window - 1) / window, f = 1;
         while (f < windows) f <<= 1;
-        lanes_w = max(4, lanes_per_a / f);
+        lanes_w = max(4, min(lanes_per_a, 2 * lanes_per_a / f));   // (measured on hub tile-rows of an R-MAT graph)
     }
     __shared__ int s_j_end;
     uint32_t win_base = 0;
