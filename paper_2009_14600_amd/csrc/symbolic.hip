@@ -823,6 +823,11 @@ __global__ __launch_bounds__(256) void k_row_ptr(const int32_t *__restrict__ row
     constexpr int kItems = kChunkRows / 256;
     const bool last = blockIdx.x == gridDim.x - 1;
     const int64_t tile_rows_before = (int64_t)blockIdx.x * kChunkTileRows;
+    // the block's own row lengths, requested first: they travel while the tile-rows before are added up
+    const int64_t base = (int64_t)blockIdx.x * kChunkRows + (int64_t)threadIdx.x * kItems;
+    int32_t x[kItems];
+#pragma unroll
+    for (int i = 0; i < kItems; ++i) x[i] = base + i < c_rows ? row_nnz[base + i] : 0;
     uint64_t before = 0;
     uint32_t largest = 0;
     // four tile-rows per load, four loads in flight (the array is padded to a multiple of four)
@@ -846,14 +851,9 @@ __global__ __launch_bounds__(256) void k_row_ptr(const int32_t *__restrict__ row
     }
     uint64_t entries_before;
     (void)block_exclusive_scan64<256>(before, &entries_before, lds);
-    const int64_t base = (int64_t)blockIdx.x * kChunkRows + (int64_t)threadIdx.x * kItems;
-    int32_t x[kItems];
     uint64_t mine = 0;
 #pragma unroll
-    for (int i = 0; i < kItems; ++i) {
-        x[i] = base + i < c_rows ? row_nnz[base + i] : 0;
-        mine += (uint32_t)x[i];
-    }
+    for (int i = 0; i < kItems; ++i) mine += (uint32_t)x[i];
     uint64_t total;
     uint64_t run = entries_before + block_exclusive_scan64<256>(mine, &total, lds);
 #pragma unroll
