@@ -92,7 +92,7 @@ enum {
                                /*    through 64-bit pointers; 0 (default): chosen from the sizes    */
     TSP_OPT_NUMERIC_RUN = 4,   /* output tiles one wave of the multiplication kernel walks: 4 or 8; */
                                /*    0 (default): 4, or a whole tile-row of C where every tile-row  */
-                               /*    has at most 16 tiles, 64 task-list entries and 384 entries     */
+                               /*    has at most 60 tiles, 64 task-list entries and 448 entries     */
     TSP_OPT_MATRIX_CORES = 5,  /* 1 (default): block products on the MFMA units (Section 4.3);      */
                                /*    0: on the vector ALUs, one fp32 FMA per inner index and output */
                                /*    element (the paper's comparison build, Section 5, Algorithm 2) */

@@ -58,8 +58,8 @@ constexpr int kNumThreads = 256;       // 4 waves per block
 constexpr int kGroupTiles = 4;         // output tiles computed together and written out row by row
 constexpr int kXcds = 8;
 constexpr int kBlockEntries = 64;      // task-list entries staged at a time: one per lane
-constexpr int kRowTiles = 16;          // whole-tile-row kernel: most output tiles a tile-row may have
-constexpr int kRowEntries = 384;       // ... and most structural entries (its output is assembled in LDS)
+constexpr int kRowTiles = 60;          // whole-tile-row kernel: most output tiles a tile-row may have (one lane each)
+constexpr int kRowEntries = 448;       // ... and most structural entries (its output is assembled in LDS)
 
 struct Header {          // tile headers of one task-list entry, as the lanes of the wave read them from LDS
     uint32_t lm, lo, rm, ro;   // group masks and BYTE offsets of the first group: left form of A, right form of B
@@ -150,7 +150,7 @@ __global__ __launch_bounds__(kNumThreads) void k_numeric(
     const uint32_t *__restrict__ c_row_off, const int64_t *__restrict__ c_row_ptr, int32_t *__restrict__ c_col,
     float *__restrict__ c_val, int64_t *__restrict__ scalars_to_clear) {
     if (scalars_to_clear && blockIdx.x == 0 && threadIdx.x < kScalars) scalars_to_clear[threadIdx.x] = 0;
-    static_assert(kTilesPerWave % kGroupTiles == 0 && kTilesPerWave <= 32, "whole groups; offsets fit one wave load");
+    static_assert(kTilesPerWave % kGroupTiles == 0 && kTilesPerWave < 64, "whole groups; offsets fit one wave load");
     // headers of the 64 task-list entries a wave is working on, one 16-byte record per entry; one
     // spare record per wave: the second half-wave may address the entry after the last one
     __shared__ uint4 lds_heads[kNumThreads / 64][kBlockEntries + 16];
@@ -167,7 +167,7 @@ __global__ __launch_bounds__(kNumThreads) void k_numeric(
     int64_t run_begin;
     int run_tiles;
     if constexpr (kWholeRows) {
-        static_assert(kTilesPerWave == kRowTiles, "the unrolled groups cover a whole tile-row");
+        static_assert(kTilesPerWave == kRowTiles, "the groups cover a whole tile-row");
         if (wave >= c_tile_rows) return;
         run_begin = c_tile_row_ptr[wave];                                       // wave = tile-row of C
         run_tiles = min(c_tile_row_ptr[wave + 1] - (int)run_begin, kTilesPerWave);
@@ -197,7 +197,7 @@ __global__ __launch_bounds__(kNumThreads) void k_numeric(
     const int64_t base = ((int64_t)__builtin_amdgcn_readlane((int)(off_lane >> 32), 0) << 32) |
                          (uint32_t)__builtin_amdgcn_readlane((int)off_lane, 0);
     const int rel_lane = (int)(off_lane - base);
-    const int rel_end = __builtin_amdgcn_readlane(rel_lane, kTilesPerWave);        // lanes >= run_tiles hold the end
+    const int rel_end = __builtin_amdgcn_readlane(rel_lane, kWholeRows ? run_tiles : kTilesPerWave);   // lanes >= run_tiles hold the end
 
     // 64 consecutive task-list entries starting at relative position `start`, one per lane: the
     // headers of their tiles go to LDS, where any lane can read any entry's record with one load
@@ -299,7 +299,8 @@ __global__ __launch_bounds__(kNumThreads) void k_numeric(
     int row_entries = 0;                          // whole-tile-row kernel: entries of the tile-row
     if constexpr (kWholeRows)
         row_entries = (int)min(c_row_ptr[min((int64_t)(I_first + 1) * T, c_rows)] - base_first, (int64_t)kRowEntries);
-#pragma unroll
+    // (the tile-group kernels unroll their one or two groups; a whole tile-row's groups are a loop)
+#pragma unroll(kWholeRows ? 1 : kTilesPerWave / kGroupTiles)
     for (int g = 0; g < kTilesPerWave / kGroupTiles; ++g) {
         if (g * kGroupTiles < run_tiles) {        // uniform
             // The row masks and row positions of the group's four tiles, requested before the

@@ -101,6 +101,21 @@ def laplacian_2d(g: int = 512) -> CSRMatrix:
                     f"laplacian2d_{g}")
 
 
+def laplacian_3d(g: int = 64) -> CSRMatrix:
+    """7-point Laplacian on a g x g x g grid, natural ordering, diagonal 6, off-diagonals -1."""
+    n = g ** 3
+    idx = np.arange(n, dtype=np.int64)
+    x, y, z = idx % g, (idx // g) % g, idx // (g * g)
+    rs, cs, vs = [idx], [idx], [np.full(n, 6.0)]
+    for dx, dy, dz in ((-1, 0, 0), (1, 0, 0), (0, -1, 0), (0, 1, 0), (0, 0, -1), (0, 0, 1)):
+        ok = ((x + dx >= 0) & (x + dx < g) & (y + dy >= 0) & (y + dy < g) & (z + dz >= 0) & (z + dz < g))
+        rs.append(idx[ok])
+        cs.append(idx[ok] + dx + dy * g + dz * g * g)
+        vs.append(np.full(int(ok.sum()), -1.0))
+    return from_coo(n, n, np.concatenate(rs), np.concatenate(cs), np.concatenate(vs),
+                    f"laplacian3d_{g}")
+
+
 def stencil27_3d(g: int = 48, dof: int = 3, periodic: bool = True,
                  seed: int = BASE_SEED + 3) -> CSRMatrix:
     """27-point stencil on a g^3 grid, ``dof`` unknowns per node, dense dof x dof couplings.

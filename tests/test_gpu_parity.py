@@ -460,18 +460,19 @@ def _variant_handle(tsp, **options):
 
 
 def _mesh_cases():
-    """Products whose tile-rows of C are short and sparse (at most 16 output tiles, 64 task-list entries
-    and 384 entries per tile-row): the multiplication kernel takes a whole tile-row per wave and
+    """Products whose tile-rows of C are short and sparse (at most 60 output tiles, 64 task-list entries
+    and 448 entries per tile-row): the multiplication kernel takes a whole tile-row per wave and
     assembles its output in LDS.  Grid edges that are no multiple of 16 give ragged last tile-rows."""
     yield "laplacian 37x37", inputs.laplacian_2d(37), None
     yield "laplacian 64x64", inputs.laplacian_2d(64), None
-    # one inner tile column, 16 and 17 output tiles per tile-row: either side of the limit
-    for n_cols in (256, 272):
+    yield "laplacian 13x13x13", inputs.laplacian_3d(13), None      # about 20 output tiles per tile-row
+    # one inner tile column; 16, 60 and 61 output tiles per tile-row: inside and either side of the limit
+    for n_cols, density in ((256, 0.1), (960, 0.025), (976, 0.025)):
         A = inputs.random_sparse(70, 16, 0.07, 91, empty_row_fraction=0.2)
-        B = inputs.random_sparse(16, n_cols, 0.1, 92)
+        B = inputs.random_sparse(16, n_cols, density, 92)
         yield f"single inner tile, {n_cols} columns", A, B
-    # entries per tile-row either side of 384
-    for density in (0.07, 0.12):
+    # entries per tile-row either side of 448
+    for density in (0.10, 0.12):
         A = inputs.random_sparse(64, 16, 0.0625, 93)
         B = inputs.random_sparse(16, 256, density, 94, values="smallint")
         yield f"single inner tile, density {density}", A, B
