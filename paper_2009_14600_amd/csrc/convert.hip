@@ -290,6 +290,108 @@ __device__ __forceinline__ void convert_rows(const ConvArgs<RP, VT> &a) {
             ++t;
         }
     }
+    // A tile-row with more tiles than a window holds, and too many entries for the registers, would
+    // read all its entries again for every window.  Its CSR rows are sorted by column, so the entries of
+    // a window of tiles are one stretch of every row: each window walks the 16 rows from where the
+    // previous one ended (s_cur), and the tile-row is read once per pass.
+    const bool long_row = !cached && ntiles > kWindow;              // uniform over the group
+    // (where each row's walk stands: lane r of every wave keeps row r's place)
+    int cur = long_row ? s_rp[min((int)(threadIdx.x & 63), T)] : 0;
+    // f(r, c, value or 0, tile inside the window) for the window's entries; `advance`: the last pass of the window
+    auto for_each_window_entry = [&](int win0, int nw, bool with_values, bool advance, auto f) {
+        for (int r = 0; r < T; ++r) {
+            const int end = s_rp[r + 1];
+            int stop = end;                                           // first entry of this lane's stride past the window
+            for (int e = __builtin_amdgcn_readlane(cur, r) + gt; e < end; e += G) {
+                const int c = a.col[e];
+                const int t = tile_rank(c) - win0;
+                if (t >= nw) {
+                    stop = e;
+                    break;
+                }
+                if (t >= 0) f(r, c, with_values ? a.val[e] : VT(0), t);
+            }
+            if (advance) {
+                stop = -group_max<G>(-stop, s_red);
+                if ((int)(threadIdx.x & 63) == r) cur = stop;
+            }
+        }
+    };
+    if (__builtin_expect(long_row, 0)) {          // (its own copy of the loop: the common path below stays as it is)
+        for (int win0 = 0; win0 < ntiles; win0 += kWindow) {
+            const int nw = min(kWindow, ntiles - win0);
+            // 2. row masks of the tiles of this window
+            for (int k = gt; k < nw * 8; k += G) s_mask[k] = 0;
+            group_sync<G>();
+            for_each_window_entry(win0, nw, false, false, [&](int r, int c, VT, int t) {
+                atomicOr(&s_mask[t * 8 + (r >> 1)], 1u << ((r & 1) * 16 + (c & 15)));
+            });
+            group_sync<G>();
+            for (int t = gt; t < nw; t += G) {
+                uint32_t lm = 0, rm = 0;
+    #pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    const uint32_t m2 = s_mask[t * 8 + k];              // rows 2k (low half) and 2k+1 (high half)
+                    lm |= ((m2 & 0x000000FFu) ? 1u << (2 * k) : 0u) | ((m2 & 0x0000FF00u) ? 1u << (16 + 2 * k) : 0u) |
+                          ((m2 & 0x00FF0000u) ? 1u << (2 * k + 1) : 0u) | ((m2 & 0xFF000000u) ? 1u << (17 + 2 * k) : 0u);
+                    const uint32_t cols = (m2 | (m2 >> 16)) & 0xFFFFu;  // columns present in rows 2k, 2k+1
+                    rm |= k < 4 ? cols : cols << 16;
+                }
+                s_lm[t] = lm;
+                s_rm[t] = rm;
+                s_lo[t] = __popc(lm);
+                s_ro[t] = __popc(rm);
+            }
+            group_sync<G>();
+            const uint32_t ltot = group_exclusive_scan<G>(s_lo, nw, s_red);
+            const uint32_t rtot = group_exclusive_scan<G>(s_ro, nw, s_red);
+            // the window's groups are zeroed; the entries drop their values into their slots below
+            const uint4 zero = make_uint4(0, 0, 0, 0);
+            if (a.forms & TSP_FORM_LEFT)
+                for (int64_t g = (int64_t)lrun + gt, end = min((int64_t)lrun + ltot, a.group_capacity); g < end; g += G)
+                    a.ldata[g] = zero;
+            if (a.forms & TSP_FORM_RIGHT)
+                for (int64_t g = (int64_t)rrun + gt, end = min((int64_t)rrun + rtot, a.group_capacity); g < end; g += G)
+                    a.rdata[g] = zero;
+            // tile headers and bitmaps
+            for (int t = gt; t < nw; t += G) {
+                const int64_t tg = t0 + win0 + t;
+                if (tg < a.tile_capacity) {
+                    uint4 *dst = reinterpret_cast<uint4 *>(a.row_mask + tg * T);
+                    dst[0] = make_uint4(s_mask[t * 8 + 0], s_mask[t * 8 + 1], s_mask[t * 8 + 2], s_mask[t * 8 + 3]);
+                    dst[1] = make_uint4(s_mask[t * 8 + 4], s_mask[t * 8 + 5], s_mask[t * 8 + 6], s_mask[t * 8 + 7]);
+                    a.lmask[tg] = s_lm[t];
+                    a.rmask[tg] = s_rm[t];
+                    if (a.forms & TSP_FORM_LEFT) a.lhead[tg] = make_uint2(s_lm[t], lrun + s_lo[t]);
+                    if (a.forms & TSP_FORM_RIGHT) a.rhead[tg] = make_uint2(s_rm[t], rrun + s_ro[t]);
+                }
+            }
+            // the zeros must be in L2 before any value is stored over them: every wave waits for its own
+            // stores, then the group meets
+            __builtin_amdgcn_s_waitcnt(0x0F70);
+            group_sync<G>();
+            // 3. values
+            for_each_window_entry(win0, nw, true, true, [&](int r, int c, VT value, int t) {
+                const int cc = c & 15;
+                const uint16_t v = to_half_bits(value);
+                if (a.forms & TSP_FORM_LEFT) {
+                    const int g = (cc >> 3) * 16 + r;
+                    const int64_t idx = (int64_t)lrun + s_lo[t] + __popc(s_lm[t] & ((1u << g) - 1u));
+                    if (idx < a.group_capacity) l16[idx * 8 + (cc & 7)] = v;
+                }
+                if (a.forms & TSP_FORM_RIGHT) {
+                    const int g = (r >> 3) * 16 + cc;
+                    const int64_t idx = (int64_t)rrun + s_ro[t] + __popc(s_rm[t] & ((1u << g) - 1u));
+                    if (idx < a.group_capacity) r16[idx * 8 + (r & 7)] = v;
+                }
+            });
+            lrun += ltot;
+            rrun += rtot;
+            group_sync<G>();
+        }
+        finish(ntiles, ROW_FAST);
+        return;
+    }
     for (int win0 = 0; win0 < ntiles; win0 += kWindow) {
         const int nw = min(kWindow, ntiles - win0);
         // 2. row masks of the tiles of this window

@@ -521,3 +521,24 @@ def test_seeded_sweep_of_small_products(tsp, handle, oracle):
         B = inputs.random_sparse(K, N, density, 8000 + case, empty_row_fraction=empty, values=kind)
         print(f"sweep {case}: {M}x{K}x{N} d={density:.4f} {kind} empty={empty} {upload}", flush=True)
         run_and_check(tsp, handle, oracle, A, B, **upload)
+
+
+def test_mesh_with_dense_rows(tsp, handle, oracle):
+    """A few full rows in an otherwise short-rowed matrix (a constraint row in a mesh problem): their
+    tile-rows have far more tiles than a window of the converter and of the task-list kernel holds and go
+    through the window-by-window paths of both, inside kernels chosen for the short rows."""
+    L = inputs.laplacian_2d(48)
+    n = L.rows
+    rows = np.repeat(np.arange(n), np.diff(L.row_ptr))
+    cols, vals = L.col_idx.astype(np.int64), L.val.astype(np.float64)
+    rng = np.random.default_rng(5)
+    dense = (7, n // 2 + 3, n - 1)
+    keep = ~np.isin(rows, dense)
+    rows = np.concatenate([rows[keep]] + [np.full(n, r) for r in dense])
+    cols = np.concatenate([cols[keep]] + [np.arange(n) for _ in dense])
+    vals = np.concatenate([vals[keep]] + [rng.uniform(-1, 1, n) for _ in dense])
+    A = inputs.from_coo(n, n, rows, cols, vals, "laplacian_with_dense_rows")
+    nnz, _ = run_and_check(tsp, handle, oracle, A)
+    assert nnz > 3 * n
+    B = inputs.random_sparse(n, 90, 0.02, 77)
+    run_and_check(tsp, handle, oracle, A, B)
