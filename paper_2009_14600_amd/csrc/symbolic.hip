@@ -120,7 +120,7 @@ __device__ __forceinline__ void for_each_survivor(const TileRefs &A, const TileR
 template <bool kLongRows, class F>
 __device__ __forceinline__ void for_each_survivor_below(const TileRefs &A, const TileRefs &B, int a_begin, int a_end,
                                                         int lanes_per_a, int j_end, int32_t *cursor, bool from_cursor,
-                                                        bool keep_cursor, F f) {
+                                                        bool keep_cursor, int *lds_next_col, F f) {
     const int sub = threadIdx.x / lanes_per_a, l = threadIdx.x % lanes_per_a;
     const int nsub = blockDim.x / lanes_per_a;
     // all lanes of a group of lanes_per_a lanes run the same trip count of the outer loop (the reduction
@@ -128,6 +128,7 @@ __device__ __forceinline__ void for_each_survivor_below(const TileRefs &A, const
     for (int a0 = a_begin; a0 < a_end; a0 += nsub) {
         const int a = a0 + sub;
         int stop = INT_MAX;                                   // first tile of this lane's stride at or past j_end
+        int stop_col = INT_MAX;                               // ... and its tile column
         if (a < a_end) {
             const uint32_t K = (uint32_t)A.tcol[a];
             if (K < (uint32_t)B.tile_rows) {
@@ -152,6 +153,7 @@ __device__ __forceinline__ void for_each_survivor_below(const TileRefs &A, const
                             if (open && col[u] >= j_end) {
                                 open = false;
                                 stop = b + u * lanes_per_a;
+                                stop_col = col[u];
                             }
                             if (open && (col_occ & fold16(occ[u]))) f(a, b + u * lanes_per_a, col[u]);
                         }
@@ -161,6 +163,7 @@ __device__ __forceinline__ void for_each_survivor_below(const TileRefs &A, const
                     if (col >= j_end) {
                         open = false;
                         stop = b;
+                        stop_col = col;
                     } else if (col_occ & fold16(B.lmask[b])) {
                         f(a, b, col);
                     }
@@ -169,9 +172,14 @@ __device__ __forceinline__ void for_each_survivor_below(const TileRefs &A, const
             }
         }
         if (keep_cursor) {                                    // uniform
-            for (int d = lanes_per_a >> 1; d >= 1; d >>= 1) stop = min(stop, __shfl_xor(stop, d, 64));
-            if (l == 0 && a < a_end && stop != INT_MAX)
+            for (int d = lanes_per_a >> 1; d >= 1; d >>= 1) {
+                stop = min(stop, __shfl_xor(stop, d, 64));
+                stop_col = min(stop_col, __shfl_xor(stop_col, d, 64));   // (sorted: the earliest stop has the lowest column)
+            }
+            if (l == 0 && a < a_end && stop != INT_MAX) {
                 __hip_atomic_store(&cursor[a], stop, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (stop_col != INT_MAX) atomicMin(lds_next_col, stop_col);
+            }
         }
     }
 }
@@ -424,7 +432,7 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_emit(
     const int32_t *__restrict__ row_jmin, const int32_t *__restrict__ row_words,
     const int32_t *__restrict__ c_tile_row_ptr, const int64_t *__restrict__ row_pair_ptr,
     int32_t *__restrict__ c_tile_row, int32_t *__restrict__ c_tile_col, int64_t *__restrict__ pair_off,
-    int32_t *__restrict__ pair_a, int32_t *__restrict__ pair_b, int32_t *cursor) {
+    int32_t *__restrict__ pair_a, int32_t *__restrict__ pair_b, int32_t *cursor, int64_t A_capacity) {
     extern __shared__ uint32_t lds_dyn[];
     __shared__ uint32_t red[32];
     uint32_t *bm = lds_dyn;
@@ -475,7 +483,10 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_emit(
         while (f < windows) f <<= 1;
         lanes_w = max(4, min(lanes_per_a, 2 * lanes_per_a / f));   // (measured on hub tile-rows of an R-MAT graph)
     }
-    __shared__ int s_j_end;
+    __shared__ int s_j_end, s_next_col;
+    // per chunk of 32 A tiles (at the index of its first tile, behind the cursors): the lowest tile column
+    // its tiles of A still have ahead in B's tile-rows; a window below that column skips the chunk
+    int32_t *const chunk_next_col = cursor ? cursor + A_capacity : nullptr;
     uint32_t win_base = 0;
     for (int win0 = 0; win0 < nC; win0 += window) {
         const int nw = min(window, nC - win0);
@@ -498,9 +509,14 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_emit(
             if (more) j_end = s_j_end;
         }
         // every surviving pair of A tiles [ch, ch_end) whose C tile lies in this window
+        auto skip_chunk = [&](int ch) {             // uniform: nothing of this chunk lies in the window
+            return multi && win0 > 0 &&
+                   __hip_atomic_load(&chunk_next_col[ch], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= j_end;
+        };
         auto walk = [&](int ch, int ch_end, bool keep, auto f) {
             if (multi)
-                for_each_survivor_below<kLongRows>(A, B, ch, ch_end, lanes_w, j_end, cursor, win0 > 0, keep && more, f);
+                for_each_survivor_below<kLongRows>(A, B, ch, ch_end, lanes_w, j_end, cursor, win0 > 0, keep && more,
+                                                   &s_next_col, f);
             else
                 for_each_survivor<kLongRows>(A, B, ch, ch_end, lanes_per_a, &dummy, f);
         };
@@ -514,6 +530,7 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_emit(
         for (int c = threadIdx.x; c < nw; c += blockDim.x) cnt[c] = 0;
         // count pass: 32 A tiles at a time
         for (int ch = a0; ch < a1; ch += 32) {
+            if (skip_chunk(ch)) continue;
             for (int c = threadIdx.x; c < nw; c += blockDim.x) contrib[c] = 0;
             __syncthreads();
             walk(ch, min(ch + 32, a1), false, [&](int a, int, int J) {
@@ -529,6 +546,11 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_emit(
             pair_off[c0 + win0 + c] = row_base + (int64_t)win_base + (int64_t)cnt[c];
         // emit pass
         for (int ch = a0; ch < a1; ch += 32) {
+            if (skip_chunk(ch)) continue;
+            if (multi && more) {                     // (uniform) the chunk's next column is collected by the last walk
+                if (threadIdx.x == 0) s_next_col = INT_MAX;
+                __syncthreads();
+            }
             if (!one_chunk) {
                 for (int c = threadIdx.x; c < nw; c += blockDim.x) contrib[c] = 0;
                 __syncthreads();
@@ -548,6 +570,8 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_emit(
                 }
             });
             __syncthreads();
+            if (multi && more && threadIdx.x == 0)
+                __hip_atomic_store(&chunk_next_col[ch], s_next_col, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             if (!one_chunk) {
                 for (int c = threadIdx.x; c < nw; c += blockDim.x) cnt[c] += __popc(contrib[c]);
                 __syncthreads();
@@ -1076,7 +1100,7 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
         // tile-rows with more C tiles than the LDS window holds are worked off in several windows and keep,
         // in one word per tile of A, where the previous window ended in B's tile-row
         if (h[S_MAX_ROW_C_TILES] > window) {
-            cursor = ctx_alloc_n<int32_t>(ctx, (size_t)A->tile_capacity, s);
+            cursor = ctx_alloc_n<int32_t>(ctx, 2 * (size_t)A->tile_capacity, s);    // and one per chunk of 32 of them
             if (!cursor) return cleanup(TSP_ERR_ALLOC_FAILED);
         }
         KernelTimer kt(ctx, TSP_KERNEL_SYM_EMIT, s);
@@ -1099,7 +1123,8 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
             hipLaunchKernelGGL(long_rows ? k_sym_emit<true> : k_sym_emit<false>, dim3((unsigned)ntr), dim3(threads),
                                lds, s, ra, rb, lanes, words_cap, window, row_jmin, row_words,
                                P->c_tile_row_ptr,
-                               row_pair_ptr, P->c_tile_row, P->c_tile_col, P->pair_off, P->pair_a, P->pair_b, cursor);
+                               row_pair_ptr, P->c_tile_row, P->c_tile_col, P->pair_off, P->pair_a, P->pair_b, cursor,
+                               A->tile_capacity);
         SYM_CHECK(hipGetLastError());
     } else {
         SYM_CHECK(hipMemsetAsync(P->pair_off, 0, sizeof(int64_t), s));
