@@ -157,10 +157,11 @@ int tsp_trim(tsp_handle handle, void *stream);
  * On success *C is filled: rows = A.rows, cols = B.cols, nnz, row_ptr (TSP_I64), col_idx,
  * val (TSP_F32), the three arrays freshly taken from the handle's allocator and owned by the
  * caller, who releases them with tsp_csr_free.  Columns ascend strictly within each row.
- * On failure *C is zeroed and nothing is leaked.  The call synchronises the stream twice (the
- * sizes of the task list and of C are read back to size the allocations, the steps Algorithm 1
- * calls AllocateMemGPU); the multiplication pass that fills col_idx and val is enqueued after the
- * second and is NOT waited for: C.nnz and the pointers are final when the call returns, the
+ * On failure *C is zeroed and nothing is leaked.  The calling thread waits twice for results of
+ * the device (the sizes of the task list and of C, which size the allocations: the steps Algorithm 1
+ * calls AllocateMemGPU; it polls pinned memory for them for up to half a millisecond, then blocks);
+ * the multiplication pass that fills col_idx and val is enqueued after the second wait and is NOT
+ * waited for: C.nnz and the pointers are final when the call returns, the
  * contents once the stream has reached that point (hipStreamSynchronize, or further work on the
  * same stream).  With TSP_OPT_PHASE_TIMERS the call waits for the end.
  * Errors: INVALID_ARG, SHAPE_MISMATCH, NOT_CANONICAL, ALLOC_FAILED, INDEX_OVERFLOW, HIP,

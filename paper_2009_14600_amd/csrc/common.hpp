@@ -31,6 +31,7 @@ enum Scalar {
     S_INTERNAL = 11,         // != 0: a bounded device-side wait ran out (should never happen)
     S_MAX_ROW_PAIRS = 12,    // max over C tile-rows of the number of task-list entries
     S_MAX_ROW_ENTRIES = 13,  // max over C tile-rows of the number of structural entries
+    S_PUBLISHED = 31,        // host mirror only: the tag of the publication the mirror holds (publish_scalars)
 };
 
 struct Block {
@@ -61,6 +62,8 @@ struct tsp_context {
     int64_t *d_scalars = nullptr;                  // device, kScalars entries
     bool scalars_clean = false;                    // all zero: the previous tsp_spgemm left them so
     int64_t *h_scalars = nullptr;                  // pinned host mirror
+    int64_t *h_scalars_dev = nullptr;              // the mirror's address on the device
+    int64_t publish_tag = 0;                       // tag of the last publication asked for
     hipEvent_t ev[2 * TSP_PHASE_COUNT_ + 2]{};     // begin/end per phase, + total begin/end
     bool ev_created = false;
     bool ev_recorded[2 * TSP_PHASE_COUNT_ + 2]{};
@@ -105,6 +108,8 @@ void *ctx_alloc(tsp_context *ctx, size_t bytes, hipStream_t s);          // NULL
 void ctx_free(tsp_context *ctx, void *p, hipStream_t s);                 // back into the cache
 int hip_fail(tsp_context *ctx, hipError_t e);                            // records e, returns TSP_ERR_HIP
 int read_scalars(tsp_context *ctx, hipStream_t s);                       // d_scalars -> h_scalars, syncs
+// Waits until the kernel that was given `tag` has put the scalar block into h_scalars (publish_scalars).
+int wait_published_scalars(tsp_context *ctx, int64_t tag, hipStream_t s);
 // Slots for a chained scan over `blocks` blocks and a fresh epoch tag; nullptr on failure.
 void *chain_prepare(tsp_context *ctx, int64_t blocks, unsigned *epoch, hipStream_t s);
 void phase_begin(tsp_context *ctx, int phase, hipStream_t s);
@@ -166,6 +171,23 @@ __device__ __forceinline__ void wave_sync() {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// The scalar block copied into the host's pinned mirror, followed by `tag`, by the block of a kernel that
+// knows every other writer of the block has finished (all threads of that block call this, at least
+// kScalars of them).  The host polls the mirror for the tag: it has the sizes it waits for as soon as
+// they exist, without a copy (a launch of its own) and without waiting for the queue to drain.
+__device__ __forceinline__ void publish_scalars(int64_t *d_scalars, int64_t *h_scalars_dev, int64_t tag) {
+    __threadfence();                               // this block's own plain stores to the scalar block
+    __syncthreads();
+    if (threadIdx.x < kScalars && threadIdx.x != S_PUBLISHED) {
+        const int64_t v = __hip_atomic_load(&d_scalars[threadIdx.x], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(&h_scalars_dev[threadIdx.x], v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    }
+    __threadfence_system();                        // the values before the tag
+    __syncthreads();
+    if (threadIdx.x == 0)
+        __hip_atomic_store(&h_scalars_dev[S_PUBLISHED], tag, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
 }
 
 // Cross-lane operations on the data-parallel-primitive path (VALU speed, no LDS round trips).

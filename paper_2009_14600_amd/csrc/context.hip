@@ -1,5 +1,7 @@
 // Handle, device-memory cache, options, statistics, error strings.
 #include "common.hpp"
+
+#include <chrono>
 #include "chain.hpp"
 
 #include <algorithm>
@@ -71,6 +73,20 @@ int read_scalars(tsp_context *ctx, hipStream_t s) {
     TSP_HIP_CHECK(ctx, hipMemcpyAsync(ctx->h_scalars, ctx->d_scalars, sizeof(int64_t) * kScalars,
                                       hipMemcpyDeviceToHost, s));
     TSP_HIP_CHECK(ctx, hipStreamSynchronize(s));
+    return TSP_OK;
+}
+
+int wait_published_scalars(tsp_context *ctx, int64_t tag, hipStream_t s) {
+    // The kernel is short (tens of microseconds after the launch): poll the mirror for a while before
+    // falling back to a blocking wait, whose wake-up alone costs several microseconds.
+    const auto t0 = std::chrono::steady_clock::now();
+    for (unsigned spins = 0;; ++spins) {
+        if (__atomic_load_n(&ctx->h_scalars[S_PUBLISHED], __ATOMIC_ACQUIRE) == tag) return TSP_OK;
+        if ((spins & 1023) == 1023 &&
+            std::chrono::steady_clock::now() - t0 > std::chrono::microseconds(500)) break;
+    }
+    TSP_HIP_CHECK(ctx, hipStreamSynchronize(s));
+    if (__atomic_load_n(&ctx->h_scalars[S_PUBLISHED], __ATOMIC_ACQUIRE) != tag) return hip_fail(ctx, hipErrorUnknown);
     return TSP_OK;
 }
 
@@ -180,7 +196,10 @@ extern "C" int tsp_create(tsp_handle *handle, const tsp_allocator *allocator) {
     hipError_t e = hipGetDevice(&ctx->device);
     if (e == hipSuccess) e = hipMalloc((void **)&ctx->d_scalars, sizeof(int64_t) * kScalars);
     if (e == hipSuccess) e = hipHostMalloc((void **)&ctx->h_scalars, sizeof(int64_t) * kScalars, hipHostMallocDefault);
+    if (e == hipSuccess) e = hipHostGetDevicePointer((void **)&ctx->h_scalars_dev, ctx->h_scalars, 0);
+    if (e == hipSuccess) std::memset(ctx->h_scalars, 0, sizeof(int64_t) * kScalars);
     if (e != hipSuccess) {
+        if (ctx->h_scalars) (void)hipHostFree(ctx->h_scalars);
         if (ctx->d_scalars) (void)hipFree(ctx->d_scalars);
         (void)hipGetLastError();
         delete ctx;

@@ -336,7 +336,8 @@ __global__ __launch_bounds__(kRowScanThreads) void k_sym_row_scan(
     int64_t ntr, const int32_t *__restrict__ row_c_tiles, const int32_t *__restrict__ row_pairs,
     const int32_t *__restrict__ row_words, const int32_t *__restrict__ row_cand,
     int32_t *__restrict__ c_tile_row_ptr, int64_t *__restrict__ row_pair_ptr, ChainSlot *slots, unsigned epoch,
-    int64_t *__restrict__ d_scalars, TileCount count_a, TileCount count_b) {
+    int64_t *__restrict__ d_scalars, TileCount count_a, TileCount count_b, int64_t *h_scalars_dev,
+    int64_t publish_tag) {
     __shared__ uint64_t lds[kRowScanThreads / 64 + kChainValues];
     __shared__ int lds_m[3][kRowScanThreads / 64];
     __shared__ uint32_t lds_t[2][kRowScanThreads / 64];
@@ -370,27 +371,8 @@ __global__ __launch_bounds__(kRowScanThreads) void k_sym_row_scan(
         lds_t[0][wave] = tiles_a;
         lds_t[1][wave] = tiles_b;
     }
-    unsigned long long agg[kChainValues], prefix[kChainValues];
-    uint64_t total, unused;
-    const uint64_t local_c = block_exclusive_scan64<kRowScanThreads>(sc, &total, lds);
-    agg[0] = total;
-    const uint64_t local_p = block_exclusive_scan64<kRowScanThreads>(sp, &total, lds);
-    agg[1] = total;
-    (void)block_exclusive_scan64<kRowScanThreads>(cand, &total, lds);
-    agg[2] = total;
-    (void)unused;
-    chain_exclusive_prefix(slots, epoch, agg, prefix, lds + kRowScanThreads / 64, d_scalars + S_INTERNAL);
-    uint64_t run_c = prefix[0] + local_c, run_p = prefix[1] + local_p;
-#pragma unroll
-    for (int k = 0; k < kRowScanItems; ++k) {
-        if (i0 + k < ntr) {
-            c_tile_row_ptr[i0 + k] = (int32_t)run_c;
-            row_pair_ptr[i0 + k] = (int64_t)run_p;
-        }
-        run_c += (uint32_t)xc[k];
-        run_p += (uint32_t)xp[k];
-    }
-    // maxima: one atomic per block (a few dozen blocks at most per million rows)
+    // maxima and tile counts: one atomic per block (a few dozen blocks at most per million rows), issued
+    // before the block's sums go into the chain, so that whoever has taken those sums in sees them too
     max_c = wave_max(max_c);
     max_w = wave_max(max_w);
     max_p = wave_max(max_p);
@@ -418,13 +400,39 @@ __global__ __launch_bounds__(kRowScanThreads) void k_sym_row_scan(
         }
         if (ta) atomicAdd((unsigned long long *)&d_scalars[count_a.slot], ta);
         if (tb) atomicAdd((unsigned long long *)&d_scalars[count_b.slot], tb);
-        if (blockIdx.x == gridDim.x - 1) {
+    }
+    unsigned long long agg[kChainValues], prefix[kChainValues];
+    uint64_t total, unused;
+    const uint64_t local_c = block_exclusive_scan64<kRowScanThreads>(sc, &total, lds);
+    agg[0] = total;
+    const uint64_t local_p = block_exclusive_scan64<kRowScanThreads>(sp, &total, lds);
+    agg[1] = total;
+    (void)block_exclusive_scan64<kRowScanThreads>(cand, &total, lds);
+    agg[2] = total;
+    (void)unused;
+    chain_exclusive_prefix(slots, epoch, agg, prefix, lds + kRowScanThreads / 64, d_scalars + S_INTERNAL);
+    uint64_t run_c = prefix[0] + local_c, run_p = prefix[1] + local_p;
+#pragma unroll
+    for (int k = 0; k < kRowScanItems; ++k) {
+        if (i0 + k < ntr) {
+            c_tile_row_ptr[i0 + k] = (int32_t)run_c;
+            row_pair_ptr[i0 + k] = (int64_t)run_p;
+        }
+        run_c += (uint32_t)xc[k];
+        run_p += (uint32_t)xp[k];
+    }
+    // The last block of the chain has taken in, directly or through the blocks before it, the sums of all
+    // others, each released after its block's atomics: it writes the totals and hands the scalar block
+    // to the host.
+    if (blockIdx.x == gridDim.x - 1) {
+        if (threadIdx.x == 0) {
             c_tile_row_ptr[ntr] = (int32_t)(prefix[0] + agg[0]);
             row_pair_ptr[ntr] = (int64_t)(prefix[1] + agg[1]);
             d_scalars[S_C_TILES] = (int64_t)(prefix[0] + agg[0]);
             d_scalars[S_PAIRS] = (int64_t)(prefix[1] + agg[1]);
             d_scalars[S_CANDIDATES] = (int64_t)(prefix[2] + agg[2]);
         }
+        publish_scalars(d_scalars, h_scalars_dev, publish_tag);
     }
 }
 
@@ -848,7 +856,8 @@ __global__ __launch_bounds__(256) void k_count_masks(int64_t c_tiles, const int6
 // tile-row and also leaves nnz(C) and the largest tile-row.
 __global__ __launch_bounds__(256) void k_row_ptr(const int32_t *__restrict__ row_nnz, int64_t c_rows,
                                                  const uint32_t *__restrict__ tile_row_entries, int64_t c_tile_rows,
-                                                 int64_t *__restrict__ c_row_ptr, int64_t *d_scalars) {
+                                                 int64_t *__restrict__ c_row_ptr, int64_t *d_scalars,
+                                                 int64_t *h_scalars_dev, int64_t publish_tag) {
     __shared__ uint64_t lds[256 / 64];
     constexpr int kItems = kChunkRows / 256;
     const bool last = blockIdx.x == gridDim.x - 1;
@@ -902,6 +911,8 @@ __global__ __launch_bounds__(256) void k_row_ptr(const int32_t *__restrict__ row
             d_scalars[S_C_NNZ] = (int64_t)(entries_before + total);
             d_scalars[S_MAX_ROW_ENTRIES] = (int64_t)largest;
         }
+        // no other block of this launch writes a scalar, and the kernels before it have finished
+        publish_scalars(d_scalars, h_scalars_dev, publish_tag);
     }
 }
 
@@ -1063,10 +1074,10 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
         if (!slots) return cleanup(TSP_ERR_ALLOC_FAILED);
         hipLaunchKernelGGL(k_sym_row_scan, dim3((unsigned)blocks), dim3(kRowScanThreads), 0, s, ntr, row_c_tiles,
                            row_pairs, row_words, row_cand, P->c_tile_row_ptr, row_pair_ptr, slots, epoch,
-                           ctx->d_scalars, ca, cb);
+                           ctx->d_scalars, ca, cb, ctx->h_scalars_dev, ++ctx->publish_tag);
         SYM_CHECK(hipGetLastError());
     }
-    if (!rc) rc = read_scalars(ctx, s);                                    // ---- sync 1: sizes of the task list
+    if (!rc) rc = wait_published_scalars(ctx, ctx->publish_tag, s);        // ---- sync 1: sizes of the task list
     if (rc) return cleanup(rc);
     const int64_t *h = ctx->h_scalars;
     if (h[S_INVALID]) return cleanup(TSP_ERR_NOT_CANONICAL);
@@ -1151,19 +1162,21 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
                            P->c_row_mask, P->c_row_off, row_nnz, ctx->d_scalars, tile_row_entries);
     }
     SYM_CHECK(hipGetLastError());
+    bool published = false;                        // k_row_ptr puts the scalar block into the host's mirror
     {
         KernelTimer kt(ctx, TSP_KERNEL_SCAN_ROWS, s);
         if (n_chunks > 0 && n_chunks <= kMaxChunks) {
             hipLaunchKernelGGL(k_row_ptr, dim3((unsigned)n_chunks), dim3(256), 0, s, row_nnz, P->c_rows, tile_row_entries,
-                               ntr, P->c_row_ptr, ctx->d_scalars);
+                               ntr, P->c_row_ptr, ctx->d_scalars, ctx->h_scalars_dev, ++ctx->publish_tag);
             SYM_CHECK(hipGetLastError());
+            published = true;
         } else {
             rc = scan_exclusive_i32_to_i64(ctx, row_nnz, P->c_row_ptr, P->c_rows, ctx->d_scalars + S_C_NNZ,
                                            ctx->d_scalars + S_MAX_ROW_ENTRIES, tmp, s);
         }
     }
     phase_end(ctx, TSP_PHASE_COUNT, s);
-    if (!rc) rc = read_scalars(ctx, s);                                    // ---- sync 2: nnz(C)
+    if (!rc) rc = published ? wait_published_scalars(ctx, ctx->publish_tag, s) : read_scalars(ctx, s);   // ---- sync 2: nnz(C)
     if (rc) return cleanup(rc);
     if (ctx->h_scalars[S_UNSUPPORTED]) return cleanup(TSP_ERR_UNSUPPORTED);
     if (ctx->h_scalars[S_INTERNAL]) return cleanup(TSP_ERR_HIP);
