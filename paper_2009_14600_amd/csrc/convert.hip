@@ -16,7 +16,9 @@
 //      follow the two group masks (which 8-element row pieces / column pieces are non-empty) and,
 //      by a prefix sum inside the tile-row, the group offsets;
 //   3. the groups are zeroed and every entry stores its value into its slot of the left-form and
-//      of the right-form group of its tile.
+//      of the right-form group of its tile: in LDS, from where the groups are written out whole, when
+//      a block owns the tile-row and the groups of a window of tiles fit the staging area; in memory
+//      otherwise.
 // The element storage is laid out for the matrix-core operand registers (see tsp_tiles_view in
 // tsp.h).  Tile-rows whose tile columns span more than the LDS bitmap take a second path: 16 lanes
 // merge the 16 sorted rows, one tile per step (any span, one tile at a time).
@@ -39,14 +41,18 @@ template <int G> constexpr int conv_block_threads() { return G == 64 ? 256 : G; 
 template <> struct ConvCfg<64> {                  // one wave per tile-row, four tile-rows per block
     static constexpr int kWords = 512;            // bitmap words: tile columns may span 16384
     static constexpr int kWindow = 32;            // tiles handled per pass over the entries
+    static constexpr int kStage = 0;              // element groups a window may assemble in LDS (0: none; this
+                                                  // kernel lives on blocks per CU, and LDS decides how many)
 };
 template <> struct ConvCfg<128> {                 // one 128-thread block per tile-row
     static constexpr int kWords = 1024;
     static constexpr int kWindow = 64;
+    static constexpr int kStage = 512;
 };
 template <> struct ConvCfg<256> {                 // one 256-thread block per tile-row
     static constexpr int kWords = 1024;           // span of 32768 tile columns
     static constexpr int kWindow = 128;
+    static constexpr int kStage = 1024;
 };
 
 __device__ __forceinline__ uint16_t to_half_bits(uint16_t v) { return v; }
@@ -139,6 +145,9 @@ __device__ __forceinline__ uint32_t group_exclusive_scan(uint32_t *arr, int n, i
 template <int G, int kConvCache, typename RP, typename VT>
 __device__ __forceinline__ void convert_rows(const ConvArgs<RP, VT> &a) {
     constexpr int kWords = ConvCfg<G>::kWords, kWindow = ConvCfg<G>::kWindow, kGroups = conv_block_threads<G>() / G;
+    constexpr int kStage = ConvCfg<G>::kStage;
+    static_assert(kStage == 0 || kGroups == 1, "the staging area belongs to one tile-row");
+    __shared__ uint4 s_stage[kStage > 0 ? kStage : 1];
     __shared__ int s_rp_all[kGroups][20];
     __shared__ uint32_t s_bm_all[kGroups][kWords], s_pre_all[kGroups][kWords];
     __shared__ uint32_t s_mask_all[kGroups][kWindow * 8];
@@ -290,6 +299,35 @@ __device__ __forceinline__ void convert_rows(const ConvArgs<RP, VT> &a) {
             ++t;
         }
     }
+    // Entries held in registers: from here on only the tile, the row and the column inside the tile of an
+    // entry are needed, so the column register takes those three (tile << 8 | row << 4 | column % 16) and
+    // the later passes look nothing up again.  (A tile-row in registers has at most G*kConvCache <= 2^23 tiles.)
+    // Not in the one-wave kernels: there the lookups are cheaper than the registers the packing costs.
+    constexpr bool kPlaced = G > 64;
+    if (kPlaced && cached) {
+#pragma unroll
+        for (int k = 0; k < kConvCache; ++k) {
+            const int64_t e = e0 + gt + (int64_t)k * G;
+            if (e < e1) c_reg[k] = (tile_rank(c_reg[k]) << 8) | (row_of(e) << 4) | (c_reg[k] & 15);
+        }
+    }
+    // f(tile of the entry, row inside the tile, column inside the tile, value) for every entry of this thread
+    auto for_each_placed_entry = [&](auto f) {
+        if (cached) {
+#pragma unroll
+            for (int k = 0; k < kConvCache; ++k) {
+                const int64_t e = e0 + gt + (int64_t)k * G;
+                if (e >= e1) continue;
+                if (kPlaced) f(c_reg[k] >> 8, (c_reg[k] >> 4) & 15, c_reg[k] & 15, v_reg[k]);
+                else f(tile_rank(c_reg[k]), row_of(e), c_reg[k] & 15, v_reg[k]);
+            }
+        } else {
+            for (int64_t e = e0 + gt; e < e1; e += G) {
+                const int c = a.col[e];
+                f(tile_rank(c), row_of(e), c & 15, a.val[e]);
+            }
+        }
+    };
     // A tile-row with more tiles than a window holds, and too many entries for the registers, would
     // read all its entries again for every window.  Its CSR rows are sorted by column, so the entries of
     // a window of tiles are one stretch of every row: each window walks the 16 rows from where the
@@ -397,12 +435,9 @@ __device__ __forceinline__ void convert_rows(const ConvArgs<RP, VT> &a) {
         // 2. row masks of the tiles of this window
         for (int k = gt; k < nw * 8; k += G) s_mask[k] = 0;
         group_sync<G>();
-        for_each_entry([&](int64_t e, int c, VT, int) {
-            const int t = tile_rank(c) - win0;
-            if (t >= 0 && t < nw) {
-                const int r = row_of(e);
-                atomicOr(&s_mask[t * 8 + (r >> 1)], 1u << ((r & 1) * 16 + (c & 15)));
-            }
+        for_each_placed_entry([&](int tile, int r, int cc, VT) {
+            const int t = tile - win0;
+            if (t >= 0 && t < nw) atomicOr(&s_mask[t * 8 + (r >> 1)], 1u << ((r & 1) * 16 + cc));
         });
         group_sync<G>();
         for (int t = gt; t < nw; t += G) {
@@ -423,14 +458,22 @@ __device__ __forceinline__ void convert_rows(const ConvArgs<RP, VT> &a) {
         group_sync<G>();
         const uint32_t ltot = group_exclusive_scan<G>(s_lo, nw, s_red);
         const uint32_t rtot = group_exclusive_scan<G>(s_ro, nw, s_red);
-        // the window's groups are zeroed; the entries drop their values into their slots below
+        // Where the window's groups fit the staging area they are put together in LDS and written out whole
+        // (no wait for zeros to reach L2, no two-byte stores to memory).
+        const uint32_t lstage = (a.forms & TSP_FORM_LEFT) ? ltot : 0u, rstage = (a.forms & TSP_FORM_RIGHT) ? rtot : 0u;
+        const bool staged = kStage > 0 && lstage + rstage <= (uint32_t)kStage;      // uniform over the group
+        // otherwise the groups are zeroed in memory and the entries drop their values into their slots below
         const uint4 zero = make_uint4(0, 0, 0, 0);
+        if (staged) {
+            for (uint32_t g = gt; g < lstage + rstage; g += G) s_stage[g] = zero;
+        } else {
         if (a.forms & TSP_FORM_LEFT)
             for (int64_t g = (int64_t)lrun + gt, end = min((int64_t)lrun + ltot, a.group_capacity); g < end; g += G)
                 a.ldata[g] = zero;
         if (a.forms & TSP_FORM_RIGHT)
             for (int64_t g = (int64_t)rrun + gt, end = min((int64_t)rrun + rtot, a.group_capacity); g < end; g += G)
                 a.rdata[g] = zero;
+        }
         // tile headers and bitmaps
         for (int t = gt; t < nw; t += G) {
             const int64_t tg = t0 + win0 + t;
@@ -444,15 +487,41 @@ __device__ __forceinline__ void convert_rows(const ConvArgs<RP, VT> &a) {
                 if (a.forms & TSP_FORM_RIGHT) a.rhead[tg] = make_uint2(s_rm[t], rrun + s_ro[t]);
             }
         }
+        if (staged) {
+            group_sync<G>();
+            uint16_t *const stage16 = reinterpret_cast<uint16_t *>(s_stage);
+            for_each_placed_entry([&](int tile, int r, int cc, VT value) {
+                const int t = tile - win0;
+                if (t >= 0 && t < nw) {
+                    const uint16_t v = to_half_bits(value);
+                    if (a.forms & TSP_FORM_LEFT) {
+                        const int g = (cc >> 3) * 16 + r;
+                        stage16[(s_lo[t] + __popc(s_lm[t] & ((1u << g) - 1u))) * 8 + (cc & 7)] = v;
+                    }
+                    if (a.forms & TSP_FORM_RIGHT) {
+                        const int g = (r >> 3) * 16 + cc;
+                        stage16[(lstage + s_ro[t] + __popc(s_rm[t] & ((1u << g) - 1u))) * 8 + (r & 7)] = v;
+                    }
+                }
+            });
+            group_sync<G>();
+            for (uint32_t g = gt; g < lstage; g += G)
+                if ((int64_t)lrun + g < a.group_capacity) a.ldata[(int64_t)lrun + g] = s_stage[g];
+            for (uint32_t g = gt; g < rstage; g += G)
+                if ((int64_t)rrun + g < a.group_capacity) a.rdata[(int64_t)rrun + g] = s_stage[lstage + g];
+            lrun += ltot;
+            rrun += rtot;
+            group_sync<G>();
+            continue;
+        }
         // the zeros must be in L2 before any value is stored over them: every wave waits for its own
         // stores, then the group meets
         __builtin_amdgcn_s_waitcnt(0x0F70);
         group_sync<G>();
         // 3. values
-        for_each_entry([&](int64_t e, int c, VT value, int) {
-            const int t = tile_rank(c) - win0;
+        for_each_placed_entry([&](int tile, int r, int cc, VT value) {
+            const int t = tile - win0;
             if (t >= 0 && t < nw) {
-                const int r = row_of(e), cc = c & 15;
                 const uint16_t v = to_half_bits(value);
                 if (a.forms & TSP_FORM_LEFT) {
                     const int g = (cc >> 3) * 16 + r;
