@@ -596,23 +596,33 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_emit(
     }
 }
 
-typedef unsigned short ushort2v __attribute__((ext_vector_type(2)));
 // OR over the set bits k of `am` of row mask k of the B tile; x, y hold the 16 row masks, two per
-// 32-bit word (row 2i in the low half).  Each word is multiplied, half by half, with the two bits
-// (0 or 1) of `am` that select its rows: one packed 16-bit multiply does the selection of two rows.
-__device__ __forceinline__ uint32_t boolean_row_product(uint32_t am, const uint4 &x, const uint4 &y) {
-    const uint32_t w[8] = {x.x, x.y, x.z, x.w, y.x, y.y, y.z, y.w};
-    const uint32_t am2 = am | ((am >> 1) << 16);              // bit 2i+1 of am sits at bit 16+2i
-    uint32_t acc = 0;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const uint32_t sel = (am2 >> (2 * i)) & 0x00010001u;   // low half: bit 2i of am, high half: bit 2i+1
-        union { uint32_t u; ushort2v v; } a, b, r;
-        a.u = w[i];
-        b.u = sel;
-        r.v = a.v * b.v;
-        acc |= r.u;
+// 32-bit word (row 2i in the low half).  Four bits of `am` select among four rows, i.e. two words: the
+// two AND masks (all ones in the half whose row is selected) come from a 16-entry table in LDS, so a
+// word costs one and-or, and a nibble two instructions for its table address.  Entries of the table
+// are 8 bytes: 16 of them cover every LDS bank once, and lanes with the same nibble read the same address.
+struct RowSelectTable {
+    uint2 entry[16];
+    __device__ __forceinline__ void fill() {       // by the first 16 threads of the block; a barrier follows
+        if (threadIdx.x < 16) {
+            const uint32_t v = threadIdx.x;
+            entry[v] = make_uint2(((v & 1u) ? 0x0000FFFFu : 0u) | ((v & 2u) ? 0xFFFF0000u : 0u),
+                                  ((v & 4u) ? 0x0000FFFFu : 0u) | ((v & 8u) ? 0xFFFF0000u : 0u));
+        }
     }
+};
+__device__ __forceinline__ uint32_t boolean_row_product(uint32_t am, const uint4 &x, const uint4 &y,
+                                                        const RowSelectTable &table) {
+    const uint2 m0 = table.entry[am & 15u], m1 = table.entry[(am >> 4) & 15u];
+    const uint2 m2 = table.entry[(am >> 8) & 15u], m3 = table.entry[(am >> 12) & 15u];
+    uint32_t acc = x.x & m0.x;
+    acc |= x.y & m0.y;
+    acc |= x.z & m1.x;
+    acc |= x.w & m1.y;
+    acc |= y.x & m2.x;
+    acc |= y.y & m2.y;
+    acc |= y.z & m3.x;
+    acc |= y.w & m3.y;
     return acc;
 }
 
@@ -639,6 +649,9 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_emit_listed(
     extern __shared__ uint32_t lds_dyn[];
     __shared__ uint32_t red[32];
     __shared__ int s_n;
+    __shared__ RowSelectTable row_select;
+    __shared__ uint32_t s_part[kSymThreads / 16][T];
+    if (kFuseMasks) row_select.fill();               // (many barriers before its first use)
     uint32_t *bm = lds_dyn;
     uint32_t *wpre = bm + words_cap;
     uint32_t *contrib = wpre + words_cap;
@@ -750,49 +763,62 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_emit_listed(
         for (int k0 = g * kPairsPerTrip; k0 < n; k0 += groups * kPairsPerTrip) {
             uint32_t am[kPairsPerTrip];
             uint4 x[kPairsPerTrip], y[kPairsPerTrip];
+            int c_of[kPairsPerTrip];
+            // (a trip past the end of the list reads the last entry again and selects nothing of it: no
+            // branches and no zero-filled registers around the loads)
 #pragma unroll
             for (int u = 0; u < kPairsPerTrip; ++u) {
-                am[u] = 0;
-                x[u] = y[u] = make_uint4(0, 0, 0, 0);
-                if (k0 + u < n) {
-                    am[u] = a_row_mask[(int64_t)list_a[k0 + u] * T + r];
-                    const uint4 *bp = reinterpret_cast<const uint4 *>(b_row_mask + (int64_t)list_b[k0 + u] * T);
-                    x[u] = bp[0];
-                    y[u] = bp[1];
-                }
+                const int k = min(k0 + u, n - 1);
+                am[u] = a_row_mask[(int64_t)list_a[k] * T + r];
+                const uint4 *bp = reinterpret_cast<const uint4 *>(b_row_mask + (int64_t)list_b[k] * T);
+                x[u] = bp[0];
+                y[u] = bp[1];
+                c_of[u] = list_c[k];
             }
 #pragma unroll
             for (int u = 0; u < kPairsPerTrip; ++u) {
-                if (k0 + u < n) {
-                    const uint32_t m = boolean_row_product(am[u], x[u], y[u]);
-                    const uint32_t m16 = (m | (m >> 16)) & 0xFFFFu;
-                    if (m16) atomicOr(&cmask[list_c[k0 + u] * 8 + (r >> 1)], m16 << ((r & 1) * 16));
-                }
+                const uint32_t m = boolean_row_product(k0 + u < n ? am[u] : 0u, x[u], y[u], row_select);
+                const uint32_t m16 = (m | (m >> 16)) & 0xFFFFu;
+                if (m16) atomicOr(&cmask[c_of[u] * 8 + (r >> 1)], m16 << ((r & 1) * 16));
             }
         }
     }
     __syncthreads();
     uint32_t *out_words = reinterpret_cast<uint32_t *>(c_row_mask) + (int64_t)c0 * 8;
     for (int w = threadIdx.x; w < nC * 8; w += nthreads) out_words[w] = cmask[w];
-    // ... and what k_row_offsets does for this tile-row: lane r takes CSR row 16I+r
-    if (threadIdx.x < T) {
-        const int r = threadIdx.x, word = r >> 1, shift = (r & 1) * 16;
-        uint32_t total = 0;
-        for (int c = 0; c < nC; ++c) total += __popc((cmask[c * 8 + word] >> shift) & 0xFFFFu);
-        const int64_t row = (int64_t)I * T + r;
-        if (row < c_rows) row_nnz[row] = (int32_t)total;
+    // ... and what k_row_offsets does for this tile-row: lane r of every 16-lane group takes CSR row
+    // 16I+r for a stretch of the C tiles, the groups' sums are exchanged through LDS.
+    {
+        const int g = threadIdx.x >> 4, r = threadIdx.x & 15, groups = nthreads >> 4;
+        const int word = r >> 1, shift = (r & 1) * 16;
+        const int stretch = (nC + groups - 1) / groups;
+        const int cb = min(nC, g * stretch), ce = min(nC, cb + stretch);
+        uint32_t part = 0;
+        for (int c = cb; c < ce; ++c) part += __popc((cmask[c * 8 + word] >> shift) & 0xFFFFu);
+        s_part[g][r] = part;
+        __syncthreads();
+        uint32_t total = 0, earlier = 0;           // entries of row r in the tile-row, and in the stretches before this one
+        for (int h = 0; h < groups; ++h) {
+            const uint32_t v = s_part[h][r];
+            total += v;
+            earlier += h < g ? v : 0u;
+        }
         uint64_t before = total;                   // inclusive prefix over the 16 rows
 #pragma unroll
         for (int d = 1; d < T; d <<= 1) {
             const uint64_t up = __shfl_up(before, d, T);
             if (r >= d) before += up;
         }
-        if (r == T - 1) {
-            if (before > 0xFFFFFFFFull) d_scalars[S_UNSUPPORTED] = 1;
-            tile_row_entries[I] = (uint32_t)before;
+        if (g == 0) {
+            const int64_t row = (int64_t)I * T + r;
+            if (row < c_rows) row_nnz[row] = (int32_t)total;
+            if (r == T - 1) {
+                if (before > 0xFFFFFFFFull) d_scalars[S_UNSUPPORTED] = 1;
+                tile_row_entries[I] = (uint32_t)before;
+            }
         }
-        uint32_t run = (uint32_t)(before - total);
-        for (int c = 0; c < nC; ++c) {
+        uint32_t run = (uint32_t)(before - total) + earlier;
+        for (int c = cb; c < ce; ++c) {
             c_row_off[(int64_t)(c0 + c) * T + r] = run;
             run += __popc((cmask[c * 8 + word] >> shift) & 0xFFFFu);
         }
@@ -813,6 +839,9 @@ __global__ __launch_bounds__(256) void k_count_masks(int64_t c_tiles, const int6
     // one mask and reads all 16 back (two 16-byte LDS loads instead of two 16-byte global loads per
     // lane: the kernel is bound by the vector-memory address path, not by LDS)
     __shared__ uint4 lds_b[256 / 16][4][2];
+    __shared__ RowSelectTable row_select;
+    row_select.fill();
+    __syncthreads();
     const int per_xcd = gridDim.x / 8;
     const int64_t logical = (int64_t)(blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
     const int64_t c = (logical * blockDim.x + threadIdx.x) >> 4;
@@ -845,7 +874,7 @@ __global__ __launch_bounds__(256) void k_count_masks(int64_t c_tiles, const int6
             for (int u = 0; u < 4; ++u) reinterpret_cast<uint16_t *>(mine[u])[r] = (uint16_t)bm[u];
             wave_sync();
 #pragma unroll
-            for (int u = 0; u < 4; ++u) acc |= boolean_row_product(am[u], mine[u][0], mine[u][1]);
+            for (int u = 0; u < 4; ++u) acc |= boolean_row_product(am[u], mine[u][0], mine[u][1], row_select);
         }
     }
     if (in) c_row_mask[c * T + r] = (uint16_t)((acc | (acc >> 16)) & 0xFFFFu);
