@@ -754,8 +754,8 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_emit_listed(
     if constexpr (!kFuseMasks) return;
     // Counting pass (Section 4.2) for the tile-row's C tiles, from the same list: 16 lanes per pair, lane
     // r forms row r of the boolean product of the two bitmaps and ORs it into the C tile's bitmap in LDS.
-    // kPairsPerTrip pairs per trip, their bitmaps requested together (the pass is bound by its vector ALU
-    // work, not by the gathers: four or two per trip take the same time, eight cost registers).
+    // kPairsPerTrip pairs per trip, their bitmaps requested together (four or two per trip take the same
+    // time, eight cost registers).
     for (int w = threadIdx.x; w < nC * 8; w += nthreads) cmask[w] = 0;
     __syncthreads();
     {
