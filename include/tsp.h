@@ -96,9 +96,14 @@ enum {
     TSP_OPT_MATRIX_CORES = 5,  /* 1 (default): block products on the MFMA units (Section 4.3);      */
                                /*    0: on the vector ALUs, one fp32 FMA per inner index and output */
                                /*    element (the paper's comparison build, Section 5, Algorithm 2) */
-    TSP_OPT_COMPACT_ZEROS = 6  /* 1: tsp_spgemm finishes with tsp_compact_zeros (the compaction     */
+    TSP_OPT_COMPACT_ZEROS = 6, /* 1: tsp_spgemm finishes with tsp_compact_zeros (the compaction     */
                                /*    steps that end Algorithm 1); 0 (default): C keeps every        */
                                /*    structural position                                            */
+    TSP_OPT_WORK_ORDER = 7     /* order in which the general task-list kernel takes the tile-rows   */
+                               /*    of C: 1: heaviest first (by candidate pairs, Section 4.1),     */
+                               /*    2: by index, 0 (default): heaviest first where a few tile-rows */
+                               /*    are far heavier than the rest.  The result does not depend on  */
+                               /*    it                                                             */
 };
 
 /* Phases reported in tsp_stats.phase_us, in pipeline order. */

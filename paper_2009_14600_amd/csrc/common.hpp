@@ -51,6 +51,7 @@ struct tsp_context {
     int validate = 1;
     int timers = 0;
     int force_wide = 0;                            // use the 64-bit-pointer kernels whatever the sizes
+    int work_order = 0;                            // TSP_OPT_WORK_ORDER
     int numeric_run_len = 0;                       // tiles per wave of the multiplication kernel, 0: automatic
     int matrix_cores = 1;                          // 0: block products on the vector ALUs
     int compact = 0;                               // 1: tsp_spgemm removes zero-valued entries from C

@@ -233,6 +233,10 @@ extern "C" int tsp_set_option(tsp_handle ctx, int key, int64_t value) {
         case TSP_OPT_WIDE_INDEX: ctx->force_wide = value != 0; return TSP_OK;
         case TSP_OPT_COMPACT_ZEROS: ctx->compact = value != 0; return TSP_OK;
         case TSP_OPT_MATRIX_CORES: ctx->matrix_cores = value != 0; return TSP_OK;
+        case TSP_OPT_WORK_ORDER:
+            if (value < 0 || value > 2) return TSP_ERR_INVALID_ARG;
+            ctx->work_order = (int)value;
+            return TSP_OK;
         case TSP_OPT_NUMERIC_RUN:
             if (value != 0 && value != 4 && value != 8) return TSP_ERR_INVALID_ARG;
             ctx->numeric_run_len = (int)value;

@@ -461,6 +461,59 @@ __global__ __launch_bounds__(kRowScanThreads) void k_sym_row_scan(
     }
 }
 
+// Tile-rows in descending order of work, for products with a few very heavy tile-rows (hubs of a power-law
+// graph): a block per tile-row in index order starts a heavy tile-row in the middle of the range when most
+// of the launch is over, and the launch then waits for that one block.  A counting sort by the power of two
+// of the work (32 buckets, heaviest first; the order inside a bucket is left to the atomics and has no
+// influence on any result: every tile-row writes to places of its own).
+constexpr int kOrderThreads = 256, kOrderItems = 4, kOrderBuckets = 32;
+__device__ __forceinline__ int work_bucket(int32_t work) { return work <= 0 ? 0 : 32 - __clz(work); }   // 0..31
+
+__global__ __launch_bounds__(kOrderThreads) void k_work_hist(int64_t ntr, const int32_t *__restrict__ work,
+                                                             uint32_t *__restrict__ hist) {
+    __shared__ uint32_t lds_hist[kOrderBuckets];
+    if (threadIdx.x < kOrderBuckets) lds_hist[threadIdx.x] = 0;
+    __syncthreads();
+    const int64_t i0 = ((int64_t)blockIdx.x * kOrderThreads + threadIdx.x) * kOrderItems;
+#pragma unroll
+    for (int k = 0; k < kOrderItems; ++k)
+        if (i0 + k < ntr) atomicAdd(&lds_hist[work_bucket(work[i0 + k])], 1u);
+    __syncthreads();
+    if (threadIdx.x < kOrderBuckets && lds_hist[threadIdx.x]) atomicAdd(&hist[threadIdx.x], lds_hist[threadIdx.x]);
+}
+
+// hist: the finished histogram; taken: 32 zeroed counters (places handed out per bucket so far)
+__global__ __launch_bounds__(kOrderThreads) void k_work_order(int64_t ntr, const int32_t *__restrict__ work,
+                                                              const uint32_t *__restrict__ hist,
+                                                              uint32_t *__restrict__ taken, int32_t *__restrict__ order) {
+    __shared__ uint32_t lds_count[kOrderBuckets], lds_base[kOrderBuckets];
+    if (threadIdx.x < kOrderBuckets) lds_count[threadIdx.x] = 0;
+    __syncthreads();
+    const int64_t i0 = ((int64_t)blockIdx.x * kOrderThreads + threadIdx.x) * kOrderItems;
+    int bucket[kOrderItems];
+    uint32_t rank[kOrderItems];
+#pragma unroll
+    for (int k = 0; k < kOrderItems; ++k) {
+        bucket[k] = i0 + k < ntr ? work_bucket(work[i0 + k]) : -1;
+        rank[k] = bucket[k] >= 0 ? atomicAdd(&lds_count[bucket[k]], 1u) : 0u;
+    }
+    __syncthreads();
+    if (threadIdx.x < kOrderBuckets) {
+        // first place of the bucket: after all heavier buckets; then this block's share of it
+        uint32_t heavier = 0;
+        for (int b = (int)threadIdx.x + 1; b < kOrderBuckets; ++b) heavier += hist[b];
+        const uint32_t mine = lds_count[threadIdx.x];
+        lds_base[threadIdx.x] = heavier + (mine ? atomicAdd(&taken[threadIdx.x], mine) : 0u);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < kOrderItems; ++k)
+        if (bucket[k] >= 0) {
+            const uint32_t at = lds_base[bucket[k]] + rank[k];
+            if (at < (uint32_t)ntr) order[at] = (int32_t)(i0 + k);     // (always, unless `work` changed between the two launches)
+        }
+}
+
 // Pass 2 per tile-row: C tile coordinates, task-list offsets, task list.
 // Dynamic LDS: 2*words_cap + 2*window words.  Tile-rows with more C tiles than the window holds take
 // several windows; `cursor` (one word per tile of A, nullptr when no tile-row needs it) carries their
@@ -471,16 +524,18 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_emit(
     const int32_t *__restrict__ row_jmin, const int32_t *__restrict__ row_words,
     const int32_t *__restrict__ c_tile_row_ptr, const int64_t *__restrict__ row_pair_ptr,
     int32_t *__restrict__ c_tile_row, int32_t *__restrict__ c_tile_col, int64_t *__restrict__ pair_off,
-    int32_t *__restrict__ pair_a, int32_t *__restrict__ pair_b, int32_t *cursor, int64_t A_capacity) {
+    int32_t *__restrict__ pair_a, int32_t *__restrict__ pair_b, int32_t *cursor, int64_t A_capacity,
+    const int32_t *__restrict__ order) {
     extern __shared__ uint32_t lds_dyn[];
     __shared__ uint32_t red[32];
     uint32_t *bm = lds_dyn;
     uint32_t *wpre = bm + words_cap;
     uint32_t *contrib = wpre + words_cap;
     uint32_t *cnt = contrib + window;
-    const int I = blockIdx.x;
+    // block b takes tile-row b, or the tile-row the host's order of work puts in place b
+    const int I = order ? min(max(order[blockIdx.x], 0), (int)gridDim.x - 1) : (int)blockIdx.x;
     const int c0 = c_tile_row_ptr[I], nC = c_tile_row_ptr[I + 1] - c0;
-    if (I == (int)gridDim.x - 1 && threadIdx.x == 0) pair_off[c_tile_row_ptr[gridDim.x]] = row_pair_ptr[gridDim.x];
+    if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) pair_off[c_tile_row_ptr[gridDim.x]] = row_pair_ptr[gridDim.x];
     if (nC <= 0 || (nC > window && !cursor)) return;      // (the host provides the cursors whenever a tile-row needs them)
     const int a0 = A.trp[I], a1 = A.tend[I];
     const int jmin = row_jmin[I];
@@ -1043,7 +1098,8 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
     int32_t *row_jmin = nullptr, *row_c_tiles = nullptr, *row_pairs = nullptr, *row_nnz = nullptr;
     uint32_t *tile_row_entries = nullptr;
     int32_t *row_words = nullptr, *row_cand = nullptr;
-    int32_t *cursor = nullptr;
+    int32_t *cursor = nullptr, *order = nullptr;
+    uint32_t *order_hist = nullptr;
     int64_t *row_pair_ptr = nullptr, *tmp = nullptr;
     auto cleanup = [&](int code) {
         ctx_free(ctx, row_jmin, s);
@@ -1052,6 +1108,8 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
         ctx_free(ctx, row_words, s);
         ctx_free(ctx, row_cand, s);
         ctx_free(ctx, cursor, s);
+        ctx_free(ctx, order, s);
+        ctx_free(ctx, order_hist, s);
         ctx_free(ctx, row_nnz, s);
         ctx_free(ctx, tile_row_entries, s);
         ctx_free(ctx, row_pair_ptr, s);
@@ -1190,12 +1248,27 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
                                row_pair_ptr, P->c_tile_row, P->c_tile_col, P->pair_off, P->pair_a, P->pair_b,
                                A->row_mask, B->row_mask, P->c_row_mask, P->c_row_off, row_nnz, P->c_rows,
                                ctx->d_scalars, tile_row_entries);
-        } else
+        } else {
+            // a few tile-rows far heavier than the rest (and enough work for two small launches to pay):
+            // the heaviest go first
+            const bool skewed =
+                ntr >= 1024 && P->candidates >= (int64_t)1 << 22 && h[S_MAX_ROW_PAIRS] > 8 * (P->pairs / ntr + 1);
+            if (ctx->work_order == 1 || (ctx->work_order == 0 && skewed)) {
+                order = ctx_alloc_n<int32_t>(ctx, (size_t)ntr, s);
+                order_hist = ctx_alloc_n<uint32_t>(ctx, 2 * kOrderBuckets, s);
+                if (!order || !order_hist) return cleanup(TSP_ERR_ALLOC_FAILED);
+                SYM_CHECK(hipMemsetAsync(order_hist, 0, 2 * kOrderBuckets * sizeof(uint32_t), s));
+                const unsigned grid = (unsigned)((ntr + kOrderThreads * kOrderItems - 1) / (kOrderThreads * kOrderItems));
+                hipLaunchKernelGGL(k_work_hist, dim3(grid), dim3(kOrderThreads), 0, s, ntr, row_cand, order_hist);
+                hipLaunchKernelGGL(k_work_order, dim3(grid), dim3(kOrderThreads), 0, s, ntr, row_cand, order_hist,
+                                   order_hist + kOrderBuckets, order);
+            }
             hipLaunchKernelGGL(long_rows ? k_sym_emit<true> : k_sym_emit<false>, dim3((unsigned)ntr), dim3(threads),
                                lds, s, ra, rb, lanes, words_cap, window, row_jmin, row_words,
                                P->c_tile_row_ptr,
                                row_pair_ptr, P->c_tile_row, P->c_tile_col, P->pair_off, P->pair_a, P->pair_b, cursor,
-                               A->tile_capacity);
+                               A->tile_capacity, order);
+        }
         SYM_CHECK(hipGetLastError());
     } else {
         SYM_CHECK(hipMemsetAsync(P->pair_off, 0, sizeof(int64_t), s));

@@ -451,6 +451,45 @@ def test_tile_rows_with_more_output_tiles_than_the_symbolic_window(tsp, handle, 
     C.free()
 
 
+# ------------------------------------------------------------------ heaviest tile-rows first
+def test_tile_rows_taken_in_order_of_work(tsp, oracle):
+    """The general task-list kernel with its blocks taking the tile-rows heaviest first (forced here; on
+    its own the library does that only for large skewed products): a power-law graph, whose hub
+    tile-rows are spread over the index range, and a wide product with more tile-rows than one block of
+    the ordering kernels covers.  Same result as by index, and as the oracle's."""
+    ordered = _variant_handle(tsp, OPT_WORK_ORDER=1)
+    by_index = _variant_handle(tsp, OPT_WORK_ORDER=2)
+    try:
+        G = inputs.rmat(scale=11, edge_factor=12, seed=2024)
+        print(f"work order: R-MAT scale 11, nnz {G.nnz}", flush=True)
+        dG = tsp.to_device(G)
+        C1 = ordered.spgemm(dG, dG)
+        assert ordered.stats()["pairs"] > 0
+        C2 = by_index.spgemm(dG, dG)
+        for x, y in zip(C1.to_host(), C2.to_host()):
+            assert np.array_equal(x, y)
+        assert_matches_oracle(C1, oracle.spgemm(G, G, threads=4), "R-MAT, heaviest tile-rows first")
+        C1.free()
+        C2.free()
+        # 18000 rows: 1125 tile-rows (two blocks of the ordering kernels, the second ragged), of which one
+        # in 50 is heavy; a tile-row with thousands of candidate pairs keeps the list kernel out
+        rng = np.random.default_rng(91)
+        M, K, N = 18000, 600, 3000
+        heavy = np.arange(0, M, 50 * 16)[:, None] + np.arange(16)[None, :]
+        heavy = heavy[heavy < M]
+        rows = np.concatenate([np.repeat(np.arange(M), 2), np.repeat(heavy, 200)])
+        cols = np.concatenate([rng.integers(0, K, 2 * M), rng.integers(0, K, 200 * heavy.size)])
+        keys = np.unique(rows * K + cols)                                  # no duplicate positions
+        rows, cols = keys // K, keys % K
+        A = inputs.from_coo(M, K, rows, cols, rng.integers(1, 4, rows.size).astype(np.float64), "skewed rows")
+        B = inputs.random_sparse(K, N, 0.05, 92, values="smallint")
+        print(f"work order: skewed {M}x{K}x{N}, nnz(A) {A.nnz}", flush=True)
+        run_and_check(tsp, ordered, oracle, A, B)
+    finally:
+        ordered.close()
+        by_index.close()
+
+
 # ------------------------------------------------------------------ variants of the multiplication kernel
 def _variant_handle(tsp, **options):
     h = tsp.Handle(validate=True)
