@@ -1061,6 +1061,53 @@ __global__ __launch_bounds__(256) void k_row_offsets(int64_t c_tile_rows, int64_
     }
 }
 
+// The same for tile-rows with many tiles: a block per tile-row, its 16 lane groups each take a stretch of
+// the tiles and exchange their sums through LDS (a hub tile-row of a power-law graph has tens of
+// thousands of tiles, which one lane group would walk twice on its own).
+__global__ __launch_bounds__(256) void k_row_offsets_wide(int64_t c_rows, const int32_t *__restrict__ c_tile_row_ptr,
+                                                          const uint16_t *__restrict__ c_row_mask,
+                                                          uint32_t *__restrict__ c_row_off,
+                                                          int32_t *__restrict__ row_nnz, int64_t *d_scalars,
+                                                          uint32_t *__restrict__ tile_row_entries) {
+    __shared__ uint32_t s_part[256 / 16][T];
+    const int64_t I = blockIdx.x;
+    const int g = threadIdx.x >> 4, r = threadIdx.x & 15;
+    constexpr int kGroups = 256 / 16;
+    const int64_t c0 = c_tile_row_ptr[I], c1 = c_tile_row_ptr[I + 1];
+    const int64_t stretch = (c1 - c0 + kGroups - 1) / kGroups;
+    const int64_t cb = min(c1, c0 + g * stretch), ce = min(c1, cb + stretch);
+    uint32_t part = 0;
+    for (int64_t c = cb; c < ce; ++c) part += __popc(c_row_mask[c * T + r]);
+    s_part[g][r] = part;
+    __syncthreads();
+    uint32_t total = 0, earlier = 0;
+#pragma unroll
+    for (int h = 0; h < kGroups; ++h) {
+        const uint32_t v = s_part[h][r];
+        total += v;
+        earlier += h < g ? v : 0u;
+    }
+    uint64_t before = total;                       // inclusive prefix over the 16 rows
+#pragma unroll
+    for (int d = 1; d < T; d <<= 1) {
+        const uint64_t up = __shfl_up(before, d, T);
+        if (r >= d) before += up;
+    }
+    if (g == 0) {
+        const int64_t row = I * T + r;
+        if (row < c_rows) row_nnz[row] = (int32_t)total;
+        if (r == T - 1) {
+            if (before > 0xFFFFFFFFull) d_scalars[S_UNSUPPORTED] = 1;
+            tile_row_entries[I] = (uint32_t)before;
+        }
+    }
+    uint32_t run = (uint32_t)(before - total) + earlier;
+    for (int64_t c = cb; c < ce; ++c) {
+        c_row_off[c * T + r] = run;
+        run += __popc(c_row_mask[c * T + r]);
+    }
+}
+
 void plan_release(tsp_context *ctx, tsp_plan_s *p, hipStream_t s) {
     if (!p) return;
     ctx_free(ctx, p->c_tile_row_ptr, s);
@@ -1283,10 +1330,14 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
                            A->row_mask, B->row_mask, P->c_row_mask);
     }
     if (ntr > 0 && !fused_masks) {             // (otherwise done by the list kernel as well)
-        const unsigned grid = (unsigned)((ntr * 16 + 255) / 256);
         KernelTimer kt(ctx, TSP_KERNEL_ROW_OFFSETS, s);
-        hipLaunchKernelGGL(k_row_offsets, dim3(grid), dim3(256), 0, s, ntr, P->c_rows, P->c_tile_row_ptr,
-                           P->c_row_mask, P->c_row_off, row_nnz, ctx->d_scalars, tile_row_entries);
+        if (P->c_tiles >= 32 * ntr)                // tile-rows of 32 tiles and more on average: a block each
+            hipLaunchKernelGGL(k_row_offsets_wide, dim3((unsigned)ntr), dim3(256), 0, s, P->c_rows, P->c_tile_row_ptr,
+                               P->c_row_mask, P->c_row_off, row_nnz, ctx->d_scalars, tile_row_entries);
+        else
+            hipLaunchKernelGGL(k_row_offsets, dim3((unsigned)((ntr * 16 + 255) / 256)), dim3(256), 0, s, ntr, P->c_rows,
+                               P->c_tile_row_ptr, P->c_row_mask, P->c_row_off, row_nnz, ctx->d_scalars,
+                               tile_row_entries);
     }
     SYM_CHECK(hipGetLastError());
     bool published = false;                        // k_row_ptr puts the scalar block into the host's mirror
