@@ -90,11 +90,12 @@ __device__ __forceinline__ uint32_t block_exclusive_scan_lds(uint32_t *arr, int 
 // short tile-row of B takes one round trip; otherwise only full trips are batched and the rest goes tile by
 // tile (better where f is heavy: the list kernel, whose f appends to an LDS list, loses 3 % with batching,
 // the other kernels gain 10-30 % of their time).
+// tid, nthreads: this thread's place among the threads that share the tile-row (a block, or part of a wave).
 template <bool kLongRows, bool kBatched, class F>
 __device__ __forceinline__ void for_each_survivor(const TileRefs &A, const TileRefs &B, int a_begin, int a_end,
-                                                  int lanes_per_a, uint32_t *candidates, F f) {
-    const int sub = threadIdx.x / lanes_per_a, l = threadIdx.x % lanes_per_a;
-    const int nsub = blockDim.x / lanes_per_a;
+                                                  int lanes_per_a, uint32_t *candidates, int tid, int nthreads, F f) {
+    const int sub = tid / lanes_per_a, l = tid % lanes_per_a;
+    const int nsub = nthreads / lanes_per_a;
     for (int a = a_begin + sub; a < a_end; a += nsub) {
         const uint32_t K = (uint32_t)A.tcol[a];
         if (K >= (uint32_t)B.tile_rows) continue;            // only possible for a non-canonical input
@@ -142,6 +143,13 @@ __device__ __forceinline__ void for_each_survivor(const TileRefs &A, const TileR
             }
         }
     }
+}
+
+template <bool kLongRows, bool kBatched, class F>
+__device__ __forceinline__ void for_each_survivor(const TileRefs &A, const TileRefs &B, int a_begin, int a_end,
+                                                  int lanes_per_a, uint32_t *candidates, F f) {
+    for_each_survivor<kLongRows, kBatched>(A, B, a_begin, a_end, lanes_per_a, candidates, (int)threadIdx.x,
+                                           (int)blockDim.x, f);
 }
 
 // The same walk, restricted to the B tiles whose tile column is below j_end, for tile-rows of C that are
@@ -338,6 +346,86 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_count(TileRefs A, TileRefs 
         row_pairs[I] = (int32_t)surv;
         row_words[I] = words;
         row_cand[I] = (int32_t)cand;
+    }
+}
+
+// The same pass with two tile-rows per wave (32 lanes each), for operands with short tile-rows: the pass
+// is a chain of dependent gathers, its duration is the number of waves over the waves the chip holds
+// times the length of that chain, and tile-rows with a few dozen candidates leave most lanes of a wave
+// idle anyway.  The two halves of a wave never wait for each other (no block barriers: LDS traffic
+// inside a wave is ordered by wave_sync).  Dynamic LDS: 2*max_words words.
+template <bool kLongRows>
+__global__ __launch_bounds__(64) void k_sym_count_half(TileRefs A, TileRefs B, int lanes_per_a, int max_words,
+                                                       int32_t *__restrict__ row_jmin,
+                                                       int32_t *__restrict__ row_c_tiles,
+                                                       int32_t *__restrict__ row_pairs,
+                                                       int32_t *__restrict__ row_words,
+                                                       int32_t *__restrict__ row_cand,
+                                                       int64_t *__restrict__ d_scalars) {
+    extern __shared__ uint32_t lds_dyn[];
+    __shared__ int s_ext[2][2];                    // first and last candidate tile column of the tile-row
+    __shared__ uint32_t s_cnt[2][3];               // C tiles, surviving pairs, candidates
+    constexpr int kLanes = 32;
+    const int half = threadIdx.x / kLanes, tid = threadIdx.x % kLanes;
+    const int I = (int)blockIdx.x * 2 + half;
+    uint32_t *bm = lds_dyn + half * max_words;
+    if (tid == 0) {
+        s_ext[half][0] = INT_MAX;
+        s_ext[half][1] = -1;
+        s_cnt[half][0] = s_cnt[half][1] = s_cnt[half][2] = 0;
+    }
+    wave_sync();
+    const bool live = I < A.tile_rows;             // (an odd number of tile-rows: the last half idles)
+    const int a0 = live ? A.trp[I] : 0, a1 = live ? A.tend[I] : 0;
+    int jmin = INT_MAX, jmax = -1;
+    for (int a = a0 + tid; a < a1; a += kLanes) {
+        const uint32_t K = (uint32_t)A.tcol[a];
+        if (K >= (uint32_t)B.tile_rows) continue;
+        const int b0 = B.trp[K], b1 = B.tend[K];
+        if (b0 < b1) {
+            jmin = min(jmin, B.tcol[b0]);
+            jmax = max(jmax, B.tcol[b1 - 1]);
+        }
+    }
+    if (jmax >= 0) {
+        atomicMin(&s_ext[half][0], jmin);
+        atomicMax(&s_ext[half][1], jmax);
+    }
+    wave_sync();
+    jmin = s_ext[half][0];
+    jmax = s_ext[half][1];
+    const int64_t span = (int64_t)jmax - jmin + 1;
+    const int words = (int)((span + 31) >> 5);
+    const bool any = live && jmax >= 0 && jmin >= 0;
+    const bool fits = words <= max_words;
+    if (any && !fits && tid == 0) d_scalars[S_UNSUPPORTED] = 1;
+    const bool walk = any && fits;                 // uniform over the half
+    if (walk)
+        for (int w = tid; w < words; w += kLanes) bm[w] = 0;
+    wave_sync();
+    uint32_t cand = 0, surv = 0;
+    if (walk)
+        for_each_survivor<kLongRows, true>(A, B, a0, a1, lanes_per_a, &cand, tid, kLanes, [&](int, int, int J) {
+            const uint32_t j = (uint32_t)(J - jmin);
+            if (j < (uint32_t)span) {
+                atomicOr(&bm[j >> 5], 1u << (j & 31));
+                ++surv;
+            }
+        });
+    wave_sync();
+    uint32_t tiles = 0;
+    if (walk)
+        for (int w = tid; w < words; w += kLanes) tiles += __popc(bm[w]);
+    if (tiles) atomicAdd(&s_cnt[half][0], tiles);
+    if (surv) atomicAdd(&s_cnt[half][1], surv);
+    if (cand) atomicAdd(&s_cnt[half][2], cand);
+    wave_sync();
+    if (live && tid == 0) {
+        row_jmin[I] = walk ? jmin : 0;
+        row_c_tiles[I] = (int32_t)s_cnt[half][0];
+        row_pairs[I] = (int32_t)s_cnt[half][1];
+        row_words[I] = walk ? words : 0;
+        row_cand[I] = (int32_t)s_cnt[half][2];
     }
 }
 
@@ -1214,6 +1302,13 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
         // measured, up to about six words per thread)
         const int64_t grid_words = (B->tile_cols + 31) / 32;
         const int direct_words = grid_words <= std::min<int64_t>(kDirectWords, 6 * threads) ? (int)grid_words : 0;
+        // short tile-rows of A: two per wave (with more of them than the chip holds waves, half the time)
+        if (threads == 64 && direct_words == 0 && per_row <= 128)
+            hipLaunchKernelGGL(long_rows ? k_sym_count_half<true> : k_sym_count_half<false>,
+                               dim3((unsigned)((ntr + 1) / 2)), dim3(64), 2 * max_words * sizeof(uint32_t), s, ra, rb,
+                               std::min(lanes, 8), max_words, row_jmin, row_c_tiles, row_pairs, row_words, row_cand,
+                               ctx->d_scalars);
+        else
         hipLaunchKernelGGL(long_rows ? k_sym_count<true> : k_sym_count<false>, dim3((unsigned)ntr), dim3(threads),
                            max_words * sizeof(uint32_t), s, ra, rb,
                            lanes, max_words, direct_words, row_jmin, row_c_tiles, row_pairs, row_words, row_cand, ctx->d_scalars);

@@ -451,6 +451,28 @@ def test_tile_rows_with_more_output_tiles_than_the_symbolic_window(tsp, handle, 
     C.free()
 
 
+# ------------------------------------------------------------------ two tile-rows per wave in the counting kernel
+def test_short_tile_rows_against_a_wide_operand(tsp, handle, oracle):
+    """Short tile-rows of A against a B too wide for the counting kernel's whole-grid bitmap: the kernel
+    that gives each tile-row half a wave.  An odd number of tile-rows (the last half-wave idles), empty
+    tile-rows, rows whose candidates lie far apart, and a B with empty tile-rows."""
+    rng = np.random.default_rng(123)
+    M, K = 16 * 201 - 5, 1 << 18
+    rows = np.repeat(np.arange(M), 3)
+    cols = rng.integers(0, K, rows.size)
+    keep = (rows // 16) % 7 != 3                                       # every seventh tile-row of A empty
+    keys = np.unique(rows[keep] * K + cols[keep])
+    A = inputs.from_coo(M, K, keys // K, keys % K, rng.uniform(-1, 1, keys.size), "short rows, wide inner dimension")
+    i = np.arange(K)
+    band = np.concatenate([i, i[:-1], i[1:], i[: K - 700]])
+    bcol = np.concatenate([i, i[:-1] + 1, i[1:] - 1, i[: K - 700] + 700])
+    live = (band // 16) % 5 != 2                                       # every fifth tile-row of B empty
+    B = inputs.from_coo(K, K, band[live], bcol[live], rng.uniform(-1, 1, int(live.sum())), "band")
+    print(f"short tile-rows: A {A.rows}x{A.cols} nnz {A.nnz}, B nnz {B.nnz}", flush=True)
+    nnz, _ = run_and_check(tsp, handle, oracle, A, B)
+    assert nnz > A.nnz
+
+
 # ------------------------------------------------------------------ heaviest tile-rows first
 def test_tile_rows_taken_in_order_of_work(tsp, oracle):
     """The general task-list kernel with its blocks taking the tile-rows heaviest first (forced here; on
