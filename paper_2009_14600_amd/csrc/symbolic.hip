@@ -764,6 +764,44 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_emit(
     }
 }
 
+// The threads that work on one tile-row together: a whole block (kTeamLanes == 0), or a part of a wave
+// (kTeamLanes lanes), whose LDS traffic needs no block barrier.
+template <int kTeamLanes>
+struct Team {
+    __device__ static __forceinline__ int tid() { return kTeamLanes ? (int)threadIdx.x % kTeamLanes : (int)threadIdx.x; }
+    __device__ static __forceinline__ int size() { return kTeamLanes ? kTeamLanes : (int)blockDim.x; }
+    __device__ static __forceinline__ int index() { return kTeamLanes ? (int)threadIdx.x / kTeamLanes : 0; }
+    __device__ static __forceinline__ void sync() {
+        if (kTeamLanes) wave_sync();
+        else __syncthreads();
+    }
+};
+
+// In-place exclusive scan of arr[0..n) by the team; returns the total.
+template <int kTeamLanes>
+__device__ __forceinline__ uint32_t team_exclusive_scan_lds(uint32_t *arr, int n, uint32_t *lds /*[>=17], block only*/) {
+    if constexpr (kTeamLanes == 0) {
+        return block_exclusive_scan_lds(arr, n, lds);
+    } else {
+        const int tid = Team<kTeamLanes>::tid();
+        uint32_t carry = 0;
+        for (int base = 0; base < n; base += kTeamLanes) {
+            const int i = base + tid;
+            const uint32_t x = i < n ? arr[i] : 0;
+            uint32_t v = x;
+#pragma unroll
+            for (int o = 1; o < kTeamLanes; o <<= 1) {
+                const uint32_t up = __shfl_up(v, o, kTeamLanes);
+                if (tid >= o) v += up;
+            }
+            if (i < n) arr[i] = carry + v - x;
+            carry += __shfl(v, kTeamLanes - 1, kTeamLanes);
+        }
+        wave_sync();
+        return carry;
+    }
+}
+
 // OR over the set bits k of `am` of row mask k of the B tile; x, y hold the 16 row masks, two per
 // 32-bit word (row 2i in the low half).  Four bits of `am` select among four rows, i.e. two words: the
 // two AND masks (all ones in the half whose row is selected) come from a 16-entry table in LDS, so a
@@ -802,12 +840,13 @@ __device__ __forceinline__ uint32_t boolean_row_product(uint32_t am, const uint4
 // Dynamic LDS: 2*words_cap + 10*window + 3*list_cap words (list_cap: most entries any tile-row has).
 constexpr int kPairsPerTrip = 2;       // pairs a lane group of the fused counting pass takes per trip
 constexpr int kListCap = 1024;
+constexpr int kListTeamLanes = 32;     // lanes that share a tile-row where tile-rows have few candidates (16: slower)
 constexpr int kListTiles = 512;        // and at most this many C tiles per tile-row (their bitmaps sit in LDS)
 // kFuseMasks: also run the counting pass (worth it when there are enough tile-rows to fill the chip;
 // with few, long tile-rows the separate kernel, one lane group per C tile, has more parallelism).
-template <bool kLongRows, bool kFuseMasks>
-__global__ __launch_bounds__(kSymThreads) void k_sym_emit_listed(
-    TileRefs A, TileRefs B, int lanes_per_a, int words_cap, int window, int list_cap,
+template <bool kLongRows, bool kFuseMasks, int kTeamLanes>
+__global__ __launch_bounds__(kTeamLanes ? 64 : kSymThreads) void k_sym_emit_listed(
+    TileRefs A, TileRefs B, int lanes_per_a, int words_cap, int window, int list_cap, int team_words,
     const int32_t *__restrict__ row_jmin, const int32_t *__restrict__ row_words,
     const int32_t *__restrict__ c_tile_row_ptr, const int64_t *__restrict__ row_pair_ptr,
     int32_t *__restrict__ c_tile_row, int32_t *__restrict__ c_tile_col, int64_t *__restrict__ pair_off,
@@ -815,37 +854,46 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_emit_listed(
     const uint16_t *__restrict__ b_row_mask, uint16_t *__restrict__ c_row_mask, uint32_t *__restrict__ c_row_off,
     int32_t *__restrict__ row_nnz, int64_t c_rows, int64_t *d_scalars, uint32_t *__restrict__ tile_row_entries) {
     extern __shared__ uint32_t lds_dyn[];
+    using team = Team<kTeamLanes>;
+    constexpr int kTeams = kTeamLanes ? 64 / kTeamLanes : 1;
     __shared__ uint32_t red[32];
-    __shared__ int s_n;
+    __shared__ int s_n_all[kTeams];
     __shared__ RowSelectTable row_select;
-    __shared__ uint32_t s_part[kSymThreads / 16][T];
-    if (kFuseMasks) row_select.fill();               // (many barriers before its first use)
-    uint32_t *bm = lds_dyn;
+    __shared__ uint32_t s_part_all[kTeams][(kTeamLanes ? kTeamLanes : kSymThreads) / 16][T];
+    if (kFuseMasks) {
+        row_select.fill();                           // (barriers before its first use; in a wave of two teams
+        if (kTeamLanes) wave_sync();                 // the other team may have left by then)
+    }
+    const int tid = team::tid(), team_index = team::index();
+    int &s_n = s_n_all[team_index];
+    uint32_t(*const s_part)[T] = s_part_all[team_index];
+    uint32_t *bm = lds_dyn + (size_t)team_index * team_words;
     uint32_t *wpre = bm + words_cap;
     uint32_t *contrib = wpre + words_cap;
     uint32_t *cnt = contrib + window;
     int *list_a = reinterpret_cast<int *>(cnt + window), *list_b = list_a + list_cap;
     int *list_c = list_b + list_cap;                 // tile column, later the C tile's position in the row
     uint32_t *cmask = reinterpret_cast<uint32_t *>(list_c + list_cap);   // 8 words (16 row masks) per C tile
-    const int I = blockIdx.x, nthreads = (int)blockDim.x;
+    const int I = (int)blockIdx.x * kTeams + team_index, nthreads = team::size();
+    if (I >= A.tile_rows) return;                    // (an odd number of tile-rows: the last team idles)
     const int c0 = c_tile_row_ptr[I], nC = c_tile_row_ptr[I + 1] - c0;
-    if (I == (int)gridDim.x - 1 && threadIdx.x == 0) pair_off[c_tile_row_ptr[gridDim.x]] = row_pair_ptr[gridDim.x];
+    if (I == A.tile_rows - 1 && tid == 0) pair_off[c_tile_row_ptr[A.tile_rows]] = row_pair_ptr[A.tile_rows];
     if (nC <= 0) {                                   // an empty tile-row of C: its 16 rows are empty
-        if (kFuseMasks && threadIdx.x < T && (int64_t)I * T + threadIdx.x < c_rows) row_nnz[(int64_t)I * T + threadIdx.x] = 0;
-        if (kFuseMasks && threadIdx.x == 0) tile_row_entries[I] = 0;
+        if (kFuseMasks && tid < T && (int64_t)I * T + tid < c_rows) row_nnz[(int64_t)I * T + tid] = 0;
+        if (kFuseMasks && tid == 0) tile_row_entries[I] = 0;
         return;
     }
     const int a0 = A.trp[I], a1 = A.tend[I];
     const int jmin = row_jmin[I];
     const int64_t row_base = row_pair_ptr[I];
-    if (threadIdx.x == 0) s_n = 0;
+    if (tid == 0) s_n = 0;
     // the bitmap extent the first pass found for this tile-row
     const int words = min(row_words[I], words_cap);
     const int64_t span = (int64_t)words * 32;
-    for (int w = threadIdx.x; w < words; w += nthreads) bm[w] = 0;
-    __syncthreads();
+    for (int w = tid; w < words; w += nthreads) bm[w] = 0;
+    team::sync();
     uint32_t dummy = 0;
-    for_each_survivor<kLongRows, false>(A, B, a0, a1, lanes_per_a, &dummy, [&](int a, int b, int J) {
+    for_each_survivor<kLongRows, false>(A, B, a0, a1, lanes_per_a, &dummy, tid, nthreads, [&](int a, int b, int J) {
         const uint32_t j = (uint32_t)(J - jmin);
         if (j < (uint32_t)span) {
             atomicOr(&bm[j >> 5], 1u << (j & 31));
@@ -857,12 +905,12 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_emit_listed(
             }
         }
     });
-    __syncthreads();
+    team::sync();
     const int n = min(s_n, list_cap);
-    for (int w = threadIdx.x; w < words; w += nthreads) wpre[w] = __popc(bm[w]);
-    __syncthreads();
-    block_exclusive_scan_lds(wpre, words, red);
-    for (int w = threadIdx.x; w < words; w += nthreads) {     // C tile coordinates, ascending J
+    for (int w = tid; w < words; w += nthreads) wpre[w] = __popc(bm[w]);
+    team::sync();
+    team_exclusive_scan_lds<kTeamLanes>(wpre, words, red);
+    for (int w = tid; w < words; w += nthreads) {     // C tile coordinates, ascending J
         uint32_t bits = bm[w];
         int c = c0 + (int)wpre[w];
         while (bits) {
@@ -873,38 +921,38 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_emit_listed(
             ++c;
         }
     }
-    for (int k = threadIdx.x; k < n; k += nthreads) {          // tile column -> position of the C tile in the row
+    for (int k = tid; k < n; k += nthreads) {          // tile column -> position of the C tile in the row
         const uint32_t j = (uint32_t)list_c[k];
         list_c[k] = (int)wpre[j >> 5] + __popc(bm[j >> 5] & ((1u << (j & 31)) - 1u));
     }
-    for (int c = threadIdx.x; c < nC; c += nthreads) cnt[c] = 0;
+    for (int c = tid; c < nC; c += nthreads) cnt[c] = 0;
     const bool one_chunk = (a1 - a0) <= 32;
     // count pass: which of 32 A tiles at a time contribute to each C tile
     for (int ch = a0; ch < a1; ch += 32) {
-        for (int c = threadIdx.x; c < nC; c += nthreads) contrib[c] = 0;
-        __syncthreads();
-        for (int k = threadIdx.x; k < n; k += nthreads) {
+        for (int c = tid; c < nC; c += nthreads) contrib[c] = 0;
+        team::sync();
+        for (int k = tid; k < n; k += nthreads) {
             const uint32_t rel = (uint32_t)(list_a[k] - ch);
             if (rel < 32u) atomicOr(&contrib[list_c[k]], 1u << rel);
         }
-        __syncthreads();
-        for (int c = threadIdx.x; c < nC; c += nthreads) cnt[c] += __popc(contrib[c]);
-        __syncthreads();
+        team::sync();
+        for (int c = tid; c < nC; c += nthreads) cnt[c] += __popc(contrib[c]);
+        team::sync();
     }
-    block_exclusive_scan_lds(cnt, nC, red);
-    for (int c = threadIdx.x; c < nC; c += nthreads) pair_off[c0 + c] = row_base + (int64_t)cnt[c];
+    team_exclusive_scan_lds<kTeamLanes>(cnt, nC, red);
+    for (int c = tid; c < nC; c += nthreads) pair_off[c0 + c] = row_base + (int64_t)cnt[c];
     // emit pass: a pair sits after the pairs of its C tile with a lower A tile
     for (int ch = a0; ch < a1; ch += 32) {
         if (!one_chunk) {
-            for (int c = threadIdx.x; c < nC; c += nthreads) contrib[c] = 0;
-            __syncthreads();
-            for (int k = threadIdx.x; k < n; k += nthreads) {
+            for (int c = tid; c < nC; c += nthreads) contrib[c] = 0;
+            team::sync();
+            for (int k = tid; k < n; k += nthreads) {
                 const uint32_t rel = (uint32_t)(list_a[k] - ch);
                 if (rel < 32u) atomicOr(&contrib[list_c[k]], 1u << rel);
             }
-            __syncthreads();
+            team::sync();
         }
-        for (int k = threadIdx.x; k < n; k += nthreads) {
+        for (int k = tid; k < n; k += nthreads) {
             const uint32_t rel = (uint32_t)(list_a[k] - ch);
             if (rel < 32u) {
                 const int c = list_c[k];
@@ -914,9 +962,9 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_emit_listed(
             }
         }
         if (!one_chunk) {
-            __syncthreads();
-            for (int c = threadIdx.x; c < nC; c += nthreads) cnt[c] += __popc(contrib[c]);
-            __syncthreads();
+            team::sync();
+            for (int c = tid; c < nC; c += nthreads) cnt[c] += __popc(contrib[c]);
+            team::sync();
         }
     }
     if constexpr (!kFuseMasks) return;
@@ -924,10 +972,10 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_emit_listed(
     // r forms row r of the boolean product of the two bitmaps and ORs it into the C tile's bitmap in LDS.
     // kPairsPerTrip pairs per trip, their bitmaps requested together (four or two per trip take the same
     // time, eight cost registers).
-    for (int w = threadIdx.x; w < nC * 8; w += nthreads) cmask[w] = 0;
-    __syncthreads();
+    for (int w = tid; w < nC * 8; w += nthreads) cmask[w] = 0;
+    team::sync();
     {
-        const int g = threadIdx.x >> 4, r = threadIdx.x & 15, groups = nthreads >> 4;
+        const int g = tid >> 4, r = tid & 15, groups = nthreads >> 4;
         for (int k0 = g * kPairsPerTrip; k0 < n; k0 += groups * kPairsPerTrip) {
             uint32_t am[kPairsPerTrip];
             uint4 x[kPairsPerTrip], y[kPairsPerTrip];
@@ -951,20 +999,20 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_emit_listed(
             }
         }
     }
-    __syncthreads();
+    team::sync();
     uint32_t *out_words = reinterpret_cast<uint32_t *>(c_row_mask) + (int64_t)c0 * 8;
-    for (int w = threadIdx.x; w < nC * 8; w += nthreads) out_words[w] = cmask[w];
+    for (int w = tid; w < nC * 8; w += nthreads) out_words[w] = cmask[w];
     // ... and what k_row_offsets does for this tile-row: lane r of every 16-lane group takes CSR row
     // 16I+r for a stretch of the C tiles, the groups' sums are exchanged through LDS.
     {
-        const int g = threadIdx.x >> 4, r = threadIdx.x & 15, groups = nthreads >> 4;
+        const int g = tid >> 4, r = tid & 15, groups = nthreads >> 4;
         const int word = r >> 1, shift = (r & 1) * 16;
         const int stretch = (nC + groups - 1) / groups;
         const int cb = min(nC, g * stretch), ce = min(nC, cb + stretch);
         uint32_t part = 0;
         for (int c = cb; c < ce; ++c) part += __popc((cmask[c * 8 + word] >> shift) & 0xFFFFu);
         s_part[g][r] = part;
-        __syncthreads();
+        team::sync();
         uint32_t total = 0, earlier = 0;           // entries of row r in the tile-row, and in the stretches before this one
         for (int h = 0; h < groups; ++h) {
             const uint32_t v = s_part[h][r];
@@ -1382,11 +1430,17 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
         if (listed) {
             const int list_cap = (int)std::max<int64_t>(h[S_MAX_ROW_PAIRS], 1);
             fused_masks = ntr >= 1024;
-            auto kernel = fused_masks ? (long_rows ? k_sym_emit_listed<true, true> : k_sym_emit_listed<false, true>)
-                                      : (long_rows ? k_sym_emit_listed<true, false> : k_sym_emit_listed<false, false>);
-            hipLaunchKernelGGL(kernel, dim3((unsigned)ntr), dim3(threads),
-                               lds + (size_t)(3 * list_cap + (fused_masks ? 8 * window : 0)) * sizeof(int), s, ra, rb,
-                               lanes, words_cap, window, list_cap, row_jmin, row_words, P->c_tile_row_ptr,
+            const int team_words = 2 * words_cap + 2 * window + 3 * list_cap + (fused_masks ? 8 * window : 0);
+            // tile-rows with few candidates: two per wave (see k_sym_count_half)
+            const bool halves = fused_masks && threads == 64;
+            auto kernel = !fused_masks ? (long_rows ? k_sym_emit_listed<true, false, 0> : k_sym_emit_listed<false, false, 0>)
+                          : halves     ? (long_rows ? k_sym_emit_listed<true, true, kListTeamLanes> : k_sym_emit_listed<false, true, kListTeamLanes>)
+                                       : (long_rows ? k_sym_emit_listed<true, true, 0> : k_sym_emit_listed<false, true, 0>);
+            constexpr int kTeamsPerWave = 64 / kListTeamLanes;
+            hipLaunchKernelGGL(kernel, dim3((unsigned)(halves ? (ntr + kTeamsPerWave - 1) / kTeamsPerWave : ntr)), dim3(threads),
+                               (size_t)team_words * (halves ? kTeamsPerWave : 1) * sizeof(uint32_t), s, ra, rb,
+                               halves ? std::min(lanes, 8) : lanes, words_cap, window, list_cap, team_words, row_jmin,
+                               row_words, P->c_tile_row_ptr,
                                row_pair_ptr, P->c_tile_row, P->c_tile_col, P->pair_off, P->pair_a, P->pair_b,
                                A->row_mask, B->row_mask, P->c_row_mask, P->c_row_off, row_nnz, P->c_rows,
                                ctx->d_scalars, tile_row_entries);

@@ -471,6 +471,11 @@ def test_short_tile_rows_against_a_wide_operand(tsp, handle, oracle):
     print(f"short tile-rows: A {A.rows}x{A.cols} nnz {A.nnz}, B nnz {B.nnz}", flush=True)
     nnz, _ = run_and_check(tsp, handle, oracle, A, B)
     assert nnz > A.nnz
+    # enough short tile-rows for the task-list kernel to run the counting pass itself, two tile-rows per
+    # wave: 1073 tile-rows, an odd number, the last one ragged
+    L = inputs.laplacian_2d(131)
+    print(f"short tile-rows: {L.name} rows {L.rows}", flush=True)
+    run_and_check(tsp, handle, oracle, L)
 
 
 # ------------------------------------------------------------------ heaviest tile-rows first
