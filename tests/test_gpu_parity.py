@@ -608,3 +608,21 @@ def test_mesh_with_dense_rows(tsp, handle, oracle):
     assert nnz > 3 * n
     B = inputs.random_sparse(n, 90, 0.02, 77)
     run_and_check(tsp, handle, oracle, A, B)
+
+
+@pytest.mark.parametrize("n", [20000, 40000])
+def test_band_with_dense_rows(tsp, handle, oracle, n):
+    """The same in a band matrix, whose tile-rows the converter gives one wave each: the full rows
+    (1250 and 2500 tiles) go window by window inside the kernel built for two entries per lane."""
+    i = np.arange(n)
+    rng = np.random.default_rng(n)
+    dense = (5, n - 40)
+    rows = np.concatenate([i, i[:-1], i[1:]])
+    cols = np.concatenate([i, i[:-1] + 1, i[1:] - 1])
+    keep = ~np.isin(rows, dense)
+    rows = np.concatenate([rows[keep]] + [np.full(n, r) for r in dense])
+    cols = np.concatenate([cols[keep]] + [i for _ in dense])
+    A = inputs.from_coo(n, n, rows, cols, rng.uniform(-1, 1, rows.size), f"band with dense rows {n}")
+    print(f"{A.name}: nnz {A.nnz}", flush=True)
+    nnz, _ = run_and_check(tsp, handle, oracle, A)
+    assert nnz > 2 * n
