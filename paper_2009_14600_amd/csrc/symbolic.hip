@@ -18,11 +18,14 @@
 // (Section 4.2 runs the multiplication on 0/1 tiles for this; here integer bit operations on
 // the 16-bit row masks, which gives the same pattern), and the per-row counts give row_ptr of C.
 //
-// Kernels: k_sym_count (steps 1-3, sizes per tile-row), k_sym_row_scan (their prefix sums, one chained
-// launch), then either k_sym_emit_listed (tile-rows with few pairs: survivors enumerated once into an
-// LDS list; with enough tile-rows it also runs the counting pass and the row offsets) or k_sym_emit
-// (any tile-row; more C tiles than the LDS window holds are worked off window by window), k_count_masks
-// and k_row_offsets where the list kernel has not done their work, and k_row_ptr.
+// Kernels: k_sym_count (steps 1-3, sizes per tile-row; k_sym_count_half gives short tile-rows half a wave
+// each), k_sym_row_scan (their prefix sums, one chained launch), then either k_sym_emit_listed (tile-rows
+// with few pairs: survivors enumerated once into an LDS list; with enough tile-rows it also runs the
+// counting pass and the row offsets; a block or half a wave per tile-row) or k_sym_emit (any tile-row; more
+// C tiles than the LDS window holds are worked off window by window; on skewed products the heaviest
+// tile-rows first, in the order k_work_hist and k_work_order set up), k_count_masks and k_row_offsets
+// (k_row_offsets_wide for tile-rows with many tiles) where the list kernel has not done their work, and
+// k_row_ptr.
 #include "common.hpp"
 #include "chain.hpp"
 
