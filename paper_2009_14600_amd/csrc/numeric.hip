@@ -301,7 +301,8 @@ __global__ __launch_bounds__(kNumThreads) void k_numeric(
     if constexpr (kWholeRows)
         row_entries = (int)min(c_row_ptr[min((int64_t)(I_first + 1) * T, c_rows)] - base_first, (int64_t)kRowEntries);
     // (unrolled, but for whole tile-rows of more than 16 tiles, whose groups are a loop)
-#pragma unroll(kTilesPerWave > kRowTilesUnrolled ? 1 : kTilesPerWave / kGroupTiles)
+    constexpr int kGroupUnroll = kTilesPerWave > kRowTilesUnrolled ? 1 : kTilesPerWave / kGroupTiles;
+#pragma unroll kGroupUnroll
     for (int g = 0; g < kTilesPerWave / kGroupTiles; ++g) {
         if (g * kGroupTiles < run_tiles) {        // uniform
             // The row masks and row positions of the group's four tiles, requested before the
