@@ -161,7 +161,9 @@ void plan_release(tsp_context *ctx, tsp_plan_s *p, hipStream_t s);
 // next call (one launch less per call).
 int numeric_enqueue(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s *plan, tsp_csr *C,
                     hipStream_t s, bool last_of_call = false);
-int compact_zeros(tsp_context *ctx, const tsp_csr *C, tsp_csr *out, hipStream_t s);
+// taken (may be null): the caller owns C and gives it up; when no entry is zero *out takes C's arrays as they
+// are (no copy) and *taken is set, so that the caller does not free them.
+int compact_zeros(tsp_context *ctx, const tsp_csr *C, tsp_csr *out, hipStream_t s, bool *taken);
 
 #ifdef __HIPCC__
 // ---- device helpers -------------------------------------------------------------------

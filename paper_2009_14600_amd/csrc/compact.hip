@@ -78,7 +78,7 @@ __global__ void k_compact_clear(int64_t *d_scalars) {
 }
 
 template <typename RP>
-static int compact_run(tsp_context *ctx, const tsp_csr *C, tsp_csr *out, hipStream_t s) {
+static int compact_run(tsp_context *ctx, const tsp_csr *C, tsp_csr *out, hipStream_t s, bool *taken) {
     const int64_t rows = C->rows;
     CompactArgs<RP> a{static_cast<const RP *>(C->row_ptr), C->col_idx, static_cast<const float *>(C->val), rows, C->nnz};
     int32_t *keep = ctx_alloc_n<int32_t>(ctx, (size_t)rows + 1, s);
@@ -110,6 +110,12 @@ static int compact_run(tsp_context *ctx, const tsp_csr *C, tsp_csr *out, hipStre
     if (rc) return fail(rc);
     if (ctx->h_scalars[S_INTERNAL]) return fail(TSP_ERR_HIP);
     const int64_t nnz = ctx->h_scalars[S_C_NNZ];
+    if (taken && nnz == C->nnz) {                        // nothing to drop: the caller's arrays are the result
+        fail(TSP_OK);                                    // (releases the scratch arrays)
+        *out = *C;
+        *taken = true;
+        return TSP_OK;
+    }
     col = ctx_alloc_n<int32_t>(ctx, (size_t)nnz, s);
     val = ctx_alloc_n<float>(ctx, (size_t)nnz, s);
     if (!col || !val) return fail(TSP_ERR_ALLOC_FAILED);
@@ -131,14 +137,15 @@ static int compact_run(tsp_context *ctx, const tsp_csr *C, tsp_csr *out, hipStre
     return TSP_OK;
 }
 
-int compact_zeros(tsp_context *ctx, const tsp_csr *C, tsp_csr *out, hipStream_t s) {
+int compact_zeros(tsp_context *ctx, const tsp_csr *C, tsp_csr *out, hipStream_t s, bool *taken) {
     std::memset(out, 0, sizeof(*out));
+    if (taken) *taken = false;
     if (C->rows < 0 || C->cols < 0 || C->nnz < 0 || !C->row_ptr) return TSP_ERR_INVALID_ARG;
     if (C->val_type != TSP_F32) return TSP_ERR_INVALID_ARG;
     if (C->nnz > 0 && (!C->col_idx || !C->val)) return TSP_ERR_INVALID_ARG;
     if (C->rows >= INT32_MAX - 16) return TSP_ERR_INDEX_OVERFLOW;
-    if (C->row_ptr_type == TSP_I64) return compact_run<int64_t>(ctx, C, out, s);
-    if (C->row_ptr_type == TSP_I32) return compact_run<int32_t>(ctx, C, out, s);
+    if (C->row_ptr_type == TSP_I64) return compact_run<int64_t>(ctx, C, out, s, taken);
+    if (C->row_ptr_type == TSP_I32) return compact_run<int32_t>(ctx, C, out, s, taken);
     return TSP_ERR_INVALID_ARG;
 }
 
@@ -148,5 +155,5 @@ using namespace tsp;
 
 extern "C" int tsp_compact_zeros(tsp_handle ctx, const tsp_csr *C, tsp_csr *out, void *stream) {
     if (!ctx || !C || !out || C == out) return TSP_ERR_INVALID_ARG;
-    return compact_zeros(ctx, C, out, (hipStream_t)stream);
+    return compact_zeros(ctx, C, out, (hipStream_t)stream, nullptr);
 }

@@ -36,8 +36,9 @@ extern "C" int tsp_spgemm(tsp_handle ctx, const tsp_csr *A, const tsp_csr *B, ts
     if (!rc) rc = numeric_enqueue(ctx, ta, alias ? ta : tb, plan, C, s, /*last_of_call=*/true);   // the plan ends here
     if (!rc && ctx->compact) {                    // Algorithm 1, the compaction steps: strictly sparse result
         tsp_csr structural = *C;
-        rc = compact_zeros(ctx, &structural, C, s);
-        tsp_csr_free(ctx, &structural, stream);
+        bool taken = false;                       // (no entry is zero: C keeps the arrays it has)
+        rc = compact_zeros(ctx, &structural, C, s, &taken);
+        if (!taken) tsp_csr_free(ctx, &structural, stream);
     }
     total_end(ctx, s);
     if (ctx->timers) {
