@@ -19,7 +19,7 @@
 // the 16-bit row masks, which gives the same pattern), and the per-row counts give row_ptr of C.
 //
 // Kernels: k_sym_count (steps 1-3, sizes per tile-row; k_sym_count_half gives short tile-rows half a wave
-// each), k_sym_row_scan (their prefix sums, one chained launch), then either k_sym_emit_listed (tile-rows
+// each, k_sym_count_segmented does so against a very wide B), k_sym_row_scan (their prefix sums, one chained launch), then either k_sym_emit_listed (tile-rows
 // with few pairs: survivors enumerated once into an LDS list; with enough tile-rows it also runs the
 // counting pass and the row offsets; a block or half a wave per tile-row) or k_sym_emit (any tile-row; more
 // C tiles than the LDS window holds are worked off window by window; on skewed products the heaviest
@@ -39,6 +39,7 @@ constexpr int kSymThreads = 256;
 constexpr int kMaxWords = 4096;        // LDS bitmap words per tile-row: span of 131072 tile columns
 constexpr int kDirectWords = 1024;     // counting kernel: widest tile grid of B whose bitmap is indexed by the column itself
 constexpr int kWindow = 2048;          // C tiles of one tile-row handled per LDS window
+constexpr int kRowLeftOver = -1;       // row_words of a tile-row that the segmented counting kernel leaves to the full one
 constexpr int kSurvivorUnroll = 4;     // B tiles one lane requests per trip of the candidate loop: long tile-rows of B
 constexpr int kSurvivorUnrollShort = 2;   // ... and short ones
 
@@ -230,7 +231,7 @@ __device__ __forceinline__ void for_each_survivor_below(const TileRefs &A, const
 // candidates.  Dynamic LDS: max_words words.
 template <bool kLongRows>
 __global__ __launch_bounds__(kSymThreads) void k_sym_count(TileRefs A, TileRefs B, int lanes_per_a, int max_words,
-                                                           int direct_words,
+                                                           int direct_words, int only_marked,
                                                            int32_t *__restrict__ row_jmin,
                                                            int32_t *__restrict__ row_c_tiles,
                                                            int32_t *__restrict__ row_pairs,
@@ -242,6 +243,8 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_count(TileRefs A, TileRefs 
     __shared__ int s_jmin, s_jmax;
     uint32_t *bm = lds_dyn;
     const int I = blockIdx.x;
+    // second launch after k_sym_count_segmented: only the tile-rows that kernel has left to this one
+    if (only_marked && row_words[I] != kRowLeftOver) return;
     const int a0 = A.trp[I], a1 = A.tend[I];
     if (threadIdx.x == 0) {
         s_jmin = INT_MAX;
@@ -429,6 +432,99 @@ __global__ __launch_bounds__(64) void k_sym_count_half(TileRefs A, TileRefs B, i
         row_pairs[I] = (int32_t)s_cnt[half][1];
         row_words[I] = walk ? words : 0;
         row_cand[I] = (int32_t)s_cnt[half][2];
+    }
+}
+
+// The same for a B with a wide tile grid, where a bitmap over the span of a tile-row's candidates would be
+// sized for the widest span possible (up to 16 KB a tile-row, which leaves a CU a handful of waves) while
+// the candidates of a short tile-row sit in a few clusters: the bitmap is kept in segments of 1024 tile
+// columns, handed out on demand from kSegSlots slots per tile-row.  A tile-row that needs more is marked
+// kRowLeftOver in row_words and done by a second launch of k_sym_count with the full bitmap.  The extent of
+// the tile-row is read off the segments (no pass over B's tile-rows for it).
+constexpr int kSegSlots = 16, kSegWords = 32;      // 32 words = 1024 tile columns per segment
+template <bool kLongRows>
+__global__ __launch_bounds__(64) void k_sym_count_segmented(TileRefs A, TileRefs B, int lanes_per_a, int max_words,
+                                                            int32_t *__restrict__ row_jmin,
+                                                            int32_t *__restrict__ row_c_tiles,
+                                                            int32_t *__restrict__ row_pairs,
+                                                            int32_t *__restrict__ row_words,
+                                                            int32_t *__restrict__ row_cand,
+                                                            int64_t *__restrict__ d_scalars) {
+    __shared__ int s_seg[2][kSegSlots];                          // which segment a slot holds, -1: free
+    __shared__ uint32_t s_bits[2][kSegSlots][kSegWords];
+    __shared__ int s_ext[2][2];
+    __shared__ uint32_t s_cnt[2][4];                             // C tiles, surviving pairs, candidates, slots ran out
+    constexpr int kLanes = 32;
+    const int half = threadIdx.x / kLanes, tid = threadIdx.x % kLanes;
+    const int I = (int)blockIdx.x * 2 + half;
+    if (tid < kSegSlots) s_seg[half][tid] = -1;
+    for (int w = tid; w < kSegSlots * kSegWords; w += kLanes) s_bits[half][w / kSegWords][w % kSegWords] = 0;
+    if (tid == 0) {
+        s_ext[half][0] = INT_MAX;
+        s_ext[half][1] = -1;
+        s_cnt[half][0] = s_cnt[half][1] = s_cnt[half][2] = s_cnt[half][3] = 0;
+    }
+    wave_sync();
+    const bool live = I < A.tile_rows;
+    const int a0 = live ? A.trp[I] : 0, a1 = live ? A.tend[I] : 0;
+    uint32_t cand = 0, surv = 0;
+    bool out_of_slots = false;
+    for_each_survivor<kLongRows, true>(A, B, a0, a1, lanes_per_a, &cand, tid, kLanes, [&](int, int, int J) {
+        if (J < 0) return;                         // (tile columns come from the converter and are not negative)
+        const int seg = J >> 10;
+        int slot = -1;
+        for (int k = 0; k < kSegSlots && slot < 0; ++k) {
+            int held = s_seg[half][k];
+            if (held == -1) held = atomicCAS(&s_seg[half][k], -1, seg);   // free: claim it (or see who did)
+            if (held == -1 || held == seg) slot = k;
+        }
+        if (slot < 0) {
+            out_of_slots = true;
+            return;
+        }
+        atomicOr(&s_bits[half][slot][(J >> 5) & (kSegWords - 1)], 1u << (J & 31));
+        ++surv;
+    });
+    if (out_of_slots) s_cnt[half][3] = 1;
+    wave_sync();
+    uint32_t tiles = 0;
+    int jmin = INT_MAX, jmax = -1;
+    for (int w = tid; w < kSegSlots * kSegWords; w += kLanes) {
+        const uint32_t bits = s_bits[half][w / kSegWords][w % kSegWords];
+        if (bits) {
+            const int first = s_seg[half][w / kSegWords] * 1024 + (w % kSegWords) * 32;   // word-aligned extent
+            tiles += __popc(bits);
+            jmin = min(jmin, first);
+            jmax = max(jmax, first + 31);
+        }
+    }
+    if (jmax >= 0) {
+        atomicMin(&s_ext[half][0], jmin);
+        atomicMax(&s_ext[half][1], jmax);
+    }
+    if (tiles) atomicAdd(&s_cnt[half][0], tiles);
+    if (surv) atomicAdd(&s_cnt[half][1], surv);
+    if (cand) atomicAdd(&s_cnt[half][2], cand);
+    wave_sync();
+    if (live && tid == 0) {
+        const bool any = s_ext[half][1] >= 0;
+        const int words = any ? (s_ext[half][1] - s_ext[half][0] + 1) >> 5 : 0;
+        if (s_cnt[half][3]) {                      // left to the kernel with the full bitmap
+            row_words[I] = kRowLeftOver;
+        } else if (words > max_words) {            // span beyond what the later passes hold
+            d_scalars[S_UNSUPPORTED] = 1;
+            row_jmin[I] = 0;
+            row_c_tiles[I] = 0;
+            row_pairs[I] = 0;
+            row_words[I] = 0;
+            row_cand[I] = 0;
+        } else {
+            row_jmin[I] = any ? s_ext[half][0] : 0;
+            row_c_tiles[I] = (int32_t)s_cnt[half][0];
+            row_pairs[I] = (int32_t)s_cnt[half][1];
+            row_words[I] = words;
+            row_cand[I] = (int32_t)s_cnt[half][2];
+        }
     }
 }
 
@@ -1353,16 +1449,25 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
         // measured, up to about six words per thread)
         const int64_t grid_words = (B->tile_cols + 31) / 32;
         const int direct_words = grid_words <= std::min<int64_t>(kDirectWords, 6 * threads) ? (int)grid_words : 0;
-        // short tile-rows of A: two per wave (with more of them than the chip holds waves, half the time)
-        if (threads == 64 && direct_words == 0 && per_row <= 128)
+        // short tile-rows of A: two per wave (with more of them than the chip holds waves, half the time);
+        // against a wide B with the bitmap in segments, and a second launch for the tile-rows it leaves over
+        const bool halves = threads == 64 && direct_words == 0 && per_row <= 128;
+        if (halves && max_words > 1024) {
+            hipLaunchKernelGGL(long_rows ? k_sym_count_segmented<true> : k_sym_count_segmented<false>,
+                               dim3((unsigned)((ntr + 1) / 2)), dim3(64), 0, s, ra, rb, std::min(lanes, 8), max_words,
+                               row_jmin, row_c_tiles, row_pairs, row_words, row_cand, ctx->d_scalars);
+            hipLaunchKernelGGL(long_rows ? k_sym_count<true> : k_sym_count<false>, dim3((unsigned)ntr), dim3(threads),
+                               max_words * sizeof(uint32_t), s, ra, rb, lanes, max_words, 0, /*only_marked=*/1,
+                               row_jmin, row_c_tiles, row_pairs, row_words, row_cand, ctx->d_scalars);
+        } else if (halves)
             hipLaunchKernelGGL(long_rows ? k_sym_count_half<true> : k_sym_count_half<false>,
                                dim3((unsigned)((ntr + 1) / 2)), dim3(64), 2 * max_words * sizeof(uint32_t), s, ra, rb,
                                std::min(lanes, 8), max_words, row_jmin, row_c_tiles, row_pairs, row_words, row_cand,
                                ctx->d_scalars);
         else
-        hipLaunchKernelGGL(long_rows ? k_sym_count<true> : k_sym_count<false>, dim3((unsigned)ntr), dim3(threads),
-                           max_words * sizeof(uint32_t), s, ra, rb,
-                           lanes, max_words, direct_words, row_jmin, row_c_tiles, row_pairs, row_words, row_cand, ctx->d_scalars);
+            hipLaunchKernelGGL(long_rows ? k_sym_count<true> : k_sym_count<false>, dim3((unsigned)ntr), dim3(threads),
+                               max_words * sizeof(uint32_t), s, ra, rb, lanes, max_words, direct_words,
+                               /*only_marked=*/0, row_jmin, row_c_tiles, row_pairs, row_words, row_cand, ctx->d_scalars);
         SYM_CHECK(hipGetLastError());
     }
     {

@@ -478,6 +478,30 @@ def test_short_tile_rows_against_a_wide_operand(tsp, handle, oracle):
     run_and_check(tsp, handle, oracle, L)
 
 
+def test_short_tile_rows_against_a_very_wide_operand(tsp, handle, oracle):
+    """B wider than half a million columns: the counting kernel keeps a tile-row's bitmap in segments of
+    1024 tile columns, 16 per tile-row.  Even tile-rows of A are clustered (a few segments), odd ones are
+    scattered over more segments than a tile-row may hold and are left to the kernel with the full bitmap."""
+    rng = np.random.default_rng(321)
+    K = 1 << 20
+    tile_rows = 151
+    M = 16 * tile_rows - 3
+    rows = np.repeat(np.arange(M), 3)
+    centre = rng.integers(100, K - 100, tile_rows)                       # one cluster per tile-row
+    clustered = centre[rows // 16] + rng.integers(-40, 40, rows.size)
+    scattered = rng.integers(0, K, rows.size)
+    cols = np.where((rows // 16) % 2 == 0, clustered, scattered)
+    keys = np.unique(rows * K + cols)
+    A = inputs.from_coo(M, K, keys // K, keys % K, rng.uniform(-1, 1, keys.size), "clustered and scattered tile-rows")
+    i = np.arange(K)
+    band = np.concatenate([i, i[:-1], i[1:]])
+    bcol = np.concatenate([i, i[:-1] + 1, i[1:] - 1])
+    B = inputs.from_coo(K, K, band, bcol, rng.uniform(-1, 1, band.size), "band 2^20")
+    print(f"very wide operand: A {A.rows}x{A.cols} nnz {A.nnz}, B nnz {B.nnz}", flush=True)
+    nnz, _ = run_and_check(tsp, handle, oracle, A, B)
+    assert nnz > A.nnz
+
+
 # ------------------------------------------------------------------ heaviest tile-rows first
 def test_tile_rows_taken_in_order_of_work(tsp, oracle):
     """The general task-list kernel with its blocks taking the tile-rows heaviest first (forced here; on
