@@ -109,6 +109,12 @@ void *ctx_alloc(tsp_context *ctx, size_t bytes, hipStream_t s);          // NULL
 void ctx_free(tsp_context *ctx, void *p, hipStream_t s);                 // back into the cache
 int hip_fail(tsp_context *ctx, hipError_t e);                            // records e, returns TSP_ERR_HIP
 int read_scalars(tsp_context *ctx, hipStream_t s);                       // d_scalars -> h_scalars, syncs
+// row_ptr[0..rows] = exclusive prefix of row_len[0..rows) in one launch, the total into S_C_NNZ of the
+// scalar block, which the launch also hands to the host (wait_published_scalars with ctx->publish_tag).
+// group_len[g] = sum of row_len over rows 16g..16g+15, padded with zeros to a multiple of four entries.
+// Returns false, without launching anything, for more rows than one launch covers.
+bool row_ptr_in_one_launch(tsp_context *ctx, const int32_t *row_len, int64_t rows, const uint32_t *group_len,
+                           int64_t *row_ptr, hipStream_t s);
 // Waits until the kernel that was given `tag` has put the scalar block into h_scalars (publish_scalars).
 int wait_published_scalars(tsp_context *ctx, int64_t tag, hipStream_t s);
 // Slots for a chained scan over `blocks` blocks and a fresh epoch tag; nullptr on failure.

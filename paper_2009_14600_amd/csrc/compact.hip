@@ -30,18 +30,34 @@ __device__ __forceinline__ void row_range(const CompactArgs<RP> &a, int64_t row,
 // +0.0 and -0.0 are zeros, NaN is not
 __device__ __forceinline__ bool survives(float v) { return !(v == 0.0f); }
 
+// A block counts 16 consecutive rows; their sum goes to group_keep (what row_ptr_in_one_launch wants).
+static_assert(kCompactThreads / kCompactLanes == T, "a block covers one group of 16 rows");
 template <typename RP>
-__global__ __launch_bounds__(kCompactThreads) void k_compact_count(CompactArgs<RP> a, int32_t *__restrict__ keep) {
+__global__ __launch_bounds__(kCompactThreads) void k_compact_count(CompactArgs<RP> a, int32_t *__restrict__ keep,
+                                                                  uint32_t *__restrict__ group_keep) {
+    __shared__ int s_rows[T];
     const int64_t row = ((int64_t)blockIdx.x * kCompactThreads + threadIdx.x) / kCompactLanes;
     const int l = threadIdx.x % kCompactLanes;
-    if (row >= a.rows) return;                 // whole 16-lane groups leave together
-    int64_t e0, e1;
-    row_range(a, row, e0, e1);
     int n = 0;
-    for (int64_t e = e0 + l; e < e1; e += kCompactLanes) n += survives(a.val[e]) ? 1 : 0;
+    if (row < a.rows) {                        // whole 16-lane groups
+        int64_t e0, e1;
+        row_range(a, row, e0, e1);
+        for (int64_t e = e0 + l; e < e1; e += kCompactLanes) n += survives(a.val[e]) ? 1 : 0;
+    }
 #pragma unroll
     for (int d = kCompactLanes / 2; d > 0; d >>= 1) n += __shfl_xor(n, d, kCompactLanes);
-    if (l == 0) keep[row] = n;
+    if (l == 0) {
+        if (row < a.rows) keep[row] = n;
+        s_rows[threadIdx.x / kCompactLanes] = n;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t sum = 0;
+        for (int r = 0; r < T; ++r) sum += (uint32_t)s_rows[r];
+        group_keep[blockIdx.x] = sum;
+    }
+    // zeros behind the last group, up to a multiple of four entries (the array has four spare ones)
+    if (blockIdx.x == 0 && threadIdx.x < 4) group_keep[gridDim.x + threadIdx.x] = 0;
 }
 
 template <typename RP>
@@ -85,28 +101,39 @@ static int compact_run(tsp_context *ctx, const tsp_csr *C, tsp_csr *out, hipStre
     int64_t *new_row_ptr = ctx_alloc_n<int64_t>(ctx, (size_t)rows + 1, s);
     int32_t *col = nullptr;
     float *val = nullptr;
+    const int64_t row_blocks = (rows * kCompactLanes + kCompactThreads - 1) / kCompactThreads;   // groups of 16 rows
+    uint32_t *group_keep = ctx_alloc_n<uint32_t>(ctx, (size_t)row_blocks + 4, s);
     auto fail = [&](int code) {
         ctx_free(ctx, keep, s);
+        ctx_free(ctx, group_keep, s);
         ctx_free(ctx, new_row_ptr, s);
         ctx_free(ctx, col, s);
         ctx_free(ctx, val, s);
         return code;
     };
-    if (!keep || !new_row_ptr) return fail(TSP_ERR_ALLOC_FAILED);
-    const int64_t row_blocks = (rows * kCompactLanes + kCompactThreads - 1) / kCompactThreads;
-    int64_t *tmp = ctx_alloc_n<int64_t>(ctx, scan_tmp_entries(rows), s);
-    if (!tmp) return fail(TSP_ERR_ALLOC_FAILED);
-    hipLaunchKernelGGL(k_compact_clear, dim3(1), dim3(64), 0, s, ctx->d_scalars);
+    if (!keep || !new_row_ptr || !group_keep) return fail(TSP_ERR_ALLOC_FAILED);
+    if (!ctx->scalars_clean) hipLaunchKernelGGL(k_compact_clear, dim3(1), dim3(64), 0, s, ctx->d_scalars);
     ctx->scalars_clean = false;
     if (rows > 0)
-        hipLaunchKernelGGL(k_compact_count<RP>, dim3((unsigned)row_blocks), dim3(kCompactThreads), 0, s, a, keep);
-    // new row_ptr = exclusive prefix of the survivor counts, the total to the scalar block
-    int rc = scan_exclusive_i32_to_i64(ctx, keep, new_row_ptr, rows, ctx->d_scalars + S_C_NNZ, nullptr, tmp, s);
-    ctx_free(ctx, tmp, s);
-    if (rc) return fail(rc);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return fail(hip_fail(ctx, e));
-    rc = read_scalars(ctx, s);                           // host synchronisation: the new nnz
+        hipLaunchKernelGGL(k_compact_count<RP>, dim3((unsigned)row_blocks), dim3(kCompactThreads), 0, s, a, keep,
+                           group_keep);
+    // new row_ptr = exclusive prefix of the survivor counts, the total to the scalar block and on to the host:
+    // one launch that writes the scalars into the host's mirror itself, or three and a copy for very many rows
+    int rc = TSP_OK;
+    if (row_ptr_in_one_launch(ctx, keep, rows, group_keep, new_row_ptr, s)) {
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return fail(hip_fail(ctx, e));
+        rc = wait_published_scalars(ctx, ctx->publish_tag, s);   // host synchronisation: the new nnz
+    } else {
+        int64_t *tmp = ctx_alloc_n<int64_t>(ctx, scan_tmp_entries(rows), s);
+        if (!tmp) return fail(TSP_ERR_ALLOC_FAILED);
+        rc = scan_exclusive_i32_to_i64(ctx, keep, new_row_ptr, rows, ctx->d_scalars + S_C_NNZ, nullptr, tmp, s);
+        ctx_free(ctx, tmp, s);
+        if (rc) return fail(rc);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return fail(hip_fail(ctx, e));
+        rc = read_scalars(ctx, s);                           // host synchronisation: the new nnz
+    }
     if (rc) return fail(rc);
     if (ctx->h_scalars[S_INTERNAL]) return fail(TSP_ERR_HIP);
     const int64_t nnz = ctx->h_scalars[S_C_NNZ];
@@ -122,10 +149,11 @@ static int compact_run(tsp_context *ctx, const tsp_csr *C, tsp_csr *out, hipStre
     if (rows > 0 && nnz > 0) {
         hipLaunchKernelGGL(k_compact_fill<RP>, dim3((unsigned)row_blocks), dim3(kCompactThreads), 0, s, a, new_row_ptr,
                            col, val);
-        e = hipGetLastError();
+        const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return fail(hip_fail(ctx, e));
     }
     ctx_free(ctx, keep, s);
+    ctx_free(ctx, group_keep, s);
     out->rows = C->rows;
     out->cols = C->cols;
     out->nnz = nnz;

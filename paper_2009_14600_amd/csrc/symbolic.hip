@@ -1343,6 +1343,15 @@ __global__ __launch_bounds__(256) void k_row_offsets_wide(int64_t c_rows, const 
     }
 }
 
+bool row_ptr_in_one_launch(tsp_context *ctx, const int32_t *row_len, int64_t rows, const uint32_t *group_len,
+                           int64_t *row_ptr, hipStream_t s) {
+    const int64_t groups = (rows + T - 1) / T, chunks = (groups + kChunkTileRows - 1) / kChunkTileRows;
+    if (chunks < 1 || chunks > kMaxChunks) return false;
+    hipLaunchKernelGGL(k_row_ptr, dim3((unsigned)chunks), dim3(256), 0, s, row_len, rows, group_len, groups, row_ptr,
+                       ctx->d_scalars, ctx->h_scalars_dev, ++ctx->publish_tag);
+    return true;
+}
+
 void plan_release(tsp_context *ctx, tsp_plan_s *p, hipStream_t s) {
     if (!p) return;
     ctx_free(ctx, p->c_tile_row_ptr, s);
