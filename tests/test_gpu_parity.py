@@ -406,6 +406,28 @@ def test_compact_zeros_on_a_caller_matrix_with_int32_row_ptr(tsp, handle):
     assert np.array_equal(v.view(np.uint32), val[keep].view(np.uint32))
 
 
+def test_compact_zeros_with_more_rows_than_one_prefix_sum_launch_covers(tsp, handle):
+    """600,000 rows (the one-launch prefix sum stops at 524,288): the new row_ptr comes from the three-kernel
+    scan.  Rows of 0 to 3 entries, a ragged last group of rows, expected result from the definition."""
+    import torch
+    rng = np.random.default_rng(13)
+    rows, cols = 600_003, 50
+    lens = rng.integers(0, 4, rows)
+    row_ptr = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    nnz = int(row_ptr[-1])
+    first = rng.integers(0, cols - 3, rows)
+    col = (np.repeat(first, lens) + (np.arange(nnz) - np.repeat(row_ptr[:-1], lens))).astype(np.int32)
+    val = rng.integers(-1, 2, nnz).astype(np.float32)
+    C = tsp.DeviceCSR(rows, cols, torch.from_numpy(row_ptr).cuda(), torch.from_numpy(col).cuda(),
+                      torch.from_numpy(val).cuda())
+    D = handle.compact_zeros(C)
+    keep = ~(val == 0.0)
+    want_ptr = np.concatenate([[0], np.cumsum(keep)])[row_ptr]
+    rp, c, v = D.to_host()
+    D.free()
+    assert np.array_equal(rp, want_ptr) and np.array_equal(c, col[keep]) and np.array_equal(v, val[keep])
+
+
 # ------------------------------------------------------------------ precision study (Section 6.3, Eq. 3)
 def test_smape_against_full_precision_as_in_the_paper(tsp, handle, oracle):
     """The paper's two observations on synthetic inputs: 0/1 patterns give SMAPE 0 %; real
