@@ -473,6 +473,21 @@ def test_tile_rows_with_more_output_tiles_than_the_symbolic_window(tsp, handle, 
     C.free()
 
 
+# ------------------------------------------------------------------ more rows than the one-launch row_ptr covers
+def test_band_matrix_with_600000_rows(tsp, handle, oracle):
+    """Beyond 524,288 rows row_ptr of C comes from the three-kernel scan instead of the one-launch prefix sum,
+    and the sizing scan chains several dozen blocks.  A band matrix keeps the oracle's work small."""
+    n = 600_007
+    i = np.arange(n)
+    rng = np.random.default_rng(600)
+    rows = np.concatenate([i, i[:-1], i[1:], i[:-5]])
+    cols = np.concatenate([i, i[:-1] + 1, i[1:] - 1, i[:-5] + 5])
+    A = inputs.from_coo(n, n, rows, cols, rng.uniform(-1, 1, rows.size), "band 600007")
+    print(f"{A.name}: nnz {A.nnz}", flush=True)
+    nnz, _ = run_and_check(tsp, handle, oracle, A)
+    assert nnz > 2 * A.nnz
+
+
 # ------------------------------------------------------------------ two tile-rows per wave in the counting kernel
 def test_short_tile_rows_against_a_wide_operand(tsp, handle, oracle):
     """Short tile-rows of A against a B too wide for the counting kernel's whole-grid bitmap: the kernel
