@@ -295,6 +295,10 @@ __global__ __launch_bounds__(kNumThreads) void k_numeric(
 
     int h_start = 0;                              // relative position of the first staged entry
     stage_headers(0);
+    Group next_a, next_b;                         // whole-tile-row kernel: operands of the next tile's first step
+    next_a.u = next_b.u = make_uint4(0, 0, 0, 0);
+    if constexpr (kWholeRows && kMatrixCores)
+        load_operands(0, __builtin_amdgcn_readlane(rel_lane, 1) > 1, next_a, next_b);
     const int64_t base_first = c_row_ptr[(int64_t)I_first * T];
     uint32_t(*const my_entries)[kWholeRows ? kRowEntries : 1] = lds_entries[kWholeRows ? wave_in_block : 0];
     int row_entries = 0;                          // whole-tile-row kernel: entries of the tile-row
@@ -344,6 +348,27 @@ __global__ __launch_bounds__(kNumThreads) void k_numeric(
                 em.first = c_row_off[c_mine * T + row_l];
             }
             float4v acc[kGroupTiles];
+            if constexpr (kWholeRows && kMatrixCores) {
+                // Every task-list entry of the tile-row is staged (at most 64: the host has checked), so a
+                // tile's operands do not wait for anything but the tile before it: the first step of the next
+                // tile is requested before the current tile is multiplied, and a wave goes through one memory
+                // round trip per two tiles instead of one per tile (the tiles of such a tile-row have one
+                // or two steps each, and the round trips were 60 % of a wave's life).
+#pragma unroll
+                for (int t = 0; t < kGroupTiles; ++t) {
+                    acc[t] = float4v{0.f, 0.f, 0.f, 0.f};
+                    const int tile = g * kGroupTiles + t;
+                    if (tile < run_tiles) {       // uniform
+                        const int r0 = __builtin_amdgcn_readlane(rel_lane, tile);
+                        const int r1 = __builtin_amdgcn_readlane(rel_lane, tile + 1);
+                        const Group a_now = next_a, b_now = next_b;
+                        if (tile + 1 < run_tiles)
+                            load_operands(r1, __builtin_amdgcn_readlane(rel_lane, tile + 2) - r1 > 1, next_a, next_b);
+                        if (r1 > r0) acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a_now.h, b_now.h, acc[t], 0, 0, 0);
+                        if (r1 - r0 > 2) multiply(r0 + 2, r1 - r0 - 2, acc[t]);
+                    }
+                }
+            } else
 #pragma unroll
             for (int t = 0; t < kGroupTiles; ++t) {
                 acc[t] = float4v{0.f, 0.f, 0.f, 0.f};
