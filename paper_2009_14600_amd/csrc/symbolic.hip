@@ -1075,12 +1075,14 @@ __global__ __launch_bounds__(kTeamLanes ? 64 : kSymThreads) void k_sym_emit_list
     team::sync();
     {
         const int g = tid >> 4, r = tid & 15, groups = nthreads >> 4;
-        for (int k0 = g * kPairsPerTrip; k0 < n; k0 += groups * kPairsPerTrip) {
-            uint32_t am[kPairsPerTrip];
-            uint4 x[kPairsPerTrip], y[kPairsPerTrip];
-            int c_of[kPairsPerTrip];
-            // (a trip past the end of the list reads the last entry again and selects nothing of it: no
-            // branches and no zero-filled registers around the loads)
+        // The bitmaps of the next trip are requested before the products of the current one are formed: a trip
+        // is a memory round trip for a few dozen instructions of work.  (A trip past the end of the list reads
+        // the last entry again and selects nothing of it: no branches and no zero-filled registers around
+        // the loads.)
+        uint32_t am[kPairsPerTrip];
+        uint4 x[kPairsPerTrip], y[kPairsPerTrip];
+        int c_of[kPairsPerTrip];
+        auto request = [&](int k0) {
 #pragma unroll
             for (int u = 0; u < kPairsPerTrip; ++u) {
                 const int k = min(k0 + u, n - 1);
@@ -1090,12 +1092,41 @@ __global__ __launch_bounds__(kTeamLanes ? 64 : kSymThreads) void k_sym_emit_list
                 y[u] = bp[1];
                 c_of[u] = list_c[k];
             }
+        };
+        const int stride = groups * kPairsPerTrip;
+        if constexpr (kTeamLanes != 0) {
+            // (half a wave per tile-row: the second set of registers would cost the kernel its eighth wave per
+            // SIMD, and with it the single round in which all tile-rows of a large product are resident)
+            for (int k0 = g * kPairsPerTrip; k0 < n; k0 += stride) {
+                request(k0);
+#pragma unroll
+                for (int u = 0; u < kPairsPerTrip; ++u) {
+                    const uint32_t m = boolean_row_product(k0 + u < n ? am[u] : 0u, x[u], y[u], row_select);
+                    const uint32_t m16 = (m | (m >> 16)) & 0xFFFFu;
+                    if (m16) atomicOr(&cmask[c_of[u] * 8 + (r >> 1)], m16 << ((r & 1) * 16));
+                }
+            }
+        } else {
+        if (g * kPairsPerTrip < n) request(g * kPairsPerTrip);
+        for (int k0 = g * kPairsPerTrip; k0 < n; k0 += stride) {
+            uint32_t am_now[kPairsPerTrip];
+            uint4 x_now[kPairsPerTrip], y_now[kPairsPerTrip];
+            int c_now[kPairsPerTrip];
 #pragma unroll
             for (int u = 0; u < kPairsPerTrip; ++u) {
-                const uint32_t m = boolean_row_product(k0 + u < n ? am[u] : 0u, x[u], y[u], row_select);
-                const uint32_t m16 = (m | (m >> 16)) & 0xFFFFu;
-                if (m16) atomicOr(&cmask[c_of[u] * 8 + (r >> 1)], m16 << ((r & 1) * 16));
+                am_now[u] = k0 + u < n ? am[u] : 0u;
+                x_now[u] = x[u];
+                y_now[u] = y[u];
+                c_now[u] = c_of[u];
             }
+            if (k0 + stride < n) request(k0 + stride);
+#pragma unroll
+            for (int u = 0; u < kPairsPerTrip; ++u) {
+                const uint32_t m = boolean_row_product(am_now[u], x_now[u], y_now[u], row_select);
+                const uint32_t m16 = (m | (m >> 16)) & 0xFFFFu;
+                if (m16) atomicOr(&cmask[c_now[u] * 8 + (r >> 1)], m16 << ((r & 1) * 16));
+            }
+        }
         }
     }
     team::sync();
