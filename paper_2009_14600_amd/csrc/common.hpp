@@ -31,7 +31,7 @@ enum Scalar {
     S_INTERNAL = 11,         // != 0: a bounded device-side wait ran out (should never happen)
     S_MAX_ROW_PAIRS = 12,    // max over C tile-rows of the number of task-list entries
     S_MAX_ROW_ENTRIES = 13,  // max over C tile-rows of the number of structural entries
-    S_PUBLISHED = 31,        // host mirror only: the tag of the publication the mirror holds (publish_scalars)
+    S_PUBLISHED = 31,        // host mirror only: a slot without a value (publish_scalars tags every slot)
 };
 
 struct Block {
@@ -182,21 +182,24 @@ __device__ __forceinline__ void wave_sync() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-// The scalar block copied into the host's pinned mirror, followed by `tag`, by the block of a kernel that
-// knows every other writer of the block has finished (all threads of that block call this, at least
-// kScalars of them).  The host polls the mirror for the tag: it has the sizes it waits for as soon as
-// they exist, without a copy (a launch of its own) and without waiting for the queue to drain.
+// The scalar block copied into the host's pinned mirror by the block of a kernel that knows every other
+// writer of the block has finished (all threads of that block call this, at least kScalars of them).  The
+// host polls the mirror: it has the sizes it waits for as soon as they exist, without a copy (a launch of
+// its own) and without waiting for the queue to drain.  Every 8-byte slot carries the publication's tag in
+// its top 16 bits (the scalars are counts below 2^48), so the host knows a slot is new by the slot itself:
+// no store has to be ordered behind another across the bus, and the kernel does not wait for a fence.
+constexpr int kPublishTagShift = 48;
+__host__ __device__ inline uint64_t publish_tag16(int64_t tag) { return (uint64_t)(tag % 65535) + 1u; }   // never 0
 __device__ __forceinline__ void publish_scalars(int64_t *d_scalars, int64_t *h_scalars_dev, int64_t tag) {
     __threadfence();                               // this block's own plain stores to the scalar block
     __syncthreads();
-    if (threadIdx.x < kScalars && threadIdx.x != S_PUBLISHED) {
-        const int64_t v = __hip_atomic_load(&d_scalars[threadIdx.x], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_store(&h_scalars_dev[threadIdx.x], v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    if (threadIdx.x < kScalars) {
+        const uint64_t v = threadIdx.x == S_PUBLISHED
+                               ? 0u
+                               : (uint64_t)__hip_atomic_load(&d_scalars[threadIdx.x], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const uint64_t slot = (publish_tag16(tag) << kPublishTagShift) | (v & ((1ull << kPublishTagShift) - 1u));
+        __hip_atomic_store(&h_scalars_dev[threadIdx.x], (int64_t)slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
     }
-    __threadfence_system();                        // the values before the tag
-    __syncthreads();
-    if (threadIdx.x == 0)
-        __hip_atomic_store(&h_scalars_dev[S_PUBLISHED], tag, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
 }
 
 // Cross-lane operations on the data-parallel-primitive path (VALU speed, no LDS round trips).

@@ -78,16 +78,27 @@ int read_scalars(tsp_context *ctx, hipStream_t s) {
 
 int wait_published_scalars(tsp_context *ctx, int64_t tag, hipStream_t s) {
     // The kernel is short (tens of microseconds after the launch): poll the mirror for a while before
-    // falling back to a blocking wait, whose wake-up alone costs several microseconds.
+    // falling back to a blocking wait, whose wake-up alone costs several microseconds.  The publication is
+    // complete when every slot carries its tag; the tags are then taken off.
+    const uint64_t want = publish_tag16(tag);
+    auto complete = [&]() {
+        for (int i = 0; i < kScalars; ++i)
+            if (((uint64_t)__atomic_load_n(&ctx->h_scalars[i], __ATOMIC_ACQUIRE) >> kPublishTagShift) != want) return false;
+        return true;
+    };
+    auto strip = [&]() {
+        for (int i = 0; i < kScalars; ++i) ctx->h_scalars[i] &= (int64_t)((1ull << kPublishTagShift) - 1u);
+        return TSP_OK;
+    };
     const auto t0 = std::chrono::steady_clock::now();
     for (unsigned spins = 0;; ++spins) {
-        if (__atomic_load_n(&ctx->h_scalars[S_PUBLISHED], __ATOMIC_ACQUIRE) == tag) return TSP_OK;
+        if (complete()) return strip();
         if ((spins & 1023) == 1023 &&
             std::chrono::steady_clock::now() - t0 > std::chrono::microseconds(500)) break;
     }
     TSP_HIP_CHECK(ctx, hipStreamSynchronize(s));
-    if (__atomic_load_n(&ctx->h_scalars[S_PUBLISHED], __ATOMIC_ACQUIRE) != tag) return hip_fail(ctx, hipErrorUnknown);
-    return TSP_OK;
+    if (!complete()) return hip_fail(ctx, hipErrorUnknown);
+    return strip();
 }
 
 void *chain_prepare(tsp_context *ctx, int64_t blocks, unsigned *epoch, hipStream_t s) {
