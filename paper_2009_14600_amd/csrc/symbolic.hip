@@ -92,8 +92,8 @@ __device__ __forceinline__ uint32_t block_exclusive_scan_lds(uint32_t *arr, int 
 // kLongRows: built for operands whose B tile-rows are long (more tiles than lanes share an A tile).
 // kBatched: every trip requests several B tiles, those past the end of the tile-row switched off, so a
 // short tile-row of B takes one round trip; otherwise only full trips are batched and the rest goes tile by
-// tile (better where f is heavy: the list kernel, whose f appends to an LDS list, loses 3 % with batching,
-// the other kernels gain 10-30 % of their time).
+// tile (better where f is heavy: the list kernel with a block per tile-row, whose f appends to an LDS list,
+// loses 3 % with batching; the other kernels gain up to 30 % of their time).
 // tid, nthreads: this thread's place among the threads that share the tile-row (a block, or part of a wave).
 template <bool kLongRows, bool kBatched, class F>
 __device__ __forceinline__ void for_each_survivor(const TileRefs &A, const TileRefs &B, int a_begin, int a_end,
@@ -992,7 +992,7 @@ __global__ __launch_bounds__(kTeamLanes ? 64 : kSymThreads) void k_sym_emit_list
     for (int w = tid; w < words; w += nthreads) bm[w] = 0;
     team::sync();
     uint32_t dummy = 0;
-    for_each_survivor<kLongRows, false>(A, B, a0, a1, lanes_per_a, &dummy, tid, nthreads, [&](int a, int b, int J) {
+    for_each_survivor<kLongRows, (kTeamLanes != 0)>(A, B, a0, a1, lanes_per_a, &dummy, tid, nthreads, [&](int a, int b, int J) {
         const uint32_t j = (uint32_t)(J - jmin);
         if (j < (uint32_t)span) {
             atomicOr(&bm[j >> 5], 1u << (j & 31));
