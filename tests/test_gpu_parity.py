@@ -170,6 +170,10 @@ def test_runs_are_bit_identical(tsp, handle):
 # ------------------------------------------------------------------ error paths (forced from the host)
 def test_error_codes(tsp, handle):
     import torch
+    for key, value in [(tsp.OPT_WORK_ORDER, 3), (tsp.OPT_WORK_ORDER, -1), (tsp.OPT_NUMERIC_RUN, 5), (99, 0)]:
+        with pytest.raises(tsp.TspError) as e:                      # option values out of range, unknown option
+            handle.set_option(key, value)
+        assert e.value.status == -1
     A = tsp.to_device(inputs.random_sparse(20, 30, 0.2, 1))
     B = tsp.to_device(inputs.random_sparse(31, 10, 0.2, 2))
     with pytest.raises(tsp.TspError) as e:
