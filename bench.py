@@ -6,16 +6,27 @@ phase, counting pass, MFMA numeric phase, CSR emission, allocation of C) with th
 resident in HBM.  Prints ONE JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 1..5] [--no-cpu-baseline]
+                  [--no-per-workload]
+
+The headline (value, ms_per_step, roofline, cpu_baseline) is the workload --workload names, by
+default the largest of the five benchmark configurations (R-MAT scale 18: 9.49e9 intermediate
+products, 2.96e9 entries of C); `per_workload` carries the same figures for all five.
 
 metric: spGEMM GFLOP/s = 2 * intermediate products / second.
-roofline: for the kernel that takes the most device time in a step, algorithmic HBM bytes per
-launch divided by its average duration (HIP events on the launch stream, recorded by the
-library around every kernel), against the 8 TB/s HBM peak.
+roofline: for the kernel that takes the most device time in a step, the bytes the method itself has
+to move in one launch (packed fp16 elements, a 32-byte bitmap and a 16-byte record per tile, 8 bytes
+per task-list entry, 8 bytes per entry of C: `algorithmic_bytes`) divided by the kernel's average
+duration (HIP events on the launch stream, recorded by the library around every kernel), against the
+8 TB/s HBM peak.  `layout_bytes_per_launch` is the same count for the arrays this library actually
+keeps (operand groups of 16 bytes, row offsets per output tile), for comparison.
+phase_hbm: the same for the conversion, the symbolic phase (with the counting pass), the numeric
+phase with its CSR emission, and a separately timed tsp_compact_zeros call on the result.
 cpu_baseline: the CPU oracle (row-wise Gustavson, fp64) timed on this machine's host cores.
 """
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
 import os
 import sys
@@ -29,17 +40,33 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_F16_PEAK_TFLOPS = 2500.0  # dense fp16 MFMA, published
-
+CSRC = os.path.join(ROOT, "paper_2009_14600_amd", "csrc")
 
 # HBM bytes per launch measured with rocprofv3 (--pmc FETCH_SIZE, then --pmc WRITE_SIZE, one run each, on
-# this bench at --steps 3), scaled by what the same counters read for a 1 GiB device copy: fetched bytes =
-# 2048 * FETCH_SIZE, written bytes = 1024 * WRITE_SIZE.  profiles/hbm_traffic_all_kernels.txt holds the
-# readings and commands.  Keyed by (workload, kernel); a kernel that has changed since needs a new reading.
-MEASURED_TRAFFIC_BYTES = {
-    (2, "numeric"): 2048 * 30665.9 + 1024 * 26555.3,
-    (2, "sym_emit"): 2048 * 11415.9 + 1024 * 24759.9,      # with the counting pass and the row offsets
-    (3, "numeric"): 2048 * 341237.0 + 1024 * 1196171.5,
+# this bench with --no-per-workload --steps 3), scaled by what the same counters read for a 1 GiB device
+# copy: fetched bytes = 2048 * FETCH_SIZE, written bytes = 1024 * WRITE_SIZE.  Every reading carries the
+# first 12 hex digits of the SHA-256 of the kernel's source file as it was when the reading was taken; a
+# reading whose source has changed since is not reported (traffic: null) instead of going stale silently.
+# profiles/hbm_traffic_*.txt hold the readings and the commands.
+#   (workload, kernel): (source file, sha256[:12] at the time, FETCH_SIZE, WRITE_SIZE)
+MEASURED_TRAFFIC = {
 }
+
+KERNEL_SOURCE = {"convert": "convert.hip", "sym_count": "symbolic.hip", "scan_sym": "symbolic.hip",
+                 "sym_emit": "symbolic.hip", "count_masks": "symbolic.hip", "row_offsets": "symbolic.hip",
+                 "scan_rows": "symbolic.hip", "numeric": "numeric.hip"}
+
+
+def source_digest(name: str) -> str:
+    with open(os.path.join(CSRC, name), "rb") as f:
+        return hashlib.sha256(f.read()).hexdigest()[:12]
+
+
+def measured_traffic(workload: int, kernel: str):
+    rec = MEASURED_TRAFFIC.get((workload, kernel))
+    if rec is None or source_digest(rec[0]) != rec[1]:
+        return None
+    return int(2048 * rec[2] + 1024 * rec[3])
 
 
 def popcount32(x):
@@ -50,57 +77,145 @@ def popcount32(x):
     return ((x * 0x01010101) >> 24).astype(np.int64)
 
 
-def algorithmic_bytes(kernel, A, st, groups_left, groups_right):
-    """Bytes the method itself has to move in one launch of `kernel` (every array read or written
-    exactly once; re-reads of tiles through the task list are not counted)."""
+def algorithmic_bytes(kernel, A, st):
+    """Bytes the method itself has to move in one launch of `kernel`: every object read or written
+    once, in the paper's packed tile format (Section 2.1.2 at a tile edge of 16: 2 bytes per stored
+    element, a 32-byte bitmap and a 16-byte record {tile column, occupancy words, element offset} per
+    tile), 8 bytes per task-list entry, 16 bytes of coordinates and segment offset per output tile, a
+    32-byte bitmap per output tile, 8 bytes per entry of C and 8 per row pointer of C.  Re-reads of
+    tiles through the task list are not counted, nor is anything this library's own layout adds."""
     n, nnz = A.rows, A.nnz
     ta, ct, pairs, cnnz = st["a_tiles"], st["c_tiles"], st["pairs"], st["c_nnz"]
     ntr = (n + 15) // 16
-    tile_meta = ta * (4 + 32 + 4 + 4 + 8 + 8)          # tile_col, row masks, 2 group masks, 2 headers {mask, first group}
+    tiles_packed = 2 * nnz + 48 * ta
+    table = {
+        "convert": 4 * (n + 1) + 6 * nnz + tiles_packed,                   # CSR in, tiles out
+        "sym_count": 16 * ta + 16 * ntr,                                   # tile records in, sizes per tile-row out
+        "scan_sym": 24 * ntr,
+        "sym_emit": 16 * ta + 16 * ntr + 8 * pairs + 16 * ct,              # tile records in, task list out
+        "count_masks": 8 * pairs + 16 * ct + 32 * ta + 32 * ct,            # task list and bitmaps in, C bitmaps out
+        "row_offsets": 32 * ct + 4 * n,                                    # C bitmaps in, entries per row out
+        "scan_rows": 4 * n + 8 * (n + 1),
+        "numeric": tiles_packed + 8 * pairs + 16 * ct + 32 * ct + 8 * cnnz + 8 * (n + 1),
+        # the task-list kernel when it also runs the counting pass: the task list and the C bitmaps are not read back
+        "sym_emit_fused": 16 * ta + 16 * ntr + 8 * pairs + 16 * ct + 32 * ta + 32 * ct + 4 * n,
+    }
+    return int(table[kernel])
+
+
+def layout_bytes(kernel, A, st, groups_left, groups_right):
+    """The same count for the arrays this library keeps (operand groups of 16 bytes in both forms,
+    60 bytes of tile metadata, 64 bytes of row offsets per output tile)."""
+    n, nnz = A.rows, A.nnz
+    ta, ct, pairs, cnnz = st["a_tiles"], st["c_tiles"], st["pairs"], st["c_nnz"]
+    ntr = (n + 15) // 16
+    tile_meta = ta * (4 + 32 + 4 + 4 + 8 + 8)
     csr_in = 4 * (n + 1) + 6 * nnz
     table = {
         "convert": csr_in + 8 * ntr + tile_meta + 16 * (groups_left + groups_right),
-        # symbolic kernels: tile CSR of A, and per candidate the B tile's column and occupancy word
         "sym_count": 8 * ntr + 8 * ta + 8 * st["candidate_pairs"] + 12 * ntr,
         "sym_emit": 8 * ntr + 8 * ta + 8 * st["candidate_pairs"] + 16 * ntr + 16 * ct + 8 * pairs,
         "count_masks": 8 * ct + 8 * pairs + 32 * ta + 32 * ta + 32 * ct,
         "row_offsets": 4 * ntr + 32 * ct + 64 * ct + 4 * n,
-        "numeric": (8 * ct + 8 * pairs + 8 * ct + 32 * ct + 64 * ct + 8 * (n + 1)      # task list, C tile info
-                    + 16 * ta + 16 * (groups_left + groups_right)                    # tile headers and groups, each once
-                    + 8 * cnnz),                                                     # C col_idx + val
+        "numeric": (8 * ct + 8 * pairs + 8 * ct + 32 * ct + 64 * ct + 8 * (n + 1)
+                    + 16 * ta + 16 * (groups_left + groups_right) + 8 * cnnz),
         "scan_sym": 24 * ntr, "scan_rows": 16 * n,
     }
     return int(table[kernel])
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=None)
-    ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", type=int, default=2, help="benchmark configuration 1..5 (see inputs.CONFIG_NAMES)")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-validate", action="store_true", help="switch the input validation kernel off")
-    ap.add_argument("--no-matrix-cores", action="store_true",
-                    help="block products on the vector ALUs instead of MFMA (the paper's nonTCU comparison)")
-    ap.add_argument("--compact-zeros", action="store_true",
-                    help="finish every step with the compaction of zero-valued entries (paper Section 4.4)")
-    ap.add_argument("--numeric-run", type=int, default=0, help="tiles per wave of the multiplication kernel (0: automatic)")
-    args = ap.parse_args()
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build measures one GPU only (--gpus 1); the path has no multi-GPU part",
-              file=sys.stderr)
-        sys.exit(2)
+def hbm(bytes_, us):
+    gbs = bytes_ / (us * 1e-6) / 1e9 if us > 0 else 0.0
+    return {"algorithmic_bytes": int(bytes_), "us": round(us, 2), "achieved_gbs": round(gbs, 1),
+            "frac": round(gbs / HBM_PEAK_GBS, 5)}
 
-    import torch
-    from paper_2009_14600_amd import inputs, tsp
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        sys.exit(2)
-    tsp.load_library()
-    torch.cuda.set_device(0)
 
-    A = inputs.config(args.workload)
+def cpu_model() -> str:
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def oracle_leg(A, handle, tsp, sA, budget_products, seconds):
+    """The CPU oracle on a leading block of rows holding about `budget_products` products: timed (when
+    seconds > 0), and compared with the same rows of the GPU result (Eq. 3's SMAPE between the fp32
+    result and the oracle's fp64 sums of the same fp16 inputs, and the largest error over the bound)."""
+    from concurrent.futures import ThreadPoolExecutor
+    from oracle import reference
+    reference.build_lib()
+    threads = min(16, os.cpu_count() or 1)
+    rl = np.diff(A.row_ptr).astype(np.int64)
+    csum = np.concatenate([[0], np.cumsum(rl[A.col_idx])])
+    per_row = csum[A.row_ptr.astype(np.int64)]          # products of rows [0, i)
+    rows = int(np.searchsorted(per_row, budget_products, side="right"))
+    rows = max(1, min(A.rows, rows))
+    sample_products = int(per_row[rows])
+    ops = (reference._Operand(A), reference._Operand(A))   # fp16 -> fp64 widening, once, outside the timing
+    bounds = np.searchsorted(per_row[:rows + 1], np.linspace(0, sample_products, 8 * threads + 1)).astype(np.int64)
+    bounds[0], bounds[-1] = 0, rows
+    bounds = np.unique(bounds)
+
+    def run(nthreads):
+        if nthreads == 1:
+            return [reference.spgemm_rows(A, A, 0, rows, _ops=ops)]
+        with ThreadPoolExecutor(max_workers=nthreads) as pool:
+            return list(pool.map(lambda i: reference.spgemm_rows(A, A, int(bounds[i]), int(bounds[i + 1]), _ops=ops),
+                                 range(bounds.shape[0] - 1)))
+
+    def timed(nthreads):
+        t0 = time.perf_counter()
+        parts = run(nthreads)
+        dt = time.perf_counter() - t0
+        reps = int(min(2000, seconds / max(dt, 1e-4)))
+        if reps > 1:
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                run(nthreads)
+            dt = (time.perf_counter() - t0) / reps
+        return parts, dt, max(reps, 1)
+
+    out = {}
+    if seconds > 0:
+        p1, t1, _ = timed(1)
+        parts, tn, reps = timed(threads)
+        assert sum(p.products for p in p1) == sample_products
+        out["cpu_baseline"] = {
+            "value": round(2.0 * sample_products / tn / 1e9, 4), "unit": "GFLOP/s", "cores": threads, "kind": "oracle",
+            "sample": f"rows [0,{rows}) of {A.rows} of C = A*A ({sample_products} products, "
+                      f"{sum(p.nnz for p in parts)} entries of C), mean of {reps} runs",
+            "includes": "per block of rows: the sizing pass (structural row lengths) and the value pass "
+                        "(dense accumulator, fp64 sums and sums of magnitudes, column sort); excludes the "
+                        "one-off widening of the fp16 inputs to fp64 and the generation of the inputs",
+            "cpu": cpu_model(), "host_cores_visible": os.cpu_count(),
+            "single_thread_value": round(2.0 * sample_products / t1 / 1e9, 4),
+            "seconds": round(tn, 3), "single_thread_seconds": round(t1, 3)}
+    else:
+        parts = run(threads)
+    # the same rows of the GPU result
+    raw = handle.spgemm_raw(sA, sA)
+    C = handle._wrap_output(raw)
+    rp = C.row_ptr[:rows + 1].cpu().numpy()
+    hi = int(rp[-1])
+    col, val = C.col_idx[:hi].cpu().numpy(), C.val[:hi].cpu().numpy().astype(np.float64)
+    C.free()
+    ref_col = np.concatenate([p.col for p in parts])
+    ref_val = np.concatenate([p.val for p in parts])
+    ref_mag = np.concatenate([p.mag for p in parts])
+    same = ref_col.shape == col.shape and np.array_equal(ref_col, col)
+    out["accuracy"] = {"rows": rows, "entries": int(hi), "pattern_equal": bool(same)}
+    if same and hi:
+        out["accuracy"]["smape_percent"] = round(reference.smape_percent(ref_val, val), 8)
+        out["accuracy"]["max_error_over_bound"] = round(float(np.max(np.abs(val - ref_val) / (1e-5 * ref_mag + 1e-7))), 5)
+    return out
+
+
+def run_workload(index, steps, warmup, args, tsp, inputs, torch, headline):
+    A = inputs.config(index)
     products = int(np.diff(A.row_ptr).astype(np.int64)[A.col_idx].sum())
     flop = 2.0 * products
     dA = tsp.to_device(A)
@@ -127,8 +242,10 @@ def main():
     step()
     torch.cuda.synchronize()
     est = max(time.perf_counter() - t0, 1e-5)
-    steps = args.steps if args.steps is not None else int(min(200, max(5, 10.0 / est)))
-    warmup = args.warmup if args.warmup is not None else min(5, steps)
+    if steps is None:
+        steps = int(min(200, max(5, (10.0 if headline else 1.0) / est)))
+    if warmup is None:
+        warmup = min(5, steps)
 
     for _ in range(warmup):
         step()
@@ -144,10 +261,11 @@ def main():
 
     # per-kernel device time: same steps again with the library's event timers on
     handle.set_option(tsp.OPT_PHASE_TIMERS, 1)
+    tsteps = min(steps, 20)
     ksum = {k: 0.0 for k in tsp.KERNELS}
     psum = {k: 0.0 for k in tsp.PHASES}
     total_us = 0.0
-    for _ in range(steps):
+    for _ in range(tsteps):
         step()
         s2 = handle.stats()
         for k in ksum:
@@ -156,10 +274,10 @@ def main():
             psum[k] += s2["phase_us"][k]
         total_us += s2["total_us"]
     handle.set_option(tsp.OPT_PHASE_TIMERS, 0)
-    kavg = {k: v / steps for k, v in ksum.items()}
-    pavg = {k: v / steps for k, v in psum.items()}
+    kavg = {k: v / tsteps for k, v in ksum.items()}
+    pavg = {k: v / tsteps for k, v in psum.items()}
 
-    # group counts of the tile storage, for the algorithmic byte model
+    # group counts of the tile storage, for the layout's own byte count
     tiles = handle.convert(dA)
     tv = tiles.view()
     valid = tsp.tile_indices(tv)                           # the tile arrays have unused slots between tile-rows
@@ -167,18 +285,20 @@ def main():
     groups_right = int(popcount32(tv["right_group_mask"][valid].cpu().numpy().view(np.uint32)).sum())
     tiles.free()
 
+    fused_count = kavg.get("count_masks", 0.0) == 0.0       # the task-list kernel ran the counting pass as well
     dominant = max(kavg, key=kavg.get)
-    dom_bytes = algorithmic_bytes(dominant, A, st, groups_left, groups_right)
-    if dominant == "sym_emit" and kavg.get("count_masks", 0.0) == 0.0:
-        # the task-list kernel also ran the counting pass and the row offsets (they report 0 then)
-        dom_bytes += sum(algorithmic_bytes(k, A, st, groups_left, groups_right) for k in ("count_masks", "row_offsets"))
+    dom_bytes = algorithmic_bytes(dominant, A, st)
+    dom_layout = layout_bytes(dominant, A, st, groups_left, groups_right)
+    if dominant == "sym_emit" and fused_count:
+        dom_bytes = algorithmic_bytes("sym_emit_fused", A, st)
+        dom_layout += sum(layout_bytes(k, A, st, groups_left, groups_right) for k in ("count_masks", "row_offsets"))
     dom_us = kavg[dominant]
     achieved = dom_bytes / (dom_us * 1e-6) / 1e9 if dom_us > 0 else 0.0
     roofline = {"kernel": dominant, "bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 5),
-                "traffic": (int(MEASURED_TRAFFIC_BYTES[(args.workload, dominant)])
-                            if (args.workload, dominant) in MEASURED_TRAFFIC_BYTES else None),
-                "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_us": round(dom_us, 2)}
+                "traffic": measured_traffic(index, dominant),
+                "algorithmic_bytes_per_launch": dom_bytes, "layout_bytes_per_launch": dom_layout,
+                "avg_launch_us": round(dom_us, 2)}
     # the numeric kernel is the one dense contraction: issued MFMA work against the matrix-core peak
     num_us = kavg["numeric"]
     mfma_flop = st["pairs"] * 2.0 * 16 ** 3
@@ -190,61 +310,123 @@ def main():
     end_to_end = {"compulsory_bytes": whole_bytes,
                   "hbm_frac": round(whole_bytes / (elapsed / steps) / 1e9 / HBM_PEAK_GBS, 5)}
 
-    cpu = None
-    if not args.no_cpu_baseline:
-        from oracle import reference
-        reference.build_lib()
-        threads = min(16, os.cpu_count() or 1)
-        # bounded sample: leading rows holding about a fixed number of products
-        rl = np.diff(A.row_ptr).astype(np.int64)
-        csum = np.concatenate([[0], np.cumsum(rl[A.col_idx])])
-        per_row = csum[A.row_ptr.astype(np.int64)]          # products of rows [0, i)
-        budget = 4e8                      # products: a few seconds of single-thread oracle work per run
-        rows = int(np.searchsorted(per_row, budget, side="right"))
-        rows = max(1, min(A.rows, rows))
-        sample_products = int(per_row[rows])
-        sub = inputs.CSRMatrix(rows, A.cols, A.row_ptr[:rows + 1], A.col_idx[:A.row_ptr[rows]],
-                               A.val[:A.row_ptr[rows]])
-        def timed(nthreads, seconds=10.0):
-            """Repeat the sample until about `seconds` of wall time have gone by; mean time of one run."""
-            t0 = time.perf_counter()
-            r = reference.spgemm(sub, A, threads=nthreads)
-            dt = time.perf_counter() - t0
-            reps = int(min(2000, seconds / max(dt, 1e-4)))
-            if reps > 1:
-                t0 = time.perf_counter()
-                for _ in range(reps):
-                    reference.spgemm(sub, A, threads=nthreads)
-                dt = (time.perf_counter() - t0) / reps
-            return r, dt, max(reps, 1)
+    # achieved HBM rate per pass (algorithmic bytes over the device time of the pass's kernels)
+    sym_kernels = ("sym_count", "scan_sym", "sym_emit", "count_masks", "row_offsets", "scan_rows")
+    sym_bytes = sum(algorithmic_bytes(k, A, st) for k in sym_kernels if kavg[k] > 0.0 and not (fused_count and k == "sym_emit"))
+    if fused_count:
+        sym_bytes += algorithmic_bytes("sym_emit_fused", A, st)
+    phase_hbm = {
+        "convert": hbm(algorithmic_bytes("convert", A, st), kavg["convert"]),
+        "symbolic_and_count": hbm(sym_bytes, sum(kavg[k] for k in sym_kernels)),
+        "numeric_and_csr_emission": hbm(algorithmic_bytes("numeric", A, st), kavg["numeric"]),
+    }
+    if not args.compact_zeros:
+        # the compaction of zero-valued entries (Section 4.4) as a call of its own on the result: reads C,
+        # writes the compacted copy when an entry is zero (otherwise only the survivor count runs)
+        raw = handle.spgemm_raw(sA, sA)
+        cz = handle._lib.tsp_compact_zeros
+        import ctypes
+        reps = 3
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        us = 0.0
+        out_nnz = raw.nnz
+        for _ in range(reps + 1):
+            out = type(raw)()
+            ev0.record()
+            rc = cz(handle._h, ctypes.byref(raw), ctypes.byref(out), handle._stream())
+            ev1.record()
+            torch.cuda.synchronize()
+            if rc != 0:
+                break
+            out_nnz = out.nnz
+            handle._free_csr(out)
+            us = ev0.elapsed_time(ev1) * 1e3                # the last repetition counts (the first sizes the workspace)
+        moved = 8 * raw.nnz + 8 * (A.rows + 1) + 4 * A.rows + (8 * out_nnz + 8 * (A.rows + 1) + 8 * raw.nnz if out_nnz != raw.nnz else 0)
+        phase_hbm["compact_zeros"] = dict(hbm(moved, us), entries_removed=int(raw.nnz - out_nnz),
+                                          note="separate call on the result, its host wait included")
+        handle._free_csr(raw)
 
-        r1, t1, _ = timed(1)
-        _, tn, reps = timed(threads)
-        assert r1.products == sample_products
-        cpu = {"value": round(2.0 * sample_products / tn / 1e9, 4), "unit": "GFLOP/s", "cores": threads,
-               "kind": "oracle",
-               "sample": f"rows [0,{rows}) of {A.rows} of C = A*A ({sample_products} products, {r1.nnz} entries of C), "
-                         f"mean of {reps} runs",
-               "single_thread_value": round(2.0 * sample_products / t1 / 1e9, 4),
-               "seconds": round(tn, 3), "single_thread_seconds": round(t1, 3)}
+    res = {
+        "workload": f"configs[{index - 1}]: {inputs.CONFIG_NAMES[index]}",
+        "value": round(gflops, 3), "ms_per_step": round(ms_per_step, 5), "steps": steps, "warmup": warmup,
+        "config": {"workload": f"configs[{index - 1}]: {inputs.CONFIG_NAMES[index]}",
+                   "rows": A.rows, "nnz_A": A.nnz, "products": products, "nnz_C": st["c_nnz"],
+                   "a_tiles": st["a_tiles"], "pairs": st["pairs"], "c_tiles": st["c_tiles"],
+                   "validate_inputs": not args.no_validate, "matrix_cores": not args.no_matrix_cores,
+                   "compact_zeros": args.compact_zeros, "first_call_ms": round(first * 1e3, 3)},
+        "roofline": roofline, "mfma": mfma, "end_to_end": end_to_end, "phase_hbm": phase_hbm,
+        "kernel_us": {k: round(v, 2) for k, v in kavg.items()},
+        "phase_us": {k: round(v, 2) for k, v in pavg.items()},
+        "device_us_per_step_with_timers": round(total_us / tsteps, 2),
+    }
+    if not args.no_cpu_baseline:
+        leg = oracle_leg(A, handle, tsp, sA, 4e8 if headline else 2e7, 10.0 if headline else 0.0)
+        res["accuracy_vs_oracle_sample"] = leg["accuracy"]
+        if headline:
+            res["cpu_baseline"] = leg["cpu_baseline"]
+    handle.close()
+    del dA
+    torch.cuda.empty_cache()
+    return res
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--workload", type=int, default=4, help="headline benchmark configuration 1..5 (see inputs.CONFIG_NAMES)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-per-workload", action="store_true", help="measure the headline workload only")
+    ap.add_argument("--no-validate", action="store_true", help="switch the input validation kernel off")
+    ap.add_argument("--no-matrix-cores", action="store_true",
+                    help="block products on the vector ALUs instead of MFMA (the paper's nonTCU comparison)")
+    ap.add_argument("--compact-zeros", action="store_true",
+                    help="finish every step with the compaction of zero-valued entries (paper Section 4.4)")
+    ap.add_argument("--numeric-run", type=int, default=0, help="tiles per wave of the multiplication kernel (0: automatic)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures one GPU only (--gpus 1); the path has no multi-GPU part",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2009_14600_amd import inputs, tsp
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    tsp.load_library()
+    torch.cuda.set_device(0)
+
+    per = []
+    if not args.no_per_workload:
+        for index in (1, 2, 3, 5, 4):
+            if index == args.workload:
+                continue
+            r = run_workload(index, None, None, args, tsp, inputs, torch, headline=False)
+            per.append(r)
+            print(f"bench.py: workload {index}: {r['value']} GFLOP/s, {r['ms_per_step']} ms per step", file=sys.stderr, flush=True)
+    head = run_workload(args.workload, args.steps, args.warmup, args, tsp, inputs, torch, headline=True)
+    per.append(head)
+    per.sort(key=lambda r: r["workload"])
 
     line = {
         "metric": "spGEMM GFLOP/s (2 x intermediate products / s), C = A*A, CSR in -> CSR out",
-        "value": round(gflops, 3), "unit": "GFLOP/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
-        "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak",
+        "value": head["value"], "unit": "GFLOP/s", "n_gpus": 1, "steps": head["steps"], "warmup": head["warmup"],
+        "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f16 x f16 -> f32", "data": "synthetic",
-        "config": {"workload": f"configs[{args.workload - 1}]: {inputs.CONFIG_NAMES[args.workload]}",
-                   "rows": A.rows, "nnz_A": A.nnz, "products": products, "nnz_C": st["c_nnz"],
-                   "a_tiles": st["a_tiles"], "pairs": st["pairs"], "c_tiles": st["c_tiles"],
-                   "validate_inputs": not args.no_validate, "matrix_cores": not args.no_matrix_cores, "compact_zeros": args.compact_zeros, "first_call_ms": round(first * 1e3, 3)},
-        "roofline": roofline, "mfma": mfma, "end_to_end": end_to_end,
-        "kernel_us": {k: round(v, 2) for k, v in kavg.items()},
-        "phase_us": {k: round(v, 2) for k, v in pavg.items()},
-        "device_us_per_step_with_timers": round(total_us / steps, 2),
-        "cpu_baseline": cpu,
+        "config": head["config"],
+        "roofline": head["roofline"], "mfma": head["mfma"], "end_to_end": head["end_to_end"],
+        "phase_hbm": head["phase_hbm"],
+        "kernel_us": head["kernel_us"], "phase_us": head["phase_us"],
+        "device_us_per_step_with_timers": head["device_us_per_step_with_timers"],
+        "accuracy_vs_oracle_sample": head.get("accuracy_vs_oracle_sample"),
+        "cpu_baseline": head.get("cpu_baseline"),
+        "per_workload": [{k: r[k] for k in ("workload", "value", "ms_per_step", "steps", "roofline", "mfma", "end_to_end",
+                                            "phase_hbm", "kernel_us", "accuracy_vs_oracle_sample") if k in r}
+                         for r in per],
     }
     print(json.dumps(line))
-    handle.close()
 
 
 if __name__ == "__main__":

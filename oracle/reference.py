@@ -63,7 +63,7 @@ class _Operand:
         self.col = np.ascontiguousarray(m.col_idx, dtype=np.int32)
         if full_precision:
             # the values as stored (fp32 or fp64 inputs, not rounded): the "full precision" side of
-            # the paper's precision comparison (Section 6.3)
+            # the paper's precision comparison (Section 6.4)
             self.val = np.ascontiguousarray(np.asarray(m.val).astype(np.float64))
         else:
             # the inputs are fp16 numbers (others are rounded to nearest-even fp16 first, Section
@@ -126,7 +126,7 @@ def spgemm(A, B, threads: int = 1, full_precision: bool = False) -> OracleResult
     """All of C = A*B.  threads > 1 runs independent row blocks on a thread pool (the C
     calls release the GIL); every row is still computed by the same serial code, so the
     result does not depend on the thread count.  full_precision: use the stored values
-    without the rounding to fp16 (the reference side of the precision study, Section 6.3)."""
+    without the rounding to fp16 (the reference side of the precision study, Section 6.4)."""
     ops = (_Operand(A, full_precision), _Operand(B, full_precision))
     rows = ops[0].rows
     if threads <= 1 or rows < 4 * threads:

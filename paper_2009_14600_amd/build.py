@@ -31,7 +31,8 @@ def build_library(force: bool = True, verbose: bool = False) -> str:
     """Compile every translation unit and link the shared library.  force=False skips the work
     when the library is newer than every source."""
     srcs = [os.path.join(CSRC, s) for s in SOURCES]
-    deps = srcs + [os.path.join(CSRC, "common.hpp"), os.path.join(ROOT, "include", "tsp.h")]
+    deps = srcs + [os.path.join(CSRC, h) for h in sorted(os.listdir(CSRC)) if h.endswith(".hpp")]
+    deps.append(os.path.join(ROOT, "include", "tsp.h"))
     if not force and os.path.exists(LIB) and all(os.path.getmtime(LIB) >= os.path.getmtime(d) for d in deps):
         return LIB
     os.makedirs(OBJ, exist_ok=True)

@@ -206,7 +206,8 @@ extern "C" int tsp_create(tsp_handle *handle, const tsp_allocator *allocator) {
     }
     hipError_t e = hipGetDevice(&ctx->device);
     if (e == hipSuccess) e = hipMalloc((void **)&ctx->d_scalars, sizeof(int64_t) * kScalars);
-    if (e == hipSuccess) e = hipHostMalloc((void **)&ctx->h_scalars, sizeof(int64_t) * kScalars, hipHostMallocDefault);
+    if (e == hipSuccess) e = hipHostMalloc((void **)&ctx->h_scalars, sizeof(int64_t) * kScalars,
+                                             hipHostMallocCoherent | hipHostMallocMapped);   // polled: fine-grained whatever the environment says
     if (e == hipSuccess) e = hipHostGetDevicePointer((void **)&ctx->h_scalars_dev, ctx->h_scalars, 0);
     if (e == hipSuccess) std::memset(ctx->h_scalars, 0, sizeof(int64_t) * kScalars);
     if (e != hipSuccess) {

@@ -247,6 +247,11 @@ __device__ __forceinline__ void convert_rows(const ConvArgs<RP, VT> &a) {
         bad |= jmin < 0 || jmax >= (a.cols + T - 1) / T;
         const bool any_bad = group_max<G>(bad ? 1 : 0, s_red) != 0;
         if (gt == 0) {
+            // an empty range until the merge kernel writes the real one: where that kernel does not run
+            // (a matrix too narrow for an over-wide span, so only bad indices lead here) the later kernels
+            // must still find bounds they can walk
+            a.tile_row_ptr[I] = (int32_t)t0;
+            a.tile_row_end[I] = (int32_t)t0;
             a.row_class[I] = ROW_MERGE;
             if (any_bad && a.validate) a.d_scalars[S_INVALID] = 1;
         }

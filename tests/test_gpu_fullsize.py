@@ -1,12 +1,16 @@
 """The five benchmark workloads at full size, in the configuration bench.py times (tsp_spgemm,
 A*A, default options).  Needs an MI355X.
 
-Workloads 1, 2 and 5 are compared entry by entry with the oracle.  Workloads 3 and 4 are too
-large for that (0.12 and 2.96 billion entries): their structure is checked on the device at full
-size (row_ptr monotone, columns strictly ascending, closed-form or oracle-counted sizes, the
-checksum identity sum(C) = (1^T A)(A 1)), and sampled rows, hub rows included, are compared
-entry by entry with rows the oracle computes one by one.
+All five are compared entry by entry with the oracle.  Workloads 1, 2 and 5 in one piece;
+workloads 3 and 4 (0.12 and 2.96 billion entries) in consecutive blocks of rows: the block's
+col_idx and val are copied back, the oracle computes the same rows on a thread pool, every
+column must be equal and every value inside the tolerance, and the block is dropped.  Before
+that their structure is checked on the device at full size (row_ptr monotone, columns strictly
+ascending, closed-form or oracle-counted sizes, the checksum identity sum(C) = (1^T A)(A 1)).
 """
+import os
+from concurrent.futures import ThreadPoolExecutor
+
 import numpy as np
 import pytest
 
@@ -75,14 +79,50 @@ def _structure_checks_on_device(torch, C, A):
         assert bool(ascending.all()), f"columns not ascending in entries [{lo},{hi}]"
 
 
-def _sampled_rows(tsp, oracle, C, A, rows):
-    rp = C.row_ptr
-    for i in rows:
-        lo, hi = int(rp[i]), int(rp[i + 1])
-        ref = oracle.spgemm_rows(A, A, int(i), int(i) + 1)
-        assert hi - lo == ref.nnz, f"row {i}: {hi - lo} entries, oracle {ref.nnz}"
-        assert np.array_equal(C.col_idx[lo:hi].cpu().numpy(), ref.col), f"row {i}: columns differ"
-        _check_values(C.val[lo:hi].cpu().numpy(), ref, f"row {i}")
+def _streamed_comparison(oracle, C, A, say, block_entries=120_000_000):
+    """Every entry of C against the oracle, block of rows by block of rows.  Returns the number of
+    entries compared and the oracle's product count."""
+    threads = min(16, os.cpu_count() or 1)
+    ops = (oracle._Operand(A), oracle._Operand(A))
+    rp = C.row_ptr.cpu().numpy().astype(np.int64)
+    assert rp[0] == 0 and rp[-1] == C.nnz
+    compared = products = 0
+    r0 = 0
+    with ThreadPoolExecutor(max_workers=threads) as pool:
+        while r0 < C.rows:
+            # as many rows as fit the block (at least one)
+            r1 = max(r0 + 1, int(np.searchsorted(rp, rp[r0] + block_entries, side="right")) - 1)
+            r1 = min(r1, C.rows)
+            lo, hi = int(rp[r0]), int(rp[r1])
+            col = C.col_idx[lo:hi].cpu().numpy()
+            val = C.val[lo:hi].cpu().numpy()
+            # sub-blocks of about equal numbers of entries, several per thread
+            cuts = np.searchsorted(rp[r0:r1 + 1], np.linspace(lo, hi, 4 * threads + 1)).astype(np.int64) + r0
+            cuts[0], cuts[-1] = r0, r1
+            cuts = np.unique(cuts)
+
+            def part(k):
+                s0, s1 = int(cuts[k]), int(cuts[k + 1])
+                ref = oracle.spgemm_rows(A, A, s0, s1, _ops=ops)
+                if not np.array_equal(ref.row_ptr + rp[s0], rp[s0:s1 + 1]):
+                    return f"rows [{s0},{s1}): row lengths differ", 0, 0
+                a, b = int(rp[s0]) - lo, int(rp[s1]) - lo
+                if not np.array_equal(col[a:b], ref.col):
+                    first = int(np.nonzero(col[a:b] != ref.col)[0][0])
+                    return f"rows [{s0},{s1}): column differs at entry {lo + a + first}", 0, 0
+                err = np.abs(val[a:b].astype(np.float64) - ref.val)
+                bad = np.nonzero(err > RTOL_S * ref.mag + ATOL)[0]
+                if bad.size:
+                    return f"rows [{s0},{s1}): {bad.size} values out of tolerance, first at entry {lo + a + int(bad[0])}", 0, 0
+                return None, ref.nnz, ref.products
+
+            for message, n, p in pool.map(part, range(cuts.shape[0] - 1)):
+                assert message is None, message
+                compared += n
+                products += p
+            say(f"rows [{r0},{r1}) of {C.rows}: {compared} of {C.nnz} entries equal to the oracle's")
+            r0 = r1
+    return compared, products
 
 
 def _checksum(torch, C, A):
@@ -97,7 +137,7 @@ def _checksum(torch, C, A):
     assert abs(got - want) <= RTOL_S * scale + ATOL * C.nnz, (got, want, scale)
 
 
-def test_stencil27_full_size(tsp, handle, oracle):
+def test_stencil27_full_size(tsp, handle, oracle, capsys):
     import torch
     A = inputs.config(3)
     assert A.nnz == 81 * A.rows == 26873856
@@ -111,15 +151,16 @@ def test_stencil27_full_size(tsp, handle, oracle):
     print("workload 3: structure", flush=True)
     _structure_checks_on_device(torch, C, A)
     _checksum(torch, C, A)
-    print("workload 3: sampled rows", flush=True)
-    rng = np.random.default_rng(3)
-    rows = np.concatenate([[0, 1, 15, 16, A.rows - 1, 3 * 48 * 48 - 1, 3 * 48 * 48], rng.integers(0, A.rows, 40)])
-    _sampled_rows(tsp, oracle, C, A, rows)
+    def say(text):
+        with capsys.disabled():
+            print(f"\n  workload 3: {text}", end="", flush=True)
+    compared, products = _streamed_comparison(oracle, C, A, say)
+    assert compared == C.nnz and products == 81 * 81 * A.rows == 2176782336
     C.free()
     handle.trim()
 
 
-def test_rmat_full_size(tsp, handle, oracle):
+def test_rmat_full_size(tsp, handle, oracle, capsys):
     import torch
     A = inputs.config(4)
     deg = np.diff(A.row_ptr).astype(np.int64)
@@ -141,10 +182,12 @@ def test_rmat_full_size(tsp, handle, oracle):
         assert bool((chunk == torch.round(chunk)).all()) and float(chunk.min()) >= 1.0
         total += int(chunk.sum(dtype=torch.float64))
     assert total == products
-    print("workload 4: sampled rows", flush=True)
+    def say(text):
+        with capsys.disabled():
+            print(f"\n  workload 4: {text}", end="", flush=True)
+    compared, oracle_products = _streamed_comparison(oracle, C, A, say)
+    assert compared == C.nnz == 2962529917 and oracle_products == products == 9487075854
     rng = np.random.default_rng(4)
-    rows = np.concatenate([[0, 1, 2, 17, A.rows - 1], np.argsort(-deg)[:3], rng.integers(0, A.rows, 30)])
-    _sampled_rows(tsp, oracle, C, A, rows)
     diag_rows = rng.integers(0, A.rows, 200)
     for i in diag_rows:                                # c_ii = deg(i)
         lo, hi = int(C.row_ptr[i]), int(C.row_ptr[i + 1])

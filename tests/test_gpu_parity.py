@@ -190,6 +190,17 @@ def test_error_codes(tsp, handle):
     with pytest.raises(tsp.TspError) as e:
         handle.spgemm(bad, bad)
     assert e.value.status == -3
+    bad.col_idx = cols.clone()
+    bad.col_idx[5] = -7                                             # negative column: the tile-row leaves the
+    with pytest.raises(tsp.TspError) as e:                          # converter's fast path with an empty range
+        handle.spgemm(bad, bad)
+    assert e.value.status == -3
+    first_of_row = int(bad.row_ptr[2])
+    bad.col_idx = cols.clone()
+    bad.col_idx[first_of_row] = -1                                  # ... also as the first entry of a row
+    with pytest.raises(tsp.TspError) as e:
+        handle.spgemm(bad, bad)
+    assert e.value.status == -3
     bad.col_idx = cols
     rp = bad.row_ptr.clone()
     bad.row_ptr[3] = rp[4] + 1                                      # non-monotone row_ptr
@@ -432,7 +443,7 @@ def test_compact_zeros_with_more_rows_than_one_prefix_sum_launch_covers(tsp, han
     assert np.array_equal(rp, want_ptr) and np.array_equal(c, col[keep]) and np.array_equal(v, val[keep])
 
 
-# ------------------------------------------------------------------ precision study (Section 6.3, Eq. 3)
+# ------------------------------------------------------------------ precision study (Section 6.4, Eq. 3)
 def test_smape_against_full_precision_as_in_the_paper(tsp, handle, oracle):
     """The paper's two observations on synthetic inputs: 0/1 patterns give SMAPE 0 %; real
     fp32 inputs, rounded to fp16 on the device, give a SMAPE of a few hundredths of a percent

@@ -50,25 +50,74 @@ def test_cancellation_and_stored_zero_stay_structural(oracle):
     assert res.products == 5
 
 
-# ---------------------------------------------------------------- fp16 decoding
+# ---------------------------------------------------------------- fp16 decoding and rounding
+def _decode_binary16(bits: int) -> float:
+    """IEEE 754 binary16 from its fields, written out here so that the pin does not repeat the
+    library conversion the oracle uses: 1 sign bit, 5 exponent bits (bias 15), 10 fraction bits;
+    exponent field 0 = subnormal (no hidden one, exponent -14)."""
+    import math
+    sign = -1.0 if bits >> 15 else 1.0
+    exponent, fraction = (bits >> 10) & 0x1F, bits & 0x3FF
+    if exponent == 0:
+        return sign * math.ldexp(fraction, -24)
+    return sign * math.ldexp(1024 + fraction, exponent - 25)
+
+
 def test_fp16_decode_all_bit_patterns(oracle):
-    """diag(every finite fp16 bit pattern) * I reproduces numpy's independent fp16 -> fp64."""
-    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
-    halves = bits.view(np.float16)
-    finite = np.isfinite(halves)
-    bits, halves = bits[finite], halves[finite]
+    """diag(every finite fp16 bit pattern) * I: the oracle's widening of its fp16 inputs (Section
+    2.6: the inputs are fp16 numbers) against a decoder by sign, exponent and fraction fields."""
+    bits = np.array([b for b in range(65536) if (b >> 10) & 0x1F != 0x1F], dtype=np.uint16)   # finite ones
     n = bits.shape[0]
+    assert n == 63488
+    expect = np.array([_decode_binary16(int(b)) for b in bits], dtype=np.float64)
     ar = np.arange(n)
-    D = inputs.CSRMatrix(n, n, np.arange(n + 1, dtype=np.int32), ar.astype(np.int32), halves)
+    D = inputs.CSRMatrix(n, n, np.arange(n + 1, dtype=np.int32), ar.astype(np.int32), bits.view(np.float16))
     I = inputs.CSRMatrix(n, n, np.arange(n + 1, dtype=np.int32), ar.astype(np.int32),
                          np.ones(n, dtype=np.float16))
     res = oracle.spgemm(D, I)
     assert np.array_equal(res.col, ar)
-    expect = halves.astype(np.float64)
     assert np.array_equal(res.val, expect)
     nz = expect != 0          # -0.0 accumulates onto +0.0 and comes out +0.0
     assert np.array_equal(np.signbit(res.val[nz]), np.signbit(expect[nz]))
     assert np.array_equal(res.mag, np.abs(expect))
+    # spot values fixed by the format itself
+    assert _decode_binary16(0x3C00) == 1.0 and _decode_binary16(0x7BFF) == 65504.0
+    assert _decode_binary16(0x0001) == 2.0 ** -24 and _decode_binary16(0x0400) == 2.0 ** -14
+    assert _decode_binary16(0xC000) == -2.0
+
+
+def test_fp32_inputs_round_to_nearest_even_fp16(oracle):
+    """fp32 inputs are converted to fp16 before use (Section 2.6; Section 6.3 counts the conversion
+    into the run time): round to nearest, ties to the even fraction.  Hand-picked values, each
+    with the result worked out from the format (spacing 2^-10 in [1,2), 2 in [2048,4096), 2^-24
+    among the subnormals)."""
+    cases = [
+        (1.0 + 2.0 ** -11, 1.0),                         # tie between 1 and 1+2^-10: even fraction 0
+        (1.0 + 3.0 * 2.0 ** -11, 1.0 + 2.0 ** -9),       # tie between 1+2^-10 (odd) and 1+2^-9 (even)
+        (1.0 + 2.0 ** -11 + 2.0 ** -20, 1.0 + 2.0 ** -10),   # just above the tie: up
+        (1.0 + 2.0 ** -11 - 2.0 ** -20, 1.0),            # just below: down
+        (2049.0, 2048.0),                                # tie, spacing 2: even multiple
+        (2051.0, 2052.0),
+        (-2049.0, -2048.0),
+        (2.0 ** -25, 0.0),                               # tie between 0 and the smallest subnormal
+        (3.0 * 2.0 ** -25, 2.0 ** -23),                  # tie between 2^-24 (odd) and 2^-23 (even)
+        (2.0 ** -24 + 2.0 ** -26, 2.0 ** -24),           # subnormal, nearest
+        (65504.0, 65504.0),                              # largest finite fp16 stays
+        (0.1, 0.0999755859375),                          # 0.1 = 1.6 * 2^-4: fraction 0.6*1024 = 614.4 -> 614
+        (1.0 / 3.0, 0.333251953125),                     # 1.3333 * 2^-2: fraction 341.33 -> 341
+    ]
+    x = np.array([c[0] for c in cases], dtype=np.float32)
+    want = np.array([c[1] for c in cases], dtype=np.float64)
+    n = x.shape[0]
+    ar = np.arange(n, dtype=np.int32)
+    D = inputs.CSRMatrix(n, n, np.arange(n + 1, dtype=np.int32), ar, x)
+    I = inputs.CSRMatrix(n, n, np.arange(n + 1, dtype=np.int32), ar, np.ones(n, dtype=np.float32))
+    res = oracle.spgemm(D, I)
+    assert np.array_equal(res.val, want), (res.val, want)
+    res = oracle.spgemm(I, D)                            # the right operand takes the same rounding
+    assert np.array_equal(res.val, want)
+    full = oracle.spgemm(D, I, full_precision=True)      # and the full-precision mode does not round
+    assert np.array_equal(full.val, x.astype(np.float64))
 
 
 # ---------------------------------------------------------------- closed forms
@@ -246,7 +295,7 @@ def test_compaction_equals_nonzeros_of_the_dense_product(oracle, M, K, N, densit
     assert np.array_equal(got, want)
 
 
-# ------------------------------------------------------------------ precision measure (Section 6.3, Eq. 3)
+# ------------------------------------------------------------------ precision measure (Section 6.4, Eq. 3)
 def test_smape_hand_computed(oracle):
     """x = (1, 2), x^ = (1.1, 1.8): 100/2 * (0.1/2.1 + 0.2/3.8) = 5.01253...%; symmetric in its
     arguments; a pair of zeros contributes nothing."""
