@@ -191,6 +191,25 @@ int tsp_csr_free(tsp_handle handle, tsp_csr *C, void *stream);
  */
 int tsp_compact_zeros(tsp_handle handle, const tsp_csr *C, tsp_csr *out, void *stream);
 
+/*
+ * tsp_compact_zeros for callers that cannot allocate device memory: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same result as tsp_compact_zeros, but the call
+ * allocates nothing, on the device or through the handle's allocator: the caller brings the output
+ * arrays, and the pass's scratch (survivor counts per row and per 16 rows) lives in a fixed device array
+ * inside the library (about 2.2 MB per GPU the library runs on, held until the process ends).
+ * In: C as for tsp_compact_zeros.  In/out: *out with row_ptr -> int64[C.rows + 1], col_idx ->
+ * int32[capacity], val -> float[capacity], capacity >= C.nnz, device arrays owned by the caller, not
+ * overlapping C's; on success rows, cols, nnz and the two type fields are filled in and the arrays hold
+ * the compacted matrix (entries past nnz are not written).  Do not pass *out to tsp_csr_free.
+ * Limits: 1 <= C.rows <= TSP_COMPACT_STATIC_MAX_ROWS, else TSP_ERR_UNSUPPORTED and nothing is enqueued.
+ * Synchronises the stream once (the new nnz).  All calls on one GPU share the one scratch array, which
+ * keeps the previous call's contents (every call overwrites what it reads): calls that overlap on the
+ * same GPU, from any handle or stream, race.
+ * Errors: INVALID_ARG, UNSUPPORTED, HIP.
+ */
+#define TSP_COMPACT_STATIC_MAX_ROWS 524288
+int tsp_compact_zeros_static(tsp_handle handle, const tsp_csr *C, tsp_csr *out, void *stream);
+
 /* ----- the pipeline phase by phase (tsp_spgemm is exactly these calls in order) ----------- */
 
 enum {

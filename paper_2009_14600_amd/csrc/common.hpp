@@ -170,6 +170,9 @@ int numeric_enqueue(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s
 // taken (may be null): the caller owns C and gives it up; when no entry is zero *out takes C's arrays as they
 // are (no copy) and *taken is set, so that the caller does not free them.
 int compact_zeros(tsp_context *ctx, const tsp_csr *C, tsp_csr *out, hipStream_t s, bool *taken);
+// Looks up, once per device, the address of the fixed scratch array behind tsp_compact_zeros_static on the
+// current device (tsp_create calls it, so that the entry point itself finds the pointer ready).
+int static_scratch_setup(tsp_context *ctx, unsigned char **ptr);
 
 #ifdef __HIPCC__
 // ---- device helpers -------------------------------------------------------------------

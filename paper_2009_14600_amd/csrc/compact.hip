@@ -6,6 +6,8 @@
 // output is already CSR, so a row-wise stream compaction does both.
 #include "common.hpp"
 
+#include <mutex>
+
 namespace tsp {
 
 constexpr int kCompactThreads = 256;
@@ -177,9 +179,87 @@ int compact_zeros(tsp_context *ctx, const tsp_csr *C, tsp_csr *out, hipStream_t 
     return TSP_ERR_INVALID_ARG;
 }
 
+// ---- the same compaction without any allocation (tsp_compact_zeros_static) -----------------------
+// The survivor counts per row and their sums per 16 rows, which compact_run takes from the handle's
+// allocator, live in a file-scope device array instead.  Every device the library runs on holds its own
+// copy of the array, at its own address, until the process ends; the address is looked up once per device
+// (static_scratch_setup) and only that pointer is ever handed to kernels.
+constexpr int64_t kStaticMaxRows = TSP_COMPACT_STATIC_MAX_ROWS;
+constexpr size_t kStaticKeepBytes = ((size_t)(kStaticMaxRows + 1) * sizeof(int32_t) + 255) & ~size_t(255);
+constexpr size_t kStaticGroupBytes = ((size_t)(kStaticMaxRows / T + 4) * sizeof(uint32_t) + 255) & ~size_t(255);
+static __device__ __align__(256) unsigned char scratch[kStaticKeepBytes + kStaticGroupBytes];
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_lock;
+static unsigned char *g_scratch_ptr[kMaxDevices];      // device address of `scratch` on every device seen so far
+
+// Device address of the scratch array on the current device (looked up on the first call per device).
+int static_scratch_setup(tsp_context *ctx, unsigned char **ptr) {
+    int device = -1;
+    TSP_HIP_CHECK(ctx, hipGetDevice(&device));
+    if (device < 0 || device >= kMaxDevices) return TSP_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> guard(g_scratch_lock);
+    if (!g_scratch_ptr[device]) {
+        void *p = nullptr;
+        TSP_HIP_CHECK(ctx, hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return hip_fail(ctx, hipErrorInvalidSymbol);
+        g_scratch_ptr[device] = static_cast<unsigned char *>(p);
+    }
+    if (ptr) *ptr = g_scratch_ptr[device];
+    return TSP_OK;
+}
+
+template <typename RP>
+static int compact_run_static(tsp_context *ctx, const tsp_csr *C, tsp_csr *out, hipStream_t s) {
+    const int64_t rows = C->rows;
+    unsigned char *base = nullptr;
+    int rc = static_scratch_setup(ctx, &base);
+    if (rc) return rc;
+    int32_t *keep = reinterpret_cast<int32_t *>(base);
+    uint32_t *group_keep = reinterpret_cast<uint32_t *>(base + kStaticKeepBytes);
+    int64_t *new_row_ptr = static_cast<int64_t *>(out->row_ptr);
+    CompactArgs<RP> a{static_cast<const RP *>(C->row_ptr), C->col_idx, static_cast<const float *>(C->val), rows, C->nnz};
+    const int64_t row_blocks = (rows * kCompactLanes + kCompactThreads - 1) / kCompactThreads;
+    if (!ctx->scalars_clean) hipLaunchKernelGGL(k_compact_clear, dim3(1), dim3(64), 0, s, ctx->d_scalars);
+    ctx->scalars_clean = false;
+    // (nothing in the scratch array has to start at zero: the count kernel writes every word the prefix sum reads)
+    hipLaunchKernelGGL(k_compact_count<RP>, dim3((unsigned)row_blocks), dim3(kCompactThreads), 0, s, a, keep, group_keep);
+    if (!row_ptr_in_one_launch(ctx, keep, rows, group_keep, new_row_ptr, s)) return TSP_ERR_UNSUPPORTED;
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(ctx, e);
+    rc = wait_published_scalars(ctx, ctx->publish_tag, s);       // host synchronisation: the new nnz
+    if (rc) return rc;
+    if (ctx->h_scalars[S_INTERNAL]) return TSP_ERR_HIP;
+    const int64_t nnz = ctx->h_scalars[S_C_NNZ];
+    if (nnz > 0) {
+        hipLaunchKernelGGL(k_compact_fill<RP>, dim3((unsigned)row_blocks), dim3(kCompactThreads), 0, s, a, new_row_ptr,
+                           out->col_idx, static_cast<float *>(out->val));
+        e = hipGetLastError();
+        if (e != hipSuccess) return hip_fail(ctx, e);
+    }
+    out->rows = C->rows;
+    out->cols = C->cols;
+    out->nnz = nnz;
+    out->row_ptr_type = TSP_I64;
+    out->val_type = TSP_F32;
+    return TSP_OK;
+}
+
 }  // namespace tsp
 
 using namespace tsp;
+
+extern "C" int tsp_compact_zeros_static(tsp_handle ctx, const tsp_csr *C, tsp_csr *out, void *stream) {
+    if (!ctx || !C || !out || C == out) return TSP_ERR_INVALID_ARG;
+    if (C->rows < 0 || C->cols < 0 || C->nnz < 0 || !C->row_ptr || !out->row_ptr) return TSP_ERR_INVALID_ARG;
+    if (C->val_type != TSP_F32) return TSP_ERR_INVALID_ARG;
+    if (C->nnz > 0 && (!C->col_idx || !C->val || !out->col_idx || !out->val)) return TSP_ERR_INVALID_ARG;
+    if (C->rows < 1 || C->rows > kStaticMaxRows) return TSP_ERR_UNSUPPORTED;      // the scratch array has a fixed size
+    hipStream_t s = (hipStream_t)stream;
+    if (C->row_ptr_type == TSP_I64) return compact_run_static<int64_t>(ctx, C, out, s);
+    if (C->row_ptr_type == TSP_I32) return compact_run_static<int32_t>(ctx, C, out, s);
+    return TSP_ERR_INVALID_ARG;
+}
 
 extern "C" int tsp_compact_zeros(tsp_handle ctx, const tsp_csr *C, tsp_csr *out, void *stream) {
     if (!ctx || !C || !out || C == out) return TSP_ERR_INVALID_ARG;

@@ -217,6 +217,12 @@ extern "C" int tsp_create(tsp_handle *handle, const tsp_allocator *allocator) {
         delete ctx;
         return TSP_ERR_HIP;
     }
+    if (static_scratch_setup(ctx, nullptr) != TSP_OK) {      // address of the no-allocation scratch on this device
+        (void)hipHostFree(ctx->h_scalars);
+        (void)hipFree(ctx->d_scalars);
+        delete ctx;
+        return TSP_ERR_HIP;
+    }
     *handle = ctx;
     return TSP_OK;
 }

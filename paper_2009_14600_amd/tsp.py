@@ -25,7 +25,7 @@ KERNELS = ("convert", "sym_count", "scan_sym", "sym_emit", "count_masks", "row_o
 EXPORTS = [
     "tsp_create", "tsp_destroy", "tsp_set_option", "tsp_trim", "tsp_spgemm", "tsp_csr_free",
     "tsp_convert", "tsp_tiles_free", "tsp_tiles_get_view", "tsp_symbolic", "tsp_plan_free",
-    "tsp_plan_get_view", "tsp_numeric", "tsp_compact_zeros", "tsp_get_stats", "tsp_strerror",
+    "tsp_plan_get_view", "tsp_numeric", "tsp_compact_zeros", "tsp_compact_zeros_static", "tsp_get_stats", "tsp_strerror",
     "tsp_last_hip_error",
 ]
 
@@ -110,6 +110,7 @@ def load_library():
     lib.tsp_plan_get_view.argtypes = [vp, P(_PlanView)]
     lib.tsp_numeric.argtypes = [vp, vp, vp, vp, P(_Csr), vp]
     lib.tsp_compact_zeros.argtypes = [vp, P(_Csr), P(_Csr), vp]
+    lib.tsp_compact_zeros_static.argtypes = [vp, P(_Csr), P(_Csr), vp]
     lib.tsp_get_stats.argtypes = [vp, P(_Stats)]
     lib.tsp_strerror.argtypes = [ci]
     lib.tsp_strerror.restype = ctypes.c_char_p
@@ -277,6 +278,14 @@ class Handle:
         out = _Csr()
         _check(self._lib.tsp_compact_zeros(self._h, ctypes.byref(sc), ctypes.byref(out), self._stream()))
         return self._wrap_output(out)
+
+    def compact_zeros_static(self, C: DeviceCSR, out_row_ptr, out_col_idx, out_val) -> int:
+        """tsp_compact_zeros_static: the compaction into arrays the caller brings (int64[rows+1],
+        int32[>= C.nnz], float32[>= C.nnz] tensors on the GPU); returns the new nnz."""
+        sc = C._struct()
+        out = _Csr(0, 0, 0, out_row_ptr.data_ptr(), out_col_idx.data_ptr(), out_val.data_ptr(), TSP_I64, TSP_F32)
+        _check(self._lib.tsp_compact_zeros_static(self._h, ctypes.byref(sc), ctypes.byref(out), self._stream()))
+        return int(out.nnz)
 
     def spgemm_raw(self, sa: _Csr, sb: _Csr):
         """tsp_spgemm on prepared structs; returns the raw output struct (benchmark loop)."""
