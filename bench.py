@@ -227,6 +227,8 @@ def run_workload(index, steps, warmup, args, tsp, inputs, torch, headline):
         handle.set_option(tsp.OPT_COMPACT_ZEROS, 1)
     if args.numeric_run:
         handle.set_option(tsp.OPT_NUMERIC_RUN, args.numeric_run)
+    if args.strip_order:
+        handle.set_option(tsp.OPT_STRIP_ORDER, args.strip_order)
 
     def step():
         out = handle.spgemm_raw(sA, sA)
@@ -384,6 +386,8 @@ def main():
     ap.add_argument("--compact-zeros", action="store_true",
                     help="finish every step with the compaction of zero-valued entries (paper Section 4.4)")
     ap.add_argument("--numeric-run", type=int, default=0, help="tiles per wave of the multiplication kernel (0: automatic)")
+    ap.add_argument("--strip-order", type=int, default=0,
+                    help="order of the output tiles in the counting and multiplication kernels (0: automatic, 1: strips, 2: row-major)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU only (--gpus 1); the path has no multi-GPU part",

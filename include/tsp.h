@@ -99,11 +99,19 @@ enum {
     TSP_OPT_COMPACT_ZEROS = 6, /* 1: tsp_spgemm finishes with tsp_compact_zeros (the compaction     */
                                /*    steps that end Algorithm 1); 0 (default): C keeps every        */
                                /*    structural position                                            */
-    TSP_OPT_WORK_ORDER = 7     /* order in which the general task-list kernel takes the tile-rows   */
+    TSP_OPT_WORK_ORDER = 7,    /* order in which the general task-list kernel takes the tile-rows   */
                                /*    of C: 1: heaviest first (by candidate pairs, Section 4.1),     */
                                /*    2: by index, 0 (default): heaviest first where a few tile-rows */
                                /*    are far heavier than the rest.  The result does not depend on  */
                                /*    it                                                             */
+    TSP_OPT_STRIP_ORDER = 8    /* order in which the counting and the multiplication kernel (4.2,   */
+                               /*    4.3) take the output tiles: 1: in vertical strips of tile      */
+                               /*    columns sized so that the tiles of B a strip meets stay in the  */
+                               /*    L2 cache; 0 (default) and 2: row-major as the task list is      */
+                               /*    sorted (faster wherever measured: the strips cut the memory     */
+                               /*    traffic, which does not bind these kernels); a value of 16 or   */
+                               /*    more: strips of about that many tiles of B.  The result does    */
+                               /*    not depend on it                                                */
 };
 
 /* Phases reported in tsp_stats.phase_us, in pipeline order. */

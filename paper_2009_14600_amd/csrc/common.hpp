@@ -52,6 +52,7 @@ struct tsp_context {
     int timers = 0;
     int force_wide = 0;                            // use the 64-bit-pointer kernels whatever the sizes
     int work_order = 0;                            // TSP_OPT_WORK_ORDER
+    int strip_order = 0;                           // TSP_OPT_STRIP_ORDER
     int numeric_run_len = 0;                       // tiles per wave of the multiplication kernel, 0: automatic
     int matrix_cores = 1;                          // 0: block products on the vector ALUs
     int compact = 0;                               // 1: tsp_spgemm removes zero-valued entries from C
@@ -100,6 +101,11 @@ struct tsp_plan_s {
     uint16_t *c_row_mask = nullptr;
     uint32_t *c_row_off = nullptr;
     int64_t *c_row_ptr = nullptr;
+    // order of work in vertical strips (strips.hip), absent for short tile-rows of C
+    int2 *strip_desc = nullptr;              // per workgroup {first output tile, tiles (0: none)}
+    int64_t strip_capacity = 0;              // descriptors allocated: an upper bound of the workgroups
+    int32_t *strip_block_ptr = nullptr;      // [strip_entries + 1]; the last entry is the number of workgroups
+    int64_t strip_entries = 0;
 };
 
 namespace tsp {
@@ -162,6 +168,8 @@ int convert_enqueue(tsp_context *ctx, const tsp_csr *A, int forms, int scalar_sl
 void tiles_release(tsp_context *ctx, tsp_tiles_s *t, hipStream_t s);
 int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **out, hipStream_t s);
 void plan_release(tsp_context *ctx, tsp_plan_s *p, hipStream_t s);
+// Order of work in vertical strips for the kernels that walk the task list of a plan with long tile-rows.
+int strips_build(tsp_context *ctx, tsp_plan_s *P, const tsp_tiles_s *B, hipStream_t s);
 // last_of_call (tsp_spgemm): C gets the plan's row_ptr array itself instead of a copy, so the plan cannot
 // be used again, and the kernel zeroes the handle's scalar block, which nothing reads any more, for the
 // next call (one launch less per call).
@@ -183,6 +191,20 @@ __device__ __forceinline__ void wave_sync() {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// Workgroup b of a launch runs on XCD b % 8, each XCD with an L2 cache of its own.  Logical block index
+// for workgroup b such that `chunk` consecutive logical blocks run on one XCD (and share its L2) and the
+// chunks are dealt to the XCDs in turn (so that a part of the index range that is heavier than the rest
+// does not fall to one XCD).  chunk = ceil(blocks / 8) gives every XCD one contiguous eighth.  The launch
+// must cover ceil(blocks / (8 chunk)) * 8 chunk workgroups; indices past `blocks` have nothing to do.
+__device__ __forceinline__ int64_t xcd_chunked_index(unsigned b, int chunk) {
+    const unsigned q = b >> 3, x = b & 7u;
+    return ((int64_t)(q / (unsigned)chunk) * 8 + x) * chunk + q % (unsigned)chunk;
+}
+inline int64_t xcd_chunked_grid(int64_t blocks, int chunk) {
+    const int64_t span = 8 * (int64_t)chunk;
+    return (blocks + span - 1) / span * span;
 }
 
 // The scalar block copied into the host's pinned mirror by the block of a kernel that knows every other

@@ -41,6 +41,7 @@
 // counts alone does not change its duration; on very sparse tiles it is bound by instruction issue.
 #include "common.hpp"
 
+#include <algorithm>
 #include <new>
 #include <utility>
 
@@ -149,7 +150,8 @@ __global__ __launch_bounds__(kNumThreads) void k_numeric(
     const uint4 *__restrict__ a_ldata_, const uint2 *__restrict__ b_rhead_, const uint4 *__restrict__ b_rdata_, const int32_t *__restrict__ c_tile_row,
     const int32_t *__restrict__ c_tile_col, const uint16_t *__restrict__ c_row_mask,
     const uint32_t *__restrict__ c_row_off, const int64_t *__restrict__ c_row_ptr, int32_t *__restrict__ c_col,
-    float *__restrict__ c_val, int64_t *__restrict__ scalars_to_clear) {
+    float *__restrict__ c_val, int64_t *__restrict__ scalars_to_clear, const int2 *__restrict__ strip_desc,
+    const int32_t *__restrict__ strip_total, const int xcd_chunk) {
     if (scalars_to_clear && blockIdx.x == 0 && threadIdx.x < kScalars) scalars_to_clear[threadIdx.x] = 0;
     static_assert(kTilesPerWave % kGroupTiles == 0 && kTilesPerWave < 64, "whole groups; offsets fit one wave load");
     // headers of the 64 task-list entries a wave is working on, one 16-byte record per entry; one
@@ -160,8 +162,7 @@ __global__ __launch_bounds__(kNumThreads) void k_numeric(
     // column and value of every entry of the wave's tile-row, in CSR order (whole-tile-row kernel only)
     __shared__ uint32_t lds_entries[kWholeRows ? kNumThreads / 64 : 1][2][kWholeRows ? kRowEntries : 1];
     // consecutive logical blocks on the same XCD (workgroups are dealt to the XCDs round-robin)
-    const int per_xcd = gridDim.x / kXcds;
-    const int logical = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
+    const int64_t logical = xcd_chunked_index(blockIdx.x, xcd_chunk);
     // wave-uniform values are kept in scalar registers; their loads become scalar loads
     const int wave_in_block = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t wave = (int64_t)logical * (kNumThreads / 64) + wave_in_block;
@@ -172,6 +173,13 @@ __global__ __launch_bounds__(kNumThreads) void k_numeric(
         if (wave >= c_tile_rows) return;
         run_begin = c_tile_row_ptr[wave];                                       // wave = tile-row of C
         run_tiles = min(c_tile_row_ptr[wave + 1] - (int)run_begin, kTilesPerWave);
+        if (run_tiles <= 0 || run_begin + run_tiles > c_tiles) return;
+    } else if (strip_desc) {
+        // order in vertical strips: the block's tiles are the ones its descriptor names
+        if (logical >= *strip_total) return;
+        const int2 d = strip_desc[logical];
+        run_begin = (int64_t)d.x + wave_in_block * kTilesPerWave;
+        run_tiles = min(kTilesPerWave, d.y - wave_in_block * kTilesPerWave);
         if (run_tiles <= 0 || run_begin + run_tiles > c_tiles) return;
     } else {
         run_begin = wave * kTilesPerWave;
@@ -510,7 +518,15 @@ int numeric_enqueue(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s
         const int64_t tiles_per_block = (int64_t)(kNumThreads / 64) * tiles_per_wave;
         int64_t blocks = whole_rows ? (P->c_tile_rows + kNumThreads / 64 - 1) / (kNumThreads / 64)
                                     : (P->c_tiles + tiles_per_block - 1) / tiles_per_block;
-        blocks = (blocks + kXcds - 1) / kXcds * kXcds;             // the XCD remap needs a multiple of 8
+        const bool strips = P->strip_desc && !whole_rows && tiles_per_wave == kGroupTiles;
+        static_assert(kGroupTiles * (kNumThreads / 64) == 16, "a strip descriptor names the 16 tiles of one block");
+        if (strips) blocks = P->strip_capacity;
+        // Consecutive blocks share tiles of B, so they should share an L2 cache: on even products every XCD
+        // takes one contiguous eighth of the blocks; where a few tile-rows are far heavier than the rest
+        // (hubs of a power-law graph sit at the low indices) short runs of blocks are dealt to the XCDs in turn
+        const bool skewed = P->max_row_pairs > 8 * (P->pairs / std::max<int64_t>(P->c_tile_rows, 1) + 1);
+        const int xcd_chunk = skewed || strips ? 64 : (int)std::max<int64_t>((blocks + kXcds - 1) / kXcds, 1);
+        blocks = xcd_chunked_grid(blocks, xcd_chunk);
         const NumericSizes z{(uint64_t)P->pairs, (uint64_t)A->tile_capacity, (uint64_t)B->tile_capacity,
                              (uint64_t)A->group_capacity, (uint64_t)B->group_capacity};
         const uint64_t limit = (1ull << 32) - 64;
@@ -528,7 +544,9 @@ int numeric_enqueue(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s
                            (int32_t)P->c_tile_rows, P->c_tile_row_ptr, P->pair_off,
                            P->pair_a, P->pair_b, A->lhead, A->ldata, B->rhead, B->rdata,
                            P->c_tile_row, P->c_tile_col, P->c_row_mask, P->c_row_off, P->c_row_ptr, col, val,
-                           last_of_call && !ctx->compact ? ctx->d_scalars : nullptr);
+                           last_of_call && !ctx->compact ? ctx->d_scalars : nullptr,
+                           strips ? P->strip_desc : nullptr, strips ? P->strip_block_ptr + P->strip_entries : nullptr,
+                           xcd_chunk);
         if (last_of_call && !ctx->compact && hipPeekAtLastError() == hipSuccess) ctx->scalars_clean = true;
         e = hipGetLastError();
     }

@@ -1180,7 +1180,9 @@ __global__ __launch_bounds__(256) void k_count_masks(int64_t c_tiles, const int6
                                                      const int32_t *__restrict__ pair_b,
                                                      const uint16_t *__restrict__ a_row_mask,
                                                      const uint16_t *__restrict__ b_row_mask,
-                                                     uint16_t *__restrict__ c_row_mask) {
+                                                     uint16_t *__restrict__ c_row_mask,
+                                                     const int2 *__restrict__ strip_desc,
+                                                     const int32_t *__restrict__ strip_total, const int xcd_chunk) {
     // the 16 row masks of the B tiles of a batch of four pairs, per 16-lane group: every lane fetches
     // one mask and reads all 16 back (two 16-byte LDS loads instead of two 16-byte global loads per
     // lane: the kernel is bound by the vector-memory address path, not by LDS)
@@ -1188,12 +1190,18 @@ __global__ __launch_bounds__(256) void k_count_masks(int64_t c_tiles, const int6
     __shared__ RowSelectTable row_select;
     row_select.fill();
     __syncthreads();
-    const int per_xcd = gridDim.x / 8;
-    const int64_t logical = (int64_t)(blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
-    const int64_t c = (logical * blockDim.x + threadIdx.x) >> 4;
+    const int64_t logical = xcd_chunked_index(blockIdx.x, xcd_chunk);
+    // the block's 16 output tiles: consecutive ones, or the ones its descriptor names (order in strips)
+    int64_t c = (logical * blockDim.x + threadIdx.x) >> 4;
+    bool in = c < c_tiles;
+    if (strip_desc) {
+        int2 d = make_int2(0, 0);
+        if (logical < *strip_total) d = strip_desc[logical];
+        c = (int64_t)d.x + (threadIdx.x >> 4);
+        in = (int)(threadIdx.x >> 4) < d.y && c < c_tiles;
+    }
     const int r = threadIdx.x & 15;
     uint4(*const mine)[2] = lds_b[threadIdx.x >> 4];
-    const bool in = c < c_tiles;
     const int64_t s0 = in ? pair_off[c] : 0, s1 = in ? pair_off[c + 1] : 0;
     uint32_t acc = 0;
     // the 16-lane groups of a wave run different trip counts; the cross-lane reads stay inside a group
@@ -1394,7 +1402,18 @@ void plan_release(tsp_context *ctx, tsp_plan_s *p, hipStream_t s) {
     ctx_free(ctx, p->c_row_mask, s);
     ctx_free(ctx, p->c_row_off, s);
     ctx_free(ctx, p->c_row_ptr, s);
+    ctx_free(ctx, p->strip_desc, s);
+    ctx_free(ctx, p->strip_block_ptr, s);
     delete p;
+}
+
+// Strip order (strips.hip) for the kernels that walk the task list: only on request (TSP_OPT_STRIP_ORDER).
+// Measured on a power-law graph (262,144 rows, 2.5e9 task-list entries): the strips cut the traffic behind
+// the L2 caches to a quarter (multiplication kernel 540 -> 133 GB, counting kernel 222 -> 52 GB), and both
+// kernels took 3-5 % longer: on such tiles they are bound by the instructions issued per task-list entry,
+// not by memory.
+static bool strips_wanted(const tsp_context *ctx, const tsp_plan_s *, const tsp_tiles_s *) {
+    return ctx->strip_order == 1 || ctx->strip_order >= 16;
 }
 
 static int lanes_per_a_tile(const tsp_tiles_s *B) {
@@ -1620,11 +1639,23 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
     phase_end(ctx, TSP_PHASE_SYMBOLIC, s);
 
     phase_begin(ctx, TSP_PHASE_COUNT, s);
+    // Long tile-rows of C (every one of them meets most tile-rows of B again): the kernels that walk the task
+    // list take the output tiles in vertical strips, so that the part of B a strip needs stays in the L2 cache
+    if (P->c_tiles > 0 && strips_wanted(ctx, P, B)) {
+        rc = strips_build(ctx, P, B, s);
+        if (rc) return cleanup(rc);
+    }
     if (P->c_tiles > 0 && !fused_masks) {       // (otherwise the list kernel has done the counting pass already)
-        const unsigned grid = (unsigned)(((P->c_tiles * 16 + 255) / 256 + 7) / 8 * 8);   // multiple of 8: XCD remap
+        int64_t blocks = (P->c_tiles * 16 + 255) / 256;
+        if (P->strip_desc) blocks = P->strip_capacity;                             // (an upper bound of the workgroups)
+        // (short runs of blocks dealt to the XCDs in turn where the work is skewed: see numeric_enqueue)
+        const bool skewed = P->max_row_pairs > 8 * (P->pairs / std::max<int64_t>(ntr, 1) + 1);
+        const int xcd_chunk = skewed || P->strip_desc ? 64 : (int)std::max<int64_t>((blocks + 7) / 8, 1);
+        const unsigned grid = (unsigned)xcd_chunked_grid(blocks, xcd_chunk);
         KernelTimer kt(ctx, TSP_KERNEL_COUNT_MASKS, s);
         hipLaunchKernelGGL(k_count_masks, dim3(grid), dim3(256), 0, s, P->c_tiles, P->pair_off, P->pair_a, P->pair_b,
-                           A->row_mask, B->row_mask, P->c_row_mask);
+                           A->row_mask, B->row_mask, P->c_row_mask, P->strip_desc,
+                           P->strip_desc ? P->strip_block_ptr + P->strip_entries : nullptr, xcd_chunk);
     }
     if (ntr > 0 && !fused_masks) {             // (otherwise done by the list kernel as well)
         KernelTimer kt(ctx, TSP_KERNEL_ROW_OFFSETS, s);

@@ -19,6 +19,7 @@ TSP_F16, TSP_F32 = 0, 1
 FORM_LEFT, FORM_RIGHT = 1, 2
 OPT_VALIDATE, OPT_PHASE_TIMERS, OPT_WIDE_INDEX, OPT_NUMERIC_RUN, OPT_MATRIX_CORES, OPT_COMPACT_ZEROS = 1, 2, 3, 4, 5, 6
 OPT_WORK_ORDER = 7
+OPT_STRIP_ORDER = 8
 PHASES = ("convert", "symbolic", "count", "numeric")
 KERNELS = ("convert", "sym_count", "scan_sym", "sym_emit", "count_masks", "row_offsets", "scan_rows", "numeric")
 

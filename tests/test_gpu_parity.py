@@ -593,6 +593,43 @@ def test_tile_rows_taken_in_order_of_work(tsp, oracle):
         by_index.close()
 
 
+# ------------------------------------------------------------------ output tiles taken in vertical strips
+def test_output_tiles_taken_in_vertical_strips(tsp, oracle):
+    """The counting and the multiplication kernel with their workgroups taking the output tiles strip by
+    strip (forced here, with strips of a few dozen tiles of B; on its own the library does that only for
+    large products with long tile-rows): same result, bit for bit, as row-major, and as the oracle's.
+    A power-law graph (general task-list kernel and separate counting kernel), a stencil (list kernel with
+    the counting pass fused: only the multiplication kernel takes the strips), a rectangular product,
+    also with 64-bit addressing and on the vector ALUs."""
+    cases = [
+        ("R-MAT scale 11", inputs.rmat(scale=11, edge_factor=12, seed=2024), None, {}),
+        ("R-MAT scale 10, wide index", inputs.rmat(scale=10, edge_factor=16, seed=5), None, {"OPT_WIDE_INDEX": 1}),
+        ("stencil", inputs.config(3, small=True), None, {}),
+        ("rectangular", inputs.random_sparse(300, 170, 0.06, 31, empty_row_fraction=0.1),
+         inputs.random_sparse(170, 1500, 0.05, 32), {}),
+        ("rectangular, vector ALUs", inputs.random_sparse(200, 90, 0.1, 33), inputs.random_sparse(90, 900, 0.08, 34),
+         {"OPT_MATRIX_CORES": 0}),
+    ]
+    for name, A, B, extra in cases:
+        for per_strip in (16, 57, 1):
+            striped = _variant_handle(tsp, OPT_STRIP_ORDER=per_strip, OPT_NUMERIC_RUN=4, **extra)
+            row_major = _variant_handle(tsp, OPT_STRIP_ORDER=2, OPT_NUMERIC_RUN=4, **extra)
+            try:
+                print(f"strips: {name}, {per_strip} tiles of B per strip", flush=True)
+                dA = tsp.to_device(A)
+                dB = dA if B is None else tsp.to_device(B)
+                C1 = striped.spgemm(dA, dB)
+                C2 = row_major.spgemm(dA, dB)
+                for x, y in zip(C1.to_host(), C2.to_host()):
+                    assert np.array_equal(x, y)
+                assert_matches_oracle(C1, oracle.spgemm(A, A if B is None else B, threads=4), f"{name}, strips")
+                C1.free()
+                C2.free()
+            finally:
+                striped.close()
+                row_major.close()
+
+
 # ------------------------------------------------------------------ variants of the multiplication kernel
 def _variant_handle(tsp, **options):
     h = tsp.Handle(validate=True)
