@@ -1171,10 +1171,14 @@ __global__ __launch_bounds__(kTeamLanes ? 64 : kSymThreads) void k_sym_emit_list
     }
 }
 
-// Counting pass: 16 lanes per C tile, lane r owns row r of the tile.  For each pair of the tile's
-// segment: c_mask[r] |= OR over the set bits k of the A tile's row mask r of the B tile's row mask k.
-// The segment's entries are read 16 at a time, one per lane, and the bitmaps of four pairs are
-// requested together so that their latencies overlap.
+// Counting pass (Section 4.2) as a kernel of its own: a block takes 16 consecutive C tiles, whose task-list
+// segments are one contiguous stretch, and every lane takes one entry of the stretch at a time: it fetches
+// the 16 row masks of the A tile and of the B tile (32 bytes each), forms all 16 rows of the boolean
+// product (row r: OR over the set bits k of the A tile's row mask r of the B tile's row mask k) and ORs
+// them into the bitmap of the entry's C tile, which the block keeps in LDS.  With a lane per entry no
+// lane idles on a short segment or on an empty row of a sparse A tile: 16 lanes per C tile, each owning
+// one row, issued three times as many instructions per entry on tiles with two or three elements.
+constexpr int kMaskTiles = 16;         // C tiles per block (also the block of the order in strips)
 __global__ __launch_bounds__(256) void k_count_masks(int64_t c_tiles, const int64_t *__restrict__ pair_off,
                                                      const int32_t *__restrict__ pair_a,
                                                      const int32_t *__restrict__ pair_b,
@@ -1183,55 +1187,53 @@ __global__ __launch_bounds__(256) void k_count_masks(int64_t c_tiles, const int6
                                                      uint16_t *__restrict__ c_row_mask,
                                                      const int2 *__restrict__ strip_desc,
                                                      const int32_t *__restrict__ strip_total, const int xcd_chunk) {
-    // the 16 row masks of the B tiles of a batch of four pairs, per 16-lane group: every lane fetches
-    // one mask and reads all 16 back (two 16-byte LDS loads instead of two 16-byte global loads per
-    // lane: the kernel is bound by the vector-memory address path, not by LDS)
-    __shared__ uint4 lds_b[256 / 16][4][2];
+    __shared__ uint32_t cmask[kMaskTiles][8];      // row masks 2i (low half) and 2i+1 of every tile
+    __shared__ uint32_t seg[kMaskTiles + 1];       // first entry of every tile's segment, from the block's first
     __shared__ RowSelectTable row_select;
     row_select.fill();
-    __syncthreads();
     const int64_t logical = xcd_chunked_index(blockIdx.x, xcd_chunk);
-    // the block's 16 output tiles: consecutive ones, or the ones its descriptor names (order in strips)
-    int64_t c = (logical * blockDim.x + threadIdx.x) >> 4;
-    bool in = c < c_tiles;
+    // the block's output tiles: consecutive ones, or the ones its descriptor names (order in strips)
+    int64_t c_first = logical * kMaskTiles;
+    int tiles = (int)max((int64_t)0, min((int64_t)kMaskTiles, c_tiles - c_first));
     if (strip_desc) {
         int2 d = make_int2(0, 0);
         if (logical < *strip_total) d = strip_desc[logical];
-        c = (int64_t)d.x + (threadIdx.x >> 4);
-        in = (int)(threadIdx.x >> 4) < d.y && c < c_tiles;
+        c_first = d.x;
+        tiles = c_first + d.y <= c_tiles ? d.y : 0;
     }
-    const int r = threadIdx.x & 15;
-    uint4(*const mine)[2] = lds_b[threadIdx.x >> 4];
-    const int64_t s0 = in ? pair_off[c] : 0, s1 = in ? pair_off[c + 1] : 0;
-    uint32_t acc = 0;
-    // the 16-lane groups of a wave run different trip counts; the cross-lane reads stay inside a group
-    for (int64_t base = s0; __any(base < s1); base += 16) {
-        int a_mine = 0, b_mine = 0;
-        if (base + r < s1) {
-            a_mine = pair_a[base + r];
-            b_mine = pair_b[base + r];
-        }
-        const int cnt = (int)max((int64_t)0, min((int64_t)16, s1 - base));
-        for (int i = 0; __any(i < cnt); i += 4) {
-            uint32_t am[4], bm[4];
+    if (tiles <= 0) return;                        // whole block
+    const int64_t base = pair_off[c_first];
+    if (threadIdx.x <= kMaskTiles) {
+        const int64_t off = pair_off[c_first + min((int)threadIdx.x, tiles)] - base;
+        seg[threadIdx.x] = (uint32_t)min(max(off, (int64_t)0), (int64_t)0x7FFFFFFF);
+    }
+    if (threadIdx.x < kMaskTiles * 8) cmask[threadIdx.x >> 3][threadIdx.x & 7] = 0;
+    __syncthreads();
+    const uint32_t total = seg[kMaskTiles];
+    for (uint32_t e = threadIdx.x; e < total; e += 256) {
+        int t = 0;                                 // the C tile of entry e: the last tile whose segment starts at or before it
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int a = __shfl(a_mine, (i + u) & 15, 16), b = __shfl(b_mine, (i + u) & 15, 16);
-                am[u] = bm[u] = 0;
-                if (i + u < cnt) {
-                    am[u] = a_row_mask[(int64_t)a * T + r];
-                    bm[u] = b_row_mask[(int64_t)b * T + r];
-                }
+        for (int step = kMaskTiles / 2; step >= 1; step >>= 1)
+            if (seg[t + step] <= e) t += step;
+        const int64_t a = pair_a[base + e], b = pair_b[base + e];
+        const uint4 *ap = reinterpret_cast<const uint4 *>(a_row_mask + a * T);
+        const uint4 *bp = reinterpret_cast<const uint4 *>(b_row_mask + b * T);
+        const uint4 a0 = ap[0], a1 = ap[1], x = bp[0], y = bp[1];
+        const uint32_t aw[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            uint32_t w = 0;
+            if (aw[i]) {                           // (both rows of the word empty: the usual case on sparse tiles)
+                const uint32_t lo = boolean_row_product(aw[i] & 0xFFFFu, x, y, row_select);
+                const uint32_t hi = boolean_row_product(aw[i] >> 16, x, y, row_select);
+                w = ((lo | (lo >> 16)) & 0xFFFFu) | ((hi | (hi << 16)) & 0xFFFF0000u);
             }
-            wave_sync();                           // the previous batch has been read
-#pragma unroll
-            for (int u = 0; u < 4; ++u) reinterpret_cast<uint16_t *>(mine[u])[r] = (uint16_t)bm[u];
-            wave_sync();
-#pragma unroll
-            for (int u = 0; u < 4; ++u) acc |= boolean_row_product(am[u], mine[u][0], mine[u][1], row_select);
+            if (w) atomicOr(&cmask[t][i], w);
         }
     }
-    if (in) c_row_mask[c * T + r] = (uint16_t)((acc | (acc >> 16)) & 0xFFFFu);
+    __syncthreads();
+    const int t = threadIdx.x >> 4, r = threadIdx.x & 15;
+    if (t < tiles) c_row_mask[(c_first + t) * T + r] = (uint16_t)((cmask[t][r >> 1] >> ((r & 1) * 16)) & 0xFFFFu);
 }
 
 // row_ptr of C from the row lengths: block b takes rows [2048 b, 2048 b + 2048), starts from the
