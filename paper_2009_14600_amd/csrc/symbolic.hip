@@ -237,7 +237,9 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_count(TileRefs A, TileRefs 
                                                            int32_t *__restrict__ row_pairs,
                                                            int32_t *__restrict__ row_words,
                                                            int32_t *__restrict__ row_cand,
-                                                           int64_t *__restrict__ d_scalars) {
+                                                           int64_t *__restrict__ d_scalars,
+                                                           uint32_t *__restrict__ save_bitmap,
+                                                           uint32_t *__restrict__ save_cnt) {
     extern __shared__ uint32_t lds_dyn[];
     __shared__ uint32_t red[32];
     __shared__ int s_jmin, s_jmax;
@@ -257,8 +259,24 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_count(TileRefs A, TileRefs 
         // B's whole tile grid fits the bitmap: mark tile columns as they are, and read the extent of the
         // tile-row off the bitmap afterwards (no pass over the tile-rows of B for it: three dependent
         // gathers less)
+        // With save_bitmap the pass also keeps what the task-list kernel would otherwise find out again by
+        // walking the candidates twice more: the tile-row's bitmap, and the number of surviving pairs per tile
+        // column (16-bit counters, two per word, behind the bitmap: a tile-row of A has fewer than 65535 tiles,
+        // or the task-list kernel ignores them).
+        uint32_t *cnt16 = bm + direct_words;
         for (int w = threadIdx.x; w < direct_words; w += blockDim.x) bm[w] = 0;
+        if (save_bitmap)
+            for (int w = threadIdx.x; w < direct_words * 16; w += blockDim.x) cnt16[w] = 0;
         __syncthreads();
+        if (save_bitmap)
+            for_each_survivor<kLongRows, true>(A, B, a0, a1, lanes_per_a, &cand, [&](int, int, int J) {
+                if ((uint32_t)J < (uint32_t)direct_words * 32u) {
+                    atomicOr(&bm[J >> 5], 1u << (J & 31));
+                    atomicAdd(&cnt16[J >> 1], 1u << ((J & 1) * 16));
+                    ++surv;
+                }
+            });
+        else
         for_each_survivor<kLongRows, true>(A, B, a0, a1, lanes_per_a, &cand, [&](int, int, int J) {
             if ((uint32_t)J < (uint32_t)direct_words * 32u) {
                 atomicOr(&bm[J >> 5], 1u << (J & 31));
@@ -266,6 +284,11 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_count(TileRefs A, TileRefs 
             }
         });
         __syncthreads();
+        if (save_bitmap) {
+            for (int w = threadIdx.x; w < direct_words; w += blockDim.x) save_bitmap[(int64_t)I * direct_words + w] = bm[w];
+            for (int w = threadIdx.x; w < direct_words * 16; w += blockDim.x)
+                save_cnt[(int64_t)I * direct_words * 16 + w] = cnt16[w];
+        }
         uint32_t tiles = 0;
         for (int w = threadIdx.x; w < direct_words; w += blockDim.x) {
             const uint32_t bits = bm[w];
@@ -712,7 +735,8 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_emit(
     const int32_t *__restrict__ c_tile_row_ptr, const int64_t *__restrict__ row_pair_ptr,
     int32_t *__restrict__ c_tile_row, int32_t *__restrict__ c_tile_col, int64_t *__restrict__ pair_off,
     int32_t *__restrict__ pair_a, int32_t *__restrict__ pair_b, int32_t *cursor, int64_t A_capacity,
-    const int32_t *__restrict__ order) {
+    const int32_t *__restrict__ order, const uint32_t *__restrict__ saved_bitmap,
+    const uint32_t *__restrict__ saved_cnt, int saved_words, int64_t pairs) {
     extern __shared__ uint32_t lds_dyn[];
     __shared__ uint32_t red[32];
     uint32_t *bm = lds_dyn;
@@ -729,13 +753,19 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_emit(
     // the bitmap extent the first pass found for this tile-row (rows over the limit have nC = 0)
     const int words = min(row_words[I], words_cap);
     const int64_t span = (int64_t)words * 32;
-    for (int w = threadIdx.x; w < words; w += blockDim.x) bm[w] = 0;
-    __syncthreads();
     uint32_t dummy = 0;
-    for_each_survivor<kLongRows, true>(A, B, a0, a1, lanes_per_a, &dummy, [&](int, int, int J) {
-        const uint32_t j = (uint32_t)(J - jmin);
-        if (j < (uint32_t)span) atomicOr(&bm[j >> 5], 1u << (j & 31));
-    });
+    // what the counting kernel has kept for this tile-row: its bitmap and the pairs per tile column
+    const bool saved = saved_bitmap && a1 - a0 < 65535 && (jmin & 31) == 0 && (jmin >> 5) + words <= saved_words;
+    if (saved) {
+        for (int w = threadIdx.x; w < words; w += blockDim.x) bm[w] = saved_bitmap[(int64_t)I * saved_words + (jmin >> 5) + w];
+    } else {
+        for (int w = threadIdx.x; w < words; w += blockDim.x) bm[w] = 0;
+        __syncthreads();
+        for_each_survivor<kLongRows, true>(A, B, a0, a1, lanes_per_a, &dummy, [&](int, int, int J) {
+            const uint32_t j = (uint32_t)(J - jmin);
+            if (j < (uint32_t)span) atomicOr(&bm[j >> 5], 1u << (j & 31));
+        });
+    }
     __syncthreads();
     for (int w = threadIdx.x; w < words; w += blockDim.x) wpre[w] = __popc(bm[w]);
     __syncthreads();
@@ -753,7 +783,9 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_emit(
         }
     }
     const int64_t row_base = row_pair_ptr[I];
-    const bool one_chunk = (a1 - a0) <= 32;
+    // (a tile-row of at most 32 A tiles: the count pass leaves the contributor words of its only chunk
+    // behind for the emit pass; not so when the counts come from the counting kernel and no count pass runs)
+    const bool one_chunk = (a1 - a0) <= 32 && !saved;
     // A tile-row with more C tiles than the LDS window holds is worked off window by window, and every
     // window only walks its own stretch of B's tile-rows (for_each_survivor_below): the stretches are
     // shorter than the tile-rows, so fewer lanes share an A tile and more A tiles are in flight.
@@ -809,8 +841,24 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_emit(
             return (c >= 0 && c < nw) ? c : -1;
         };
         for (int c = threadIdx.x; c < nw; c += blockDim.x) cnt[c] = 0;
+        if (saved) {
+            __syncthreads();
+            // pairs per C tile of the window, as the counting kernel left them per tile column
+            const uint16_t *per_col = reinterpret_cast<const uint16_t *>(saved_cnt) + (int64_t)I * saved_words * 32;
+            for (int w = threadIdx.x; w < words; w += blockDim.x) {
+                uint32_t bits = bm[w];
+                int c = (int)wpre[w] - win0;       // position in the window of the word's first C tile
+                while (bits) {
+                    const int bit = __ffs(bits) - 1;
+                    bits &= bits - 1;
+                    if (c >= 0 && c < nw) cnt[c] = per_col[jmin + w * 32 + bit];
+                    ++c;
+                }
+            }
+            __syncthreads();
+        }
         // count pass: 32 A tiles at a time
-        for (int ch = a0; ch < a1; ch += 32) {
+        for (int ch = a0; ch < a1 && !saved; ch += 32) {
             if (skip_chunk(ch)) continue;
             for (int c = threadIdx.x; c < nw; c += blockDim.x) contrib[c] = 0;
             __syncthreads();
@@ -846,8 +894,10 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_emit(
                 if (c >= 0) {
                     const int64_t pos = row_base + (int64_t)win_base + (int64_t)cnt[c] +
                                         __popc(contrib[c] & ((1u << (a - ch)) - 1u));
-                    pair_a[pos] = a;
-                    pair_b[pos] = b;
+                    if ((uint64_t)pos < (uint64_t)pairs) {     // (always: the counts and the walks see the same survivors)
+                        pair_a[pos] = a;
+                        pair_b[pos] = b;
+                    }
                 }
             });
             __syncthreads();
@@ -1443,6 +1493,8 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
     int32_t *row_words = nullptr, *row_cand = nullptr;
     int32_t *cursor = nullptr, *order = nullptr;
     uint32_t *order_hist = nullptr;
+    uint32_t *saved_bitmap = nullptr, *saved_cnt = nullptr;   // kept by the counting kernel for the task-list kernel
+    int saved_words = 0;
     int64_t *row_pair_ptr = nullptr, *tmp = nullptr;
     auto cleanup = [&](int code) {
         ctx_free(ctx, row_jmin, s);
@@ -1457,6 +1509,8 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
         ctx_free(ctx, tile_row_entries, s);
         ctx_free(ctx, row_pair_ptr, s);
         ctx_free(ctx, tmp, s);
+        ctx_free(ctx, saved_bitmap, s);
+        ctx_free(ctx, saved_cnt, s);
         if (code) plan_release(ctx, P, s);
         return code;
     };
@@ -1504,7 +1558,7 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
         // many more of them are in flight (the kernels are bound by dependent loads, not by work)
         const int max_words = (int)std::min<int64_t>(kMaxWords, (B->tile_cols + 31) / 32 + 1);
         const int64_t per_row = A->nnz / ntr;
-        const int threads = per_row <= 256 ? 64 : per_row <= 4096 ? 128 : kSymThreads;
+        int threads = per_row <= 256 ? 64 : per_row <= 4096 ? 128 : kSymThreads;
         // where B's tile grid is narrow the bitmap simply covers all of it (worth it while the two sweeps
         // over the whole bitmap cost a block less than the three dependent gathers they replace:
         // measured, up to about six words per thread)
@@ -1513,13 +1567,29 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
         // short tile-rows of A: two per wave (with more of them than the chip holds waves, half the time);
         // against a wide B with the bitmap in segments, and a second launch for the tile-rows it leaves over
         const bool halves = threads == 64 && direct_words == 0 && per_row <= 128;
+        // Long tile-rows of A against a B whose tile grid fits the bitmap (hubs of a graph meet most of B): the
+        // pass keeps the bitmaps and the pairs per tile column for the general task-list kernel, which then
+        // walks the candidates twice instead of four times.  (Such products never take the list kernel; where
+        // that one runs, keeping 34 bytes per tile column of every tile-row would cost more than it saves.)
+        size_t count_lds = (size_t)max_words * sizeof(uint32_t);
+        if (direct_words > 0 && per_row >= 256 && (int64_t)ntr * direct_words * 17 * 4 <= ((int64_t)1 << 30) &&
+            (size_t)direct_words * 17 * sizeof(uint32_t) <= 60 * 1024) {
+            saved_words = direct_words;
+            saved_bitmap = ctx_alloc_n<uint32_t>(ctx, (size_t)ntr * direct_words, s);
+            saved_cnt = ctx_alloc_n<uint32_t>(ctx, (size_t)ntr * direct_words * 16, s);
+            if (!saved_bitmap || !saved_cnt) return cleanup(TSP_ERR_ALLOC_FAILED);
+            count_lds = std::max(count_lds, (size_t)direct_words * 17 * sizeof(uint32_t));
+            // (the counters take LDS, LDS decides how many blocks a CU holds, and the pass lives on waves in
+            // flight: larger blocks keep as many)
+            if (count_lds > 8 * 1024) threads = kSymThreads;
+        }
         if (halves && max_words > 1024) {
             hipLaunchKernelGGL(long_rows ? k_sym_count_segmented<true> : k_sym_count_segmented<false>,
                                dim3((unsigned)((ntr + 1) / 2)), dim3(64), 0, s, ra, rb, std::min(lanes, 8), max_words,
                                row_jmin, row_c_tiles, row_pairs, row_words, row_cand, ctx->d_scalars);
             hipLaunchKernelGGL(long_rows ? k_sym_count<true> : k_sym_count<false>, dim3((unsigned)ntr), dim3(threads),
                                max_words * sizeof(uint32_t), s, ra, rb, lanes, max_words, 0, /*only_marked=*/1,
-                               row_jmin, row_c_tiles, row_pairs, row_words, row_cand, ctx->d_scalars);
+                               row_jmin, row_c_tiles, row_pairs, row_words, row_cand, ctx->d_scalars, nullptr, nullptr);
         } else if (halves)
             hipLaunchKernelGGL(long_rows ? k_sym_count_half<true> : k_sym_count_half<false>,
                                dim3((unsigned)((ntr + 1) / 2)), dim3(64), 2 * max_words * sizeof(uint32_t), s, ra, rb,
@@ -1527,8 +1597,9 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
                                ctx->d_scalars);
         else
             hipLaunchKernelGGL(long_rows ? k_sym_count<true> : k_sym_count<false>, dim3((unsigned)ntr), dim3(threads),
-                               max_words * sizeof(uint32_t), s, ra, rb, lanes, max_words, direct_words,
-                               /*only_marked=*/0, row_jmin, row_c_tiles, row_pairs, row_words, row_cand, ctx->d_scalars);
+                               count_lds, s, ra, rb, lanes, max_words, direct_words,
+                               /*only_marked=*/0, row_jmin, row_c_tiles, row_pairs, row_words, row_cand, ctx->d_scalars,
+                               saved_bitmap, saved_cnt);
         SYM_CHECK(hipGetLastError());
     }
     {
@@ -1632,7 +1703,7 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
                                lds, s, ra, rb, lanes, words_cap, window, row_jmin, row_words,
                                P->c_tile_row_ptr,
                                row_pair_ptr, P->c_tile_row, P->c_tile_col, P->pair_off, P->pair_a, P->pair_b, cursor,
-                               A->tile_capacity, order);
+                               A->tile_capacity, order, saved_bitmap, saved_cnt, saved_words, P->pairs);
         }
         SYM_CHECK(hipGetLastError());
     } else {
