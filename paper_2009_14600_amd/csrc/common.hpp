@@ -56,6 +56,8 @@ struct tsp_context {
     int numeric_run_len = 0;                       // tiles per wave of the multiplication kernel, 0: automatic
     int matrix_cores = 1;                          // 0: block products on the vector ALUs
     int compact = 0;                               // 1: tsp_spgemm removes zero-valued entries from C
+    bool hint_general = false;                     // the last product took the general task-list kernel ...
+    int64_t hint_sizes[4] = {-1, -1, -1, -1};      // ... with these rows and nnz of A and of B
     int last_hip = 0;
     tsp_stats stats{};
     void *chain_slots = nullptr;                   // device, for the chained scans (chain.hpp)

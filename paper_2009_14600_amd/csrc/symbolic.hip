@@ -1567,12 +1567,16 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
         // short tile-rows of A: two per wave (with more of them than the chip holds waves, half the time);
         // against a wide B with the bitmap in segments, and a second launch for the tile-rows it leaves over
         const bool halves = threads == 64 && direct_words == 0 && per_row <= 128;
-        // Long tile-rows of A against a B whose tile grid fits the bitmap (hubs of a graph meet most of B): the
-        // pass keeps the bitmaps and the pairs per tile column for the general task-list kernel, which then
-        // walks the candidates twice instead of four times.  (Such products never take the list kernel; where
-        // that one runs, keeping 34 bytes per tile column of every tile-row would cost more than it saves.)
+        // A product that takes the general task-list kernel, against a B whose tile grid fits the bitmap (hubs of
+        // a graph meet most of B): the pass keeps the bitmaps and the pairs per tile column for that kernel, which
+        // then walks the candidates twice instead of four times.  The counters cost the pass LDS and time (on
+        // such a graph 26 -> 42 ms, for 133 -> 100 ms in the task-list kernel), and where the list kernel runs
+        // they are wasted; which kernel will run is known only after this pass, so the handle goes by what the
+        // previous call with operands of the same sizes did.  The result is the same either way.
         size_t count_lds = (size_t)max_words * sizeof(uint32_t);
-        if (direct_words > 0 && per_row >= 256 && (int64_t)ntr * direct_words * 17 * 4 <= ((int64_t)1 << 30) &&
+        const bool general_expected = ctx->hint_general && ctx->hint_sizes[0] == A->rows && ctx->hint_sizes[1] == A->nnz &&
+                                      ctx->hint_sizes[2] == B->rows && ctx->hint_sizes[3] == B->nnz;
+        if (direct_words > 0 && general_expected && (int64_t)ntr * direct_words * 17 * 4 <= ((int64_t)1 << 30) &&
             (size_t)direct_words * 17 * sizeof(uint32_t) <= 60 * 1024) {
             saved_words = direct_words;
             saved_bitmap = ctx_alloc_n<uint32_t>(ctx, (size_t)ntr * direct_words, s);
@@ -1667,6 +1671,11 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
         // (the fused counting pass of the list kernel wants more lanes than the enumeration does)
         const int threads = per_row <= 256 ? 64 : per_row <= 512 ? 128 : kSymThreads;
         listed = h[S_MAX_ROW_PAIRS] <= kListCap && h[S_MAX_ROW_C_TILES] <= kListTiles;
+        ctx->hint_general = !listed;
+        ctx->hint_sizes[0] = A->rows;
+        ctx->hint_sizes[1] = A->nnz;
+        ctx->hint_sizes[2] = B->rows;
+        ctx->hint_sizes[3] = B->nnz;
         if (listed) {
             const int list_cap = (int)std::max<int64_t>(h[S_MAX_ROW_PAIRS], 1);
             fused_masks = ntr >= 1024;

@@ -168,7 +168,8 @@ def test_rmat_full_size(tsp, handle, oracle, capsys):
     assert products == int((deg ** 2).sum())           # symmetric 0/1 matrix
     dA = tsp.to_device(A)
     print(f"workload 4: multiplying ({products} products)", flush=True)
-    C = handle.spgemm(dA, dA)
+    handle.spgemm(dA, dA).free()                       # (the second call with the same operands is the one bench.py times:
+    C = handle.spgemm(dA, dA)                          # the counting kernel then keeps its counters for the task-list kernel)
     print(f"workload 4: nnz(C) = {C.nnz}", flush=True)
     assert C.nnz > 2 ** 31                             # needs the 64-bit row_ptr
     counts, _ = oracle.row_nnz(A, A, 0, 256)           # the hub rows: the longest rows of C
