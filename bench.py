@@ -279,6 +279,18 @@ def run_workload(index, steps, warmup, args, tsp, inputs, torch, headline):
     kavg = {k: v / tsteps for k, v in ksum.items()}
     pavg = {k: v / tsteps for k, v in psum.items()}
 
+    # the library's own count of the intermediate products (an extra kernel, so outside the timed steps),
+    # against the count from the row lengths above; and the paper's selection criteria for this operand
+    handle.set_option(tsp.OPT_COUNT_PRODUCTS, 1)
+    step()
+    torch.cuda.synchronize()
+    s3 = handle.stats()
+    handle.set_option(tsp.OPT_COUNT_PRODUCTS, 0)
+    assert s3["products"] == products, (s3["products"], products)
+    regime = {"nnz_A_over_300000": A.nnz > 300000, "mean_row_A": round(s3["a_mean_row"], 2),
+              "entries_per_tile_A": round(s3["a_tile_fill"], 2), "in_paper_regime": bool(s3["in_paper_regime"]),
+              "well_filled_tiles": bool(s3["well_filled_tiles"])}
+
     # group counts of the tile storage, for the layout's own byte count
     tiles = handle.convert(dA)
     tv = tiles.view()
@@ -355,7 +367,8 @@ def run_workload(index, steps, warmup, args, tsp, inputs, torch, headline):
                    "rows": A.rows, "nnz_A": A.nnz, "products": products, "nnz_C": st["c_nnz"],
                    "a_tiles": st["a_tiles"], "pairs": st["pairs"], "c_tiles": st["c_tiles"],
                    "validate_inputs": not args.no_validate, "matrix_cores": not args.no_matrix_cores,
-                   "compact_zeros": args.compact_zeros, "first_call_ms": round(first * 1e3, 3)},
+                   "compact_zeros": args.compact_zeros, "first_call_ms": round(first * 1e3, 3),
+                   "selection_criteria": regime},
         "roofline": roofline, "mfma": mfma, "end_to_end": end_to_end, "phase_hbm": phase_hbm,
         "kernel_us": {k: round(v, 2) for k, v in kavg.items()},
         "phase_us": {k: round(v, 2) for k, v in pavg.items()},

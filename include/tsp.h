@@ -104,6 +104,9 @@ enum {
                                /*    2: by index, 0 (default): heaviest first where a few tile-rows */
                                /*    are far heavier than the rest.  The result does not depend on  */
                                /*    it                                                             */
+    TSP_OPT_COUNT_PRODUCTS = 10, /* 1: tsp_spgemm also counts the intermediate products (one small    */
+                               /*    kernel over the entries of A) and reports them in tsp_stats;    */
+                               /*    0 (default): tsp_stats.products = -1                            */
     TSP_OPT_STRIP_ORDER = 8    /* order in which the counting and the multiplication kernel (4.2,   */
                                /*    4.3) take the output tiles: 1: in vertical strips of tile      */
                                /*    columns sized so that the tiles of B a strip meets stay in the  */
@@ -151,6 +154,17 @@ typedef struct {
     float total_us;                  /* first event to last event of the last tsp_spgemm, if timers on */
     float kernel_us[TSP_KERNEL_COUNT_]; /* device time per kernel of the last tsp_spgemm, if timers on  */
                                      /* (when B is not A, the conversion entries describe B's)        */
+    int64_t products;                /* intermediate products of the last tsp_spgemm (the paper's      */
+                                     /* NNZ of C-bar, Table 1; 2 * products = the FLOP of the product), */
+                                     /* counted when TSP_OPT_COUNT_PRODUCTS is on, else -1              */
+    /* The paper's selection criteria for the last product's left operand (Section 6.1): the tiled method */
+    /* pays off for NNZ(A) > 300000 with more than 42 entries per row on average, and for well-filled     */
+    /* tiles (5 of 64 slots of an 8x8 tile and more, i.e. 20 entries per 16x16 tile).  Reported, not acted */
+    /* on: this library has no non-tiled path to fall back to.                                            */
+    float a_mean_row;                /* NNZ(A) / rows                                                  */
+    float a_tile_fill;               /* NNZ(A) / tiles(A): entries per 16x16 tile                      */
+    int32_t in_paper_regime;         /* 1: NNZ(A) > 300000 and a_mean_row > 42                         */
+    int32_t well_filled_tiles;       /* 1: a_tile_fill >= 20                                           */
 } tsp_stats;
 
 /* Create a handle on the current HIP device.  allocator == NULL selects hipMalloc/hipFree. */

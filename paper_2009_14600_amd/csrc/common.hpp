@@ -31,6 +31,7 @@ enum Scalar {
     S_INTERNAL = 11,         // != 0: a bounded device-side wait ran out (should never happen)
     S_MAX_ROW_PAIRS = 12,    // max over C tile-rows of the number of task-list entries
     S_MAX_ROW_ENTRIES = 13,  // max over C tile-rows of the number of structural entries
+    S_PRODUCTS = 14,         // intermediate products (TSP_OPT_COUNT_PRODUCTS)
     S_PUBLISHED = 31,        // host mirror only: a slot without a value (publish_scalars tags every slot)
 };
 
@@ -53,6 +54,7 @@ struct tsp_context {
     int force_wide = 0;                            // use the 64-bit-pointer kernels whatever the sizes
     int work_order = 0;                            // TSP_OPT_WORK_ORDER
     int strip_order = 0;                           // TSP_OPT_STRIP_ORDER
+    int count_products = 0;                        // TSP_OPT_COUNT_PRODUCTS
     int numeric_run_len = 0;                       // tiles per wave of the multiplication kernel, 0: automatic
     int matrix_cores = 1;                          // 0: block products on the vector ALUs
     int compact = 0;                               // 1: tsp_spgemm removes zero-valued entries from C

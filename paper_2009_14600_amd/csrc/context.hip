@@ -255,6 +255,7 @@ extern "C" int tsp_set_option(tsp_handle ctx, int key, int64_t value) {
             if (value < 0 || value > 2) return TSP_ERR_INVALID_ARG;
             ctx->work_order = (int)value;
             return TSP_OK;
+        case TSP_OPT_COUNT_PRODUCTS: ctx->count_products = value != 0; return TSP_OK;
         case TSP_OPT_STRIP_ORDER:
             if (value < 0 || (value > 2 && value < 16) || value > (1 << 30)) return TSP_ERR_INVALID_ARG;
             ctx->strip_order = (int)value;

@@ -1776,6 +1776,11 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
     ctx->stats.pairs = P->pairs;
     ctx->stats.c_tiles = P->c_tiles;
     ctx->stats.c_nnz = P->c_nnz;
+    // the paper's selection criteria (Section 6.1) for the left operand
+    ctx->stats.a_mean_row = A->rows > 0 ? (float)((double)A->nnz / (double)A->rows) : 0.f;
+    ctx->stats.a_tile_fill = A->ntiles > 0 ? (float)((double)A->nnz / (double)A->ntiles) : 0.f;
+    ctx->stats.in_paper_regime = A->nnz > 300000 && ctx->stats.a_mean_row > 42.f;
+    ctx->stats.well_filled_tiles = ctx->stats.a_tile_fill >= 20.f;
     *out = P;
     return cleanup(TSP_OK);
 }

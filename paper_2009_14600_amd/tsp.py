@@ -20,6 +20,7 @@ FORM_LEFT, FORM_RIGHT = 1, 2
 OPT_VALIDATE, OPT_PHASE_TIMERS, OPT_WIDE_INDEX, OPT_NUMERIC_RUN, OPT_MATRIX_CORES, OPT_COMPACT_ZEROS = 1, 2, 3, 4, 5, 6
 OPT_WORK_ORDER = 7
 OPT_STRIP_ORDER = 8
+OPT_COUNT_PRODUCTS = 10
 PHASES = ("convert", "symbolic", "count", "numeric")
 KERNELS = ("convert", "sym_count", "scan_sym", "sym_emit", "count_masks", "row_offsets", "scan_rows", "numeric")
 
@@ -56,7 +57,9 @@ class _Stats(ctypes.Structure):
                 ("pairs", ctypes.c_int64), ("c_tiles", ctypes.c_int64), ("c_nnz", ctypes.c_int64),
                 ("workspace_bytes", ctypes.c_int64), ("workspace_peak_bytes", ctypes.c_int64),
                 ("phase_us", ctypes.c_float * 4), ("total_us", ctypes.c_float),
-                ("kernel_us", ctypes.c_float * len(KERNELS))]
+                ("kernel_us", ctypes.c_float * len(KERNELS)),
+                ("products", ctypes.c_int64), ("a_mean_row", ctypes.c_float), ("a_tile_fill", ctypes.c_float),
+                ("in_paper_regime", ctypes.c_int32), ("well_filled_tiles", ctypes.c_int32)]
 
 
 class _TilesView(ctypes.Structure):

@@ -167,6 +167,30 @@ def test_runs_are_bit_identical(tsp, handle):
         assert all(np.array_equal(x, y) for x, y in zip(o, outs[0]))
 
 
+def test_products_count_and_selection_criteria(tsp, oracle):
+    """TSP_OPT_COUNT_PRODUCTS: the library's count of the intermediate products (the FLOP of the benchmark
+    metric are twice that) equals the oracle's, for A*A and for a rectangular A*B with 64-bit row pointers;
+    off, the field reads -1.  The selection criteria of Section 6.1 are reported for the left operand."""
+    h = _variant_handle(tsp, OPT_COUNT_PRODUCTS=1)
+    try:
+        A = inputs.config(5, small=True)
+        dA = tsp.to_device(A)
+        h.spgemm(dA, dA).free()
+        st = h.stats()
+        assert st["products"] == oracle.spgemm(A, A, threads=4).products > 0
+        assert abs(st["a_mean_row"] - A.nnz / A.rows) < 1e-3 and st["a_tile_fill"] > 100 and st["well_filled_tiles"] == 1
+        assert st["in_paper_regime"] == 0                                  # fewer than 300000 entries
+        L = inputs.random_sparse(90, 70, 0.1, 3, empty_row_fraction=0.2)
+        R = inputs.random_sparse(70, 200, 0.05, 4)
+        h.spgemm(tsp.to_device(L, row_ptr_dtype="i64"), tsp.to_device(R, row_ptr_dtype="i64")).free()
+        assert h.stats()["products"] == oracle.spgemm(L, R).products
+        h.set_option(tsp.OPT_COUNT_PRODUCTS, 0)
+        h.spgemm(dA, dA).free()
+        assert h.stats()["products"] == -1
+    finally:
+        h.close()
+
+
 # ------------------------------------------------------------------ error paths (forced from the host)
 def test_error_codes(tsp, handle):
     import torch
