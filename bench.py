@@ -229,6 +229,8 @@ def run_workload(index, steps, warmup, args, tsp, inputs, torch, headline):
         handle.set_option(tsp.OPT_NUMERIC_RUN, args.numeric_run)
     if args.strip_order:
         handle.set_option(tsp.OPT_STRIP_ORDER, args.strip_order)
+    if args.wide_index:
+        handle.set_option(tsp.OPT_WIDE_INDEX, 1)
 
     def step():
         out = handle.spgemm_raw(sA, sA)
@@ -399,6 +401,7 @@ def main():
     ap.add_argument("--compact-zeros", action="store_true",
                     help="finish every step with the compaction of zero-valued entries (paper Section 4.4)")
     ap.add_argument("--numeric-run", type=int, default=0, help="tiles per wave of the multiplication kernel (0: automatic)")
+    ap.add_argument("--wide-index", action="store_true", help="force the kernels that address arrays through 64-bit pointers")
     ap.add_argument("--strip-order", type=int, default=0,
                     help="order of the output tiles in the counting and multiplication kernels (0: automatic, 1: strips, 2: row-major)")
     args = ap.parse_args()

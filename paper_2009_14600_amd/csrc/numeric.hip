@@ -525,7 +525,7 @@ int numeric_enqueue(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s
         // takes one contiguous eighth of the blocks; where a few tile-rows are far heavier than the rest
         // (hubs of a power-law graph sit at the low indices) short runs of blocks are dealt to the XCDs in turn
         const bool skewed = P->max_row_pairs > 8 * (P->pairs / std::max<int64_t>(P->c_tile_rows, 1) + 1);
-        const int xcd_chunk = skewed || strips ? 64 : (int)std::max<int64_t>((blocks + kXcds - 1) / kXcds, 1);
+        const int xcd_chunk = skewed || strips ? 8 : (int)std::max<int64_t>((blocks + kXcds - 1) / kXcds, 1);
         blocks = xcd_chunked_grid(blocks, xcd_chunk);
         const NumericSizes z{(uint64_t)P->pairs, (uint64_t)A->tile_capacity, (uint64_t)B->tile_capacity,
                              (uint64_t)A->group_capacity, (uint64_t)B->group_capacity};

@@ -38,7 +38,7 @@ namespace tsp {
 constexpr int kSymThreads = 256;
 constexpr int kMaxWords = 4096;        // LDS bitmap words per tile-row: span of 131072 tile columns
 constexpr int kDirectWords = 1024;     // counting kernel: widest tile grid of B whose bitmap is indexed by the column itself
-constexpr int kWindow = 2048;          // C tiles of one tile-row handled per LDS window
+constexpr int kWindow = 4096;          // C tiles of one tile-row handled per LDS window
 constexpr int kRowLeftOver = -1;       // row_words of a tile-row that the segmented counting kernel leaves to the full one
 constexpr int kSurvivorUnroll = 4;     // B tiles one lane requests per trip of the candidate loop: long tile-rows of B
 constexpr int kSurvivorUnrollShort = 2;   // ... and short ones
@@ -1732,7 +1732,7 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
         if (P->strip_desc) blocks = P->strip_capacity;                             // (an upper bound of the workgroups)
         // (short runs of blocks dealt to the XCDs in turn where the work is skewed: see numeric_enqueue)
         const bool skewed = P->max_row_pairs > 8 * (P->pairs / std::max<int64_t>(ntr, 1) + 1);
-        const int xcd_chunk = skewed || P->strip_desc ? 64 : (int)std::max<int64_t>((blocks + 7) / 8, 1);
+        const int xcd_chunk = skewed || P->strip_desc ? 8 : (int)std::max<int64_t>((blocks + 7) / 8, 1);
         const unsigned grid = (unsigned)xcd_chunked_grid(blocks, xcd_chunk);
         KernelTimer kt(ctx, TSP_KERNEL_COUNT_MASKS, s);
         hipLaunchKernelGGL(k_count_masks, dim3(grid), dim3(256), 0, s, P->c_tiles, P->pair_off, P->pair_a, P->pair_b,

@@ -496,17 +496,17 @@ def test_smape_against_full_precision_as_in_the_paper(tsp, handle, oracle):
 
 
 # ------------------------------------------------------------------ tile-rows of C wider than the LDS window
-@pytest.mark.parametrize("M,K,N,da,db", [(40, 64, 40000, 0.5, 0.05), (40, 1024, 40000, 0.1, 0.004)])
+@pytest.mark.parametrize("M,K,N,da,db", [(40, 64, 70000, 0.5, 0.05), (40, 1024, 70000, 0.1, 0.004)])
 def test_tile_rows_with_more_output_tiles_than_the_symbolic_window(tsp, handle, oracle, M, K, N, da, db):
-    """2500 output tiles per tile-row: the task list of such a tile-row is built with its per-tile
-    words in global memory (one chunk of A tiles in the first case, several in the second)."""
+    """4375 output tiles per tile-row, more than one window of the general task-list kernel holds (4096): such
+    a tile-row is worked off window by window (one chunk of A tiles in the first case, several in the second)."""
     A = inputs.random_sparse(M, K, da, 71, values="smallint")
     B = inputs.random_sparse(K, N, db, 72, values="smallint")
     print(f"wide output tile-rows {M}x{K}x{N}", flush=True)
     dA, dB = tsp.to_device(A), tsp.to_device(B)
     C = handle.spgemm(dA, dB)
     st = handle.stats()
-    assert st["c_tiles"] > 3 * 2048
+    assert st["c_tiles"] > 3 * 4096
     ref = oracle.spgemm(A, B, threads=4)
     assert_matches_oracle(C, ref, "wide output tile-rows")
     C.free()
