@@ -371,8 +371,8 @@ def run_workload(index, steps, warmup, args, tsp, inputs, torch, headline):
         "numeric_and_csr_emission": hbm(algorithmic_bytes("numeric", A, st), kavg["numeric"]),
     }
     if not args.compact_zeros:
-        # the compaction of zero-valued entries (Section 4.4) as a call of its own on the result: reads C,
-        # writes the compacted copy when an entry is zero (otherwise only the survivor count runs)
+        # the compaction of zero-valued entries (Section 4.4) as a call of its own on the result: counts the
+        # survivors per row, then copies them into a new matrix
         raw = handle.spgemm_raw(sA, sA)
         cz = handle._lib.tsp_compact_zeros
         import ctypes
@@ -391,7 +391,9 @@ def run_workload(index, steps, warmup, args, tsp, inputs, torch, headline):
             out_nnz = out.nnz
             handle._free_csr(out)
             us = ev0.elapsed_time(ev1) * 1e3                # the last repetition counts (the first sizes the workspace)
-        moved = 8 * raw.nnz + 8 * (A.rows + 1) + 4 * A.rows + (8 * out_nnz + 8 * (A.rows + 1) + 8 * raw.nnz if out_nnz != raw.nnz else 0)
+        # counting pass: the values and row_ptr in, survivors per row out; prefix sum; copy pass: columns and values
+        # in, the survivors and the new row_ptr out
+        moved = (4 * raw.nnz + 8 * (A.rows + 1) + 4 * A.rows) + (4 * A.rows + 8 * (A.rows + 1)) + (8 * raw.nnz + 8 * out_nnz + 8 * (A.rows + 1))
         phase_hbm["compact_zeros"] = dict(hbm(moved, us), entries_removed=int(raw.nnz - out_nnz),
                                           note="separate call on the result, its host wait included")
         handle._free_csr(raw)

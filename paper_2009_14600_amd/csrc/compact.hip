@@ -33,29 +33,60 @@ __device__ __forceinline__ void row_range(const CompactArgs<RP> &a, int64_t row,
 __device__ __forceinline__ bool survives(float v) { return !(v == 0.0f); }
 
 // A block counts 16 consecutive rows; their sum goes to group_keep (what row_ptr_in_one_launch wants).
+// Rows of a few hundred entries at most: 16 lanes each.  Where the block's 16 rows hold more than
+// kCompactLongSpan entries together (products of graphs: thousands of entries per row, a hundred thousand in
+// a hub's), the whole block takes the rows one after the other, 256 consecutive entries per step, so that a
+// long row is not left to 16 lanes.
 static_assert(kCompactThreads / kCompactLanes == T, "a block covers one group of 16 rows");
+constexpr int64_t kCompactLongSpan = 4096;
+
+// entries of the block's rows [r0, r1) together (block-uniform)
+template <typename RP>
+__device__ __forceinline__ int64_t block_span(const CompactArgs<RP> &a, int64_t r0, int64_t r1) {
+    int64_t b0, b1, e0, e1;
+    row_range(a, r0, b0, e0);
+    row_range(a, r1 - 1, b1, e1);
+    return e1 - b0;
+}
+
 template <typename RP>
 __global__ __launch_bounds__(kCompactThreads) void k_compact_count(CompactArgs<RP> a, int32_t *__restrict__ keep,
                                                                   uint32_t *__restrict__ group_keep) {
     __shared__ int s_rows[T];
-    const int64_t row = ((int64_t)blockIdx.x * kCompactThreads + threadIdx.x) / kCompactLanes;
-    const int l = threadIdx.x % kCompactLanes;
-    int n = 0;
-    if (row < a.rows) {                        // whole 16-lane groups
-        int64_t e0, e1;
-        row_range(a, row, e0, e1);
-        for (int64_t e = e0 + l; e < e1; e += kCompactLanes) n += survives(a.val[e]) ? 1 : 0;
-    }
+    const int64_t r0 = (int64_t)blockIdx.x * T, r1 = min(r0 + T, a.rows);
+    if (r0 < a.rows && block_span(a, r0, r1) > kCompactLongSpan) {       // (whole block)
+        if (threadIdx.x < T) s_rows[threadIdx.x] = 0;
+        __syncthreads();
+        for (int64_t row = r0; row < r1; ++row) {
+            int64_t e0, e1;
+            row_range(a, row, e0, e1);
+            int n = 0;
+            for (int64_t e = e0 + threadIdx.x; e < e1; e += kCompactThreads) n += survives(a.val[e]) ? 1 : 0;
+            n = (int)wave_sum((uint32_t)n);
+            if ((threadIdx.x & 63) == 0 && n) atomicAdd(&s_rows[row - r0], n);
+        }
+        __syncthreads();
+        if (threadIdx.x < T && r0 + threadIdx.x < a.rows) keep[r0 + threadIdx.x] = s_rows[threadIdx.x];
+    } else {
+        const int64_t row = r0 + threadIdx.x / kCompactLanes;
+        const int l = threadIdx.x % kCompactLanes;
+        int n = 0;
+        if (row < a.rows) {                        // whole 16-lane groups
+            int64_t e0, e1;
+            row_range(a, row, e0, e1);
+            for (int64_t e = e0 + l; e < e1; e += kCompactLanes) n += survives(a.val[e]) ? 1 : 0;
+        }
 #pragma unroll
-    for (int d = kCompactLanes / 2; d > 0; d >>= 1) n += __shfl_xor(n, d, kCompactLanes);
-    if (l == 0) {
-        if (row < a.rows) keep[row] = n;
-        s_rows[threadIdx.x / kCompactLanes] = n;
+        for (int d = kCompactLanes / 2; d > 0; d >>= 1) n += __shfl_xor(n, d, kCompactLanes);
+        if (l == 0) {
+            if (row < a.rows) keep[row] = n;
+            s_rows[threadIdx.x / kCompactLanes] = n;
+        }
+        __syncthreads();
     }
-    __syncthreads();
     if (threadIdx.x == 0) {
         uint32_t sum = 0;
-        for (int r = 0; r < T; ++r) sum += (uint32_t)s_rows[r];
+        for (int r = 0; r < T; ++r) sum += r0 + r < a.rows ? (uint32_t)s_rows[r] : 0u;
         group_keep[blockIdx.x] = sum;
     }
     // zeros behind the last group, up to a multiple of four entries (the array has four spare ones)
@@ -67,7 +98,42 @@ __global__ __launch_bounds__(kCompactThreads) void k_compact_fill(CompactArgs<RP
                                                                  const int64_t *__restrict__ new_row_ptr,
                                                                  int32_t *__restrict__ out_col,
                                                                  float *__restrict__ out_val) {
-    const int64_t row = ((int64_t)blockIdx.x * kCompactThreads + threadIdx.x) / kCompactLanes;
+    const int64_t r0 = (int64_t)blockIdx.x * T, r1 = min(r0 + T, a.rows);
+    if (r0 >= a.rows) return;
+    if (block_span(a, r0, r1) > kCompactLongSpan) {                      // (whole block)
+        __shared__ uint32_t s_wave[2][kCompactThreads / 64];              // survivors per wave, two steps in flight
+        const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+        int step = 0;
+        for (int64_t row = r0; row < r1; ++row) {
+            int64_t e0, e1;
+            row_range(a, row, e0, e1);
+            int64_t at = new_row_ptr[row];
+            for (int64_t base = e0; base < e1; base += kCompactThreads, step ^= 1) {   // the whole block runs every trip
+                const int64_t e = base + threadIdx.x;
+                const bool in = e < e1;
+                const float v = in ? a.val[e] : 0.0f;
+                const bool on = in && survives(v);
+                const unsigned long long mine = __ballot(on);
+                if (lane == 0) s_wave[step][wave] = (uint32_t)__popcll(mine);
+                __syncthreads();                   // (the other buffer is free again: every wave has passed the barrier of the step before)
+                uint32_t before = 0, all = 0;
+#pragma unroll
+                for (int w = 0; w < kCompactThreads / 64; ++w) {
+                    const uint32_t n = s_wave[step][w];
+                    before += w < wave ? n : 0u;
+                    all += n;
+                }
+                if (on) {
+                    const int64_t p = at + before + __popcll(mine & ((1ull << lane) - 1ull));
+                    out_col[p] = a.col[e];
+                    out_val[p] = v;
+                }
+                at += all;
+            }
+        }
+        return;
+    }
+    const int64_t row = r0 + threadIdx.x / kCompactLanes;
     const int l = threadIdx.x % kCompactLanes;
     if (row >= a.rows) return;
     int64_t e0, e1;

@@ -369,7 +369,9 @@ def _assert_same_csr(C, want, what):
 
 
 @pytest.mark.parametrize("M,K,N,density,seed", [
-    (23, 31, 17, 0.3, 1), (300, 200, 500, 0.05, 2), (64, 2000, 64, 0.1, 3), (1, 1, 1, 1.0, 4)])
+    (23, 31, 17, 0.3, 1), (300, 200, 500, 0.05, 2), (64, 2000, 64, 0.1, 3), (1, 1, 1, 1.0, 4),
+    # rows of thousands of entries (the block takes them one after the other), next to short ones and a ragged last block
+    (40, 30, 5000, 0.4, 5), (50, 8, 9000, 0.3, 6)])
 def test_compact_zeros_small_integers(tsp, handle, oracle, M, K, N, density, seed):
     """Small-integer values: all sums are exact in fp32 and fp64, so both sides drop the same entries."""
     A = inputs.random_sparse(M, K, density, seed, empty_row_fraction=0.1, values="smallint")
