@@ -300,7 +300,7 @@ typedef struct {
     const int32_t *c_tile_row;       /* int32[c_tiles]                                              */
     const int32_t *c_tile_col;       /* int32[c_tiles], ascending inside a tile-row                 */
     const int64_t *pair_off;         /* int64[c_tiles + 1] segment offsets into the task list       */
-    const int32_t *pair_a, *pair_b;  /* int32[pairs] tile index in A / in B                         */
+    const int32_t *pair_ab;          /* int32[2 * pairs]: entry e = {tile in A, tile in B}          */
     const uint16_t *c_row_mask;      /* uint16[c_tiles * 16] structural pattern of each output tile */
     const uint32_t *c_row_off;       /* uint32[c_tiles * 16] position of the tile's first entry in  */
                                      /* CSR row 16I+r, counted from the first entry of tile-row I   */

@@ -101,7 +101,7 @@ struct tsp_plan_s {
     int32_t *c_tile_row_ptr = nullptr;
     int32_t *c_tile_row = nullptr, *c_tile_col = nullptr;
     int64_t *pair_off = nullptr;
-    int32_t *pair_a = nullptr, *pair_b = nullptr;
+    int2 *pair_ab = nullptr;                 // task list: {tile of A, tile of B} per entry
     uint16_t *c_row_mask = nullptr;
     uint32_t *c_row_off = nullptr;
     int64_t *c_row_ptr = nullptr;

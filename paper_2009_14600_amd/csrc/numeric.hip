@@ -146,7 +146,7 @@ template <bool kNarrow, int kTilesPerWave, bool kMatrixCores, bool kWholeRows = 
 __global__ __launch_bounds__(kNumThreads) void k_numeric(
     const int64_t c_tiles, const int64_t c_nnz, const NumericSizes z, const int64_t c_rows, const int32_t c_tile_rows,
     const int32_t *__restrict__ c_tile_row_ptr, const int64_t *__restrict__ pair_off,
-    const int32_t *__restrict__ pair_a_, const int32_t *__restrict__ pair_b_, const uint2 *__restrict__ a_lhead_,
+    const int2 *__restrict__ pair_ab_, const uint2 *__restrict__ a_lhead_,
     const uint4 *__restrict__ a_ldata_, const uint2 *__restrict__ b_rhead_, const uint4 *__restrict__ b_rdata_, const int32_t *__restrict__ c_tile_row,
     const int32_t *__restrict__ c_tile_col, const uint16_t *__restrict__ c_row_mask,
     const uint32_t *__restrict__ c_row_off, const int64_t *__restrict__ c_row_ptr, int32_t *__restrict__ c_col,
@@ -191,7 +191,7 @@ __global__ __launch_bounds__(kNumThreads) void k_numeric(
     const uint32_t bit = 1u << hl, below = bit - 1u;
     const int j = lane & 15, tq = lane >> 4;
     // descriptors (used by the narrow kernels only)
-    const BufferArray pair_a(pair_a_, z.pairs * 4), pair_b(pair_b_, z.pairs * 4);
+    const BufferArray pair_ab(pair_ab_, z.pairs * 8);
     const BufferArray a_lhead(a_lhead_, z.a_tiles * 8), b_rhead(b_rhead_, z.b_tiles * 8);
     const BufferArray a_ldata(a_ldata_, z.a_groups * 16), b_rdata(b_rdata_, z.b_groups * 16);
     uint4 *const my_heads = lds_heads[wave_in_block];
@@ -218,14 +218,15 @@ __global__ __launch_bounds__(kNumThreads) void k_numeric(
             // lanes without an entry are switched off, not sent out of range: a gather costs by the
             // lanes that take part in it
             if (valid) {
-                const uint32_t e = (uint32_t)(base + start + lane) * 4u;
-                const uint2 la = a_lhead.u64(pair_a.u32(e) * 8u), rb = b_rhead.u64(pair_b.u32(e) * 8u);
+                const uint2 ab = pair_ab.u64((uint32_t)(base + start + lane) * 8u);
+                const uint2 la = a_lhead.u64(ab.x * 8u), rb = b_rhead.u64(ab.y * 8u);
                 // group offsets become byte offsets: the descriptors address bytes
                 record = make_uint4(la.x, la.y << 4, rb.x, rb.y << 4);
             }
         } else if (valid) {
             const int64_t e = base + start + lane;
-            const int64_t a = pair_a_[e], b = pair_b_[e];
+            const int2 ab = pair_ab_[e];
+            const int64_t a = ab.x, b = ab.y;
             const uint2 la = a_lhead_[a], rb = b_rhead_[b];
             record = make_uint4(la.x, la.y, rb.x, rb.y);
         }
@@ -530,7 +531,7 @@ int numeric_enqueue(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s
         const NumericSizes z{(uint64_t)P->pairs, (uint64_t)A->tile_capacity, (uint64_t)B->tile_capacity,
                              (uint64_t)A->group_capacity, (uint64_t)B->group_capacity};
         const uint64_t limit = (1ull << 32) - 64;
-        const bool narrow = z.pairs * 4 < limit && z.a_groups * 16 < limit && z.b_groups * 16 < limit &&
+        const bool narrow = z.pairs * 8 < limit && z.a_groups * 16 < limit && z.b_groups * 16 < limit &&
                             z.a_tiles * 8 < limit && z.b_tiles * 8 < limit && (uint64_t)P->c_tiles * T * 4 < limit &&
                             (uint64_t)P->c_nnz * 4 < limit && !ctx->force_wide;
         auto kernel = narrow ? (tiles_per_wave == 4 ? k_numeric<true, 4, true> : k_numeric<true, 8, true>)
@@ -542,7 +543,7 @@ int numeric_enqueue(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s
             kernel = narrow ? k_numeric<true, kRowTiles, true, true> : k_numeric<false, kRowTiles, true, true>;
         hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(kNumThreads), 0, s, P->c_tiles, P->c_nnz, z, P->c_rows,
                            (int32_t)P->c_tile_rows, P->c_tile_row_ptr, P->pair_off,
-                           P->pair_a, P->pair_b, A->lhead, A->ldata, B->rhead, B->rdata,
+                           P->pair_ab, A->lhead, A->ldata, B->rhead, B->rdata,
                            P->c_tile_row, P->c_tile_col, P->c_row_mask, P->c_row_off, P->c_row_ptr, col, val,
                            last_of_call && !ctx->compact ? ctx->d_scalars : nullptr,
                            strips ? P->strip_desc : nullptr, strips ? P->strip_block_ptr + P->strip_entries : nullptr,

@@ -734,7 +734,7 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_emit(
     const int32_t *__restrict__ row_jmin, const int32_t *__restrict__ row_words,
     const int32_t *__restrict__ c_tile_row_ptr, const int64_t *__restrict__ row_pair_ptr,
     int32_t *__restrict__ c_tile_row, int32_t *__restrict__ c_tile_col, int64_t *__restrict__ pair_off,
-    int32_t *__restrict__ pair_a, int32_t *__restrict__ pair_b, int32_t *cursor, int64_t A_capacity,
+    int2 *__restrict__ pair_ab, int32_t *cursor, int64_t A_capacity,
     const int32_t *__restrict__ order, const uint32_t *__restrict__ saved_bitmap,
     const uint32_t *__restrict__ saved_cnt, int saved_words, int64_t pairs) {
     extern __shared__ uint32_t lds_dyn[];
@@ -895,8 +895,7 @@ __global__ __launch_bounds__(kSymThreads) void k_sym_emit(
                     const int64_t pos = row_base + (int64_t)win_base + (int64_t)cnt[c] +
                                         __popc(contrib[c] & ((1u << (a - ch)) - 1u));
                     if ((uint64_t)pos < (uint64_t)pairs) {     // (always: the counts and the walks see the same survivors)
-                        pair_a[pos] = a;
-                        pair_b[pos] = b;
+                        pair_ab[pos] = make_int2(a, b);
                     }
                 }
             });
@@ -999,7 +998,7 @@ __global__ __launch_bounds__(kTeamLanes ? 64 : kSymThreads) void k_sym_emit_list
     const int32_t *__restrict__ row_jmin, const int32_t *__restrict__ row_words,
     const int32_t *__restrict__ c_tile_row_ptr, const int64_t *__restrict__ row_pair_ptr,
     int32_t *__restrict__ c_tile_row, int32_t *__restrict__ c_tile_col, int64_t *__restrict__ pair_off,
-    int32_t *__restrict__ pair_a, int32_t *__restrict__ pair_b, const uint16_t *__restrict__ a_row_mask,
+    int2 *__restrict__ pair_ab, const uint16_t *__restrict__ a_row_mask,
     const uint16_t *__restrict__ b_row_mask, uint16_t *__restrict__ c_row_mask, uint32_t *__restrict__ c_row_off,
     int32_t *__restrict__ row_nnz, int64_t c_rows, int64_t *d_scalars, uint32_t *__restrict__ tile_row_entries) {
     extern __shared__ uint32_t lds_dyn[];
@@ -1106,8 +1105,7 @@ __global__ __launch_bounds__(kTeamLanes ? 64 : kSymThreads) void k_sym_emit_list
             if (rel < 32u) {
                 const int c = list_c[k];
                 const int64_t pos = row_base + (int64_t)cnt[c] + __popc(contrib[c] & ((1u << rel) - 1u));
-                pair_a[pos] = list_a[k];
-                pair_b[pos] = list_b[k];
+                pair_ab[pos] = make_int2(list_a[k], list_b[k]);
             }
         }
         if (!one_chunk) {
@@ -1230,8 +1228,7 @@ __global__ __launch_bounds__(kTeamLanes ? 64 : kSymThreads) void k_sym_emit_list
 // one row, issued three times as many instructions per entry on tiles with two or three elements.
 constexpr int kMaskTiles = 16;         // C tiles per block (also the block of the order in strips)
 __global__ __launch_bounds__(256) void k_count_masks(int64_t c_tiles, const int64_t *__restrict__ pair_off,
-                                                     const int32_t *__restrict__ pair_a,
-                                                     const int32_t *__restrict__ pair_b,
+                                                     const int2 *__restrict__ pair_ab,
                                                      const uint16_t *__restrict__ a_row_mask,
                                                      const uint16_t *__restrict__ b_row_mask,
                                                      uint16_t *__restrict__ c_row_mask,
@@ -1265,7 +1262,8 @@ __global__ __launch_bounds__(256) void k_count_masks(int64_t c_tiles, const int6
 #pragma unroll
         for (int step = kMaskTiles / 2; step >= 1; step >>= 1)
             if (seg[t + step] <= e) t += step;
-        const int64_t a = pair_a[base + e], b = pair_b[base + e];
+        const int2 ab = pair_ab[base + e];
+        const int64_t a = ab.x, b = ab.y;
         const uint4 *ap = reinterpret_cast<const uint4 *>(a_row_mask + a * T);
         const uint4 *bp = reinterpret_cast<const uint4 *>(b_row_mask + b * T);
         const uint4 a0 = ap[0], a1 = ap[1], x = bp[0], y = bp[1];
@@ -1449,8 +1447,7 @@ void plan_release(tsp_context *ctx, tsp_plan_s *p, hipStream_t s) {
     ctx_free(ctx, p->c_tile_row, s);
     ctx_free(ctx, p->c_tile_col, s);
     ctx_free(ctx, p->pair_off, s);
-    ctx_free(ctx, p->pair_a, s);
-    ctx_free(ctx, p->pair_b, s);
+    ctx_free(ctx, p->pair_ab, s);
     ctx_free(ctx, p->c_row_mask, s);
     ctx_free(ctx, p->c_row_off, s);
     ctx_free(ctx, p->c_row_ptr, s);
@@ -1641,15 +1638,14 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
     P->c_tile_row = ctx_alloc_n<int32_t>(ctx, (size_t)P->c_tiles, s);
     P->c_tile_col = ctx_alloc_n<int32_t>(ctx, (size_t)P->c_tiles, s);
     P->pair_off = ctx_alloc_n<int64_t>(ctx, (size_t)P->c_tiles + 1, s);
-    P->pair_a = ctx_alloc_n<int32_t>(ctx, (size_t)P->pairs, s);
-    P->pair_b = ctx_alloc_n<int32_t>(ctx, (size_t)P->pairs, s);
+    P->pair_ab = ctx_alloc_n<int2>(ctx, (size_t)P->pairs, s);
     P->c_row_mask = ctx_alloc_n<uint16_t>(ctx, (size_t)P->c_tiles * T, s);
     P->c_row_off = ctx_alloc_n<uint32_t>(ctx, (size_t)P->c_tiles * T, s);
     // padded to whole tile-rows: the numeric pass reads the 16 row starts of a tile-row unconditionally
     P->c_row_ptr = ctx_alloc_n<int64_t>(ctx, (size_t)P->c_tile_rows * T + T + 1, s);
     row_nnz = ctx_alloc_n<int32_t>(ctx, (size_t)P->c_rows + 1, s);
     tile_row_entries = ctx_alloc_n<uint32_t>(ctx, (size_t)ntr + 4, s);     // read four at a time
-    if (!P->c_tile_row || !P->c_tile_col || !P->pair_off || !P->pair_a || !P->pair_b || !P->c_row_mask ||
+    if (!P->c_tile_row || !P->c_tile_col || !P->pair_off || !P->pair_ab || !P->c_row_mask ||
         !P->c_row_off || !P->c_row_ptr || !row_nnz || !tile_row_entries)
         return cleanup(TSP_ERR_ALLOC_FAILED);
 
@@ -1690,7 +1686,7 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
                                (size_t)team_words * (halves ? kTeamsPerWave : 1) * sizeof(uint32_t), s, ra, rb,
                                halves ? std::min(lanes, 8) : lanes, words_cap, window, list_cap, team_words, row_jmin,
                                row_words, P->c_tile_row_ptr,
-                               row_pair_ptr, P->c_tile_row, P->c_tile_col, P->pair_off, P->pair_a, P->pair_b,
+                               row_pair_ptr, P->c_tile_row, P->c_tile_col, P->pair_off, P->pair_ab,
                                A->row_mask, B->row_mask, P->c_row_mask, P->c_row_off, row_nnz, P->c_rows,
                                ctx->d_scalars, tile_row_entries);
         } else {
@@ -1711,7 +1707,7 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
             hipLaunchKernelGGL(long_rows ? k_sym_emit<true> : k_sym_emit<false>, dim3((unsigned)ntr), dim3(threads),
                                lds, s, ra, rb, lanes, words_cap, window, row_jmin, row_words,
                                P->c_tile_row_ptr,
-                               row_pair_ptr, P->c_tile_row, P->c_tile_col, P->pair_off, P->pair_a, P->pair_b, cursor,
+                               row_pair_ptr, P->c_tile_row, P->c_tile_col, P->pair_off, P->pair_ab, cursor,
                                A->tile_capacity, order, saved_bitmap, saved_cnt, saved_words, P->pairs);
         }
         SYM_CHECK(hipGetLastError());
@@ -1735,7 +1731,7 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
         const int xcd_chunk = skewed || P->strip_desc ? 8 : (int)std::max<int64_t>((blocks + 7) / 8, 1);
         const unsigned grid = (unsigned)xcd_chunked_grid(blocks, xcd_chunk);
         KernelTimer kt(ctx, TSP_KERNEL_COUNT_MASKS, s);
-        hipLaunchKernelGGL(k_count_masks, dim3(grid), dim3(256), 0, s, P->c_tiles, P->pair_off, P->pair_a, P->pair_b,
+        hipLaunchKernelGGL(k_count_masks, dim3(grid), dim3(256), 0, s, P->c_tiles, P->pair_off, P->pair_ab,
                            A->row_mask, B->row_mask, P->c_row_mask, P->strip_desc,
                            P->strip_desc ? P->strip_block_ptr + P->strip_entries : nullptr, xcd_chunk);
     }
@@ -1823,8 +1819,7 @@ extern "C" int tsp_plan_get_view(tsp_plan p, tsp_plan_view *v) {
     v->c_tile_row = p->c_tile_row;
     v->c_tile_col = p->c_tile_col;
     v->pair_off = p->pair_off;
-    v->pair_a = p->pair_a;
-    v->pair_b = p->pair_b;
+    v->pair_ab = reinterpret_cast<const int32_t *>(p->pair_ab);
     v->c_row_mask = p->c_row_mask;
     v->c_row_off = p->c_row_off;
     v->c_row_ptr = p->c_row_ptr;

@@ -79,7 +79,7 @@ class _PlanView(ctypes.Structure):
                 ("c_tiles", ctypes.c_int64), ("pairs", ctypes.c_int64), ("c_nnz", ctypes.c_int64),
                 ("candidate_pairs", ctypes.c_int64),
                 ("c_tile_row_ptr", ctypes.c_void_p), ("c_tile_row", ctypes.c_void_p), ("c_tile_col", ctypes.c_void_p),
-                ("pair_off", ctypes.c_void_p), ("pair_a", ctypes.c_void_p), ("pair_b", ctypes.c_void_p),
+                ("pair_off", ctypes.c_void_p), ("pair_ab", ctypes.c_void_p),
                 ("c_row_mask", ctypes.c_void_p), ("c_row_off", ctypes.c_void_p), ("c_row_ptr", ctypes.c_void_p)]
 
 
@@ -381,8 +381,8 @@ class Plan:
                     c_tile_row=h._view(v.c_tile_row, v.c_tiles, torch.int32),
                     c_tile_col=h._view(v.c_tile_col, v.c_tiles, torch.int32),
                     pair_off=h._view(v.pair_off, v.c_tiles + 1, torch.int64),
-                    pair_a=h._view(v.pair_a, v.pairs, torch.int32),
-                    pair_b=h._view(v.pair_b, v.pairs, torch.int32),
+                    pair_a=h._view(v.pair_ab, 2 * v.pairs, torch.int32)[0::2],
+                    pair_b=h._view(v.pair_ab, 2 * v.pairs, torch.int32)[1::2],
                     c_row_mask=h._view(v.c_row_mask, v.c_tiles * 16, torch.int16),
                     c_row_off=h._view(v.c_row_off, v.c_tiles * 16, torch.int32),
                     c_row_ptr=h._view(v.c_row_ptr, v.c_rows + 1, torch.int64))
