@@ -36,6 +36,8 @@
 namespace tsp {
 
 constexpr int kSymThreads = 256;
+constexpr int kSymThreadsLong = 512;   // block of the counting and task-list kernels on tile-rows with very many candidates
+constexpr int64_t kLongRowCandidates = 8192;    // ... that many per tile-row on average
 constexpr int kMaxWords = 4096;        // LDS bitmap words per tile-row: span of 131072 tile columns
 constexpr int kDirectWords = 1024;     // counting kernel: widest tile grid of B whose bitmap is indexed by the column itself
 constexpr int kWindow = 4096;          // C tiles of one tile-row handled per LDS window
@@ -230,7 +232,7 @@ __device__ __forceinline__ void for_each_survivor_below(const TileRefs &A, const
 // Pass 1 per tile-row: span of candidate tile columns, number of C tiles, of surviving pairs, of
 // candidates.  Dynamic LDS: max_words words.
 template <bool kLongRows>
-__global__ __launch_bounds__(kSymThreads) void k_sym_count(TileRefs A, TileRefs B, int lanes_per_a, int max_words,
+__global__ __launch_bounds__(kSymThreadsLong) void k_sym_count(TileRefs A, TileRefs B, int lanes_per_a, int max_words,
                                                            int direct_words, int only_marked,
                                                            int32_t *__restrict__ row_jmin,
                                                            int32_t *__restrict__ row_c_tiles,
@@ -729,7 +731,7 @@ __global__ __launch_bounds__(kOrderThreads) void k_work_order(int64_t ntr, const
 // several windows; `cursor` (one word per tile of A, nullptr when no tile-row needs it) carries their
 // places in B's tile-rows from window to window.
 template <bool kLongRows>
-__global__ __launch_bounds__(kSymThreads) void k_sym_emit(
+__global__ __launch_bounds__(kSymThreadsLong) void k_sym_emit(
     TileRefs A, TileRefs B, int lanes_per_a, int words_cap, int window,
     const int32_t *__restrict__ row_jmin, const int32_t *__restrict__ row_words,
     const int32_t *__restrict__ c_tile_row_ptr, const int64_t *__restrict__ row_pair_ptr,
@@ -1581,8 +1583,9 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
             if (!saved_bitmap || !saved_cnt) return cleanup(TSP_ERR_ALLOC_FAILED);
             count_lds = std::max(count_lds, (size_t)direct_words * 17 * sizeof(uint32_t));
             // (the counters take LDS, LDS decides how many blocks a CU holds, and the pass lives on waves in
-            // flight: larger blocks keep as many)
-            if (count_lds > 8 * 1024) threads = kSymThreads;
+            // flight: larger blocks keep as many; the heaviest tile-rows, one block each, decide when the launch
+            // ends: 128, 256, 512, 1024 threads: 76, 42, 29, 32 ms on an R-MAT graph of scale 18)
+            if (count_lds > 8 * 1024) threads = kSymThreadsLong;
         }
         if (halves && max_words > 1024) {
             hipLaunchKernelGGL(long_rows ? k_sym_count_segmented<true> : k_sym_count_segmented<false>,
@@ -1704,7 +1707,10 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
                 hipLaunchKernelGGL(k_work_order, dim3(grid), dim3(kOrderThreads), 0, s, ntr, row_cand, order_hist,
                                    order_hist + kOrderBuckets, order);
             }
-            hipLaunchKernelGGL(long_rows ? k_sym_emit<true> : k_sym_emit<false>, dim3((unsigned)ntr), dim3(threads),
+            // tile-rows with very many candidates: larger blocks (each tile-row is one block's work, and the
+            // longest ones end the launch; 256, 512, 768, 1024 threads: 69, 51, 54, 67 ms on the same graph)
+            const int ethreads = per_row >= kLongRowCandidates ? kSymThreadsLong : threads;
+            hipLaunchKernelGGL(long_rows ? k_sym_emit<true> : k_sym_emit<false>, dim3((unsigned)ntr), dim3(ethreads),
                                lds, s, ra, rb, lanes, words_cap, window, row_jmin, row_words,
                                P->c_tile_row_ptr,
                                row_pair_ptr, P->c_tile_row, P->c_tile_col, P->pair_off, P->pair_ab, cursor,

@@ -619,6 +619,27 @@ def test_tile_rows_taken_in_order_of_work(tsp, oracle):
         by_index.close()
 
 
+def test_tile_rows_with_very_many_candidates_take_larger_blocks(tsp, oracle):
+    """Nearly every tile-row of A meets every tile-row of B in full: about 127 x 127 candidate pairs per
+    tile-row, above the 8192 from which the general task-list kernel runs in blocks of 512 threads; so does the counting
+    kernel on the second call of the same product, when it keeps the bitmaps and the pairs per tile
+    column for the task-list kernel.  Both calls against the oracle."""
+    h = tsp.Handle(validate=True)
+    try:
+        A = inputs.random_sparse(2048, 2048, 0.02, 4711, values="smallint")
+        print(f"very many candidates: 2048^2, nnz {A.nnz}", flush=True)
+        dA = tsp.to_device(A)
+        ref = oracle.spgemm(A, A, threads=4)
+        for call in (1, 2):
+            C = h.spgemm(dA, dA)
+            st = h.stats()
+            assert st["candidate_pairs"] >= 8192 * 128, st["candidate_pairs"]
+            assert_matches_oracle(C, ref, f"dense tile grid, call {call}")
+            C.free()
+    finally:
+        h.close()
+
+
 # ------------------------------------------------------------------ output tiles taken in vertical strips
 def test_output_tiles_taken_in_vertical_strips(tsp, oracle):
     """The counting and the multiplication kernel with their workgroups taking the output tiles strip by
