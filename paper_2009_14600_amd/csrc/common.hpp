@@ -60,6 +60,8 @@ struct tsp_context {
     int compact = 0;                               // 1: tsp_spgemm removes zero-valued entries from C
     bool hint_general = false;                     // the last product took the general task-list kernel ...
     int64_t hint_sizes[4] = {-1, -1, -1, -1};      // ... with these rows and nnz of A and of B
+    int32_t *hint_order = nullptr;                 // ... and took its tile-rows in this order (heaviest first), or null
+    int64_t hint_order_rows = 0;
     int last_hip = 0;
     tsp_stats stats{};
     void *chain_slots = nullptr;                   // device, for the chained scans (chain.hpp)

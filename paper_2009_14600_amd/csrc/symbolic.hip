@@ -241,12 +241,13 @@ __global__ __launch_bounds__(kSymThreadsLong) void k_sym_count(TileRefs A, TileR
                                                            int32_t *__restrict__ row_cand,
                                                            int64_t *__restrict__ d_scalars,
                                                            uint32_t *__restrict__ save_bitmap,
-                                                           uint32_t *__restrict__ save_cnt) {
+                                                           uint32_t *__restrict__ save_cnt,
+                                                           const int32_t *__restrict__ order) {
     extern __shared__ uint32_t lds_dyn[];
     __shared__ uint32_t red[32];
     __shared__ int s_jmin, s_jmax;
     uint32_t *bm = lds_dyn;
-    const int I = blockIdx.x;
+    const int I = order ? order[blockIdx.x] : (int)blockIdx.x;
     // second launch after k_sym_count_segmented: only the tile-rows that kernel has left to this one
     if (only_marked && row_words[I] != kRowLeftOver) return;
     const int a0 = A.trp[I], a1 = A.tend[I];
@@ -1502,7 +1503,7 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
         ctx_free(ctx, row_words, s);
         ctx_free(ctx, row_cand, s);
         ctx_free(ctx, cursor, s);
-        ctx_free(ctx, order, s);
+        if (order != ctx->hint_order) ctx_free(ctx, order, s);
         ctx_free(ctx, order_hist, s);
         ctx_free(ctx, row_nnz, s);
         ctx_free(ctx, tile_row_entries, s);
@@ -1593,7 +1594,8 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
                                row_jmin, row_c_tiles, row_pairs, row_words, row_cand, ctx->d_scalars);
             hipLaunchKernelGGL(long_rows ? k_sym_count<true> : k_sym_count<false>, dim3((unsigned)ntr), dim3(threads),
                                max_words * sizeof(uint32_t), s, ra, rb, lanes, max_words, 0, /*only_marked=*/1,
-                               row_jmin, row_c_tiles, row_pairs, row_words, row_cand, ctx->d_scalars, nullptr, nullptr);
+                               row_jmin, row_c_tiles, row_pairs, row_words, row_cand, ctx->d_scalars, nullptr, nullptr,
+                               nullptr);
         } else if (halves)
             hipLaunchKernelGGL(long_rows ? k_sym_count_half<true> : k_sym_count_half<false>,
                                dim3((unsigned)((ntr + 1) / 2)), dim3(64), 2 * max_words * sizeof(uint32_t), s, ra, rb,
@@ -1603,7 +1605,8 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
             hipLaunchKernelGGL(long_rows ? k_sym_count<true> : k_sym_count<false>, dim3((unsigned)ntr), dim3(threads),
                                count_lds, s, ra, rb, lanes, max_words, direct_words,
                                /*only_marked=*/0, row_jmin, row_c_tiles, row_pairs, row_words, row_cand, ctx->d_scalars,
-                               saved_bitmap, saved_cnt);
+                               saved_bitmap, saved_cnt,
+                               general_expected && ctx->hint_order_rows == ntr ? ctx->hint_order : nullptr);
         SYM_CHECK(hipGetLastError());
     }
     {
@@ -1671,6 +1674,10 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
         const int threads = per_row <= 256 ? 64 : per_row <= 512 ? 128 : kSymThreads;
         listed = h[S_MAX_ROW_PAIRS] <= kListCap && h[S_MAX_ROW_C_TILES] <= kListTiles;
         ctx->hint_general = !listed;
+        // (the order of the previous product goes; the general branch below may keep a new one)
+        ctx_free(ctx, ctx->hint_order, s);
+        ctx->hint_order = nullptr;
+        ctx->hint_order_rows = 0;
         ctx->hint_sizes[0] = A->rows;
         ctx->hint_sizes[1] = A->nnz;
         ctx->hint_sizes[2] = B->rows;
@@ -1706,6 +1713,10 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
                 hipLaunchKernelGGL(k_work_hist, dim3(grid), dim3(kOrderThreads), 0, s, ntr, row_cand, order_hist);
                 hipLaunchKernelGGL(k_work_order, dim3(grid), dim3(kOrderThreads), 0, s, ntr, row_cand, order_hist,
                                    order_hist + kOrderBuckets, order);
+                // the handle keeps the order: the counting kernel of the next call of this product starts with
+                // the heaviest tile-rows too
+                ctx->hint_order = order;
+                ctx->hint_order_rows = ntr;
             }
             // tile-rows with very many candidates: larger blocks (each tile-row is one block's work, and the
             // longest ones end the launch; 256, 512, 768, 1024 threads: 69, 51, 54, 67 ms on the same graph)

@@ -597,6 +597,12 @@ def test_tile_rows_taken_in_order_of_work(tsp, oracle):
         C2 = by_index.spgemm(dG, dG)
         for x, y in zip(C1.to_host(), C2.to_host()):
             assert np.array_equal(x, y)
+        # the same product again: the counting kernel now takes the tile-rows in the order the handle has kept
+        # from the first call, and keeps bitmaps and pair counts for the task-list kernel
+        C3 = ordered.spgemm(dG, dG)
+        for x, y in zip(C1.to_host(), C3.to_host()):
+            assert np.array_equal(x, y)
+        C3.free()
         assert_matches_oracle(C1, oracle.spgemm(G, G, threads=4), "R-MAT, heaviest tile-rows first")
         C1.free()
         C2.free()
