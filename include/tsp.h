@@ -318,6 +318,24 @@ int tsp_plan_get_view(tsp_plan plan, tsp_plan_view *view);
  */
 int tsp_numeric(tsp_handle handle, tsp_tiles A, tsp_tiles B, tsp_plan plan, tsp_csr *C, void *stream);
 
+/*
+ * C = A*B by the pipeline as the paper lays it out, at a tile edge of 8 (the paper's, Section 2.1.2),
+ * 16 or 32: tiles in the packed bitmap format (2 bytes per element, row masks, an element pointer per
+ * tile); the task list by expansion of all tile pairs with a matching inner tile index, cull of the
+ * pairs whose boolean tile product is empty, a stable library sort by output tile and a run-length
+ * pass (Section 4.1, Algorithm 1); the counting pass on the bitmaps (Section 4.2); the multiplication
+ * pass with the packed elements of every pair placed by the bitmap into dense tiles in LDS and
+ * multiplied on the matrix cores, one wave per output tile (Section 4.3); the output tiles written
+ * to CSR.  Same inputs, conventions, output format and ownership as tsp_spgemm, and the same result:
+ * the structural pattern exactly, the values up to the order of the fp32 additions.  It exists to show
+ * that the result does not depend on the tile edge and to measure the paper's design against this
+ * library's; it is not tuned, validates its inputs always, and synchronises the stream about ten
+ * times.  tile_edge other than 8, 16, 32: TSP_ERR_INVALID_ARG; more than 2^31 - 2 candidate tile pairs:
+ * TSP_ERR_UNSUPPORTED.  tsp_stats reports the tile and pair counts at that tile edge and, with the
+ * timers on, the four phases.
+ */
+int tsp_spgemm_paper(tsp_handle handle, int tile_edge, const tsp_csr *A, const tsp_csr *B, tsp_csr *C, void *stream);
+
 int tsp_get_stats(tsp_handle handle, tsp_stats *out);
 const char *tsp_strerror(int status);
 int tsp_last_hip_error(tsp_handle handle);   /* hipError_t of the last TSP_ERR_HIP on this handle */

@@ -11,7 +11,8 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libtsp.so")
-SOURCES = ["context.hip", "scan.hip", "convert.hip", "symbolic.hip", "numeric.hip", "compact.hip", "strips.hip", "spgemm.hip"]
+SOURCES = ["context.hip", "scan.hip", "convert.hip", "symbolic.hip", "numeric.hip", "compact.hip", "strips.hip", "spgemm.hip",
+           "paper_path.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          # MFMA accumulators in ordinary vector registers: the kernels hold few of them, and the copies to and

@@ -27,7 +27,8 @@ KERNELS = ("convert", "sym_count", "scan_sym", "sym_emit", "count_masks", "row_o
 EXPORTS = [
     "tsp_create", "tsp_destroy", "tsp_set_option", "tsp_trim", "tsp_spgemm", "tsp_csr_free",
     "tsp_convert", "tsp_tiles_free", "tsp_tiles_get_view", "tsp_symbolic", "tsp_plan_free",
-    "tsp_plan_get_view", "tsp_numeric", "tsp_compact_zeros", "tsp_compact_zeros_static", "tsp_get_stats", "tsp_strerror",
+    "tsp_plan_get_view", "tsp_numeric", "tsp_compact_zeros", "tsp_compact_zeros_static", "tsp_spgemm_paper",
+    "tsp_get_stats", "tsp_strerror",
     "tsp_last_hip_error",
 ]
 
@@ -115,6 +116,7 @@ def load_library():
     lib.tsp_numeric.argtypes = [vp, vp, vp, vp, P(_Csr), vp]
     lib.tsp_compact_zeros.argtypes = [vp, P(_Csr), P(_Csr), vp]
     lib.tsp_compact_zeros_static.argtypes = [vp, P(_Csr), P(_Csr), vp]
+    lib.tsp_spgemm_paper.argtypes = [vp, ci, P(_Csr), P(_Csr), P(_Csr), vp]
     lib.tsp_get_stats.argtypes = [vp, P(_Stats)]
     lib.tsp_strerror.argtypes = [ci]
     lib.tsp_strerror.restype = ctypes.c_char_p
@@ -274,6 +276,15 @@ class Handle:
         sb = sa if B is A else B._struct()
         out = _Csr()
         _check(self._lib.tsp_spgemm(self._h, ctypes.byref(sa), ctypes.byref(sb), ctypes.byref(out), self._stream()))
+        return self._wrap_output(out)
+
+    def spgemm_paper(self, A: DeviceCSR, B: DeviceCSR, tile_edge: int) -> DeviceCSR:
+        """C = A*B by the paper's own pipeline at a tile edge of 8, 16 or 32 (tsp_spgemm_paper)."""
+        sa = A._struct()
+        sb = sa if B is A else B._struct()
+        out = _Csr()
+        _check(self._lib.tsp_spgemm_paper(self._h, int(tile_edge), ctypes.byref(sa), ctypes.byref(sb),
+                                          ctypes.byref(out), self._stream()))
         return self._wrap_output(out)
 
     def compact_zeros(self, C: DeviceCSR) -> DeviceCSR:
