@@ -248,6 +248,50 @@ def oracle_leg(A, handle, tsp, sA, budget_products, seconds):
     return out
 
 
+PAPER_PIPELINE_MAX_PAIRS = 200_000_000     # larger task lists: its sorted candidate arrays take tens of GB and seconds
+
+
+def paper_pipeline_leg(handle, tsp, torch, dA, own_ms):
+    """The same product by the paper's own pipeline (tsp_spgemm_paper: packed bitmap tiles, task list by
+    expansion and a library sort, elements placed by bitmap into dense LDS tiles) at tile edges 8, 16 and 32:
+    time per call with its host waits, device time per phase, tile and task-list counts at that edge, and
+    whether the pattern equals the library's."""
+    own = handle.spgemm(dA, dA)
+    legs = []
+    for T in (8, 16, 32):
+        leg = {"tile_edge": T}
+        try:
+            C = handle.spgemm_paper(dA, dA, T)                 # sizes the workspace
+        except tsp.TspError as e:
+            leg["status"] = str(e)
+            legs.append(leg)
+            continue
+        leg["pattern_equal_to_library"] = bool(C.nnz == own.nnz and torch.equal(C.row_ptr, own.row_ptr)
+                                               and torch.equal(C.col_idx[:C.nnz], own.col_idx[:own.nnz]))
+        C.free()
+        handle.set_option(tsp.OPT_PHASE_TIMERS, 1)
+        reps = 3
+        phases = {k: 0.0 for k in tsp.PHASES}
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            C = handle.spgemm_paper(dA, dA, T)
+            st = handle.stats()
+            for k in phases:
+                phases[k] += st["phase_us"][k]
+            C.free()
+        torch.cuda.synchronize()
+        ms = 1e3 * (time.perf_counter() - t0) / reps
+        handle.set_option(tsp.OPT_PHASE_TIMERS, 0)
+        leg.update({"ms_per_call": round(ms, 4), "times_the_library": round(ms / own_ms, 1),
+                    "phase_us": {k: round(v / reps, 1) for k, v in phases.items()},
+                    "a_tiles": st["a_tiles"], "candidate_pairs": st["candidate_pairs"], "pairs": st["pairs"],
+                    "c_tiles": st["c_tiles"]})
+        legs.append(leg)
+    own.free()
+    return legs
+
+
 def run_workload(index, steps, warmup, args, tsp, inputs, torch, headline):
     A = inputs.config(index)
     products = int(np.diff(A.row_ptr).astype(np.int64)[A.col_idx].sum())
@@ -412,6 +456,8 @@ def run_workload(index, steps, warmup, args, tsp, inputs, torch, headline):
         "phase_us": {k: round(v, 2) for k, v in pavg.items()},
         "device_us_per_step_with_timers": round(total_us / tsteps, 2),
     }
+    if not args.no_paper_pipeline and st["pairs"] <= PAPER_PIPELINE_MAX_PAIRS:
+        res["paper_pipeline"] = paper_pipeline_leg(handle, tsp, torch, dA, ms_per_step)
     if not args.no_cpu_baseline:
         leg = oracle_leg(A, handle, tsp, sA, 4e8 if headline else 2e7, 10.0 if headline else 0.0)
         res["accuracy_vs_oracle_sample"] = leg["accuracy"]
@@ -431,6 +477,8 @@ def main():
     ap.add_argument("--workload", type=int, default=4, help="headline benchmark configuration 1..5 (see inputs.CONFIG_NAMES)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-per-workload", action="store_true", help="measure the headline workload only")
+    ap.add_argument("--no-paper-pipeline", action="store_true",
+                    help="skip the comparison runs of the paper's own pipeline at tile edges 8, 16, 32")
     ap.add_argument("--no-validate", action="store_true", help="switch the input validation kernel off")
     ap.add_argument("--no-matrix-cores", action="store_true",
                     help="block products on the vector ALUs instead of MFMA (the paper's nonTCU comparison)")
@@ -479,7 +527,7 @@ def main():
         "accuracy_vs_oracle_sample": head.get("accuracy_vs_oracle_sample"),
         "cpu_baseline": head.get("cpu_baseline"),
         "per_workload": [{k: r[k] for k in ("workload", "value", "ms_per_step", "steps", "roofline", "mfma", "end_to_end",
-                                            "phase_hbm", "kernel_us", "accuracy_vs_oracle_sample") if k in r}
+                                            "phase_hbm", "kernel_us", "accuracy_vs_oracle_sample", "paper_pipeline") if k in r}
                          for r in per],
     }
     print(json.dumps(line))
