@@ -50,40 +50,40 @@ CSRC = os.path.join(ROOT, "paper_2009_14600_amd", "csrc")
 # profiles/hbm_traffic_all_kernels.txt holds the readings and the commands.
 #   (workload, kernel): (source file, sha256[:12] at the time, FETCH_SIZE, WRITE_SIZE)
 MEASURED_TRAFFIC = {
-    (1, "convert"): ("convert.hip", "67ac7a722d7c", 201.5, 782.7),
-    (1, "count_masks"): ("symbolic.hip", "51eb043cd082", 733.8, 128.0),
-    (1, "numeric"): ("numeric.hip", "6b6705052cf3", 1235.4, 499.0),
-    (1, "row_offsets"): ("symbolic.hip", "51eb043cd082", 85.6, 262.0),
-    (1, "scan_rows"): ("symbolic.hip", "51eb043cd082", 6.6, 8.3),
-    (1, "scan_sym"): ("symbolic.hip", "51eb043cd082", 7.6, 1.3),
-    (1, "sym_count"): ("symbolic.hip", "51eb043cd082", 186.2, 10.0),
-    (1, "sym_emit"): ("symbolic.hip", "51eb043cd082", 203.6, 480.5),
-    (2, "convert"): ("convert.hip", "67ac7a722d7c", 6113.2, 43264.5),
-    (2, "numeric"): ("numeric.hip", "6b6705052cf3", 30665.5, 26555.0),
-    (2, "scan_rows"): ("symbolic.hip", "51eb043cd082", 790.4, 2048.5),
-    (2, "scan_sym"): ("symbolic.hip", "51eb043cd082", 258.2, 202.8),
-    (2, "sym_count"): ("symbolic.hip", "51eb043cd082", 6150.6, 1280.0),
-    (2, "sym_emit"): ("symbolic.hip", "51eb043cd082", 11417.9, 24759.9),
-    (3, "convert"): ("convert.hip", "67ac7a722d7c", 82439.0, 294449.4),
-    (3, "numeric"): ("numeric.hip", "6b6705052cf3", 341065.1, 1194632.8),
-    (3, "scan_rows"): ("symbolic.hip", "51eb043cd082", 994.4, 2592.3),
-    (3, "scan_sym"): ("symbolic.hip", "51eb043cd082", 313.8, 277.3),
-    (3, "sym_count"): ("symbolic.hip", "51eb043cd082", 22539.9, 3240.8),
-    (3, "sym_emit"): ("symbolic.hip", "51eb043cd082", 71403.4, 266653.0),
-    (4, "convert"): ("convert.hip", "67ac7a722d7c", 39008.7, 473531.7),
-    (4, "count_masks"): ("symbolic.hip", "51eb043cd082", 109948435.3, 4612574.6),
-    (4, "numeric"): ("numeric.hip", "6b6705052cf3", 273842076.6, 33484917.5),
-    (4, "row_offsets"): ("symbolic.hip", "51eb043cd082", 4624662.4, 9236302.0),
-    (4, "scan_rows"): ("symbolic.hip", "51eb043cd082", 790.6, 2048.8),
-    (4, "scan_sym"): ("symbolic.hip", "51eb043cd082", 258.3, 208.0),
-    (4, "sym_count"): ("symbolic.hip", "51eb043cd082", 16083649.6, 509124.8),
-    (4, "sym_emit"): ("symbolic.hip", "51eb043cd082", 56968421.2, 141168795.2),
-    (5, "convert"): ("convert.hip", "67ac7a722d7c", 14192.9, 50023.2),
-    (5, "numeric"): ("numeric.hip", "6b6705052cf3", 53939.2, 269665.9),
-    (5, "scan_rows"): ("symbolic.hip", "51eb043cd082", 406.4, 1024.3),
-    (5, "scan_sym"): ("symbolic.hip", "51eb043cd082", 155.3, 99.1),
-    (5, "sym_count"): ("symbolic.hip", "51eb043cd082", 4847.6, 1280.0),
-    (5, "sym_emit"): ("symbolic.hip", "51eb043cd082", 8705.2, 16309.8),
+    (1, "convert"): ("convert.hip", "67ac7a722d7c", 201.7, 782.7),
+    (1, "count_masks"): ("symbolic.hip", "aa30e2987bc5", 732.9, 128.0),
+    (1, "numeric"): ("numeric.hip", "15aefc848925", 1244.5, 499.0),
+    (1, "row_offsets"): ("symbolic.hip", "aa30e2987bc5", 85.6, 262.0),
+    (1, "scan_rows"): ("symbolic.hip", "aa30e2987bc5", 6.6, 8.3),
+    (1, "scan_sym"): ("symbolic.hip", "aa30e2987bc5", 7.6, 1.3),
+    (1, "sym_count"): ("symbolic.hip", "aa30e2987bc5", 186.7, 10.0),
+    (1, "sym_emit"): ("symbolic.hip", "aa30e2987bc5", 203.6, 478.3),
+    (2, "convert"): ("convert.hip", "67ac7a722d7c", 6120.0, 43311.2),
+    (2, "numeric"): ("numeric.hip", "15aefc848925", 30661.6, 26554.7),
+    (2, "scan_rows"): ("symbolic.hip", "aa30e2987bc5", 790.4, 2048.4),
+    (2, "scan_sym"): ("symbolic.hip", "aa30e2987bc5", 258.9, 211.9),
+    (2, "sym_count"): ("symbolic.hip", "aa30e2987bc5", 6150.6, 1280.0),
+    (2, "sym_emit"): ("symbolic.hip", "aa30e2987bc5", 11417.8, 24504.0),
+    (3, "convert"): ("convert.hip", "67ac7a722d7c", 82441.0, 294210.2),
+    (3, "numeric"): ("numeric.hip", "15aefc848925", 340037.1, 1195656.2),
+    (3, "scan_rows"): ("symbolic.hip", "aa30e2987bc5", 994.4, 2592.3),
+    (3, "scan_sym"): ("symbolic.hip", "aa30e2987bc5", 313.8, 279.8),
+    (3, "sym_count"): ("symbolic.hip", "aa30e2987bc5", 22565.5, 3240.5),
+    (3, "sym_emit"): ("symbolic.hip", "aa30e2987bc5", 71376.8, 266006.1),
+    (4, "convert"): ("convert.hip", "67ac7a722d7c", 38858.1, 473093.4),
+    (4, "count_masks"): ("symbolic.hip", "aa30e2987bc5", 109477505.5, 4612574.6),
+    (4, "numeric"): ("numeric.hip", "15aefc848925", 271515994.9, 33495551.0),
+    (4, "row_offsets"): ("symbolic.hip", "aa30e2987bc5", 4624662.3, 9236325.7),
+    (4, "scan_rows"): ("symbolic.hip", "aa30e2987bc5", 790.6, 2048.6),
+    (4, "scan_sym"): ("symbolic.hip", "aa30e2987bc5", 258.8, 203.1),
+    (4, "sym_count"): ("symbolic.hip", "aa30e2987bc5", 15444644.2, 508994.0),
+    (4, "sym_emit"): ("symbolic.hip", "aa30e2987bc5", 50865372.3, 70878492.5),
+    (5, "convert"): ("convert.hip", "67ac7a722d7c", 14193.0, 50444.3),
+    (5, "numeric"): ("numeric.hip", "15aefc848925", 53916.1, 269856.9),
+    (5, "scan_rows"): ("symbolic.hip", "aa30e2987bc5", 406.4, 1024.5),
+    (5, "scan_sym"): ("symbolic.hip", "aa30e2987bc5", 155.8, 99.4),
+    (5, "sym_count"): ("symbolic.hip", "aa30e2987bc5", 4858.1, 1280.0),
+    (5, "sym_emit"): ("symbolic.hip", "aa30e2987bc5", 8704.2, 16309.9),
 }
 
 KERNEL_SOURCE = {"convert": "convert.hip", "sym_count": "symbolic.hip", "scan_sym": "symbolic.hip",
