@@ -1673,6 +1673,25 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
         // (the fused counting pass of the list kernel wants more lanes than the enumeration does)
         const int threads = per_row <= 256 ? 64 : per_row <= 512 ? 128 : kSymThreads;
         listed = h[S_MAX_ROW_PAIRS] <= kListCap && h[S_MAX_ROW_C_TILES] <= kListTiles;
+        // LDS of the list kernel per tile-row: bitmap and its prefix, per-tile words of the window, the list, and
+        // the row masks of the window when it also runs the counting pass.  A launch may ask for 64 KB: a product
+        // against a very wide B (a bitmap of thousands of words) takes one tile-row per block instead of two
+        // per wave, and the general kernel when even that does not fit.
+        constexpr size_t kLdsLimit = 64 * 1024;
+        constexpr int kTeamsPerWave = 64 / kListTeamLanes;
+        const int list_cap = (int)std::max<int64_t>(h[S_MAX_ROW_PAIRS], 1);
+        int team_words = 0;
+        bool halves = false;
+        if (listed) {
+            fused_masks = ntr >= 1024;
+            team_words = 2 * words_cap + 2 * window + 3 * list_cap + (fused_masks ? 8 * window : 0);
+            // tile-rows with few candidates: two per wave (see k_sym_count_half)
+            halves = fused_masks && threads == 64 && (size_t)team_words * kTeamsPerWave * sizeof(uint32_t) <= kLdsLimit;
+            if ((size_t)team_words * sizeof(uint32_t) > kLdsLimit) {
+                listed = false;
+                fused_masks = false;
+            }
+        }
         ctx->hint_general = !listed;
         // (the order of the previous product goes; the general branch below may keep a new one)
         ctx_free(ctx, ctx->hint_order, s);
@@ -1683,16 +1702,11 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
         ctx->hint_sizes[2] = B->rows;
         ctx->hint_sizes[3] = B->nnz;
         if (listed) {
-            const int list_cap = (int)std::max<int64_t>(h[S_MAX_ROW_PAIRS], 1);
-            fused_masks = ntr >= 1024;
-            const int team_words = 2 * words_cap + 2 * window + 3 * list_cap + (fused_masks ? 8 * window : 0);
-            // tile-rows with few candidates: two per wave (see k_sym_count_half)
-            const bool halves = fused_masks && threads == 64;
             auto kernel = !fused_masks ? (long_rows ? k_sym_emit_listed<true, false, 0> : k_sym_emit_listed<false, false, 0>)
                           : halves     ? (long_rows ? k_sym_emit_listed<true, true, kListTeamLanes> : k_sym_emit_listed<false, true, kListTeamLanes>)
                                        : (long_rows ? k_sym_emit_listed<true, true, 0> : k_sym_emit_listed<false, true, 0>);
-            constexpr int kTeamsPerWave = 64 / kListTeamLanes;
-            hipLaunchKernelGGL(kernel, dim3((unsigned)(halves ? (ntr + kTeamsPerWave - 1) / kTeamsPerWave : ntr)), dim3(threads),
+            hipLaunchKernelGGL(kernel, dim3((unsigned)(halves ? (ntr + kTeamsPerWave - 1) / kTeamsPerWave : ntr)),
+                               dim3(halves ? 64 : fused_masks ? std::max(threads, 128) : threads),
                                (size_t)team_words * (halves ? kTeamsPerWave : 1) * sizeof(uint32_t), s, ra, rb,
                                halves ? std::min(lanes, 8) : lanes, words_cap, window, list_cap, team_words, row_jmin,
                                row_words, P->c_tile_row_ptr,

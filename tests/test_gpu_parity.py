@@ -580,6 +580,23 @@ def test_short_tile_rows_against_a_very_wide_operand(tsp, handle, oracle):
     assert nnz > A.nnz
 
 
+def test_many_short_tile_rows_whose_candidates_span_two_million_columns(tsp, handle, oracle):
+    """More than 1024 tile-rows of A with a few dozen candidate pairs each (the task-list kernel that also
+    runs the counting pass, two tile-rows per wave), against a B whose entries sit at both ends of two
+    million columns: the bitmap of a tile-row takes nearly 4096 words, two of them no longer fit the
+    64 KB of LDS a launch may ask for, and the kernel takes one tile-row per block instead."""
+    rng = np.random.default_rng(99)
+    M, K, N = 16 * 1025, 200, 2_000_000
+    A = inputs.from_coo(M, K, np.arange(M), rng.integers(0, K, M), rng.uniform(-1, 1, M), "one entry per row")
+    k = np.arange(K)
+    brow = np.concatenate([k, k])
+    bcol = np.concatenate([rng.integers(0, 300, K), N - 1 - rng.integers(0, 300, K)])
+    B = inputs.from_coo(K, N, brow, bcol, rng.uniform(-1, 1, 2 * K), "both ends of two million columns")
+    print(f"wide bitmaps: A {A.rows}x{A.cols} nnz {A.nnz}, B nnz {B.nnz}", flush=True)
+    nnz, _ = run_and_check(tsp, handle, oracle, A, B)
+    assert nnz == 2 * M
+
+
 # ------------------------------------------------------------------ heaviest tile-rows first
 def test_tile_rows_taken_in_order_of_work(tsp, oracle):
     """The general task-list kernel with its blocks taking the tile-rows heaviest first (forced here; on
