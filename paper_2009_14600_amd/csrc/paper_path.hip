@@ -414,9 +414,8 @@ static int sort_pairs(tsp_context *ctx, Scope &sc, const uint64_t *key_in, uint6
 
 // The operand in the form the kernels read, checked.
 static int load_operand(tsp_context *ctx, Scope &sc, const tsp_csr *M, Csr *out, int64_t *d_flag, hipStream_t s) {
-    if (M->rows < 0 || M->cols < 0 || M->nnz < 0 || M->rows >= INT32_MAX - 16 || M->cols >= INT32_MAX - 16 ||
-        M->nnz >= INT32_MAX)
-        return TSP_ERR_INVALID_ARG;
+    if (M->rows < 0 || M->cols < 0 || M->nnz < 0) return TSP_ERR_INVALID_ARG;
+    if (M->rows >= INT32_MAX - 16 || M->cols >= INT32_MAX - 16 || M->nnz >= INT32_MAX) return TSP_ERR_INDEX_OVERFLOW;
     if (!M->row_ptr || (M->nnz > 0 && (!M->col_idx || !M->val))) return TSP_ERR_INVALID_ARG;
     if (M->nnz > 0 && (M->rows == 0 || M->cols == 0)) return TSP_ERR_NOT_CANONICAL;
     if (M->row_ptr_type != TSP_I32 && M->row_ptr_type != TSP_I64) return TSP_ERR_INVALID_ARG;

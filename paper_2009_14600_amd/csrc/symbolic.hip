@@ -247,7 +247,8 @@ __global__ __launch_bounds__(kSymThreadsLong) void k_sym_count(TileRefs A, TileR
     __shared__ uint32_t red[32];
     __shared__ int s_jmin, s_jmax;
     uint32_t *bm = lds_dyn;
-    const int I = order ? order[blockIdx.x] : (int)blockIdx.x;
+    // block b takes tile-row b, or the tile-row the kept order of work puts in place b
+    const int I = order ? min(max(order[blockIdx.x], 0), (int)gridDim.x - 1) : (int)blockIdx.x;
     // second launch after k_sym_count_segmented: only the tile-rows that kernel has left to this one
     if (only_marked && row_words[I] != kRowLeftOver) return;
     const int a0 = A.trp[I], a1 = A.tend[I];

@@ -51,22 +51,30 @@ class _FailingHandle:
         self.lib.tsp_destroy(self.h)
 
 
-@pytest.mark.parametrize("maker", [
-    lambda: inputs.config(2, small=True),        # list kernel, whole-tile-row multiplication kernel
-    lambda: inputs.config(4, small=True),        # general task-list kernel, separate counting kernel
+@pytest.mark.parametrize("maker,tile_edge", [
+    (lambda: inputs.config(2, small=True), 0),   # list kernel, whole-tile-row multiplication kernel
+    (lambda: inputs.config(4, small=True), 0),   # general task-list kernel, separate counting kernel
+    (lambda: inputs.config(1, small=True), 8),   # the paper's pipeline (tsp_spgemm_paper) at two tile edges
+    (lambda: inputs.config(5, small=True), 32),
 ])
-def test_allocator_returning_null_at_every_call_site(tsp, maker):
-    """tsp_spgemm with an allocator that runs dry after k calls, for every k up to the number of calls a
-    successful product makes: status -4 (TSP_ERR_ALLOC_FAILED), *C zeroed, nothing leaked (after
-    tsp_trim the handle holds no byte and the allocator has every block back), and the handle works again
-    once memory is there."""
+def test_allocator_returning_null_at_every_call_site(tsp, maker, tile_edge):
+    """tsp_spgemm (tile_edge 0) or tsp_spgemm_paper with an allocator that runs dry after k calls, for every k
+    up to the number of calls a successful product makes: status -4 (TSP_ERR_ALLOC_FAILED), *C zeroed, nothing
+    leaked (after tsp_trim the handle holds no byte and the allocator has every block back), and the handle
+    works again once memory is there."""
     import torch
     A = maker()
     dA = tsp.to_device(A)
     sA = dA._struct()
+
+    def multiply(handle, out):
+        if tile_edge:
+            return handle.lib.tsp_spgemm_paper(handle.h, tile_edge, ctypes.byref(sA), ctypes.byref(sA), ctypes.byref(out), None)
+        return handle.lib.tsp_spgemm(handle.h, ctypes.byref(sA), ctypes.byref(sA), ctypes.byref(out), None)
+
     ok = _FailingHandle(tsp, fail_from=1 << 30)
     out = tsp._Csr()
-    assert ok.lib.tsp_spgemm(ok.h, ctypes.byref(sA), ctypes.byref(sA), ctypes.byref(out), None) == 0
+    assert multiply(ok, out) == 0
     torch.cuda.synchronize()
     want_nnz, calls = out.nnz, ok.calls
     # what a handle keeps for its whole life (the slots of its chained prefix sums), to tell it from a leak
@@ -80,7 +88,7 @@ def test_allocator_returning_null_at_every_call_site(tsp, maker):
     for k in range(calls):
         h = _FailingHandle(tsp, fail_from=k)
         out = tsp._Csr(7, 7, 7, 1, 1, 1, 1, 1)
-        status = h.lib.tsp_spgemm(h.h, ctypes.byref(sA), ctypes.byref(sA), ctypes.byref(out), None)
+        status = multiply(h, out)
         torch.cuda.synchronize()
         assert status == -4, (k, status)
         assert (out.rows, out.cols, out.nnz, out.row_ptr, out.col_idx, out.val) == (0, 0, 0, None, None, None), k
@@ -91,7 +99,7 @@ def test_allocator_returning_null_at_every_call_site(tsp, maker):
         # memory comes back: the same handle multiplies
         h.calls = -(1 << 30)
         out = tsp._Csr()
-        assert h.lib.tsp_spgemm(h.h, ctypes.byref(sA), ctypes.byref(sA), ctypes.byref(out), None) == 0
+        assert multiply(h, out) == 0
         torch.cuda.synchronize()
         assert out.nnz == want_nnz
         assert h.lib.tsp_csr_free(h.h, ctypes.byref(out), None) == 0
