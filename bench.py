@@ -50,40 +50,40 @@ CSRC = os.path.join(ROOT, "paper_2009_14600_amd", "csrc")
 # profiles/hbm_traffic_all_kernels.txt holds the readings and the commands.
 #   (workload, kernel): (source file, sha256[:12] at the time, FETCH_SIZE, WRITE_SIZE)
 MEASURED_TRAFFIC = {
-    (1, "convert"): ("convert.hip", "67ac7a722d7c", 201.7, 782.7),
-    (1, "count_masks"): ("symbolic.hip", "aa30e2987bc5", 732.9, 128.0),
-    (1, "numeric"): ("numeric.hip", "15aefc848925", 1244.5, 499.0),
-    (1, "row_offsets"): ("symbolic.hip", "aa30e2987bc5", 85.6, 262.0),
-    (1, "scan_rows"): ("symbolic.hip", "aa30e2987bc5", 6.6, 8.3),
-    (1, "scan_sym"): ("symbolic.hip", "aa30e2987bc5", 7.6, 1.3),
-    (1, "sym_count"): ("symbolic.hip", "aa30e2987bc5", 186.7, 10.0),
-    (1, "sym_emit"): ("symbolic.hip", "aa30e2987bc5", 203.6, 478.3),
-    (2, "convert"): ("convert.hip", "67ac7a722d7c", 6120.0, 43311.2),
-    (2, "numeric"): ("numeric.hip", "15aefc848925", 30661.6, 26554.7),
-    (2, "scan_rows"): ("symbolic.hip", "aa30e2987bc5", 790.4, 2048.4),
-    (2, "scan_sym"): ("symbolic.hip", "aa30e2987bc5", 258.9, 211.9),
-    (2, "sym_count"): ("symbolic.hip", "aa30e2987bc5", 6150.6, 1280.0),
-    (2, "sym_emit"): ("symbolic.hip", "aa30e2987bc5", 11417.8, 24504.0),
-    (3, "convert"): ("convert.hip", "67ac7a722d7c", 82441.0, 294210.2),
-    (3, "numeric"): ("numeric.hip", "15aefc848925", 340037.1, 1195656.2),
-    (3, "scan_rows"): ("symbolic.hip", "aa30e2987bc5", 994.4, 2592.3),
-    (3, "scan_sym"): ("symbolic.hip", "aa30e2987bc5", 313.8, 279.8),
-    (3, "sym_count"): ("symbolic.hip", "aa30e2987bc5", 22565.5, 3240.5),
-    (3, "sym_emit"): ("symbolic.hip", "aa30e2987bc5", 71376.8, 266006.1),
-    (4, "convert"): ("convert.hip", "67ac7a722d7c", 38858.1, 473093.4),
-    (4, "count_masks"): ("symbolic.hip", "aa30e2987bc5", 109477505.5, 4612574.6),
-    (4, "numeric"): ("numeric.hip", "15aefc848925", 271515994.9, 33495551.0),
-    (4, "row_offsets"): ("symbolic.hip", "aa30e2987bc5", 4624662.3, 9236325.7),
-    (4, "scan_rows"): ("symbolic.hip", "aa30e2987bc5", 790.6, 2048.6),
-    (4, "scan_sym"): ("symbolic.hip", "aa30e2987bc5", 258.8, 203.1),
-    (4, "sym_count"): ("symbolic.hip", "aa30e2987bc5", 15444644.2, 508994.0),
-    (4, "sym_emit"): ("symbolic.hip", "aa30e2987bc5", 50865372.3, 70878492.5),
-    (5, "convert"): ("convert.hip", "67ac7a722d7c", 14193.0, 50444.3),
-    (5, "numeric"): ("numeric.hip", "15aefc848925", 53916.1, 269856.9),
-    (5, "scan_rows"): ("symbolic.hip", "aa30e2987bc5", 406.4, 1024.5),
-    (5, "scan_sym"): ("symbolic.hip", "aa30e2987bc5", 155.8, 99.4),
-    (5, "sym_count"): ("symbolic.hip", "aa30e2987bc5", 4858.1, 1280.0),
-    (5, "sym_emit"): ("symbolic.hip", "aa30e2987bc5", 8704.2, 16309.9),
+    (1, "convert"): ("convert.hip", "67ac7a722d7c", 201.8, 782.7),
+    (1, "count_masks"): ("symbolic.hip", "d8cb24430ff8", 732.9, 128.0),
+    (1, "numeric"): ("numeric.hip", "15aefc848925", 1244.7, 499.0),
+    (1, "row_offsets"): ("symbolic.hip", "d8cb24430ff8", 85.6, 262.0),
+    (1, "scan_rows"): ("symbolic.hip", "d8cb24430ff8", 6.6, 8.3),
+    (1, "scan_sym"): ("symbolic.hip", "d8cb24430ff8", 7.6, 1.3),
+    (1, "sym_count"): ("symbolic.hip", "d8cb24430ff8", 187.4, 10.0),
+    (1, "sym_emit"): ("symbolic.hip", "d8cb24430ff8", 203.6, 478.3),
+    (2, "convert"): ("convert.hip", "67ac7a722d7c", 6119.4, 43244.3),
+    (2, "numeric"): ("numeric.hip", "15aefc848925", 30671.0, 26555.8),
+    (2, "scan_rows"): ("symbolic.hip", "d8cb24430ff8", 790.4, 2048.9),
+    (2, "scan_sym"): ("symbolic.hip", "d8cb24430ff8", 259.0, 207.8),
+    (2, "sym_count"): ("symbolic.hip", "d8cb24430ff8", 6150.6, 1280.0),
+    (2, "sym_emit"): ("symbolic.hip", "d8cb24430ff8", 11417.9, 24504.0),
+    (3, "convert"): ("convert.hip", "67ac7a722d7c", 82441.0, 294594.2),
+    (3, "numeric"): ("numeric.hip", "15aefc848925", 340006.2, 1194350.5),
+    (3, "scan_rows"): ("symbolic.hip", "d8cb24430ff8", 994.4, 2592.3),
+    (3, "scan_sym"): ("symbolic.hip", "d8cb24430ff8", 314.2, 280.4),
+    (3, "sym_count"): ("symbolic.hip", "d8cb24430ff8", 22555.5, 3241.0),
+    (3, "sym_emit"): ("symbolic.hip", "d8cb24430ff8", 71408.0, 266006.0),
+    (4, "convert"): ("convert.hip", "67ac7a722d7c", 38697.9, 473165.3),
+    (4, "count_masks"): ("symbolic.hip", "d8cb24430ff8", 109456017.0, 4612574.6),
+    (4, "numeric"): ("numeric.hip", "15aefc848925", 271474004.8, 33489491.4),
+    (4, "row_offsets"): ("symbolic.hip", "d8cb24430ff8", 4624660.8, 9236342.3),
+    (4, "scan_rows"): ("symbolic.hip", "d8cb24430ff8", 790.6, 2049.0),
+    (4, "scan_sym"): ("symbolic.hip", "d8cb24430ff8", 258.4, 198.5),
+    (4, "sym_count"): ("symbolic.hip", "d8cb24430ff8", 15350547.8, 508993.5),
+    (4, "sym_emit"): ("symbolic.hip", "d8cb24430ff8", 50927702.6, 70867743.0),
+    (5, "convert"): ("convert.hip", "67ac7a722d7c", 14192.8, 50073.2),
+    (5, "numeric"): ("numeric.hip", "15aefc848925", 53983.3, 270289.6),
+    (5, "scan_rows"): ("symbolic.hip", "d8cb24430ff8", 406.4, 1024.3),
+    (5, "scan_sym"): ("symbolic.hip", "d8cb24430ff8", 155.7, 100.2),
+    (5, "sym_count"): ("symbolic.hip", "d8cb24430ff8", 4857.6, 1280.0),
+    (5, "sym_emit"): ("symbolic.hip", "d8cb24430ff8", 8705.1, 16309.8),
 }
 
 KERNEL_SOURCE = {"convert": "convert.hip", "sym_count": "symbolic.hip", "scan_sym": "symbolic.hip",
