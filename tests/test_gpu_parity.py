@@ -772,6 +772,54 @@ def test_seeded_sweep_of_small_products(tsp, handle, oracle):
         run_and_check(tsp, handle, oracle, A, B, **upload)
 
 
+def test_seeded_sweep_with_hub_rows_wide_outputs_and_repeated_calls(tsp, oracle):
+    """Forty-eight products of four kinds (square with hub rows and a dense tile grid, which take the general
+    task-list kernel; a few rows times a very wide B, whose tile-rows of C pass the symbolic window; tall and
+    thin; small and ragged), each multiplied twice on one handle: the second call of a product takes what the
+    handle has kept from the first (bitmaps and pair counts from the counting kernel, the order of work)."""
+    def make(rng, M, K, d, hubs, name):
+        mask = rng.random((M, K)) < d
+        for _ in range(hubs):
+            mask[rng.integers(0, M)] |= rng.random(K) < min(1.0, 40 * d + 0.2)
+        r, c = np.nonzero(mask)
+        v = rng.integers(1, 4, r.size).astype(np.float64) if rng.random() < 0.5 else rng.uniform(-1, 1, r.size)
+        return inputs.from_coo(M, K, r, c, v, name)
+
+    h = tsp.Handle(validate=True)
+    try:
+        for case in range(48):
+            rng = np.random.default_rng(31_000 + case)
+            kind = case % 4
+            if kind == 0:
+                M = K = N = int(rng.integers(200, 2500))
+                da = db = float(10 ** rng.uniform(-2.5, -1.2))
+                hubs = int(rng.integers(0, 6))
+            elif kind == 1:
+                M, K, N = int(rng.integers(1, 300)), int(rng.integers(16, 1500)), int(rng.integers(20000, 90000))
+                da, db = float(10 ** rng.uniform(-1.5, -0.3)), float(10 ** rng.uniform(-3.2, -2.0))
+                hubs = int(rng.integers(0, 3))
+            elif kind == 2:
+                M, K, N = int(rng.integers(1000, 20000)), int(rng.integers(1, 200)), int(rng.integers(1, 400))
+                da, db = float(10 ** rng.uniform(-2.5, -1)), float(10 ** rng.uniform(-2, -0.5))
+                hubs = int(rng.integers(0, 3))
+            else:
+                M, K, N = (int(x) for x in rng.integers(1, 200, 3))
+                da = db = float(10 ** rng.uniform(-2, -0.2))
+                hubs = 0
+            A = make(rng, M, K, da, hubs, f"A{case}")
+            B = A if (kind == 0 and rng.random() < 0.5) else make(rng, K, N, db, hubs, f"B{case}")
+            print(f"sweep {case} kind {kind}: {M}x{K}x{B.cols} nnz {A.nnz}, {B.nnz}", flush=True)
+            ref = oracle.spgemm(A, B, threads=4)
+            dA = tsp.to_device(A)
+            dB = dA if B is A else tsp.to_device(B)
+            for call in (1, 2):
+                C = h.spgemm(dA, dB)
+                assert_matches_oracle(C, ref, f"sweep {case}, call {call}")
+                C.free()
+    finally:
+        h.close()
+
+
 def test_mesh_with_dense_rows(tsp, handle, oracle):
     """A few full rows in an otherwise short-rowed matrix (a constraint row in a mesh problem): their
     tile-rows have far more tiles than a window of the converter and of the task-list kernel holds and go
