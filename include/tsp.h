@@ -107,6 +107,12 @@ enum {
     TSP_OPT_COUNT_PRODUCTS = 10, /* 1: tsp_spgemm also counts the intermediate products (one small    */
                                /*    kernel over the entries of A) and reports them in tsp_stats;    */
                                /*    0 (default): tsp_stats.products = -1                            */
+    TSP_OPT_WORKSPACE_CANARIES = 11, /* 1: every block the handle takes from the allocator from now on (workspace */
+                               /*    and outputs) carries a guard zone of 256 bytes in front of and behind the */
+                               /*    part in use, filled with a pattern when the block is handed out and       */
+                               /*    compared when it is released; tsp_stats.workspace_violations counts the   */
+                               /*    words found changed: a kernel wrote outside its array.  A debugging aid:  */
+                               /*    two small launches per block.  0 (default): none                          */
     TSP_OPT_STRIP_ORDER = 8    /* order in which the counting and the multiplication kernel (4.2,   */
                                /*    4.3) take the output tiles: 1: in vertical strips of tile      */
                                /*    columns sized so that the tiles of B a strip meets stay in the  */
@@ -165,6 +171,9 @@ typedef struct {
     float a_tile_fill;               /* NNZ(A) / tiles(A): entries per 16x16 tile                      */
     int32_t in_paper_regime;         /* 1: NNZ(A) > 300000 and a_mean_row > 42                         */
     int32_t well_filled_tiles;       /* 1: a_tile_fill >= 20                                           */
+    int64_t workspace_violations;    /* words of guard zones found changed since tsp_create             */
+                                     /* (TSP_OPT_WORKSPACE_CANARIES; blocks still in use are not yet     */
+                                     /* compared: free the outputs first)                                */
 } tsp_stats;
 
 /* Create a handle on the current HIP device.  allocator == NULL selects hipMalloc/hipFree. */

@@ -39,6 +39,12 @@ struct Block {
     void *ptr;
     size_t bytes;
 };
+struct LiveBlock {           // a block handed out: with canaries the caller's part starts one guard zone into it
+    void *base;
+    size_t bytes;            // of the whole block
+    size_t user_bytes;       // of the caller's part (a multiple of 256)
+    bool guarded;
+};
 
 }  // namespace tsp
 
@@ -47,7 +53,9 @@ struct tsp_context {
     bool user_allocator = false;
     int device = 0;
     std::vector<tsp::Block> cache;                 // free blocks, reusable
-    std::unordered_map<void *, size_t> live;       // blocks handed out
+    std::unordered_map<void *, tsp::LiveBlock> live;   // blocks handed out, by the pointer the caller got
+    int canaries = 0;                              // TSP_OPT_WORKSPACE_CANARIES
+    bool canaries_used = false;                    // ... has been on at some time: the counter is worth reading
     int64_t held_bytes = 0, peak_bytes = 0;
     int validate = 1;
     int timers = 0;

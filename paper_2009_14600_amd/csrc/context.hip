@@ -25,10 +25,27 @@ int hip_fail(tsp_context *ctx, hipError_t e) {
     return TSP_ERR_HIP;
 }
 
+// Canaries (TSP_OPT_WORKSPACE_CANARIES): every block gets a guard zone of kGuardBytes in front of the caller's
+// part and one behind it, filled with a pattern when the block is handed out and compared when it comes back;
+// words that changed are counted in the slot behind the handle's scalar block.
+constexpr size_t kGuardBytes = 256;
+constexpr uint32_t kGuardWord = 0xA5C3965Au;
+__global__ void k_guard_fill(uint32_t *front, uint32_t *back) {
+    front[threadIdx.x] = kGuardWord;
+    back[threadIdx.x] = kGuardWord;
+}
+__global__ void k_guard_check(const uint32_t *front, const uint32_t *back, unsigned long long *violations) {
+    const unsigned bad = (front[threadIdx.x] != kGuardWord) + (back[threadIdx.x] != kGuardWord);
+    if (bad) atomicAdd(violations, (unsigned long long)bad);
+}
+
 // Best fit from the cache; a cached block is taken only if it wastes at most half of itself.
 void *ctx_alloc(tsp_context *ctx, size_t bytes, hipStream_t s) {
     bytes = (bytes + 255) & ~size_t(255);
     if (bytes == 0) bytes = 256;
+    const size_t user_bytes = bytes;
+    const bool guarded = ctx->canaries != 0;
+    if (guarded) bytes += 2 * kGuardBytes;
     int best = -1;
     for (int i = 0; i < (int)ctx->cache.size(); ++i) {
         size_t b = ctx->cache[i].bytes;
@@ -57,15 +74,26 @@ void *ctx_alloc(tsp_context *ctx, size_t bytes, hipStream_t s) {
         ctx->held_bytes += (int64_t)got;
         ctx->peak_bytes = std::max(ctx->peak_bytes, ctx->held_bytes);
     }
-    ctx->live.emplace(p, got);
-    return p;
+    void *user = p;
+    if (guarded) {
+        user = static_cast<char *>(p) + kGuardBytes;
+        hipLaunchKernelGGL(k_guard_fill, dim3(1), dim3(kGuardBytes / 4), 0, s, static_cast<uint32_t *>(p),
+                           reinterpret_cast<uint32_t *>(static_cast<char *>(user) + user_bytes));
+    }
+    ctx->live.emplace(user, LiveBlock{p, got, user_bytes, guarded});
+    return user;
 }
 
-void ctx_free(tsp_context *ctx, void *p, hipStream_t) {
+void ctx_free(tsp_context *ctx, void *p, hipStream_t s) {
     if (!p) return;
     auto it = ctx->live.find(p);
     if (it == ctx->live.end()) return;   // not ours: ignore
-    ctx->cache.push_back({p, it->second});
+    const LiveBlock b = it->second;
+    if (b.guarded)
+        hipLaunchKernelGGL(k_guard_check, dim3(1), dim3(kGuardBytes / 4), 0, s, static_cast<const uint32_t *>(b.base),
+                           reinterpret_cast<const uint32_t *>(static_cast<char *>(p) + b.user_bytes),
+                           reinterpret_cast<unsigned long long *>(ctx->d_scalars + kScalars));
+    ctx->cache.push_back({b.base, b.bytes});
     ctx->live.erase(it);
 }
 
@@ -205,7 +233,9 @@ extern "C" int tsp_create(tsp_handle *handle, const tsp_allocator *allocator) {
         ctx->allocator = {default_alloc, default_free, nullptr};
     }
     hipError_t e = hipGetDevice(&ctx->device);
-    if (e == hipSuccess) e = hipMalloc((void **)&ctx->d_scalars, sizeof(int64_t) * kScalars);
+    // (one slot behind the scalar block counts the words of guard zones found changed; no kernel clears it)
+    if (e == hipSuccess) e = hipMalloc((void **)&ctx->d_scalars, sizeof(int64_t) * (kScalars + 1));
+    if (e == hipSuccess) e = hipMemset(ctx->d_scalars, 0, sizeof(int64_t) * (kScalars + 1));
     if (e == hipSuccess) e = hipHostMalloc((void **)&ctx->h_scalars, sizeof(int64_t) * kScalars,
                                              hipHostMallocCoherent | hipHostMallocMapped);   // polled: fine-grained whatever the environment says
     if (e == hipSuccess) e = hipHostGetDevicePointer((void **)&ctx->h_scalars_dev, ctx->h_scalars, 0);
@@ -231,7 +261,7 @@ extern "C" int tsp_destroy(tsp_handle ctx) {
     if (!ctx) return TSP_ERR_INVALID_ARG;
     (void)hipDeviceSynchronize();
     for (auto &b : ctx->cache) ctx->allocator.free(ctx->allocator.user, b.ptr, nullptr);
-    for (auto &kv : ctx->live) ctx->allocator.free(ctx->allocator.user, kv.first, nullptr);
+    for (auto &kv : ctx->live) ctx->allocator.free(ctx->allocator.user, kv.second.base, nullptr);
     if (ctx->ev_created)
     {
         for (auto &e : ctx->ev) (void)hipEventDestroy(e);
@@ -256,6 +286,10 @@ extern "C" int tsp_set_option(tsp_handle ctx, int key, int64_t value) {
             ctx->work_order = (int)value;
             return TSP_OK;
         case TSP_OPT_COUNT_PRODUCTS: ctx->count_products = value != 0; return TSP_OK;
+        case TSP_OPT_WORKSPACE_CANARIES:
+            ctx->canaries = value != 0;
+            ctx->canaries_used = ctx->canaries_used || value != 0;
+            return TSP_OK;
         case TSP_OPT_STRIP_ORDER:
             if (value < 0 || (value > 2 && value < 16) || value > (1 << 30)) return TSP_ERR_INVALID_ARG;
             ctx->strip_order = (int)value;
@@ -283,6 +317,10 @@ extern "C" int tsp_get_stats(tsp_handle ctx, tsp_stats *out) {
     if (!ctx || !out) return TSP_ERR_INVALID_ARG;
     ctx->stats.workspace_bytes = ctx->held_bytes;
     ctx->stats.workspace_peak_bytes = ctx->peak_bytes;
+    int64_t changed = 0;
+    if (ctx->canaries_used)                                // (a blocking copy: the checks enqueued so far have run)
+        TSP_HIP_CHECK(ctx, hipMemcpy(&changed, ctx->d_scalars + kScalars, sizeof(int64_t), hipMemcpyDeviceToHost));
+    ctx->stats.workspace_violations = changed;
     *out = ctx->stats;
     return TSP_OK;
 }

@@ -21,6 +21,7 @@ OPT_VALIDATE, OPT_PHASE_TIMERS, OPT_WIDE_INDEX, OPT_NUMERIC_RUN, OPT_MATRIX_CORE
 OPT_WORK_ORDER = 7
 OPT_STRIP_ORDER = 8
 OPT_COUNT_PRODUCTS = 10
+OPT_WORKSPACE_CANARIES = 11
 PHASES = ("convert", "symbolic", "count", "numeric")
 KERNELS = ("convert", "sym_count", "scan_sym", "sym_emit", "count_masks", "row_offsets", "scan_rows", "numeric")
 
@@ -60,7 +61,8 @@ class _Stats(ctypes.Structure):
                 ("phase_us", ctypes.c_float * 4), ("total_us", ctypes.c_float),
                 ("kernel_us", ctypes.c_float * len(KERNELS)),
                 ("products", ctypes.c_int64), ("a_mean_row", ctypes.c_float), ("a_tile_fill", ctypes.c_float),
-                ("in_paper_regime", ctypes.c_int32), ("well_filled_tiles", ctypes.c_int32)]
+                ("in_paper_regime", ctypes.c_int32), ("well_filled_tiles", ctypes.c_int32),
+                ("workspace_violations", ctypes.c_int64)]
 
 
 class _TilesView(ctypes.Structure):
