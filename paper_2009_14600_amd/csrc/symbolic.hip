@@ -1230,7 +1230,8 @@ __global__ __launch_bounds__(kTeamLanes ? 64 : kSymThreads) void k_sym_emit_list
 // them into the bitmap of the entry's C tile, which the block keeps in LDS.  With a lane per entry no
 // lane idles on a short segment or on an empty row of a sparse A tile: 16 lanes per C tile, each owning
 // one row, issued three times as many instructions per entry on tiles with two or three elements.
-constexpr int kMaskTiles = 16;         // C tiles per block (also the block of the order in strips)
+constexpr int kMaskTilesStrips = 16;   // C tiles per block with the order in strips (a descriptor names 16 tiles)
+template <int kMaskTiles>
 __global__ __launch_bounds__(256) void k_count_masks(int64_t c_tiles, const int64_t *__restrict__ pair_off,
                                                      const int2 *__restrict__ pair_ab,
                                                      const uint16_t *__restrict__ a_row_mask,
@@ -1258,7 +1259,7 @@ __global__ __launch_bounds__(256) void k_count_masks(int64_t c_tiles, const int6
         const int64_t off = pair_off[c_first + min((int)threadIdx.x, tiles)] - base;
         seg[threadIdx.x] = (uint32_t)min(max(off, (int64_t)0), (int64_t)0x7FFFFFFF);
     }
-    if (threadIdx.x < kMaskTiles * 8) cmask[threadIdx.x >> 3][threadIdx.x & 7] = 0;
+    for (int w = threadIdx.x; w < kMaskTiles * 8; w += 256) cmask[w >> 3][w & 7] = 0;
     __syncthreads();
     const uint32_t total = seg[kMaskTiles];
     for (uint32_t e = threadIdx.x; e < total; e += 256) {
@@ -1284,8 +1285,9 @@ __global__ __launch_bounds__(256) void k_count_masks(int64_t c_tiles, const int6
         }
     }
     __syncthreads();
-    const int t = threadIdx.x >> 4, r = threadIdx.x & 15;
-    if (t < tiles) c_row_mask[(c_first + t) * T + r] = (uint16_t)((cmask[t][r >> 1] >> ((r & 1) * 16)) & 0xFFFFu);
+    const int r = threadIdx.x & 15;
+    for (int t = threadIdx.x >> 4; t < tiles; t += 16)
+        c_row_mask[(c_first + t) * T + r] = (uint16_t)((cmask[t][r >> 1] >> ((r & 1) * 16)) & 0xFFFFu);
 }
 
 // row_ptr of C from the row lengths: block b takes rows [2048 b, 2048 b + 2048), starts from the
@@ -1756,14 +1758,18 @@ int symbolic_run(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s **
         if (rc) return cleanup(rc);
     }
     if (P->c_tiles > 0 && !fused_masks) {       // (otherwise the list kernel has done the counting pass already)
-        int64_t blocks = (P->c_tiles * 16 + 255) / 256;
+        // output tiles per workgroup: 64 where that still gives every CU dozens of workgroups (16, 32, 64 tiles:
+        // 37.9, 35.2, 34.9 ms on an R-MAT graph of scale 18: fewer segment bounds and bitmaps to set up per entry)
+        const int mask_tiles = P->strip_desc ? kMaskTilesStrips : P->c_tiles >= 64 * 8192 ? 64 : 16;
+        int64_t blocks = (P->c_tiles + mask_tiles - 1) / mask_tiles;
         if (P->strip_desc) blocks = P->strip_capacity;                             // (an upper bound of the workgroups)
         // (short runs of blocks dealt to the XCDs in turn where the work is skewed: see numeric_enqueue)
         const bool skewed = P->max_row_pairs > 8 * (P->pairs / std::max<int64_t>(ntr, 1) + 1);
         const int xcd_chunk = skewed || P->strip_desc ? 8 : (int)std::max<int64_t>((blocks + 7) / 8, 1);
         const unsigned grid = (unsigned)xcd_chunked_grid(blocks, xcd_chunk);
         KernelTimer kt(ctx, TSP_KERNEL_COUNT_MASKS, s);
-        hipLaunchKernelGGL(k_count_masks, dim3(grid), dim3(256), 0, s, P->c_tiles, P->pair_off, P->pair_ab,
+        hipLaunchKernelGGL(mask_tiles == 64 ? k_count_masks<64> : k_count_masks<16>,
+                           dim3(grid), dim3(256), 0, s, P->c_tiles, P->pair_off, P->pair_ab,
                            A->row_mask, B->row_mask, P->c_row_mask, P->strip_desc,
                            P->strip_desc ? P->strip_block_ptr + P->strip_entries : nullptr, xcd_chunk);
     }
