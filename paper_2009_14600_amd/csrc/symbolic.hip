@@ -1407,6 +1407,7 @@ __global__ __launch_bounds__(256) void k_row_offsets_wide(int64_t c_rows, const 
     const int64_t stretch = (c1 - c0 + kGroups - 1) / kGroups;
     const int64_t cb = min(c1, c0 + g * stretch), ce = min(c1, cb + stretch);
     uint32_t part = 0;
+#pragma unroll 8
     for (int64_t c = cb; c < ce; ++c) part += __popc(c_row_mask[c * T + r]);
     s_part[g][r] = part;
     __syncthreads();
@@ -1432,7 +1433,19 @@ __global__ __launch_bounds__(256) void k_row_offsets_wide(int64_t c_rows, const 
         }
     }
     uint32_t run = (uint32_t)(before - total) + earlier;
-    for (int64_t c = cb; c < ce; ++c) {
+    // (eight masks requested together: the loop is a chain of loads otherwise)
+    int64_t c = cb;
+    for (; c + 8 <= ce; c += 8) {
+        uint32_t m[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) m[u] = c_row_mask[(c + u) * T + r];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            c_row_off[(c + u) * T + r] = run;
+            run += __popc(m[u]);
+        }
+    }
+    for (; c < ce; ++c) {
         c_row_off[c * T + r] = run;
         run += __popc(c_row_mask[c * T + r]);
     }
