@@ -50,40 +50,40 @@ CSRC = os.path.join(ROOT, "paper_2009_14600_amd", "csrc")
 # profiles/hbm_traffic_all_kernels.txt holds the readings and the commands.
 #   (workload, kernel): (source file, sha256[:12] at the time, FETCH_SIZE, WRITE_SIZE)
 MEASURED_TRAFFIC = {
-    (1, "convert"): ("convert.hip", "67ac7a722d7c", 201.8, 782.7),
-    (1, "count_masks"): ("symbolic.hip", "d8cb24430ff8", 732.9, 128.0),
-    (1, "numeric"): ("numeric.hip", "15aefc848925", 1244.7, 499.0),
-    (1, "row_offsets"): ("symbolic.hip", "d8cb24430ff8", 85.6, 262.0),
-    (1, "scan_rows"): ("symbolic.hip", "d8cb24430ff8", 6.6, 8.3),
-    (1, "scan_sym"): ("symbolic.hip", "d8cb24430ff8", 7.6, 1.3),
-    (1, "sym_count"): ("symbolic.hip", "d8cb24430ff8", 187.4, 10.0),
-    (1, "sym_emit"): ("symbolic.hip", "d8cb24430ff8", 203.6, 478.3),
-    (2, "convert"): ("convert.hip", "67ac7a722d7c", 6119.4, 43244.3),
-    (2, "numeric"): ("numeric.hip", "15aefc848925", 30671.0, 26555.8),
-    (2, "scan_rows"): ("symbolic.hip", "d8cb24430ff8", 790.4, 2048.9),
-    (2, "scan_sym"): ("symbolic.hip", "d8cb24430ff8", 259.0, 207.8),
-    (2, "sym_count"): ("symbolic.hip", "d8cb24430ff8", 6150.6, 1280.0),
-    (2, "sym_emit"): ("symbolic.hip", "d8cb24430ff8", 11417.9, 24504.0),
-    (3, "convert"): ("convert.hip", "67ac7a722d7c", 82441.0, 294594.2),
-    (3, "numeric"): ("numeric.hip", "15aefc848925", 340006.2, 1194350.5),
-    (3, "scan_rows"): ("symbolic.hip", "d8cb24430ff8", 994.4, 2592.3),
-    (3, "scan_sym"): ("symbolic.hip", "d8cb24430ff8", 314.2, 280.4),
-    (3, "sym_count"): ("symbolic.hip", "d8cb24430ff8", 22555.5, 3241.0),
-    (3, "sym_emit"): ("symbolic.hip", "d8cb24430ff8", 71408.0, 266006.0),
-    (4, "convert"): ("convert.hip", "67ac7a722d7c", 38697.9, 473165.3),
-    (4, "count_masks"): ("symbolic.hip", "d8cb24430ff8", 109456017.0, 4612574.6),
-    (4, "numeric"): ("numeric.hip", "15aefc848925", 271474004.8, 33489491.4),
-    (4, "row_offsets"): ("symbolic.hip", "d8cb24430ff8", 4624660.8, 9236342.3),
-    (4, "scan_rows"): ("symbolic.hip", "d8cb24430ff8", 790.6, 2049.0),
-    (4, "scan_sym"): ("symbolic.hip", "d8cb24430ff8", 258.4, 198.5),
-    (4, "sym_count"): ("symbolic.hip", "d8cb24430ff8", 15350547.8, 508993.5),
-    (4, "sym_emit"): ("symbolic.hip", "d8cb24430ff8", 50927702.6, 70867743.0),
-    (5, "convert"): ("convert.hip", "67ac7a722d7c", 14192.8, 50073.2),
-    (5, "numeric"): ("numeric.hip", "15aefc848925", 53983.3, 270289.6),
-    (5, "scan_rows"): ("symbolic.hip", "d8cb24430ff8", 406.4, 1024.3),
-    (5, "scan_sym"): ("symbolic.hip", "d8cb24430ff8", 155.7, 100.2),
-    (5, "sym_count"): ("symbolic.hip", "d8cb24430ff8", 4857.6, 1280.0),
-    (5, "sym_emit"): ("symbolic.hip", "d8cb24430ff8", 8705.1, 16309.8),
+    (1, "convert"): ("convert.hip", "67ac7a722d7c", 201.7, 782.7),
+    (1, "count_masks"): ("symbolic.hip", "65d32d837ef3", 733.5, 128.0),
+    (1, "numeric"): ("numeric.hip", "15aefc848925", 1244.5, 499.0),
+    (1, "row_offsets"): ("symbolic.hip", "65d32d837ef3", 91.1, 262.0),
+    (1, "scan_rows"): ("symbolic.hip", "65d32d837ef3", 6.4, 8.3),
+    (1, "scan_sym"): ("symbolic.hip", "65d32d837ef3", 7.2, 1.3),
+    (1, "sym_count"): ("symbolic.hip", "65d32d837ef3", 190.2, 10.0),
+    (1, "sym_emit"): ("symbolic.hip", "65d32d837ef3", 203.6, 478.3),
+    (2, "convert"): ("convert.hip", "67ac7a722d7c", 6119.8, 43225.2),
+    (2, "numeric"): ("numeric.hip", "15aefc848925", 30667.7, 26555.3),
+    (2, "scan_rows"): ("symbolic.hip", "65d32d837ef3", 790.2, 2048.3),
+    (2, "scan_sym"): ("symbolic.hip", "65d32d837ef3", 256.3, 201.6),
+    (2, "sym_count"): ("symbolic.hip", "65d32d837ef3", 6153.1, 1280.0),
+    (2, "sym_emit"): ("symbolic.hip", "65d32d837ef3", 11417.4, 24504.0),
+    (3, "convert"): ("convert.hip", "67ac7a722d7c", 82441.2, 294554.9),
+    (3, "numeric"): ("numeric.hip", "15aefc848925", 339997.7, 1194439.7),
+    (3, "scan_rows"): ("symbolic.hip", "65d32d837ef3", 994.2, 2592.3),
+    (3, "scan_sym"): ("symbolic.hip", "65d32d837ef3", 312.6, 275.5),
+    (3, "sym_count"): ("symbolic.hip", "65d32d837ef3", 22561.5, 3241.1),
+    (3, "sym_emit"): ("symbolic.hip", "65d32d837ef3", 71418.1, 266005.5),
+    (4, "convert"): ("convert.hip", "67ac7a722d7c", 38651.5, 473228.3),
+    (4, "count_masks"): ("symbolic.hip", "65d32d837ef3", 119845482.7, 4612574.6),
+    (4, "numeric"): ("numeric.hip", "15aefc848925", 271466093.6, 33489881.3),
+    (4, "row_offsets"): ("symbolic.hip", "65d32d837ef3", 4666765.7, 9241613.8),
+    (4, "scan_rows"): ("symbolic.hip", "65d32d837ef3", 790.4, 2048.5),
+    (4, "scan_sym"): ("symbolic.hip", "65d32d837ef3", 256.8, 202.5),
+    (4, "sym_count"): ("symbolic.hip", "65d32d837ef3", 15355671.8, 508994.7),
+    (4, "sym_emit"): ("symbolic.hip", "65d32d837ef3", 50964918.6, 70881118.9),
+    (5, "convert"): ("convert.hip", "67ac7a722d7c", 14192.7, 50072.0),
+    (5, "numeric"): ("numeric.hip", "15aefc848925", 53904.7, 270305.6),
+    (5, "scan_rows"): ("symbolic.hip", "65d32d837ef3", 406.2, 1024.4),
+    (5, "scan_sym"): ("symbolic.hip", "65d32d837ef3", 153.1, 98.6),
+    (5, "sym_count"): ("symbolic.hip", "65d32d837ef3", 4864.1, 1280.0),
+    (5, "sym_emit"): ("symbolic.hip", "65d32d837ef3", 8704.7, 16309.8),
 }
 
 KERNEL_SOURCE = {"convert": "convert.hip", "sym_count": "symbolic.hip", "scan_sym": "symbolic.hip",
