@@ -62,6 +62,7 @@ constexpr int kBlockEntries = 64;      // task-list entries staged at a time: on
 constexpr int kRowTilesUnrolled = 16;  // ... up to which its loop over the groups of four tiles is unrolled (2 % faster)
 constexpr int kRowTiles = 60;          // whole-tile-row kernel: most output tiles a tile-row may have (one lane each)
 constexpr int kRowEntries = 448;       // ... and most structural entries (its output is assembled in LDS)
+constexpr int64_t kSparseTileEntries = 3;   // kHalves is used for operands with at most this many entries per tile on average
 
 struct Header {          // tile headers of one task-list entry, as the lanes of the wave read them from LDS
     uint32_t lm, lo, rm, ro;   // group masks and BYTE offsets of the first group: left form of A, right form of B
@@ -142,7 +143,14 @@ __device__ __forceinline__ void swap_rows(float &x, float &y, bool halves) {
 // positions the counting pass assigned, and writes the stretch with full-width stores.  Written
 // tile by tile, a row of a sparse tile is a run of a few entries, and a store costs by the
 // 64-byte lines it touches, not by the bytes it carries.
-template <bool kNarrow, int kTilesPerWave, bool kMatrixCores, bool kWholeRows = false>
+//
+// kHalves: for operands whose tiles hold a few entries (a power-law graph: two per tile).  The inner dimension
+// of the instruction is four slots of eight inner indices, and a pair of tiles fills two of them, one per half
+// of its 16 inner indices.  Where the A tile has nothing in a half of its columns, or the B tile nothing in
+// that half of its rows, the slot multiplies zeros: on such a graph a pair has 1.17 halves that meet, not 2.
+// Here the halves that meet are listed when the entries are staged (entry and half, in task-list order), and a
+// step takes four of them, of up to four different pairs: 0.29 steps and operand loads per pair instead of 0.5.
+template <bool kNarrow, int kTilesPerWave, bool kMatrixCores, bool kWholeRows = false, bool kHalves = false>
 __global__ __launch_bounds__(kNumThreads) void k_numeric(
     const int64_t c_tiles, const int64_t c_nnz, const NumericSizes z, const int64_t c_rows, const int32_t c_tile_rows,
     const int32_t *__restrict__ c_tile_row_ptr, const int64_t *__restrict__ pair_off,
@@ -161,6 +169,9 @@ __global__ __launch_bounds__(kNumThreads) void k_numeric(
     __shared__ uint4 lds_operands[kMatrixCores ? 1 : kNumThreads / 64][2][64];
     // column and value of every entry of the wave's tile-row, in CSR order (whole-tile-row kernel only)
     __shared__ uint32_t lds_entries[kWholeRows ? kNumThreads / 64 : 1][2][kWholeRows ? kRowEntries : 1];
+    // kHalves: the halves of the staged entries that meet, 2 * entry + half, in task-list order
+    static_assert(!kHalves || (kMatrixCores && !kWholeRows), "the list of halves feeds the MFMA steps of the tile-group kernel");
+    __shared__ uint8_t lds_halves[kHalves ? kNumThreads / 64 : 1][kHalves ? 2 * kBlockEntries + 4 : 4];
     // consecutive logical blocks on the same XCD (workgroups are dealt to the XCDs round-robin)
     const int64_t logical = xcd_chunked_index(blockIdx.x, xcd_chunk);
     // wave-uniform values are kept in scalar registers; their loads become scalar loads
@@ -196,6 +207,9 @@ __global__ __launch_bounds__(kNumThreads) void k_numeric(
     const BufferArray a_ldata(a_ldata_, z.a_groups * 16), b_rdata(b_rdata_, z.b_groups * 16);
     uint4 *const my_heads = lds_heads[wave_in_block];
     const uint4 *const my_half = my_heads + upper;    // lanes 32-63 read the entry after the one lanes 0-31 read
+    uint8_t *const my_halves = lds_halves[kHalves ? wave_in_block : 0];
+    uint32_t halves_before = 0;                       // kHalves: listed halves of the staged entries before this lane's
+    int halves_total = 0;                             // ... and of all 64 (uniform)
 
     // segment bounds of the run's tiles, relative to the first one (one vector load, then scalars)
     const int64_t off_lane = pair_off[run_begin + min(lane, run_tiles)];
@@ -232,6 +246,17 @@ __global__ __launch_bounds__(kNumThreads) void k_numeric(
         }
         wave_sync();                               // earlier reads of the records are done
         my_heads[lane] = record;
+        if constexpr (kHalves) {
+            // a half meets when the A tile has a group in that half of its columns and the B tile one in that
+            // half of its rows (entries past the end have all-zero records and list nothing)
+            const uint32_t h0 = ((record.x & 0xFFFFu) && (record.z & 0xFFFFu)) ? 1u : 0u;
+            const uint32_t h1 = ((record.x >> 16) && (record.z >> 16)) ? 1u : 0u;
+            const uint32_t inc = wave_inclusive_scan(h0 + h1);
+            halves_before = inc - h0 - h1;
+            halves_total = __builtin_amdgcn_readlane((int)inc, 63);
+            if (h0) my_halves[halves_before] = (uint8_t)(2 * lane);
+            if (h1) my_halves[halves_before + h0] = (uint8_t)(2 * lane + 1);
+        }
         wave_sync();
     };
     // operands of a step (entry `src` of the block for lanes 0-31, entry src+1 for lanes 32-63, the
@@ -250,9 +275,45 @@ __global__ __launch_bounds__(kNumThreads) void k_numeric(
             bv.u = (h.z & mine) ? b_rdata_[(uint64_t)h.w + __popc(h.z & below)] : make_uint4(0, 0, 0, 0);
         }
     };
+    // kHalves: the operands of four listed halves, `first`.. of the staged block (those at or past `end` are
+    // zeros): lanes 16q..16q+15 take the half first+q, of whichever entry it belongs to
+    auto load_halves = [&](int first, int end, Group &av, Group &bv) {
+        const int mine = first + tq;
+        const bool live = mine < end;
+        const uint32_t item = live ? my_halves[mine] : 0u;
+        const uint4 h = my_heads[item >> 1];
+        const uint32_t slot = 1u << (j + 16 * (item & 1u)), under = slot - 1u;
+        if constexpr (kNarrow) {
+            const uint32_t ao = ((uint32_t)__popc(h.x & under) << 4) + h.y;
+            const uint32_t bo = ((uint32_t)__popc(h.z & under) << 4) + h.w;
+            av.u = a_ldata.template u128<0>((live && (h.x & slot)) ? ao : kSkip);
+            bv.u = b_rdata.template u128<0>((live && (h.z & slot)) ? bo : kSkip);
+        } else {
+            av.u = (live && (h.x & slot)) ? a_ldata_[(uint64_t)h.y + __popc(h.x & under)] : make_uint4(0, 0, 0, 0);
+            bv.u = (live && (h.z & slot)) ? b_rdata_[(uint64_t)h.w + __popc(h.z & under)] : make_uint4(0, 0, 0, 0);
+        }
+    };
     // multiply the `count` entries that start at entry `o` of the staged block into acc, two entries
     // per MFMA; the loads of up to four MFMAs are requested together
     auto multiply = [&](int o, int count, float4v &acc) {
+        if constexpr (kHalves) {
+            // the listed halves of those entries, four per MFMA
+            const int i0 = __builtin_amdgcn_readlane((int)halves_before, o);
+            const int i1 = o + count < 64 ? __builtin_amdgcn_readlane((int)halves_before, o + count) : halves_total;
+            for (int it = i0; it < i1; it += 16) {
+                Group a0, b0, a1, b1, a2, b2, a3, b3;
+                const int left = i1 - it;                                  // > 0, uniform
+                load_halves(it, i1, a0, b0);
+                if (left > 4) load_halves(it + 4, i1, a1, b1);
+                if (left > 8) load_halves(it + 8, i1, a2, b2);
+                if (left > 12) load_halves(it + 12, i1, a3, b3);
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a0.h, b0.h, acc, 0, 0, 0);
+                if (left > 4) acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1.h, b1.h, acc, 0, 0, 0);
+                if (left > 8) acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a2.h, b2.h, acc, 0, 0, 0);
+                if (left > 12) acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a3.h, b3.h, acc, 0, 0, 0);
+            }
+            return;
+        }
         if constexpr (kMatrixCores) {
             // entries in flight: short sparse tile-rows have segments of one to four entries, and the
             // registers of the deeper batch would cost their kernel a wave per SIMD
@@ -536,6 +597,10 @@ int numeric_enqueue(tsp_context *ctx, tsp_tiles_s *A, tsp_tiles_s *B, tsp_plan_s
                             (uint64_t)P->c_nnz * 4 < limit && !ctx->force_wide;
         auto kernel = narrow ? (tiles_per_wave == 4 ? k_numeric<true, 4, true> : k_numeric<true, 8, true>)
                              : (tiles_per_wave == 4 ? k_numeric<false, 4, true> : k_numeric<false, 8, true>);
+        // operands whose tiles hold a handful of entries: a step takes the halves that meet (see kHalves)
+        const bool sparse_tiles = ctx->matrix_cores && tiles_per_wave == kGroupTiles && A->ntiles > 0 && B->ntiles > 0 &&
+                                  A->nnz <= kSparseTileEntries * A->ntiles && B->nnz <= kSparseTileEntries * B->ntiles;
+        if (sparse_tiles) kernel = narrow ? k_numeric<true, 4, true, false, true> : k_numeric<false, 4, true, false, true>;
         if (!ctx->matrix_cores) kernel = narrow ? k_numeric<true, 4, false> : k_numeric<false, 4, false>;
         if (whole_rows && P->max_row_c_tiles <= kRowTilesUnrolled)
             kernel = narrow ? k_numeric<true, kRowTilesUnrolled, true, true> : k_numeric<false, kRowTilesUnrolled, true, true>;
