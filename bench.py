@@ -50,40 +50,40 @@ CSRC = os.path.join(ROOT, "paper_2009_14600_amd", "csrc")
 # profiles/hbm_traffic_all_kernels.txt holds the readings and the commands.
 #   (workload, kernel): (source file, sha256[:12] at the time, FETCH_SIZE, WRITE_SIZE)
 MEASURED_TRAFFIC = {
-    (1, "convert"): ("convert.hip", "67ac7a722d7c", 201.7, 782.7),
-    (1, "count_masks"): ("symbolic.hip", "65d32d837ef3", 733.5, 128.0),
-    (1, "numeric"): ("numeric.hip", "15aefc848925", 1244.5, 499.0),
+    (1, "convert"): ("convert.hip", "67ac7a722d7c", 201.6, 782.7),
+    (1, "count_masks"): ("symbolic.hip", "65d32d837ef3", 733.6, 128.0),
+    (1, "numeric"): ("numeric.hip", "ed6fb3a14cf6", 1264.8, 499.0),
     (1, "row_offsets"): ("symbolic.hip", "65d32d837ef3", 91.1, 262.0),
     (1, "scan_rows"): ("symbolic.hip", "65d32d837ef3", 6.4, 8.3),
     (1, "scan_sym"): ("symbolic.hip", "65d32d837ef3", 7.2, 1.3),
     (1, "sym_count"): ("symbolic.hip", "65d32d837ef3", 190.2, 10.0),
     (1, "sym_emit"): ("symbolic.hip", "65d32d837ef3", 203.6, 478.3),
-    (2, "convert"): ("convert.hip", "67ac7a722d7c", 6119.8, 43225.2),
-    (2, "numeric"): ("numeric.hip", "15aefc848925", 30667.7, 26555.3),
-    (2, "scan_rows"): ("symbolic.hip", "65d32d837ef3", 790.2, 2048.3),
-    (2, "scan_sym"): ("symbolic.hip", "65d32d837ef3", 256.3, 201.6),
+    (2, "convert"): ("convert.hip", "67ac7a722d7c", 6120.4, 43223.1),
+    (2, "numeric"): ("numeric.hip", "ed6fb3a14cf6", 30663.9, 26555.3),
+    (2, "scan_rows"): ("symbolic.hip", "65d32d837ef3", 790.2, 2048.5),
+    (2, "scan_sym"): ("symbolic.hip", "65d32d837ef3", 256.6, 214.2),
     (2, "sym_count"): ("symbolic.hip", "65d32d837ef3", 6153.1, 1280.0),
-    (2, "sym_emit"): ("symbolic.hip", "65d32d837ef3", 11417.4, 24504.0),
-    (3, "convert"): ("convert.hip", "67ac7a722d7c", 82441.2, 294554.9),
-    (3, "numeric"): ("numeric.hip", "15aefc848925", 339997.7, 1194439.7),
+    (2, "sym_emit"): ("symbolic.hip", "65d32d837ef3", 11418.3, 24504.0),
+    (3, "convert"): ("convert.hip", "67ac7a722d7c", 82440.9, 294561.7),
+    (3, "numeric"): ("numeric.hip", "ed6fb3a14cf6", 340006.1, 1194490.5),
     (3, "scan_rows"): ("symbolic.hip", "65d32d837ef3", 994.2, 2592.3),
-    (3, "scan_sym"): ("symbolic.hip", "65d32d837ef3", 312.6, 275.5),
-    (3, "sym_count"): ("symbolic.hip", "65d32d837ef3", 22561.5, 3241.1),
-    (3, "sym_emit"): ("symbolic.hip", "65d32d837ef3", 71418.1, 266005.5),
-    (4, "convert"): ("convert.hip", "67ac7a722d7c", 38651.5, 473228.3),
-    (4, "count_masks"): ("symbolic.hip", "65d32d837ef3", 119845482.7, 4612574.6),
-    (4, "numeric"): ("numeric.hip", "15aefc848925", 271466093.6, 33489881.3),
-    (4, "row_offsets"): ("symbolic.hip", "65d32d837ef3", 4666765.7, 9241613.8),
-    (4, "scan_rows"): ("symbolic.hip", "65d32d837ef3", 790.4, 2048.5),
-    (4, "scan_sym"): ("symbolic.hip", "65d32d837ef3", 256.8, 202.5),
-    (4, "sym_count"): ("symbolic.hip", "65d32d837ef3", 15355671.8, 508994.7),
-    (4, "sym_emit"): ("symbolic.hip", "65d32d837ef3", 50964918.6, 70881118.9),
-    (5, "convert"): ("convert.hip", "67ac7a722d7c", 14192.7, 50072.0),
-    (5, "numeric"): ("numeric.hip", "15aefc848925", 53904.7, 270305.6),
-    (5, "scan_rows"): ("symbolic.hip", "65d32d837ef3", 406.2, 1024.4),
-    (5, "scan_sym"): ("symbolic.hip", "65d32d837ef3", 153.1, 98.6),
+    (3, "scan_sym"): ("symbolic.hip", "65d32d837ef3", 312.2, 271.0),
+    (3, "sym_count"): ("symbolic.hip", "65d32d837ef3", 22562.4, 3241.0),
+    (3, "sym_emit"): ("symbolic.hip", "65d32d837ef3", 71423.4, 266006.1),
+    (4, "convert"): ("convert.hip", "67ac7a722d7c", 38660.3, 473242.6),
+    (4, "count_masks"): ("symbolic.hip", "65d32d837ef3", 119848216.4, 4612574.6),
+    (4, "numeric"): ("numeric.hip", "ed6fb3a14cf6", 269244343.1, 33419349.5),
+    (4, "row_offsets"): ("symbolic.hip", "65d32d837ef3", 4666779.8, 9241581.6),
+    (4, "scan_rows"): ("symbolic.hip", "65d32d837ef3", 790.4, 2049.1),
+    (4, "scan_sym"): ("symbolic.hip", "65d32d837ef3", 255.9, 196.9),
+    (4, "sym_count"): ("symbolic.hip", "65d32d837ef3", 15365684.4, 508990.6),
+    (4, "sym_emit"): ("symbolic.hip", "65d32d837ef3", 50858751.2, 70878252.9),
+    (5, "convert"): ("convert.hip", "67ac7a722d7c", 14192.6, 50065.9),
+    (5, "numeric"): ("numeric.hip", "ed6fb3a14cf6", 53954.3, 270245.2),
+    (5, "scan_rows"): ("symbolic.hip", "65d32d837ef3", 406.2, 1024.5),
+    (5, "scan_sym"): ("symbolic.hip", "65d32d837ef3", 153.4, 98.5),
     (5, "sym_count"): ("symbolic.hip", "65d32d837ef3", 4864.1, 1280.0),
-    (5, "sym_emit"): ("symbolic.hip", "65d32d837ef3", 8704.7, 16309.8),
+    (5, "sym_emit"): ("symbolic.hip", "65d32d837ef3", 8703.7, 16309.8),
 }
 
 KERNEL_SOURCE = {"convert": "convert.hip", "sym_count": "symbolic.hip", "scan_sym": "symbolic.hip",
